@@ -1,0 +1,209 @@
+/*
+ * qsync.h - C ABI of the MI355X (gfx950) quantized training operators.
+ *
+ * The library implements the low-precision operator backend of QSync (arXiv 2407.02327,
+ * section "Backend Optimization and Implementation"): for a linear operator Y = X W^T + b
+ * with a per-operator precision tag b in {INT8, FP16, FP32} (problem (1) of the paper),
+ * it finds the absolute maximum of a tensor, derives a symmetric fixed-point scale,
+ * quantizes to INT8 codes (or casts to FP16), runs the forward GEMM and the two backward
+ * GEMMs dX = dY W and dW = dY^T X with int32 / fp32 accumulation, and dequantizes with the
+ * scales and the bias fused into the GEMM epilogue.
+ *
+ * Conventions that hold for every entry point
+ *  - All data pointers are DEVICE pointers (HIP global memory) unless a parameter says
+ *    "host".  The library never allocates, frees or keeps device memory: every buffer,
+ *    including scratch ("workspace"), is owned by the caller.
+ *  - Matrices are row-major.  Inputs that take a leading dimension `ld` count it in
+ *    elements; every other matrix is packed (leading dimension = number of columns).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; they never synchronise and never copy to the host.  Scales stay on the
+ *    device.
+ *  - Return value: QSYNC_OK (0) or a negative qsync_status_t.  Arguments are validated
+ *    before any HIP call; nothing is launched when validation fails.  The library never
+ *    throws, aborts or prints.  After QSYNC_ERR_HIP, qsync_last_hip_error() returns the
+ *    hipError_t of the failing call on this thread.
+ *  - A tensor with rows*cols == 0 (or a GEMM with M*N == 0) is a successful no-op.
+ *    A GEMM with K == 0 writes the bias (or zeros).
+ *  - Inputs must be finite; behaviour on NaN/Inf is unspecified.
+ *  - Calls on different streams may run concurrently as long as their buffers are disjoint.
+ */
+#ifndef QSYNC_H
+#define QSYNC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Per-operator precision tag b_io (paper: problem (1); evaluation uses INT8, FP16, FP32). */
+typedef enum { QSYNC_INT8 = 8, QSYNC_FP16 = 16, QSYNC_FP32 = 32 } qsync_prec_t;
+
+/* Element type of a buffer. */
+typedef enum { QSYNC_F32 = 0, QSYNC_F16 = 1, QSYNC_I8 = 2, QSYNC_I32 = 3 } qsync_dtype_t;
+
+/* Granularity of a scale: one per tensor ("layer-wise"), one per row, or one per column
+ * ("channel-wise"; paper, Cost Mapper paragraph on quantization methods). */
+typedef enum { QSYNC_PER_TENSOR = 0, QSYNC_PER_ROW = 1, QSYNC_PER_COL = 2 } qsync_gran_t;
+
+/* Rounding of the fixed-point quantizer: ties-to-even, stochastic (the unbiased quantizer
+ * of the Indicator section), or floor (Discussion, "Quantization by Floor"). */
+typedef enum { QSYNC_ROUND_NEAREST = 0, QSYNC_ROUND_STOCHASTIC = 1, QSYNC_ROUND_FLOOR = 2 } qsync_round_t;
+
+typedef enum {
+    QSYNC_OK              = 0,
+    QSYNC_ERR_NULL        = -1, /* a required pointer is NULL */
+    QSYNC_ERR_BAD_ENUM    = -2, /* an enum argument holds no enumerator */
+    QSYNC_ERR_BAD_SHAPE   = -3, /* negative dimension, ld < cols, or element count overflow */
+    QSYNC_ERR_UNSUPPORTED = -4, /* valid but not implemented combination (bits, tag/dtype) */
+    QSYNC_ERR_ALIGN       = -5, /* pointer or dimension violates a kernel's alignment rule */
+    QSYNC_ERR_WORKSPACE   = -6, /* workspace NULL or smaller than the matching *_workspace_bytes */
+    QSYNC_ERR_HIP         = -7  /* a HIP runtime call failed */
+} qsync_status_t;
+
+/*
+ * qsync_absmax_scale - absolute maximum and symmetric fixed-point scale.
+ * Paper: Backend section, "Minmax Optimization" (two-step reduction: block partials, then a
+ * small second kernel); scale of the fixed-point quantizer x_bar = (x - z)/q with z = 0.
+ *
+ *   amax  = max |x| over the tensor (PER_TENSOR), each row (PER_ROW) or each column (PER_COL)
+ *   scale = amax / qmax,  inv_scale = qmax / amax,   qmax = 2^(bits-1) - 1   (one fp32 division each)
+ *   amax == 0  ->  scale = inv_scale = 1
+ *
+ * x         [rows, ld] of xdt (QSYNC_F32 or QSYNC_F16), ld >= cols.
+ * scale, inv_scale   out, 1 / rows / cols floats according to gran.  Both required.
+ * amax_opt  out, same shape, may be NULL.
+ * workspace scratch of at least qsync_absmax_workspace_bytes(rows, cols, gran) bytes, 16-byte aligned.
+ * bits      2..8.
+ * Any alignment of x and ld is accepted (vector loads are used when x and ld*sizeof(elem)
+ * are multiples of 16 bytes).
+ */
+int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld,
+                       int gran, int bits, float* scale, float* inv_scale, float* amax_opt,
+                       void* workspace, size_t workspace_bytes, void* stream);
+size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
+
+/*
+ * qsync_quantize - precision conversion of one tensor under a precision tag.
+ * Paper: Indicator section (x_bar = (x - z)/q, x_hat = round(x_bar) q + z, stochastic
+ * rounding as the unbiased quantizer), Cost Mapper (casting kernels), Backend section.
+ *
+ *   tag INT8: code = clamp(round(x * inv_scale), -qmax, qmax) as int8; the product is one
+ *             fp32 multiply.  Stochastic rounding: with f = x*inv - floor(x*inv), round up
+ *             iff u < floor(f * 2^16), where u is the 16-bit draw of the element:
+ *             Philox4x32-10, key = (seed low word, seed high word), counter = the 128-bit
+ *             integer offset + i/8 (i = row*cols + col, independent of ld), output words
+ *             cut into eight 16-bit draws, element takes draw i%8 (word (i%8)/2, low half
+ *             first).  A call consumes ceil(rows*cols/8) counters.
+ *   tag FP16: IEEE round-to-nearest-even narrowing to binary16 (copy if x is binary16).
+ *   tag FP32: copy as fp32 (widening from binary16 is exact).
+ *
+ * x         [rows, ld] of xdt (QSYNC_F32 or QSYNC_F16).
+ * inv_scale from qsync_absmax_scale with the same gran (1 / rows / cols floats); ignored
+ *           (may be NULL) for FP16 and FP32.
+ * q_opt     out, packed [rows, cols] of int8 / binary16 / fp32 according to tag, or NULL.
+ * qT_opt    out, packed [cols, rows], the transpose of q (identical codes), or NULL.
+ *           At least one of q_opt, qT_opt is required.  The GEMM entry points take some
+ *           operands in transposed form; this is where those copies are made.
+ * bits, gran, rnd, seed, offset are ignored for FP16 / FP32.
+ * Any shape and alignment is accepted; the vectorised path needs cols % 8 == 0, x and ld*sizeof(elem)
+ * multiples of 16 bytes, q 16-byte aligned (and rows % 16 == 0 for qT).
+ */
+int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld,
+                   int tag, int bits, int gran, int rnd,
+                   uint64_t philox_seed, uint64_t philox_offset, const float* inv_scale,
+                   void* q_opt, void* qT_opt, void* stream);
+
+/*
+ * qsync_qlinear_fwd - forward GEMM with the dequantizer and bias fused into the epilogue.
+ * Paper: proof of Prop. 2 (y = q_v q_w sum(v_q w_q) + b), Backend section "Dequantization
+ * Fusion" (int32 accumulation, INT32 -> FP32 conversion with the scale in the epilogue),
+ * Cost Mapper (layer-wise input with channel-wise weight -> channel-wise dequantizer).
+ *
+ *   INT8: acc[m,n] = sum_k xq[m,k] wq[n,k]  (int32, wraps mod 2^32)
+ *         Y[m,n]   = float(acc) * (sx * sw[n or 0]) + bias[n]
+ *   FP16: Y = X W^T + bias with binary16 operands, fp32 accumulation.
+ *   FP32: Y = X W^T + bias in fp32.
+ *
+ * xq  [M,K], wq [N,K] packed, element type int8 / binary16 / fp32 by tag, 16-byte aligned.
+ * sx  1 float (per-tensor activation scale); sw 1 float (wgran PER_TENSOR) or N floats
+ *     (PER_ROW of wq, i.e. per output channel).  Both ignored (may be NULL) unless tag is INT8.
+ * bias_opt  N floats or NULL.
+ * y   out, packed [M,N] of ydt (QSYNC_F32 or QSYNC_F16).
+ * acc_dump_opt  INT8 only: if non-NULL, also receives the raw int32 accumulators [M,N]
+ *     (verification aid; NULL in production).
+ * workspace     at least qsync_qlinear_workspace_bytes(tag, M, N, K) bytes, 16-byte aligned
+ *     (may be NULL if that is 0).
+ * INT8 needs K % 16 == 0 and FP16 needs K % 8 == 0 (rows of 16-byte vectors feed the matrix
+ * cores); otherwise QSYNC_ERR_ALIGN.  M and N are arbitrary.
+ */
+int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K,
+                      const void* xq, const float* sx,
+                      const void* wq, const float* sw, int wgran,
+                      const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * qsync_qlinear_bwd - both backward GEMMs of a linear operator, plus the bias gradient.
+ * Paper: Appendix proof of Prop. 1 ((dW, dX) = G[dY, C(v, x)]); Backend section (dW is
+ * produced in FP32, dX in FP16, dequantization fused in the epilogue).
+ *
+ *   dX[m,k] = sum_n dY[m,n] W[n,k]      dW[n,k] = sum_m dY[m,n] X[m,k]      db[n] = sum_m dY[m,n]
+ *   INT8: dX = float(accX) * (sdy * swb[k or 0]),  dW = float(accW) * (sdy * sx), int32 accumulators.
+ *
+ * Every operand is handed over with its contraction axis contiguous:
+ *   dyq   [M,N]  and  dyqT [N,M]   the quantized / cast gradient and its transpose
+ *   xqT   [K,M]                    transpose of the forward's activation operand
+ *   wqbT  [K,N]                    transpose of the weight operand.  For INT8 its scale swb is
+ *                                  1 float (wbgran PER_TENSOR) or K floats (PER_ROW of wqbT, one
+ *                                  per input feature k): a scale along n would lie on the
+ *                                  contraction axis of dX and could not leave the integer sum.
+ * sdy, sx  1 float each (INT8 only).
+ * dx_opt  out [M,K] of dxdt; dw_opt out [N,K] of dwdt (QSYNC_F32 or QSYNC_F16); either may be
+ *         NULL to skip that GEMM (then its operands may be NULL too).
+ * db_opt  out N floats or NULL; needs dy_float_opt, the unquantized gradient [M,N] of dydt
+ *         (QSYNC_F32 or QSYNC_F16, packed), summed in fp32.
+ * acc_dx_dump_opt [M,K], acc_dw_dump_opt [N,K]: raw int32 accumulators (INT8 only), or NULL.
+ * workspace  at least qsync_qlinear_bwd_workspace_bytes(tag, M, N, K) bytes.
+ * Alignment: INT8 needs N % 16 == 0 (for dX) and M % 16 == 0 (for dW); FP16 needs % 8.
+ */
+int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K,
+                      const void* dyq, const void* dyqT, const float* sdy,
+                      const void* xqT, const float* sx,
+                      const void* wqbT, const float* swb, int wbgran,
+                      void* dx_opt, int dxdt, void* dw_opt, int dwdt,
+                      float* db_opt, const void* dy_float_opt, int dydt,
+                      int32_t* acc_dx_dump_opt, int32_t* acc_dw_dump_opt,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
+size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
+
+/*
+ * qsync_dequantize - standalone dequantizer (used when it is not fused into a GEMM).
+ * Paper: Indicator section (x_hat = code * q), Cost Mapper (layer-wise / channel-wise
+ * dequantizers as element-wise kernels).
+ *
+ *   y[r,c] = float(a[r,c]) * tensor_scale * row_scale[r] * col_scale[c] + col_bias[c]
+ *   (absent factors are 1, absent bias is 0; evaluated in fp32 in that order)
+ *
+ * a  [rows, ld] of adt (QSYNC_I32 or QSYNC_I8).  tensor_scale is a HOST float.
+ * row_scale_opt rows floats, col_scale_opt / col_bias_opt cols floats, or NULL.
+ * y  out, packed [rows, cols] of ydt (QSYNC_F32 or QSYNC_F16).
+ */
+int qsync_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld,
+                     const float* row_scale_opt, const float* col_scale_opt, float tensor_scale,
+                     const float* col_bias_opt, void* y, int ydt, void* stream);
+
+/* hipError_t (as int) of the last failing HIP call made by this thread, 0 if none. */
+int qsync_last_hip_error(void);
+/* Static description of a qsync_status_t. */
+const char* qsync_strerror(int status);
+/* Library version, major*100 + minor. */
+int qsync_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSYNC_H */

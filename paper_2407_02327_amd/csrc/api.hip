@@ -1,0 +1,256 @@
+// C ABI of libqsync: argument validation (the "front-end security wrapper" the paper's backend
+// puts around its tensorized kernels) and dispatch to the gfx950 kernels.  Validation never
+// touches the HIP runtime, so every argument error is reported even on a machine with no GPU.
+#include "../../include/qsync.h"
+#include "kernels.h"
+
+#include <limits>
+
+using namespace qsync;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_status(hipError_t e)
+{
+    if(e == hipSuccess) return QSYNC_OK;
+    g_last_hip_error = static_cast<int>(e);
+    (void)hipGetLastError();   // clear the sticky launch error
+    return QSYNC_ERR_HIP;
+}
+
+bool is_float_dtype(int dt) { return dt == QSYNC_F32 || dt == QSYNC_F16; }
+bool is_tag(int t) { return t == QSYNC_INT8 || t == QSYNC_FP16 || t == QSYNC_FP32; }
+bool is_gran(int g) { return g == QSYNC_PER_TENSOR || g == QSYNC_PER_ROW || g == QSYNC_PER_COL; }
+bool is_round(int r) { return r == QSYNC_ROUND_NEAREST || r == QSYNC_ROUND_STOCHASTIC || r == QSYNC_ROUND_FLOOR; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// rows*cols (and a few multiples of it) must fit comfortably in int64
+bool count_ok(int64_t a, int64_t b)
+{
+    if(a < 0 || b < 0) return false;
+    if(a == 0 || b == 0) return true;
+    return a <= (std::numeric_limits<int64_t>::max() / 64) / b;
+}
+
+size_t round256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+}  // namespace
+
+extern "C" {
+
+int qsync_version(void) { return 100; }
+
+int qsync_last_hip_error(void) { return g_last_hip_error; }
+
+const char* qsync_strerror(int status)
+{
+    switch(status)
+    {
+    case QSYNC_OK: return "ok";
+    case QSYNC_ERR_NULL: return "a required pointer is NULL";
+    case QSYNC_ERR_BAD_ENUM: return "an enum argument holds no enumerator";
+    case QSYNC_ERR_BAD_SHAPE: return "bad shape: negative dimension, ld < cols, or element count overflow";
+    case QSYNC_ERR_UNSUPPORTED: return "unsupported combination of arguments";
+    case QSYNC_ERR_ALIGN: return "pointer or dimension violates an alignment rule";
+    case QSYNC_ERR_WORKSPACE: return "workspace missing or too small";
+    case QSYNC_ERR_HIP: return "a HIP runtime call failed (see qsync_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran)
+{
+    if(rows < 0 || cols < 0 || !is_gran(gran)) return 0;
+    return round256(absmax_workspace_bytes(rows, cols, gran));
+}
+
+int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran, int bits,
+                       float* scale, float* inv_scale, float* amax_opt, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    if(!x || !scale || !inv_scale) return QSYNC_ERR_NULL;
+    if(!is_float_dtype(xdt) || !is_gran(gran)) return QSYNC_ERR_BAD_ENUM;
+    if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    if(rows == 0 || cols == 0) return QSYNC_OK;
+    const size_t need = qsync_absmax_workspace_bytes(rows, cols, gran);
+    if(need > 0)
+    {
+        if(!workspace || workspace_bytes < need) return QSYNC_ERR_WORKSPACE;
+        if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
+    }
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    return hip_status(launch_absmax_scale(x, xdt, rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt,
+                                          static_cast<float*>(workspace), static_cast<hipStream_t>(stream)));
+}
+
+int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int tag, int bits, int gran,
+                   int rnd, uint64_t philox_seed, uint64_t philox_offset, const float* inv_scale, void* q_opt,
+                   void* qT_opt, void* stream)
+{
+    if(!x || (!q_opt && !qT_opt)) return QSYNC_ERR_NULL;
+    if(!is_tag(tag) || !is_float_dtype(xdt)) return QSYNC_ERR_BAD_ENUM;
+    if(tag == QSYNC_INT8)
+    {
+        if(!inv_scale) return QSYNC_ERR_NULL;
+        if(!is_gran(gran) || !is_round(rnd)) return QSYNC_ERR_BAD_ENUM;
+    }
+    if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
+    if(tag == QSYNC_INT8 && (bits < 2 || bits > 8)) return QSYNC_ERR_UNSUPPORTED;
+    if(rows == 0 || cols == 0) return QSYNC_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if(tag == QSYNC_INT8)
+    {
+        const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+        return hip_status(launch_quantize_int8(x, xdt, rows, cols, ld, qmax, gran, rnd, philox_seed, philox_offset,
+                                               inv_scale, static_cast<int8_t*>(q_opt), static_cast<int8_t*>(qT_opt),
+                                               st));
+    }
+    return hip_status(launch_convert(x, xdt, rows, cols, ld, tag == QSYNC_FP16 ? kF16 : kF32, q_opt, qT_opt, st));
+}
+
+size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K)
+{
+    if(!is_tag(tag) || M < 0 || N < 0 || K < 0) return 0;
+    return round256(plan_gemm(tag, M, N, K).workspace);
+}
+
+size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K)
+{
+    if(!is_tag(tag) || M < 0 || N < 0 || K < 0) return 0;
+    return round256(plan_gemm(tag, M, K, N).workspace) + round256(plan_gemm(tag, N, K, M).workspace)
+         + round256(colsum_workspace_bytes(M, N));
+}
+
+int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
+                      const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    if(!xq || !wq || !y) return QSYNC_ERR_NULL;
+    if(!is_tag(tag) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
+    if(tag == QSYNC_INT8)
+    {
+        if(!sx || !sw) return QSYNC_ERR_NULL;
+        if(!is_gran(wgran)) return QSYNC_ERR_BAD_ENUM;
+    }
+    if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if(tag == QSYNC_INT8 && wgran == QSYNC_PER_COL) return QSYNC_ERR_UNSUPPORTED;
+    if(tag != QSYNC_INT8 && acc_dump_opt) return QSYNC_ERR_UNSUPPORTED;
+    if(tag != QSYNC_FP32)
+    {
+        if(K % (tag == QSYNC_INT8 ? 16 : 8) != 0) return QSYNC_ERR_ALIGN;
+        if(!aligned16(xq) || !aligned16(wq)) return QSYNC_ERR_ALIGN;
+    }
+    if(M == 0 || N == 0) return QSYNC_OK;
+    const GemmPlan plan = plan_gemm(tag, M, N, K);
+    if(plan.workspace > 0)
+    {
+        if(!workspace || workspace_bytes < plan.workspace) return QSYNC_ERR_WORKSPACE;
+        if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
+    }
+    GemmProblem p{};
+    p.prec = tag; p.M = M; p.N = N; p.K = K;
+    p.A = xq; p.B = wq; p.C = y; p.c_dtype = ydt;
+    if(tag == QSYNC_INT8)
+    {
+        p.s0 = sx;
+        if(wgran == QSYNC_PER_TENSOR) p.s1 = sw; else p.col_scale = sw;
+        p.acc_dump = acc_dump_opt;
+    }
+    p.col_bias = bias_opt;
+    return hip_status(launch_gemm(p, plan, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq, const void* dyqT, const float* sdy,
+                      const void* xqT, const float* sx, const void* wqbT, const float* swb, int wbgran, void* dx_opt,
+                      int dxdt, void* dw_opt, int dwdt, float* db_opt, const void* dy_float_opt, int dydt,
+                      int32_t* acc_dx_dump_opt, int32_t* acc_dw_dump_opt, void* workspace, size_t workspace_bytes,
+                      void* stream)
+{
+    if(dx_opt && (!dyq || !wqbT)) return QSYNC_ERR_NULL;
+    if(dw_opt && (!dyqT || !xqT)) return QSYNC_ERR_NULL;
+    if(db_opt && !dy_float_opt) return QSYNC_ERR_NULL;
+    if(!is_tag(tag)) return QSYNC_ERR_BAD_ENUM;
+    if(dx_opt && !is_float_dtype(dxdt)) return QSYNC_ERR_BAD_ENUM;
+    if(dw_opt && !is_float_dtype(dwdt)) return QSYNC_ERR_BAD_ENUM;
+    if(db_opt && !is_float_dtype(dydt)) return QSYNC_ERR_BAD_ENUM;
+    if(tag == QSYNC_INT8)
+    {
+        if((dx_opt || dw_opt) && !sdy) return QSYNC_ERR_NULL;
+        if(dx_opt && !swb) return QSYNC_ERR_NULL;
+        if(dw_opt && !sx) return QSYNC_ERR_NULL;
+        if(dx_opt && !is_gran(wbgran)) return QSYNC_ERR_BAD_ENUM;
+    }
+    if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if(tag == QSYNC_INT8 && dx_opt && wbgran == QSYNC_PER_COL) return QSYNC_ERR_UNSUPPORTED;
+    if(tag != QSYNC_INT8 && (acc_dx_dump_opt || acc_dw_dump_opt)) return QSYNC_ERR_UNSUPPORTED;
+    if(tag != QSYNC_FP32)
+    {
+        const int64_t mult = tag == QSYNC_INT8 ? 16 : 8;
+        if(dx_opt && (N % mult != 0 || !aligned16(dyq) || !aligned16(wqbT))) return QSYNC_ERR_ALIGN;
+        if(dw_opt && (M % mult != 0 || !aligned16(dyqT) || !aligned16(xqT))) return QSYNC_ERR_ALIGN;
+    }
+    const GemmPlan plan_dx = plan_gemm(tag, M, K, N);
+    const GemmPlan plan_dw = plan_gemm(tag, N, K, M);
+    const size_t   off_dw  = round256(plan_dx.workspace);
+    const size_t   off_db  = off_dw + round256(plan_dw.workspace);
+    const size_t   need    = (dx_opt ? plan_dx.workspace : 0) + (dw_opt ? plan_dw.workspace : 0)
+                        + ((db_opt && M > 0 && N > 0) ? colsum_workspace_bytes(M, N) : 0);
+    if(need > 0)
+    {
+        if(!workspace || workspace_bytes < qsync_qlinear_bwd_workspace_bytes(tag, M, N, K)) return QSYNC_ERR_WORKSPACE;
+        if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
+    }
+    hipStream_t st  = static_cast<hipStream_t>(stream);
+    char*       wsb = static_cast<char*>(workspace);
+    if(dx_opt && M > 0 && K > 0)
+    {
+        GemmProblem p{};
+        p.prec = tag; p.M = M; p.N = K; p.K = N;
+        p.A = dyq; p.B = wqbT; p.C = dx_opt; p.c_dtype = dxdt;
+        if(tag == QSYNC_INT8)
+        {
+            p.s0 = sdy;
+            if(wbgran == QSYNC_PER_TENSOR) p.s1 = swb; else p.col_scale = swb;
+            p.acc_dump = acc_dx_dump_opt;
+        }
+        const int rc = hip_status(launch_gemm(p, plan_dx, wsb, st));
+        if(rc != QSYNC_OK) return rc;
+    }
+    if(dw_opt && N > 0 && K > 0)
+    {
+        GemmProblem p{};
+        p.prec = tag; p.M = N; p.N = K; p.K = M;
+        p.A = dyqT; p.B = xqT; p.C = dw_opt; p.c_dtype = dwdt;
+        if(tag == QSYNC_INT8)
+        {
+            p.s0 = sdy; p.s1 = sx;
+            p.acc_dump = acc_dw_dump_opt;
+        }
+        const int rc = hip_status(launch_gemm(p, plan_dw, wsb ? wsb + off_dw : nullptr, st));
+        if(rc != QSYNC_OK) return rc;
+    }
+    if(db_opt && N > 0)
+    {
+        const int rc = hip_status(launch_colsum(dy_float_opt, dydt, M, N, db_opt,
+                                                reinterpret_cast<float*>(wsb + off_db), st));
+        if(rc != QSYNC_OK) return rc;
+    }
+    return QSYNC_OK;
+}
+
+int qsync_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld, const float* row_scale_opt,
+                     const float* col_scale_opt, float tensor_scale, const float* col_bias_opt, void* y, int ydt,
+                     void* stream)
+{
+    if(!a || !y) return QSYNC_ERR_NULL;
+    if((adt != QSYNC_I32 && adt != QSYNC_I8) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
+    if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
+    if(rows == 0 || cols == 0) return QSYNC_OK;
+    return hip_status(launch_dequantize(a, adt == QSYNC_I32 ? kI32 : kI8, rows, cols, ld, row_scale_opt, col_scale_opt,
+                                        tensor_scale, col_bias_opt, y, ydt, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

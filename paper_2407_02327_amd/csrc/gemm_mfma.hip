@@ -1,0 +1,398 @@
+// LDS-tiled MFMA GEMM for gfx950 (CDNA4):  C[M,N] = epilogue( sum_k A[m,k] * B[n,k] ).
+//
+// Both operands are K-contiguous ("NT"), which is exactly the operand shape of the gfx950
+// 32x32 matrix instructions: every lane feeds 16 contiguous K-bytes of one row of A and of
+// one row of B (v_mfma_i32_32x32x32_i8: 16 int8; v_mfma_f32_32x32x16_f16: 8 binary16).  The
+// INT8 and FP16 kernels therefore move identical bytes and share one tiling:
+//
+//   * block tile BM x BN, K step of 128 bytes per row; 256 threads = 4 wavefronts in a 2x2
+//     grid, each owning a (BM/2) x (BN/2) sub-tile as 32x32 accumulator fragments;
+//   * global -> registers -> LDS with 16-byte accesses; LDS rows are 128 bytes and the eight
+//     16-byte chunks of a row are XOR-swizzled with the row index, so the eight lanes that
+//     read the same chunk index of eight consecutive rows hit eight different bank groups;
+//   * two LDS stages: the next K step is fetched from HBM while the current one feeds the
+//     matrix cores; one barrier per K step;
+//   * the dequantizer (scalar scales, per-column scale vector, per-column bias) runs on the
+//     accumulator registers and results go straight to C (the paper fuses dequantization at the
+//     same point: before the accumulators leave the registers);
+//   * workgroup ids are remapped so that consecutive tiles stay on one XCD (ids are dealt
+//     round-robin to the 8 XCDs, each with its own L2) and walk the tile grid in groups of
+//     rows, which keeps the A and B panels of neighbouring tiles in that L2;
+//   * split-K (for outputs with too few tiles to fill 256 CUs) writes raw partial
+//     accumulators to a workspace; a second kernel adds them in a fixed order and applies
+//     the epilogue, so results do not depend on scheduling.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace qsync {
+
+namespace {
+
+typedef int      v4i32 __attribute__((ext_vector_type(4)));
+typedef int      v16i32 __attribute__((ext_vector_type(16)));
+typedef float    v16f32 __attribute__((ext_vector_type(16)));
+typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads    = 256;
+constexpr int kRowBytes   = 128;  // K bytes per tile row and per LDS row
+constexpr int kChunks     = 8;    // 16-byte chunks per LDS row
+constexpr int kNumXcd     = 8;
+constexpr int kGroupM     = 8;    // tile rows walked together
+
+struct I8Traits
+{
+    typedef int32_t acc_t;
+    typedef v16i32  accv_t;
+    static constexpr int kElemBytes = 1;
+    __device__ static __forceinline__ accv_t mfma(const v4i32& a, const v4i32& b, const accv_t& c)
+    {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+};
+struct F16Traits
+{
+    typedef float  acc_t;
+    typedef v16f32 accv_t;
+    static constexpr int kElemBytes = 2;
+    __device__ static __forceinline__ accv_t mfma(const v4i32& a, const v4i32& b, const accv_t& c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8f16, a), __builtin_bit_cast(v8f16, b), c, 0,
+                                                      0, 0);
+    }
+};
+
+struct GemmKernelArgs
+{
+    const uint8_t* A;
+    const uint8_t* B;
+    int64_t        M, N;
+    int64_t        Kb;           // bytes per operand row (K * element size), multiple of 16
+    void*          C;
+    int            c_is_f16;
+    const float*   s0;
+    const float*   s1;
+    const float*   col_scale;
+    const float*   col_bias;
+    int32_t*       acc_dump;
+    void*          partial;      // split-K: [splits][M][N] raw accumulators
+    int            ktiles_per_split;
+    int            tiles_m, tiles_n;
+};
+
+// Logical tile index for a workgroup id: contiguous ranges per XCD, then grouped row-major.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    const int total = tiles_m * tiles_n;
+    const int per = total / kNumXcd, rem = total % kNumXcd;
+    const int xcd = bid % kNumXcd, loc = bid / kNumXcd;
+    const int L     = xcd * per + (xcd < rem ? xcd : rem) + loc;
+    const int width = kGroupM * tiles_n;
+    const int group = L / width, first = group * kGroupM;
+    const int gsz   = (tiles_m - first) < kGroupM ? (tiles_m - first) : kGroupM;
+    const int in    = L - group * width;
+    tm = first + in % gsz;
+    tn = in / gsz;
+}
+
+template <typename TR, int BM, int BN, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const GemmKernelArgs p)
+{
+    typedef typename TR::accv_t accv_t;
+    typedef typename TR::acc_t  acc_t;
+    constexpr int WTM = BM / 2, WTN = BN / 2;       // wavefront sub-tile
+    constexpr int FM = WTM / 32, FN = WTN / 32;     // 32x32 fragments per wavefront
+    constexpr int A_CHUNKS = BM * kChunks / kThreads, B_CHUNKS = BN * kChunks / kThreads;
+    constexpr int STAGE_BYTES = (BM + BN) * kRowBytes;
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile must hold 2x2 wavefronts of 32x32 fragments");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
+    const int     tid = threadIdx.x, lane = tid % kWaveSize, wave = tid / kWaveSize;
+    const int     wm = wave / 2, wn = wave % 2;
+
+    const int64_t ktiles_all = (p.Kb + kRowBytes - 1) / kRowBytes;
+    int64_t       kt_begin = 0, kt_end = ktiles_all;
+    if(SPLIT)
+    {
+        kt_begin = static_cast<int64_t>(blockIdx.y) * p.ktiles_per_split;
+        kt_end   = kt_begin + p.ktiles_per_split < ktiles_all ? kt_begin + p.ktiles_per_split : ktiles_all;
+    }
+
+    // global -> register staging: chunk q = tid + 256*i covers row q/8, 16-byte chunk q%8
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+    auto  fetch = [&](int64_t kt) {
+        const int64_t kb = kt * kRowBytes + (tid % kChunks) * 16;
+        const bool    kok = kb < p.Kb;
+#pragma unroll
+        for(int i = 0; i < A_CHUNKS; ++i)
+        {
+            const int64_t row = m0 + (tid + kThreads * i) / kChunks;
+            ra[i] = (kok && row < p.M) ? *reinterpret_cast<const uint4*>(p.A + row * p.Kb + kb) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for(int i = 0; i < B_CHUNKS; ++i)
+        {
+            const int64_t row = n0 + (tid + kThreads * i) / kChunks;
+            rb[i] = (kok && row < p.N) ? *reinterpret_cast<const uint4*>(p.B + row * p.Kb + kb) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto stash = [&](int stage) {
+        uint8_t* a_lds = lds + stage * STAGE_BYTES;
+        uint8_t* b_lds = a_lds + BM * kRowBytes;
+        const int c    = tid % kChunks;
+#pragma unroll
+        for(int i = 0; i < A_CHUNKS; ++i)
+        {
+            const int row = (tid + kThreads * i) / kChunks;
+            *reinterpret_cast<uint4*>(a_lds + row * kRowBytes + ((c ^ (row & 7)) << 4)) = ra[i];
+        }
+#pragma unroll
+        for(int i = 0; i < B_CHUNKS; ++i)
+        {
+            const int row = (tid + kThreads * i) / kChunks;
+            *reinterpret_cast<uint4*>(b_lds + row * kRowBytes + ((c ^ (row & 7)) << 4)) = rb[i];
+        }
+    };
+
+    accv_t acc[FM][FN];
+#pragma unroll
+    for(int i = 0; i < FM; ++i)
+#pragma unroll
+        for(int j = 0; j < FN; ++j)
+#pragma unroll
+            for(int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    if(kt_begin < kt_end)
+    {
+        fetch(kt_begin);
+        stash(0);
+    }
+    __syncthreads();
+
+    const int frag_row = lane & 31, khalf = lane >> 5;
+    for(int64_t kt = kt_begin; kt < kt_end; ++kt)
+    {
+        const int  stage = static_cast<int>(kt - kt_begin) & 1;
+        const bool more  = kt + 1 < kt_end;
+        if(more) fetch(kt + 1);
+
+        const uint8_t* a_lds = lds + stage * STAGE_BYTES + (wm * WTM) * kRowBytes;
+        const uint8_t* b_lds = lds + stage * STAGE_BYTES + BM * kRowBytes + (wn * WTN) * kRowBytes;
+#pragma unroll
+        for(int ks = 0; ks < 4; ++ks)
+        {
+            const int chunk = ks * 2 + khalf;
+            v4i32     af[FM], bf[FN];
+#pragma unroll
+            for(int i = 0; i < FM; ++i)
+            {
+                const int row = i * 32 + frag_row;       // (wm*WTM) is a multiple of 8: swizzle uses row & 7
+                af[i] = *reinterpret_cast<const v4i32*>(a_lds + row * kRowBytes + ((chunk ^ (row & 7)) << 4));
+            }
+#pragma unroll
+            for(int j = 0; j < FN; ++j)
+            {
+                const int row = j * 32 + frag_row;
+                bf[j] = *reinterpret_cast<const v4i32*>(b_lds + row * kRowBytes + ((chunk ^ (row & 7)) << 4));
+            }
+#pragma unroll
+            for(int i = 0; i < FM; ++i)
+#pragma unroll
+                for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(af[i], bf[j], acc[i][j]);
+        }
+        if(more) stash(stage ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: 32x32 accumulator layout: lane -> column lane%32; register v -> row
+    //      8*(v/4) + 4*(lane/32) + v%4 of the fragment.
+    if(SPLIT)
+    {
+        acc_t* part = static_cast<acc_t*>(p.partial) + static_cast<int64_t>(blockIdx.y) * p.M * p.N;
+#pragma unroll
+        for(int i = 0; i < FM; ++i)
+#pragma unroll
+            for(int j = 0; j < FN; ++j)
+            {
+                const int64_t col = n0 + wn * WTN + j * 32 + frag_row;
+#pragma unroll
+                for(int v = 0; v < 16; ++v)
+                {
+                    const int64_t row = m0 + wm * WTM + i * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
+                    if(row < p.M && col < p.N) part[row * p.N + col] = acc[i][j][v];
+                }
+            }
+        return;
+    }
+
+    float alpha = 1.0f;
+    if(p.s0) alpha *= *p.s0;
+    if(p.s1) alpha *= *p.s1;
+#pragma unroll
+    for(int j = 0; j < FN; ++j)
+    {
+        const int64_t col = n0 + wn * WTN + j * 32 + frag_row;
+        const bool    cok = col < p.N;
+        const float   f   = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
+        const float   b   = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
+#pragma unroll
+        for(int i = 0; i < FM; ++i)
+#pragma unroll
+            for(int v = 0; v < 16; ++v)
+            {
+                const int64_t row = m0 + wm * WTM + i * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
+                if(row < p.M && cok)
+                {
+                    const float y = static_cast<float>(acc[i][j][v]) * f + b;
+                    if(p.c_is_f16)
+                        static_cast<__half*>(p.C)[row * p.N + col] = __float2half_rn(y);
+                    else
+                        static_cast<float*>(p.C)[row * p.N + col] = y;
+                    if(sizeof(acc_t) == 4 && p.acc_dump) p.acc_dump[row * p.N + col] = static_cast<int32_t>(acc[i][j][v]);
+                }
+            }
+    }
+}
+
+// Adds the split-K partials in split order and applies the epilogue.
+template <typename ACC>
+__global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __restrict__ partial, int splits,
+                                                                 int64_t M, int64_t N, void* C, int c_is_f16,
+                                                                 const float* s0, const float* s1,
+                                                                 const float* __restrict__ col_scale,
+                                                                 const float* __restrict__ col_bias, int32_t* acc_dump)
+{
+    const int64_t n      = M * N;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    float         alpha  = 1.0f;
+    if(s0) alpha *= *s0;
+    if(s1) alpha *= *s1;
+    for(int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride)
+    {
+        ACC acc = 0;
+        for(int s = 0; s < splits; ++s) acc += partial[static_cast<int64_t>(s) * n + i];
+        const int64_t col = i % N;
+        const float   f   = alpha * (col_scale ? col_scale[col] : 1.0f);
+        const float   y   = static_cast<float>(acc) * f + (col_bias ? col_bias[col] : 0.0f);
+        if(c_is_f16)
+            static_cast<__half*>(C)[i] = __float2half_rn(y);
+        else
+            static_cast<float*>(C)[i] = y;
+        if(acc_dump) acc_dump[i] = static_cast<int32_t>(acc);
+    }
+}
+
+struct TileShape { int bm, bn; };
+constexpr TileShape kTiles[] = {{256, 256}, {256, 128}, {128, 128}, {64, 64}};
+constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+template <typename TR, int BM, int BN>
+hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
+{
+    constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
+    const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
+    hipError_t       e;
+    if(splits > 1)
+    {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if(e != hipSuccess) return e;
+        gemm_nt_kernel<TR, BM, BN, true><<<grid, dim3(kThreads), lds_bytes, st>>>(a);
+    }
+    else
+    {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if(e != hipSuccess) return e;
+        gemm_nt_kernel<TR, BM, BN, false><<<grid, dim3(kThreads), lds_bytes, st>>>(a);
+    }
+    return hipGetLastError();
+}
+
+template <typename TR>
+hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStream_t st)
+{
+    switch(tile)
+    {
+    case 0: return launch_tile<TR, 256, 256>(a, splits, st);
+    case 1: return launch_tile<TR, 256, 128>(a, splits, st);
+    case 2: return launch_tile<TR, 128, 128>(a, splits, st);
+    default: return launch_tile<TR, 64, 64>(a, splits, st);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t stream);   // gemm_f32.hip
+
+GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits)
+{
+    GemmPlan plan{2, 1, 0};
+    if(prec == 32 || M <= 0 || N <= 0) return plan;
+    const int64_t kb     = K * (prec == 8 ? 1 : 2);
+    const int64_t ktiles = (kb + kRowBytes - 1) / kRowBytes;
+    auto ntiles = [&](int t) { return ((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn); };
+    const int64_t cus = 256;
+    int tile = kNumTiles - 1;
+    // largest tile that still yields at least ~one workgroup per CU
+    for(int t = 0; t < kNumTiles; ++t)
+        if(ntiles(t) >= (cus * 3) / 4) { tile = t; break; }
+    if(ntiles(tile) < (cus * 3) / 4) tile = (M > 64 || N > 64) ? 2 : 3;
+    if(force_tile >= 0 && force_tile < kNumTiles) tile = force_tile;
+    int splits = 1;
+    const int64_t nt = ntiles(tile);
+    if(nt * 2 <= cus && ktiles >= 8)
+    {
+        int64_t s = cus / nt;
+        if(s > ktiles / 4) s = ktiles / 4;     // keep at least 4 K steps per split
+        if(s > 64) s = 64;
+        splits = static_cast<int>(s < 1 ? 1 : s);
+    }
+    if(force_splits >= 1) splits = force_splits;
+    if(splits > ktiles) splits = static_cast<int>(ktiles < 1 ? 1 : ktiles);
+    plan.tile      = tile;
+    plan.splits    = splits;
+    plan.workspace = splits > 1 ? static_cast<size_t>(splits) * M * N * 4 : 0;
+    return plan;
+}
+
+hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream)
+{
+    if(p.M <= 0 || p.N <= 0) return hipSuccess;
+    if(p.prec == 32) return launch_gemm_f32(p, stream);
+    const int      esz = p.prec == 8 ? 1 : 2;
+    GemmKernelArgs a;
+    a.A = static_cast<const uint8_t*>(p.A);
+    a.B = static_cast<const uint8_t*>(p.B);
+    a.M = p.M; a.N = p.N; a.Kb = p.K * esz;
+    a.C = p.C; a.c_is_f16 = p.c_dtype == kF16;
+    a.s0 = p.s0; a.s1 = p.s1; a.col_scale = p.col_scale; a.col_bias = p.col_bias;
+    a.acc_dump = p.prec == 8 ? p.acc_dump : nullptr;
+    a.partial  = workspace;
+    const int64_t ktiles = (a.Kb + kRowBytes - 1) / kRowBytes;
+    int splits = plan.splits < 1 ? 1 : plan.splits;
+    a.ktiles_per_split = static_cast<int>((ktiles + splits - 1) / splits);
+    if(a.ktiles_per_split < 1) a.ktiles_per_split = 1;
+    const TileShape ts = kTiles[plan.tile];
+    a.tiles_m = static_cast<int>((p.M + ts.bm - 1) / ts.bm);
+    a.tiles_n = static_cast<int>((p.N + ts.bn - 1) / ts.bn);
+    hipError_t e = p.prec == 8 ? launch_traits<I8Traits>(plan.tile, a, splits, stream)
+                               : launch_traits<F16Traits>(plan.tile, a, splits, stream);
+    if(e != hipSuccess || splits == 1) return e;
+    int64_t nb = (p.M * p.N + kThreads - 1) / kThreads;
+    nb         = nb > 65536 ? 65536 : nb;
+    if(p.prec == 8)
+        splitk_reduce_kernel<int32_t><<<dim3(nb), dim3(kThreads), 0, stream>>>(
+            static_cast<const int32_t*>(workspace), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale,
+            p.col_bias, a.acc_dump);
+    else
+        splitk_reduce_kernel<float><<<dim3(nb), dim3(kThreads), 0, stream>>>(
+            static_cast<const float*>(workspace), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale,
+            p.col_bias, nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace qsync

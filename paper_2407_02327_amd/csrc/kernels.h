@@ -1,0 +1,64 @@
+// Internal launch interface between the C ABI (api.hip) and the gfx950 kernels.
+// Every launcher assumes its arguments were validated by the caller; each returns the
+// hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace qsync {
+
+enum Dtype { kF32 = 0, kF16 = 1, kI8 = 2, kI32 = 3 };
+enum Gran { kPerTensor = 0, kPerRow = 1, kPerCol = 2 };
+enum Round { kNearest = 0, kStochastic = 1, kFloor = 2 };
+
+// ---- absmax / scale -------------------------------------------------------------------
+constexpr int kAbsmaxMaxBlocks = 2048;  // per-tensor stage-1 partials
+constexpr int kAbsmaxColSplits = 64;    // per-column stage-1 row splits
+size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
+hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran,
+                               float qmax, float* scale, float* inv_scale, float* amax_opt,
+                               float* workspace, hipStream_t stream);
+
+// ---- quantize / cast / copy (+ transpose) ---------------------------------------------
+hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, float qmax,
+                                int gran, int rnd, uint64_t seed, uint64_t offset, const float* inv_scale,
+                                int8_t* q, int8_t* qT, hipStream_t stream);
+hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int outdt,
+                          void* q, void* qT, hipStream_t stream);
+
+// ---- standalone dequantize, column sums -----------------------------------------------
+hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld,
+                             const float* row_scale, const float* col_scale, float tensor_scale,
+                             const float* col_bias, void* y, int ydt, hipStream_t stream);
+constexpr int kColsumSplits = 128;
+size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
+hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
+                         hipStream_t stream);
+
+// ---- GEMM  C[M,N] = epilogue( sum_k A[M,k] B[N,k] ) ------------------------------------
+// epilogue(acc) = float(acc) * (s0 * s1 * col_scale[n]) + col_bias[n]; absent factors are 1 / 0.
+struct GemmProblem {
+    int         prec;       // 8: int8 operands, int32 accumulate; 16: binary16, fp32; 32: fp32
+    int64_t     M, N, K;    // K in elements
+    const void* A;          // [M,K] packed
+    const void* B;          // [N,K] packed
+    void*       C;          // [M,N] packed, fp32 or binary16
+    int         c_dtype;    // kF32 | kF16
+    const float* s0;        // device scalars or nullptr
+    const float* s1;
+    const float* col_scale; // [N] or nullptr
+    const float* col_bias;  // [N] or nullptr
+    int32_t*    acc_dump;   // [M,N] raw int32 accumulators (prec 8 only) or nullptr
+};
+
+struct GemmPlan {
+    int     tile;          // index into the tile table (see gemm_mfma.hip)
+    int     splits;        // split-K factor (1 = epilogue fused in the GEMM kernel)
+    size_t  workspace;     // bytes needed for split-K partials
+};
+// force_tile / force_splits < 0 leave the choice to the heuristic.
+GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile = -1, int force_splits = -1);
+hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream);
+
+}  // namespace qsync

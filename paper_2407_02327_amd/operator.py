@@ -1,0 +1,129 @@
+"""Buffer plumbing for one quantized linear operator on the GPU.
+
+`QLinear` owns the device buffers of one operator (codes, scales, transposed copies,
+outputs, workspace) and sequences the C-ABI calls of ``qsync.py`` for a forward and a
+backward pass.  All arithmetic runs inside libqsync's kernels; nothing here computes.
+Buffers are allocated once in the constructor, so `forward` / `backward` allocate nothing
+and can be timed or replayed.
+
+Call order per step (paper: Cost Mapper paragraph, casting cost in the forward pass for
+inputs and weights, extra casting in the backward pass; Backend section):
+  forward : absmax+quantize X (codes and transposed codes), absmax+quantize W
+            (per output channel for the forward, per input feature and transposed for dX),
+            GEMM with fused dequantize + bias
+  backward: absmax+quantize dY (stochastic rounding; codes and transposed codes),
+            dX GEMM, dW GEMM, bias gradient
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import qsync as Q
+
+_TORCH_OF_TAG = {Q.INT8: torch.int8, Q.FP16: torch.float16, Q.FP32: torch.float32}
+
+
+def _ws(nbytes: int, device) -> Optional[torch.Tensor]:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+class QLinear:
+    def __init__(self, tag: int, M: int, N: int, K: int, x_dtype=torch.float16, w_dtype=torch.float32,
+                 dy_dtype=None, y_dtype=torch.float32, dx_dtype=torch.float16, dw_dtype=torch.float32,
+                 w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
+                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda"):
+        self.tag, self.M, self.N, self.K = tag, M, N, K
+        self.w_gran, self.dy_round, self.seed, self.bits = w_gran, dy_round, philox_seed, bits
+        self.offset = 0
+        dy_dtype = dy_dtype or x_dtype
+        dev = device
+        e = lambda *s, dt: torch.empty(*s, dtype=dt, device=dev)
+        qd = _TORCH_OF_TAG[tag]
+        f32 = torch.float32
+        # operands in the layouts the GEMMs consume (contraction axis contiguous)
+        self.xq, self.xqT = e(M, K, dt=qd), e(K, M, dt=qd)
+        self.wq, self.wqbT = e(N, K, dt=qd), e(K, N, dt=qd)
+        self.dyq, self.dyqT = e(M, N, dt=qd), e(N, M, dt=qd)
+        # scales (amax/qmax), inverse scales, and the raw maxima
+        self.sx, self.ix, self.ax = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
+        nsw = N if w_gran == Q.PER_ROW else 1
+        nswb = K if w_gran == Q.PER_ROW else 1
+        self.sw, self.iw, self.aw = e(nsw, dt=f32), e(nsw, dt=f32), e(nsw, dt=f32)
+        self.swb, self.iwb = e(nswb, dt=f32), e(nswb, dt=f32)
+        self.sdy, self.idy, self.ady = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
+        self.bias = torch.zeros(N, dtype=f32, device=dev) if bias else None
+        self.y, self.dx, self.dw = e(M, N, dt=y_dtype), e(M, K, dt=dx_dtype), e(N, K, dt=dw_dtype)
+        self.db = e(N, dt=f32)
+        self.acc = self.acc_dx = self.acc_dw = None
+        if dump_acc and tag == Q.INT8:
+            i32 = torch.int32
+            self.acc, self.acc_dx, self.acc_dw = e(M, N, dt=i32), e(M, K, dt=i32), e(N, K, dt=i32)
+        nws = max(Q.qsync_absmax_workspace_bytes(M, K, Q.PER_TENSOR), Q.qsync_absmax_workspace_bytes(N, K, Q.PER_COL),
+                  Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR))
+        self.ws_absmax = _ws(nws, dev)
+        self.ws_fwd = _ws(Q.qsync_qlinear_workspace_bytes(tag, M, N, K), dev)
+        self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K), dev)
+
+    # ---- precision conversion -----------------------------------------------------------
+    def convert_x(self, x: torch.Tensor, stream=None) -> None:
+        M, K = self.M, self.K
+        if self.tag == Q.INT8:
+            Q.qsync_absmax_scale(x, M, K, K, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, self.ws_absmax, stream)
+            Q.qsync_quantize(x, M, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq,
+                             self.xqT, stream)
+        else:
+            Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, self.xq, self.xqT, stream)
+
+    def convert_w(self, w: torch.Tensor, stream=None) -> None:
+        N, K = self.N, self.K
+        if self.tag != Q.INT8:
+            Q.qsync_quantize(w, N, K, K, self.tag, 0, 0, 0, 0, 0, None, self.wq, self.wqbT, stream)
+            return
+        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, self.ws_absmax, stream)
+        if self.w_gran == Q.PER_TENSOR:       # one quantization serves the forward and dX
+            Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq,
+                             self.wqbT, stream)
+            self.swb = self.sw
+            return
+        Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_ROW, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
+        # dX contracts over the output channels, so its weight codes carry one scale per input feature
+        Q.qsync_absmax_scale(w, N, K, K, Q.PER_COL, self.bits, self.swb, self.iwb, None, self.ws_absmax, stream)
+        Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_COL, Q.ROUND_NEAREST, 0, 0, self.iwb, None, self.wqbT,
+                         stream)
+
+    def convert_dy(self, dy: torch.Tensor, stream=None) -> None:
+        M, N = self.M, self.N
+        if self.tag == Q.INT8:
+            Q.qsync_absmax_scale(dy, M, N, N, Q.PER_TENSOR, self.bits, self.sdy, self.idy, self.ady, self.ws_absmax,
+                                 stream)
+            Q.qsync_quantize(dy, M, N, N, Q.INT8, self.bits, Q.PER_TENSOR, self.dy_round, self.seed, self.offset,
+                             self.idy, self.dyq, self.dyqT, stream)
+            self.last_dy_offset = self.offset
+            self.offset += (M * N + 7) // 8
+        else:
+            Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, self.dyq, self.dyqT, stream)
+
+    # ---- GEMMs ---------------------------------------------------------------------------
+    def gemm_fwd(self, stream=None) -> None:
+        Q.qsync_qlinear_fwd(self.tag, self.M, self.N, self.K, self.xq, self.sx, self.wq, self.sw, self.w_gran,
+                            self.bias, self.y, self.acc, self.ws_fwd, stream)
+
+    def gemm_bwd(self, dy: Optional[torch.Tensor], stream=None) -> None:
+        Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
+                            self.wqbT, self.swb, self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW,
+                            self.dx, self.dw, self.db if dy is not None else None, dy, self.acc_dx, self.acc_dw,
+                            self.ws_bwd, stream)
+
+    # ---- whole passes ----------------------------------------------------------------------
+    def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None) -> torch.Tensor:
+        self.convert_x(x, stream)
+        self.convert_w(w, stream)
+        self.gemm_fwd(stream)
+        return self.y
+
+    def backward(self, dy: torch.Tensor, stream=None):
+        self.convert_dy(dy, stream)
+        self.gemm_bwd(dy, stream)
+        return self.dx, self.dw, self.db

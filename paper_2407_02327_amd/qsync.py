@@ -1,0 +1,127 @@
+"""Thin Python binding of libqsync.so: argument marshalling only.
+
+Every function has the name and argument order of its C counterpart in
+``include/qsync.h`` and takes torch tensors (for their device pointers) where the
+C function takes pointers.  No arithmetic happens here.  The library is loaded
+from the package directory; if it is missing the import of this module fails
+loudly -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+INT8, FP16, FP32 = 8, 16, 32                       # qsync_prec_t
+F32, F16, I8, I32 = 0, 1, 2, 3                     # qsync_dtype_t
+PER_TENSOR, PER_ROW, PER_COL = 0, 1, 2             # qsync_gran_t
+ROUND_NEAREST, ROUND_STOCHASTIC, ROUND_FLOOR = 0, 1, 2
+OK, ERR_NULL, ERR_BAD_ENUM, ERR_BAD_SHAPE, ERR_UNSUPPORTED, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6, -7
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqsync.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2407_02327_amd.build`")
+lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i, _i64, _u64, _sz, _f = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64,
+                                 ctypes.c_size_t, ctypes.c_float)
+SIGNATURES = {
+    "qsync_absmax_scale": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "qsync_absmax_workspace_bytes": (_sz, [_i64, _i64, _i]),
+    "qsync_quantize": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _i, _i, _u64, _u64, _vp, _vp, _vp, _vp]),
+    "qsync_qlinear_fwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
+    "qsync_qlinear_bwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i,
+                               _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
+    "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
+    "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
+    "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _i, _vp]),
+    "qsync_last_hip_error": (_i, []),
+    "qsync_strerror": (ctypes.c_char_p, [_i]),
+    "qsync_version": (_i, []),
+}
+for _name, (_res, _args) in SIGNATURES.items():
+    _fn = getattr(lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+_DTYPE_OF = {torch.float32: F32, torch.float16: F16, torch.int8: I8, torch.int32: I32}
+
+
+class QsyncError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        msg = lib.qsync_strerror(status).decode()
+        if status == ERR_HIP:
+            msg += f" (hipError_t {lib.qsync_last_hip_error()})"
+        super().__init__(f"qsync status {status}: {msg}")
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise QsyncError(status)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    return _DTYPE_OF[t.dtype]
+
+
+def _bytes(ws: Optional[torch.Tensor]) -> int:
+    return 0 if ws is None else ws.numel() * ws.element_size()
+
+
+def qsync_absmax_workspace_bytes(rows: int, cols: int, gran: int) -> int:
+    return lib.qsync_absmax_workspace_bytes(rows, cols, gran)
+
+
+def qsync_qlinear_workspace_bytes(tag: int, M: int, N: int, K: int) -> int:
+    return lib.qsync_qlinear_workspace_bytes(tag, M, N, K)
+
+
+def qsync_qlinear_bwd_workspace_bytes(tag: int, M: int, N: int, K: int) -> int:
+    return lib.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K)
+
+
+def qsync_absmax_scale(x, rows, cols, ld, gran, bits, scale, inv_scale, amax_opt, workspace, stream=None) -> None:
+    _check(lib.qsync_absmax_scale(_ptr(x), dtype_code(x), rows, cols, ld, gran, bits, _ptr(scale), _ptr(inv_scale),
+                                  _ptr(amax_opt), _ptr(workspace), _bytes(workspace), _stream(stream)))
+
+
+def qsync_quantize(x, rows, cols, ld, tag, bits, gran, rnd, philox_seed, philox_offset, inv_scale, q_opt, qT_opt,
+                   stream=None) -> None:
+    _check(lib.qsync_quantize(_ptr(x), dtype_code(x), rows, cols, ld, tag, bits, gran, rnd, philox_seed,
+                              philox_offset, _ptr(inv_scale), _ptr(q_opt), _ptr(qT_opt), _stream(stream)))
+
+
+def qsync_qlinear_fwd(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt, workspace, stream=None) -> None:
+    _check(lib.qsync_qlinear_fwd(tag, M, N, K, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
+                                 _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _ptr(workspace), _bytes(workspace),
+                                 _stream(stream)))
+
+
+def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, dx_opt, dw_opt, db_opt, dy_float_opt,
+                      acc_dx_dump_opt, acc_dw_dump_opt, workspace, stream=None) -> None:
+    _check(lib.qsync_qlinear_bwd(tag, M, N, K, _ptr(dyq), _ptr(dyqT), _ptr(sdy), _ptr(xqT), _ptr(sx), _ptr(wqbT),
+                                 _ptr(swb), wbgran,
+                                 _ptr(dx_opt), F32 if dx_opt is None else dtype_code(dx_opt),
+                                 _ptr(dw_opt), F32 if dw_opt is None else dtype_code(dw_opt),
+                                 _ptr(db_opt), _ptr(dy_float_opt),
+                                 F32 if dy_float_opt is None else dtype_code(dy_float_opt),
+                                 _ptr(acc_dx_dump_opt), _ptr(acc_dw_dump_opt), _ptr(workspace), _bytes(workspace),
+                                 _stream(stream)))
+
+
+def qsync_dequantize(a, rows, cols, ld, row_scale_opt, col_scale_opt, tensor_scale, col_bias_opt, y,
+                     stream=None) -> None:
+    _check(lib.qsync_dequantize(_ptr(a), dtype_code(a), rows, cols, ld, _ptr(row_scale_opt), _ptr(col_scale_opt),
+                                float(tensor_scale), _ptr(col_bias_opt), _ptr(y), dtype_code(y), _stream(stream)))

@@ -1,0 +1,182 @@
+"""GPU parity: absmax/scale, quantize, cast, dequantize against the CPU oracle, element by element.
+
+Integer codes, scales (one IEEE division each) and casts must match bit for bit; dequantized
+values are held to rtol 1e-3 / atol 1e-3*max|y|.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qsync_oracle as orc
+from paper_2407_02327_amd import qsync as Q
+from tests.gpu_util import GRAN, RND, assert_bits_equal, assert_close, dev, empty, host, say, ws
+
+pytestmark = pytest.mark.gpu
+TORCH = {np.float32: torch.float32, np.float16: torch.float16}
+
+
+def _data(rng, shape, dtype, sigma=1.0):
+    x = (rng.standard_normal(shape) * sigma).astype(dtype)
+    return x
+
+
+def _gpu_absmax(xd, rows, cols, ld, gran, bits=8):
+    n = {"tensor": 1, "row": rows, "col": cols}[gran]
+    s, iv, am = empty(n, torch.float32), empty(n, torch.float32), empty(n, torch.float32)
+    w = ws(Q.qsync_absmax_workspace_bytes(rows, cols, GRAN[gran]))
+    Q.qsync_absmax_scale(xd, rows, cols, ld, GRAN[gran], bits, s, iv, am, w)
+    return s, iv, am
+
+
+SHAPES = [(1, 1), (3, 5), (64, 128), (130, 72), (257, 1000), (512, 4096), (1000, 24), (33, 8200)]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("gran", ["tensor", "row", "col"])
+def test_absmax_scale(dtype, gran):
+    rng = np.random.default_rng(1)
+    for rows, cols in SHAPES:
+        for bits in (8, 4):
+            say("absmax", dtype.__name__, gran, rows, cols, bits)
+            x = _data(rng, (rows, cols), dtype, 3.0)
+            if rows > 2:
+                x[1, :] = 0                                   # an all-zero row
+            s, iv, am = _gpu_absmax(dev(x), rows, cols, cols, gran, bits)
+            amax = orc.absmax(x, gran)
+            so, io = orc.scales_from_amax(amax, bits)
+            assert_bits_equal(host(am), amax, "amax")
+            assert_bits_equal(host(s), so, "scale")
+            assert_bits_equal(host(iv), io, "inv_scale")
+
+
+def test_absmax_strided_and_misaligned_and_zero():
+    rng = np.random.default_rng(2)
+    big = _data(rng, (70, 200), np.float32)
+    bd = dev(big)
+    for gran in ("tensor", "row", "col"):
+        say("absmax strided", gran)
+        view = bd[:, 3:3 + 150]                               # ld 200, base offset 12 bytes
+        s, iv, am = _gpu_absmax(view, 70, 150, 200, gran)
+        assert_bits_equal(host(am), orc.absmax(big[:, 3:153], gran), "amax strided")
+    z = np.zeros((16, 64), np.float16)
+    s, iv, am = _gpu_absmax(dev(z), 16, 64, 64, "tensor")
+    assert host(s)[0] == 1 and host(iv)[0] == 1 and host(am)[0] == 0
+    # large tensor: every stage-1 block is used
+    say("absmax large")
+    x = _data(rng, (4096, 4096), np.float16)
+    x[4095, 4095] = 77.0
+    s, iv, am = _gpu_absmax(dev(x), 4096, 4096, 4096, "tensor")
+    assert host(am)[0] == 77.0
+
+
+def _gpu_quantize(xd, rows, cols, ld, tag, gran, rnd, seed, offset, inv, want_q=True, want_t=True, bits=8):
+    dt = {Q.INT8: torch.int8, Q.FP16: torch.float16, Q.FP32: torch.float32}[tag]
+    q = empty((rows, cols), dt) if want_q else None
+    qt = empty((cols, rows), dt) if want_t else None
+    if q is not None:
+        q.fill_(3)
+    if qt is not None:
+        qt.fill_(3)
+    Q.qsync_quantize(xd, rows, cols, ld, tag, bits, GRAN[gran], RND[rnd], seed, offset, inv, q, qt)
+    return q, qt
+
+
+QSHAPES = [(16, 16), (16, 8), (48, 24), (128, 128), (256, 136), (144, 1000), (1024, 768), (5, 7), (17, 40), (24, 16),
+           (130, 66), (2048, 64)]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("gran", ["tensor", "row", "col"])
+@pytest.mark.parametrize("rnd", ["nearest", "stochastic", "floor"])
+def test_quantize_int8(dtype, gran, rnd):
+    rng = np.random.default_rng(3)
+    for rows, cols in QSHAPES:
+        say("quantize", dtype.__name__, gran, rnd, rows, cols)
+        x = _data(rng, (rows, cols), dtype, 0.7)
+        x[0, 0] = 0
+        seed, offset = 0x1234_5678_9ABC_DEF0 + rows, (1 << 64) - 5 if rows == 48 else 1000 * cols
+        amax = orc.absmax(x, gran)
+        so, io = orc.scales_from_amax(amax)
+        want = orc.quantize_int(x, io, gran, rnd, seed, offset)
+        q, qt = _gpu_quantize(dev(x), rows, cols, cols, Q.INT8, gran, rnd, seed, offset, dev(io))
+        assert_bits_equal(host(q), want, "codes")
+        assert_bits_equal(host(qt), want.T, "transposed codes")
+    # only one of the two outputs; fewer bits
+    x = _data(rng, (64, 64), dtype)
+    so, io = orc.scales_from_amax(orc.absmax(x, gran), 5)
+    want = orc.quantize_int(x, io, gran, rnd, 9, 9, bits=5)
+    q, _ = _gpu_quantize(dev(x), 64, 64, 64, Q.INT8, gran, rnd, 9, 9, dev(io), True, False, bits=5)
+    _, qt = _gpu_quantize(dev(x), 64, 64, 64, Q.INT8, gran, rnd, 9, 9, dev(io), False, True, bits=5)
+    assert_bits_equal(host(q), want, "codes 5 bit")
+    assert_bits_equal(host(qt), want.T, "transposed codes 5 bit")
+    assert np.abs(want).max() == 15
+
+
+def test_quantize_strided_input_and_special_values():
+    rng = np.random.default_rng(4)
+    for ld in (300, 304):                                      # ld 300: rows not 16-byte multiples -> scalar path
+        big = _data(rng, (96, ld), np.float16)
+        x = big[:, 8:8 + 256]
+        so, io = orc.scales_from_amax(orc.absmax(x))
+        say("quantize strided", ld)
+        q, qt = _gpu_quantize(dev(big)[:, 8:264], 96, 256, ld, Q.INT8, "tensor", "stochastic", 5, 0, dev(io))
+        want = orc.quantize_int(np.ascontiguousarray(x), io, "tensor", "stochastic", 5, 0)
+        assert_bits_equal(host(q), want, "strided codes")
+        assert_bits_equal(host(qt), want.T, "strided transposed codes")
+    # ties, +-amax, subnormal inputs, exact integers
+    say("quantize special values")
+    t = np.zeros((16, 16), np.float32)
+    t[0, :8] = [127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5]
+    t[1, :4] = [-127.0, 1e-41, -1e-41, 126.5]
+    so, io = orc.scales_from_amax(orc.absmax(t))
+    for rnd in ("nearest", "stochastic", "floor"):
+        q, qt = _gpu_quantize(dev(t), 16, 16, 16, Q.INT8, "tensor", rnd, 11, 3, dev(io))
+        assert_bits_equal(host(q), orc.quantize_int(t, io, "tensor", rnd, 11, 3), f"special {rnd}")
+    assert host(q).min() >= -127
+
+
+@pytest.mark.parametrize("src", [np.float32, np.float16])
+@pytest.mark.parametrize("tag", [Q.FP16, Q.FP32])
+def test_cast_and_transpose(src, tag):
+    rng = np.random.default_rng(5)
+    for rows, cols in [(1, 1), (64, 64), (70, 130), (300, 96), (33, 1000)]:
+        say("cast", src.__name__, tag, rows, cols)
+        x = _data(rng, (rows, cols), src, 100.0)
+        x[0, 0] = 1.0 + 2.0**-11 if src == np.float32 else x[0, 0]     # an exact tie for binary16
+        q, qt = _gpu_quantize(dev(x), rows, cols, cols, tag, "tensor", "nearest", 0, 0, None)
+        want = orc.cast_fp16(x) if tag == Q.FP16 else x.astype(np.float32)
+        assert_bits_equal(host(q), want, "cast")
+        assert_bits_equal(host(qt), want.T, "cast transposed")
+
+
+@pytest.mark.parametrize("adt", [np.int32, np.int8])
+@pytest.mark.parametrize("ydt", [np.float32, np.float16])
+def test_dequantize(adt, ydt):
+    rng = np.random.default_rng(6)
+    for rows, cols in [(1, 1), (64, 64), (37, 53), (256, 1024), (100, 12)]:
+        say("dequantize", adt.__name__, ydt.__name__, rows, cols)
+        lim = 127 if adt == np.int8 else 2_000_000
+        a = rng.integers(-lim, lim + 1, size=(rows, cols)).astype(adt)
+        rs = rng.uniform(0.5, 2, rows).astype(np.float32)
+        cs = rng.uniform(1e-4, 2e-4, cols).astype(np.float32)
+        cb = rng.standard_normal(cols).astype(np.float32)
+        for use in [(False, False, False), (True, False, False), (False, True, True), (True, True, True)]:
+            y = empty((rows, cols), TORCH[ydt])
+            Q.qsync_dequantize(dev(a), rows, cols, cols, dev(rs) if use[0] else None, dev(cs) if use[1] else None,
+                               0.037, dev(cb) if use[2] else None, y)
+            want = orc.dequantize(a, 0.037, rs if use[0] else None, cs if use[1] else None, cb if use[2] else None,
+                                  np.float64)
+            assert_close(host(y), want, "dequantize")
+    # strided input
+    a = rng.integers(-1000, 1000, size=(20, 64)).astype(adt if adt == np.int32 else np.int8)
+    y = empty((20, 40), TORCH[ydt])
+    Q.qsync_dequantize(dev(a)[:, 4:44], 20, 40, 64, None, None, 0.5, None, y)
+    assert_close(host(y), a[:, 4:44] * 0.5, "dequantize strided")
+
+
+def test_empty_tensors_are_noops():
+    s = empty(1, torch.float32)
+    a = empty(1, torch.int32)
+    Q.qsync_absmax_scale(s, 0, 16, 16, Q.PER_TENSOR, 8, s, s, None, None)
+    Q.qsync_quantize(s, 0, 16, 16, Q.INT8, 8, 0, 0, 0, 0, s, s, None)
+    Q.qsync_dequantize(a, 16, 0, 0, None, None, 1.0, None, s)
