@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-operator hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c2|c3] [--tag int8|fp16]
+
+One "step" is one pass of the whole hot path over one batch of the workload: for every
+linear operator of the workload, forward (absmax + quantize of X and W, GEMM with fused
+dequantize + bias) and backward (absmax + stochastic-rounding quantize of dY, dX GEMM, dW
+GEMM, bias gradient).  Inputs are seeded synthetic tensors already resident in HBM.
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"int8": 5000.0, "fp16": 2500.0}          # dense MFMA peak of MI355X, TOP/s and TFLOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_workload(name: str):
+    from paper_2407_02327_amd import workloads as wl
+    if name == "c5":
+        c = wl.config5()
+        return "config5: BERT-large-scale linears 16384x1024->4096 and 16384x4096->1024", [c["up"], c["down"]]
+    if name == "c2":
+        return "config2: BERT-base FFN linear 4096x768->3072", [wl.config2()]
+    if name == "c3":
+        return "config3: ResNet-50 3x3 conv as im2col GEMM M=200704 K=576 N=64", [wl.config3()]
+    raise SystemExit(f"unknown workload {name}")
+
+
+class EventLog:
+    """Pairs of events on the current stream around named launches (durations in ms after sync)."""
+
+    def __init__(self):
+        import torch
+        self.torch = torch
+        self.pairs = []
+
+    def run(self, name, fn):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.pairs.append((name, a, b))
+
+    def totals(self):
+        out = {}
+        for name, a, b in self.pairs:
+            t, n = out.get(name, (0.0, 0))
+            out[name] = (t + a.elapsed_time(b), n + 1)
+        return out
+
+
+def cpu_baseline(cases, tag, tokens: int):
+    """The oracle, as it stands, on a row-subset of the same workload (the first `tokens` rows of every operator)."""
+    import numpy as np
+    from oracle import qsync_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    ops = 0
+    t0 = time.perf_counter()
+    for c in cases:
+        m = min(tokens, c.x.shape[0])
+        orc.operator_fwd_bwd(tag, c.x[:m], c.w, c.bias, c.dy[:m], c.w_gran, c.dy_round, seed=c.philox_seed,
+                             y_dtype=np.float16, dx_dtype=np.float16, dw_dtype=np.float32)
+        ops += 6 * m * c.w.shape[0] * c.w.shape[1]
+    dt = time.perf_counter() - t0
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {tokens} rows of each operator (of {cases[0].x.shape[0]}), whole operator fwd+bwd "
+                      f"incl. absmax/quantize, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c5", choices=["c5", "c2", "c3"])
+    ap.add_argument("--tag", default="int8", choices=["int8", "fp16"])
+    ap.add_argument("--ydtype", default="f16", choices=["f16", "f32"], help="forward output type")
+    ap.add_argument("--cpu-tokens", type=int, default=2048, help="rows per operator given to the CPU oracle")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
+        raise SystemExit(2)
+
+    import torch
+    from paper_2407_02327_amd import qsync as Q
+    from paper_2407_02327_amd.operator import QLinear
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    tag = Q.INT8 if args.tag == "int8" else Q.FP16
+    desc, cases = build_workload(args.workload)
+    log(f"workload: {desc}; tag {args.tag}")
+    ydt = torch.float16 if args.ydtype == "f16" else torch.float32
+    tdt = {"float16": torch.float16, "float32": torch.float32}
+    ops_objs, dev_in = [], []
+    for c in cases:
+        M, N, K = c.mnk
+        op = QLinear(tag, M, N, K, x_dtype=tdt[str(c.x.dtype)], dy_dtype=tdt[str(c.dy.dtype)], y_dtype=ydt,
+                     dx_dtype=torch.float16, dw_dtype=torch.float32,
+                     w_gran=Q.PER_ROW if c.w_gran == "row" else Q.PER_TENSOR,
+                     dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
+                     philox_seed=c.philox_seed)
+        ops_objs.append(op)
+        dev_in.append((torch.from_numpy(c.x).cuda(), torch.from_numpy(c.w).cuda(), torch.from_numpy(c.dy).cuda()))
+    torch.cuda.synchronize()
+
+    ev = EventLog()
+
+    def step(record: bool):
+        run = ev.run if record else (lambda name, fn: fn())
+        for op, (x, w, dy) in zip(ops_objs, dev_in):
+            run("convert_x", lambda: op.convert_x(x))
+            run("convert_w", lambda: op.convert_w(w))
+            run("gemm_fwd", op.gemm_fwd)
+            run("convert_dy", lambda: op.convert_dy(dy))
+            run("gemm_bwd", lambda: op.gemm_bwd(dy))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+
+    gemm_ops = sum(6 * c.mnk[0] * c.mnk[1] * c.mnk[2] for c in cases)          # three GEMMs, 2MNK each
+    value = gemm_ops / (ms_per_step * 1e-3) / 1e12
+    tot = ev.totals()
+    per_step = {k: v[0] / args.steps for k, v in tot.items()}                     # ms per step per class
+    # dominant kernel: the MFMA GEMM.  gemm_bwd also holds the bias-gradient column sum, so the
+    # roofline figure uses the forward GEMM launches alone (one launch per operator per step).
+    fwd_ops = sum(2 * c.mnk[0] * c.mnk[1] * c.mnk[2] for c in cases)
+    fwd_ms = per_step["gemm_fwd"]
+    achieved = fwd_ops / (fwd_ms * 1e-3) / 1e12
+    peak = PEAK[args.tag]
+    # HBM-bound side: absmax + quantize of dY (read twice, write codes + transposed codes)
+    esz = cases[0].dy.dtype.itemsize
+    dy_bytes = sum(c.dy.size * (2 * esz + 2) for c in cases)
+    quant_gbs = dy_bytes / (per_step["convert_dy"] * 1e-3) / 1e9
+
+    out = {
+        "metric": "qlinear fwd+bwd TOPS (whole step incl. absmax/quantize/dequantize)",
+        "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.tag if args.tag == "int8" else "f16", "data": "synthetic",
+        "config": {"workload": desc, "tag": args.tag, "y_dtype": args.ydtype, "dx_dtype": "f16", "dw_dtype": "f32",
+                   "w_scale": "per-output-channel", "dy_rounding": "stochastic (Philox4x32-10)"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches)",
+                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(achieved / peak, 4), "traffic": None},
+        "breakdown_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
+        "quantize_dy": {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
+                        "bytes": "absmax read + quantize read + codes + transposed codes"},
+        "gemm_only_TOPS": round(gemm_ops / ((per_step["gemm_fwd"] + per_step["gemm_bwd"]) * 1e-3) / 1e12, 2),
+    }
+    if not args.no_cpu:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(cases, tag, args.cpu_tokens)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

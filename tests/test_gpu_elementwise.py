@@ -163,8 +163,8 @@ def test_dequantize(adt, ydt):
         for use in [(False, False, False), (True, False, False), (False, True, True), (True, True, True)]:
             y = empty((rows, cols), TORCH[ydt])
             Q.qsync_dequantize(dev(a), rows, cols, cols, dev(rs) if use[0] else None, dev(cs) if use[1] else None,
-                               0.037, dev(cb) if use[2] else None, y)
-            want = orc.dequantize(a, 0.037, rs if use[0] else None, cs if use[1] else None, cb if use[2] else None,
+                               0.01, dev(cb) if use[2] else None, y)
+            want = orc.dequantize(a, 0.01, rs if use[0] else None, cs if use[1] else None, cb if use[2] else None,
                                   np.float64)
             assert_close(host(y), want, "dequantize")
     # strided input
