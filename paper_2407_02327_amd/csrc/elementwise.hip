@@ -44,25 +44,30 @@ __global__ __launch_bounds__(kBlock) void absmax_tensor_kernel(const T* __restri
     const int64_t    stride = static_cast<int64_t>(gridDim.x) * kBlock;
     int64_t          i      = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if(VEC)
-    {   // contiguous tensor, 16-byte aligned base
+    {   // contiguous tensor, 16-byte aligned base: every block streams contiguous 32 KB pieces
         constexpr int E    = Vec16<T>::N;
+        constexpr int U    = 8;                       // 16-byte loads in flight per lane
         const int64_t nvec = n / E;
-        float         v0[E], v1[E], v2[E], v3[E];
-        for(; i + 3 * stride < nvec; i += 4 * stride)
+        const int64_t step = static_cast<int64_t>(gridDim.x) * kBlock * U;
+        for(int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock * U + threadIdx.x; c < nvec; c += step)
         {
-            Vec16<T>::load(x + i * E, v0);
-            Vec16<T>::load(x + (i + stride) * E, v1);
-            Vec16<T>::load(x + (i + 2 * stride) * E, v2);
-            Vec16<T>::load(x + (i + 3 * stride) * E, v3);
+            float v[U][E];
 #pragma unroll
-            for(int e = 0; e < E; ++e)
-                m = fmaxf(fmaxf(m, fmaxf(fabsf(v0[e]), fabsf(v1[e]))), fmaxf(fabsf(v2[e]), fabsf(v3[e])));
-        }
-        for(; i < nvec; i += stride)
-        {
-            Vec16<T>::load(x + i * E, v0);
+            for(int u = 0; u < U; ++u)
+            {
+                const int64_t idx = c + static_cast<int64_t>(u) * kBlock;
+                if(idx < nvec)
+                    Vec16<T>::load(x + idx * E, v[u]);
+                else
+                {
 #pragma unroll
-            for(int e = 0; e < E; ++e) m = fmaxf(m, fabsf(v0[e]));
+                    for(int e = 0; e < E; ++e) v[u][e] = 0.0f;
+                }
+            }
+#pragma unroll
+            for(int u = 0; u < U; ++u)
+#pragma unroll
+                for(int e = 0; e < E; ++e) m = fmaxf(m, fabsf(v[u][e]));
         }
         if(blockIdx.x == 0)
             for(int64_t j = nvec * E + threadIdx.x; j < n; j += kBlock) m = fmaxf(m, fabsf(to_f32(x[j])));
@@ -392,44 +397,69 @@ __global__ __launch_bounds__(kBlock) void dequantize_kernel(const Ti* __restrict
 }
 
 // ------------------------------------------------------------------ column sums (bias gradient)
-// Stage 1: partial[s][c] = sum over the rows of subset s; lanes own adjacent columns.
+// Stage 1: block (bx, by) sums rows by, by+gridDim.y, ... of a strip of columns.  Lanes own
+// adjacent columns (one 16-byte vector each when VEC); the block's row lanes are folded
+// through LDS, so partial[by][c] holds one value per block row.
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kBlock) void colsum_kernel(const T* __restrict__ x, int64_t rows, int64_t cols, int tpr,
                                                         float* __restrict__ partial)
 {
     constexpr int E   = VEC ? Vec16<T>::N : 1;
+    __shared__ float lds[kBlock * E];
     const int     rpb = kBlock / tpr;                       // row lanes per block
-    const int64_t c0  = (static_cast<int64_t>(blockIdx.x) * tpr + threadIdx.x % tpr) * E;
-    const int     s   = blockIdx.y * rpb + threadIdx.x / tpr;
-    const int     S   = gridDim.y * rpb;
-    if(c0 >= cols) return;
+    const int     tc = threadIdx.x % tpr, tr = threadIdx.x / tpr;
+    const int64_t c0  = (static_cast<int64_t>(blockIdx.x) * tpr + tc) * E;
+    const int64_t S   = static_cast<int64_t>(gridDim.y) * rpb;
     float acc[E];
 #pragma unroll
     for(int e = 0; e < E; ++e) acc[e] = 0.0f;
-    for(int64_t r = s; r < rows; r += S)
+    if(c0 < cols)
     {
-        if(VEC)
+        for(int64_t r = static_cast<int64_t>(blockIdx.y) * rpb + tr; r < rows; r += S)
         {
-            float v[Vec16<T>::N];
-            Vec16<T>::load(x + r * cols + c0, v);
+            if(VEC)
+            {
+                float v[Vec16<T>::N];
+                Vec16<T>::load(x + r * cols + c0, v);
 #pragma unroll
-            for(int e = 0; e < E; ++e) acc[e] += v[e];
+                for(int e = 0; e < E; ++e) acc[e] += v[e];
+            }
+            else
+                acc[0] += to_f32(x[r * cols + c0]);
         }
-        else
-            acc[0] += to_f32(x[r * cols + c0]);
     }
 #pragma unroll
-    for(int e = 0; e < E; ++e) partial[static_cast<int64_t>(s) * cols + c0 + e] = acc[e];
+    for(int e = 0; e < E; ++e) lds[(tr * tpr + tc) * E + e] = acc[e];
+    __syncthreads();
+    if(tr == 0 && c0 < cols)
+    {
+        for(int q = 1; q < rpb; ++q)
+#pragma unroll
+            for(int e = 0; e < E; ++e) acc[e] += lds[(q * tpr + tc) * E + e];
+#pragma unroll
+        for(int e = 0; e < E; ++e) partial[static_cast<int64_t>(blockIdx.y) * cols + c0 + e] = acc[e];
+    }
 }
 
+// Stage 2: 16 columns per block; sixteen threads per column fold a sixteenth of the partials
+// each (fixed assignment, fixed order), then the sixteen are added in order.
 __global__ __launch_bounds__(kBlock) void colsum_finalize_kernel(const float* __restrict__ partial, int S, int64_t cols,
                                                                  float* __restrict__ out)
 {
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if(c >= cols) return;
-    float acc = 0.0f;
-    for(int s = 0; s < S; ++s) acc += partial[static_cast<int64_t>(s) * cols + c];
-    out[c] = acc;
+    __shared__ float lds[kBlock];
+    const int     tc = threadIdx.x % 16, q = threadIdx.x / 16;
+    const int64_t c  = static_cast<int64_t>(blockIdx.x) * 16 + tc;
+    float         acc = 0.0f;
+    if(c < cols)
+        for(int s = q; s < S; s += 16) acc += partial[static_cast<int64_t>(s) * cols + c];
+    lds[threadIdx.x] = acc;
+    __syncthreads();
+    if(q == 0 && c < cols)
+    {
+        float t = 0.0f;
+        for(int i = 0; i < 16; ++i) t += lds[i * 16 + tc];
+        out[c] = t;
+    }
 }
 
 int next_pow2(int64_t v)
@@ -439,19 +469,20 @@ int next_pow2(int64_t v)
     return p;
 }
 
-// Column-sum launch shape: threads per row (power of two), row subsets S.
-void colsum_shape(int64_t cols, int E, int& tpr, int& S)
+// Column-sum launch shape: threads per row (power of two) and block rows (gridDim.y, at most
+// kColsumSplits), aiming at about five hundred blocks.
+void colsum_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
 {
     const int64_t ncv = (cols + E - 1) / E;
     tpr               = ncv >= kBlock ? kBlock : (next_pow2(ncv) < 2 ? 2 : next_pow2(ncv));
-    const int rpb     = kBlock / tpr;
-    int64_t   s       = (int64_t(1) << 20) / (cols > 0 ? cols : 1);
-    int       sp      = 1;
-    while(sp * 2 <= s) sp <<= 1;
-    if(sp > 2048) sp = 2048;
-    if(sp < 32) sp = 32;
-    if(sp < rpb) sp = rpb;
-    S = sp;
+    const int64_t gx  = (ncv + tpr - 1) / tpr;
+    const int     rpb = kBlock / tpr;
+    int64_t       g   = (512 + gx - 1) / gx;
+    const int64_t maxg = (rows + rpb - 1) / rpb;              // no more block rows than row groups
+    if(g > maxg) g = maxg;
+    if(g > kColsumSplits) g = kColsumSplits;
+    if(g < 1) g = 1;
+    gy = static_cast<int>(g);
 }
 
 }  // namespace
@@ -475,7 +506,7 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
     {
         const bool    vec  = aligned16(x) && ld == cols;
         const int64_t work = vec ? (rows * cols) / E : rows * cols;
-        int64_t       nb   = (work + kBlock * 4 - 1) / (kBlock * 4);
+        int64_t       nb   = (work + kBlock * 8 - 1) / (kBlock * 8);
         nb                 = nb < 1 ? 1 : (nb > kAbsmaxMaxBlocks ? kAbsmaxMaxBlocks : nb);
         if(vec)
             absmax_tensor_kernel<T, true><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws);
@@ -625,12 +656,7 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols)
 {
     (void)rows;
-    int tpr, S;
-    colsum_shape(cols, 1, tpr, S);
-    int tpr2, S2;
-    colsum_shape(cols, 8, tpr2, S2);
-    const int smax = S > S2 ? S : S2;
-    return sizeof(float) * static_cast<size_t>(smax) * static_cast<size_t>(cols > 0 ? cols : 0);
+    return sizeof(float) * static_cast<size_t>(kColsumSplits) * static_cast<size_t>(cols > 0 ? cols : 0);
 }
 
 template <typename T>
@@ -638,16 +664,15 @@ static hipError_t colsum_typed(const T* x, int64_t rows, int64_t cols, float* ou
 {
     constexpr int E   = Vec16<T>::N;
     const bool    vec = aligned16(x) && cols % E == 0;
-    int           tpr, S;
-    colsum_shape(cols, vec ? E : 1, tpr, S);
-    const int     rpb = kBlock / tpr;
+    int           tpr, gy;
+    colsum_shape(rows, cols, vec ? E : 1, tpr, gy);
     const int64_t ncv = (cols + (vec ? E : 1) - 1) / (vec ? E : 1);
-    const dim3    grid(static_cast<unsigned>((ncv + tpr - 1) / tpr), static_cast<unsigned>(S / rpb));
+    const dim3    grid(static_cast<unsigned>((ncv + tpr - 1) / tpr), static_cast<unsigned>(gy));
     if(vec)
         colsum_kernel<T, true><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, tpr, ws);
     else
         colsum_kernel<T, false><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, tpr, ws);
-    colsum_finalize_kernel<<<dim3((cols + kBlock - 1) / kBlock), dim3(kBlock), 0, st>>>(ws, S, cols, out);
+    colsum_finalize_kernel<<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(ws, gy, cols, out);
     return hipGetLastError();
 }
 

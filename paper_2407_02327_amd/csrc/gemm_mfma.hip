@@ -5,13 +5,18 @@
 // one row of B (v_mfma_i32_32x32x32_i8: 16 int8; v_mfma_f32_32x32x16_f16: 8 binary16).  The
 // INT8 and FP16 kernels therefore move identical bytes and share one tiling:
 //
-//   * block tile BM x BN, K step of 128 bytes per row; 256 threads = 4 wavefronts in a 2x2
-//     grid, each owning a (BM/2) x (BN/2) sub-tile as 32x32 accumulator fragments;
-//   * global -> registers -> LDS with 16-byte accesses; LDS rows are 128 bytes and the eight
-//     16-byte chunks of a row are XOR-swizzled with the row index, so the eight lanes that
-//     read the same chunk index of eight consecutive rows hit eight different bank groups;
-//   * two LDS stages: the next K step is fetched from HBM while the current one feeds the
-//     matrix cores; one barrier per K step;
+//   * block tile BM x BN, K step of 128 bytes per row; WGM x WGN wavefronts, each owning a
+//     (BM/WGM) x (BN/WGN) sub-tile as 32x32 accumulator fragments.  The large tile is
+//     256x256 with 8 wavefronts (2 per SIMD, 128 accumulator registers each), so that one
+//     wavefront's LDS reads and barrier waits hide behind the other's matrix instructions;
+//   * global -> LDS with direct 16-byte loads (global_load_lds_dwordx4), bypassing the VGPRs;
+//     LDS rows are 128 bytes.  The LDS of gfx950 serves a 16-byte read in groups of 16 lanes,
+//     one 256-byte bank row per group, so the chunk position is XOR-swizzled with (row/2)%8
+//     (applied on the global-address side of the direct load): the 16 lanes that read one
+//     chunk index of 16 consecutive rows then touch 16 different 16-byte bank groups;
+//   * two LDS stages: the next K step streams in while the current one feeds the matrix
+//     cores; fragments for the next 32-byte K chunk are requested before the current chunk's
+//     matrix instructions; one barrier per K step;
 //   * the dequantizer (scalar scales, per-column scale vector, per-column bias) runs on the
 //     accumulator registers and results go straight to C (the paper fuses dequantization at the
 //     same point: before the accumulators leave the registers);
@@ -33,7 +38,6 @@ typedef int      v16i32 __attribute__((ext_vector_type(16)));
 typedef float    v16f32 __attribute__((ext_vector_type(16)));
 typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
 
-constexpr int kThreads    = 256;
 constexpr int kRowBytes   = 128;  // K bytes per tile row and per LDS row
 constexpr int kChunks     = 8;    // 16-byte chunks per LDS row
 constexpr int kNumXcd     = 8;
@@ -94,24 +98,28 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = in / gsz;
 }
 
-template <typename TR, int BM, int BN, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const GemmKernelArgs p)
+__device__ __forceinline__ int swizzle(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) << 4; }
+
+template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKernelArgs p)
 {
     typedef typename TR::accv_t accv_t;
     typedef typename TR::acc_t  acc_t;
-    constexpr int WTM = BM / 2, WTN = BN / 2;       // wavefront sub-tile
+    constexpr int kThreads = 64 * WGM * WGN;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront sub-tile
     constexpr int FM = WTM / 32, FN = WTN / 32;     // 32x32 fragments per wavefront
-    constexpr int A_CHUNKS = BM * kChunks / kThreads, B_CHUNKS = BN * kChunks / kThreads;
     constexpr int STAGE_BYTES = (BM + BN) * kRowBytes;
-    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile must hold 2x2 wavefronts of 32x32 fragments");
+    constexpr int DPW = (BM + BN) / 8 / (WGM * WGN);    // direct-load instructions per wavefront per K tile
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wavefront sub-tiles are made of 32x32 fragments");
+    static_assert((BM + BN) % (8 * WGM * WGN) == 0 && BM % 16 == 0, "stage rows must split evenly over the wavefronts");
 
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
     const int     tid = threadIdx.x, lane = tid % kWaveSize, wave = tid / kWaveSize;
-    const int     wm = wave / 2, wn = wave % 2;
+    const int     wm = wave / WGN, wn = wave % WGN;
 
     const int64_t ktiles_all = (p.Kb + kRowBytes - 1) / kRowBytes;
     int64_t       kt_begin = 0, kt_end = ktiles_all;
@@ -121,40 +129,62 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const GemmKernelArgs 
         kt_end   = kt_begin + p.ktiles_per_split < ktiles_all ? kt_begin + p.ktiles_per_split : ktiles_all;
     }
 
-    // global -> register staging: chunk q = tid + 256*i covers row q/8, 16-byte chunk q%8
-    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-    auto  fetch = [&](int64_t kt) {
-        const int64_t kb = kt * kRowBytes + (tid % kChunks) * 16;
-        const bool    kok = kb < p.Kb;
+    // Global -> LDS with direct loads (global_load_lds_dwordx4): the data never passes through
+    // VGPRs and no LDS store instruction is issued.  One such instruction of a wavefront fills
+    // 1 KB of LDS = 8 consecutive stage rows (A rows first, then B rows): lane l lands at row l/8,
+    // chunk position l%8, so it fetches the logical chunk (l%8) ^ ((row/2)%8) of that row.
+    // Rows beyond M (or N) are clamped to the last row: they only feed accumulators of outputs
+    // that are never stored.  Chunks beyond the end of K (last, partial K tile only) are
+    // fetched from the row's first chunk of that tile and overwritten with zeros once landed.
+    const uint8_t* gp[DPW];
+    int            gchunk[DPW];
 #pragma unroll
-        for(int i = 0; i < A_CHUNKS; ++i)
+    for(int d = 0; d < DPW; ++d)
+    {
+        const int srow  = (wave * DPW + d) * 8 + lane / 8;
+        const int chunk = (lane % 8) ^ ((srow >> 1) & 7);       // BM % 16 == 0: same term for A and B rows
+        int64_t   grow;
+        const uint8_t* base;
+        if(srow < BM)
         {
-            const int64_t row = m0 + (tid + kThreads * i) / kChunks;
-            ra[i] = (kok && row < p.M) ? *reinterpret_cast<const uint4*>(p.A + row * p.Kb + kb) : make_uint4(0, 0, 0, 0);
+            grow = m0 + srow < p.M ? m0 + srow : p.M - 1;
+            base = p.A;
         }
-#pragma unroll
-        for(int i = 0; i < B_CHUNKS; ++i)
+        else
         {
-            const int64_t row = n0 + (tid + kThreads * i) / kChunks;
-            rb[i] = (kok && row < p.N) ? *reinterpret_cast<const uint4*>(p.B + row * p.Kb + kb) : make_uint4(0, 0, 0, 0);
+            grow = n0 + (srow - BM) < p.N ? n0 + (srow - BM) : p.N - 1;
+            base = p.B;
+        }
+        gp[d]     = base + grow * p.Kb + chunk * 16;
+        gchunk[d] = chunk * 16;
+    }
+    auto dma = [&](int stage, int64_t kt) {
+        const int64_t kb   = kt * kRowBytes;
+        const bool    tail = kb + kRowBytes > p.Kb;              // uniform; true for a partial last tile only
+#pragma unroll
+        for(int d = 0; d < DPW; ++d)
+        {
+            const uint8_t* src = gp[d] + kb;
+            if(tail && kb + gchunk[d] >= p.Kb) src -= gchunk[d];
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(src),
+                (__attribute__((address_space(3))) void*)(lds + stage * STAGE_BYTES + (wave * DPW + d) * 1024),
+                16, 0, 0);   // address-space casts need the C form
         }
     };
-    auto stash = [&](int stage) {
-        uint8_t* a_lds = lds + stage * STAGE_BYTES;
-        uint8_t* b_lds = a_lds + BM * kRowBytes;
-        const int c    = tid % kChunks;
-#pragma unroll
-        for(int i = 0; i < A_CHUNKS; ++i)
+    // Waits for this wavefront's direct loads, zero-fills its out-of-K chunks, then joins the block.
+    auto land = [&](int stage, int64_t kt) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
+        const int64_t kb = kt * kRowBytes;
+        if(kb + kRowBytes > p.Kb)
         {
-            const int row = (tid + kThreads * i) / kChunks;
-            *reinterpret_cast<uint4*>(a_lds + row * kRowBytes + ((c ^ (row & 7)) << 4)) = ra[i];
-        }
 #pragma unroll
-        for(int i = 0; i < B_CHUNKS; ++i)
-        {
-            const int row = (tid + kThreads * i) / kChunks;
-            *reinterpret_cast<uint4*>(b_lds + row * kRowBytes + ((c ^ (row & 7)) << 4)) = rb[i];
+            for(int d = 0; d < DPW; ++d)
+                if(kb + gchunk[d] >= p.Kb)
+                    *reinterpret_cast<uint4*>(lds + stage * STAGE_BYTES + (wave * DPW + d) * 1024 + lane * 16)
+                        = make_uint4(0, 0, 0, 0);
         }
+        __syncthreads();
     };
 
     accv_t acc[FM][FN];
@@ -167,44 +197,52 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const GemmKernelArgs 
 
     if(kt_begin < kt_end)
     {
-        fetch(kt_begin);
-        stash(0);
+        dma(0, kt_begin);
+        land(0, kt_begin);
     }
-    __syncthreads();
 
+    // Fragment reads: lane -> row lane%32 of a fragment, K chunk 2*ks + lane/32.  The swizzle term
+    // (row/2)%8 is the same for every fragment of a lane because fragments start at multiples of 32.
     const int frag_row = lane & 31, khalf = lane >> 5;
+    int       roff[4];
+#pragma unroll
+    for(int ks = 0; ks < 4; ++ks) roff[ks] = frag_row * kRowBytes + swizzle(frag_row, ks * 2 + khalf);
+    const int a_base = (wm * WTM) * kRowBytes, b_base = BM * kRowBytes + (wn * WTN) * kRowBytes;
+
+    v4i32 af[3][FM], bf[3][FN];
+    auto  load_frags = [&](int buf, const uint8_t* st, int ks) {
+#pragma unroll
+        for(int i = 0; i < FM; ++i)
+            af[buf][i] = *reinterpret_cast<const v4i32*>(st + a_base + i * 32 * kRowBytes + roff[ks]);
+#pragma unroll
+        for(int j = 0; j < FN; ++j)
+            bf[buf][j] = *reinterpret_cast<const v4i32*>(st + b_base + j * 32 * kRowBytes + roff[ks]);
+    };
+
     for(int64_t kt = kt_begin; kt < kt_end; ++kt)
     {
-        const int  stage = static_cast<int>(kt - kt_begin) & 1;
-        const bool more  = kt + 1 < kt_end;
-        if(more) fetch(kt + 1);
-
-        const uint8_t* a_lds = lds + stage * STAGE_BYTES + (wm * WTM) * kRowBytes;
-        const uint8_t* b_lds = lds + stage * STAGE_BYTES + BM * kRowBytes + (wn * WTN) * kRowBytes;
+        const int      stage = static_cast<int>(kt - kt_begin) & 1;
+        const bool     more  = kt + 1 < kt_end;
+        const uint8_t* st    = lds + stage * STAGE_BYTES;
+        if(more) dma(stage ^ 1, kt + 1);                 // lands while this tile feeds the matrix cores
+        // Fragment pipeline over the four 32-byte K chunks of the tile, three register sets deep:
+        // the reads for chunk ks+2 are issued right after the matrix instructions of chunk ks, so
+        // the wait in front of chunk ks+1 falls into the time chunk ks keeps the matrix cores busy.
+        // The scheduling fences keep the compiler from sinking the reads back to their uses.
+        load_frags(0, st, 0);
+        load_frags(1, st, 1);
 #pragma unroll
         for(int ks = 0; ks < 4; ++ks)
         {
-            const int chunk = ks * 2 + khalf;
-            v4i32     af[FM], bf[FN];
-#pragma unroll
-            for(int i = 0; i < FM; ++i)
-            {
-                const int row = i * 32 + frag_row;       // (wm*WTM) is a multiple of 8: swizzle uses row & 7
-                af[i] = *reinterpret_cast<const v4i32*>(a_lds + row * kRowBytes + ((chunk ^ (row & 7)) << 4));
-            }
-#pragma unroll
-            for(int j = 0; j < FN; ++j)
-            {
-                const int row = j * 32 + frag_row;
-                bf[j] = *reinterpret_cast<const v4i32*>(b_lds + row * kRowBytes + ((chunk ^ (row & 7)) << 4));
-            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for(int i = 0; i < FM; ++i)
 #pragma unroll
-                for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(af[i], bf[j], acc[i][j]);
+                for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(af[ks % 3][i], bf[ks % 3][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+            if(ks + 2 < 4) load_frags((ks + 2) % 3, st, ks + 2);
         }
-        if(more) stash(stage ^ 1);
-        __syncthreads();
+        if(more) land(stage ^ 1, kt + 1);
     }
 
     // ---- epilogue: 32x32 accumulator layout: lane -> column lane%32; register v -> row
@@ -258,6 +296,8 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const GemmKernelArgs 
 }
 
 // Adds the split-K partials in split order and applies the epilogue.
+constexpr int kThreads = 256;   // split-K reduction
+
 template <typename ACC>
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __restrict__ partial, int splits,
                                                                  int64_t M, int64_t N, void* C, int c_is_f16,
@@ -286,29 +326,32 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
 }
 
 struct TileShape { int bm, bn; };
-constexpr TileShape kTiles[] = {{256, 256}, {256, 128}, {128, 128}, {64, 64}};
+// 0: 256x256, 8 wavefronts (2x4, 128x64 each)   1: 128x128, 4 wavefronts (2x2, 64x64 each)
+// 2: 64x64, 4 wavefronts (2x2, 32x32 each)
+constexpr TileShape kTiles[] = {{256, 256}, {128, 128}, {64, 64}};
 constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-template <typename TR, int BM, int BN>
+template <typename TR, int BM, int BN, int WGM, int WGN>
 hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
 {
     constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
-    hipError_t       e;
+    const dim3       block(64 * WGM * WGN);
+    static bool      attr_set[2] = {false, false};   // per instantiation; benign if set twice
+    const int        which = splits > 1 ? 1 : 0;
+    if(!attr_set[which])
+    {
+        const void* fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
+                                    : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false>);
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 static_cast<int>(lds_bytes));
+        if(e != hipSuccess) return e;
+        attr_set[which] = true;
+    }
     if(splits > 1)
-    {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
-        if(e != hipSuccess) return e;
-        gemm_nt_kernel<TR, BM, BN, true><<<grid, dim3(kThreads), lds_bytes, st>>>(a);
-    }
+        gemm_nt_kernel<TR, BM, BN, WGM, WGN, true><<<grid, block, lds_bytes, st>>>(a);
     else
-    {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
-        if(e != hipSuccess) return e;
-        gemm_nt_kernel<TR, BM, BN, false><<<grid, dim3(kThreads), lds_bytes, st>>>(a);
-    }
+        gemm_nt_kernel<TR, BM, BN, WGM, WGN, false><<<grid, block, lds_bytes, st>>>(a);
     return hipGetLastError();
 }
 
@@ -317,10 +360,9 @@ hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStrea
 {
     switch(tile)
     {
-    case 0: return launch_tile<TR, 256, 256>(a, splits, st);
-    case 1: return launch_tile<TR, 256, 128>(a, splits, st);
-    case 2: return launch_tile<TR, 128, 128>(a, splits, st);
-    default: return launch_tile<TR, 64, 64>(a, splits, st);
+    case 0: return launch_tile<TR, 256, 256, 2, 4>(a, splits, st);
+    case 1: return launch_tile<TR, 128, 128, 2, 2>(a, splits, st);
+    default: return launch_tile<TR, 64, 64, 2, 2>(a, splits, st);
     }
 }
 
@@ -330,7 +372,7 @@ hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t stream);   // gemm_
 
 GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits)
 {
-    GemmPlan plan{2, 1, 0};
+    GemmPlan plan{1, 1, 0};
     if(prec == 32 || M <= 0 || N <= 0) return plan;
     const int64_t kb     = K * (prec == 8 ? 1 : 2);
     const int64_t ktiles = (kb + kRowBytes - 1) / kRowBytes;
@@ -340,7 +382,7 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
     // largest tile that still yields at least ~one workgroup per CU
     for(int t = 0; t < kNumTiles; ++t)
         if(ntiles(t) >= (cus * 3) / 4) { tile = t; break; }
-    if(ntiles(tile) < (cus * 3) / 4) tile = (M > 64 || N > 64) ? 2 : 3;
+    if(ntiles(tile) < (cus * 3) / 4) tile = (M > 64 || N > 64) ? 1 : 2;
     if(force_tile >= 0 && force_tile < kNumTiles) tile = force_tile;
     int splits = 1;
     const int64_t nt = ntiles(tile);
