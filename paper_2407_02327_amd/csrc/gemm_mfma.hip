@@ -18,8 +18,11 @@
 //     cores; fragments for the next 32-byte K chunk are requested before the current chunk's
 //     matrix instructions; one barrier per K step;
 //   * the dequantizer (scalar scales, per-column scale vector, per-column bias) runs on the
-//     accumulator registers and results go straight to C (the paper fuses dequantization at the
-//     same point: before the accumulators leave the registers);
+//     accumulator registers (the paper fuses dequantization at the same point: before the
+//     accumulators are copied to shared memory); the B fragment is fed as the instruction's
+//     first operand so that a lane holds four consecutive output columns per register quad,
+//     which are packed, passed through the wavefront's private LDS slice and stored to C as
+//     16-byte vectors along the rows;
 //   * workgroup ids are remapped so that consecutive tiles stay on one XCD (ids are dealt
 //     round-robin to the 8 XCDs, each with its own L2) and walk the tile grid in groups of
 //     rows, which keeps the A and B panels of neighbouring tiles in that L2;
@@ -28,6 +31,8 @@
 //     the epilogue, so results do not depend on scheduling.
 #include "device_utils.h"
 #include "kernels.h"
+
+#include <type_traits>
 
 namespace qsync {
 
@@ -98,6 +103,10 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = in / gsz;
 }
 
+template <typename T> __device__ __forceinline__ T from_f32_out(float v);
+template <> __device__ __forceinline__ float  from_f32_out<float>(float v) { return v; }
+template <> __device__ __forceinline__ __half from_f32_out<__half>(float v) { return __float2half_rn(v); }
+
 __device__ __forceinline__ int swizzle(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) << 4; }
 
 template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT>
@@ -118,7 +127,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
-    const int     tid = threadIdx.x, lane = tid % kWaveSize, wave = tid / kWaveSize;
+    const int     tid = threadIdx.x, lane = tid % kWaveSize;
+    const int     wave = __builtin_amdgcn_readfirstlane(tid / kWaveSize);     // wavefront index, held in an SGPR
     const int     wm = wave / WGN, wn = wave % WGN;
 
     const int64_t ktiles_all = (p.Kb + kRowBytes - 1) / kRowBytes;
@@ -136,38 +146,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // Rows beyond M (or N) are clamped to the last row: they only feed accumulators of outputs
     // that are never stored.  Chunks beyond the end of K (last, partial K tile only) are
     // fetched from the row's first chunk of that tile and overwritten with zeros once landed.
-    const uint8_t* gp[DPW];
-    int            gchunk[DPW];
+    // A wavefront's DPW instructions cover 8*DPW consecutive stage rows, all of A or all of B, so
+    // its source is one uniform base pointer plus a 32-bit lane offset per instruction.
+    constexpr bool kUniformSide = (BM / 8) % DPW == 0;
+    static_assert(kUniformSide, "a wavefront must not straddle the A/B boundary of a stage");
+    const bool     is_a      = wave * DPW < BM / 8;
+    const uint8_t* gbase     = is_a ? p.A + m0 * p.Kb : p.B + n0 * p.Kb;
+    const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
+    uint32_t       goff[DPW];
+    int            gchunk[2];                                         // the swizzle term depends on d%2 only
 #pragma unroll
     for(int d = 0; d < DPW; ++d)
     {
-        const int srow  = (wave * DPW + d) * 8 + lane / 8;
-        const int chunk = (lane % 8) ^ ((srow >> 1) & 7);       // BM % 16 == 0: same term for A and B rows
-        int64_t   grow;
-        const uint8_t* base;
-        if(srow < BM)
-        {
-            grow = m0 + srow < p.M ? m0 + srow : p.M - 1;
-            base = p.A;
-        }
-        else
-        {
-            grow = n0 + (srow - BM) < p.N ? n0 + (srow - BM) : p.N - 1;
-            base = p.B;
-        }
-        gp[d]     = base + grow * p.Kb + chunk * 16;
-        gchunk[d] = chunk * 16;
+        const int srow  = (wave * DPW + d) * 8 + lane / 8;            // row inside the stage
+        const int chunk = (lane % 8) ^ ((srow >> 1) & 7);             // BM % 16 == 0: same term for A and B rows
+        int64_t   lrow  = srow - (is_a ? 0 : BM);
+        if(lrow >= rows_left) lrow = rows_left - 1;
+        goff[d] = static_cast<uint32_t>(lrow * p.Kb + chunk * 16);
+        if(d < 2) gchunk[d] = chunk * 16;
     }
     auto dma = [&](int stage, int64_t kt) {
-        const int64_t kb   = kt * kRowBytes;
-        const bool    tail = kb + kRowBytes > p.Kb;              // uniform; true for a partial last tile only
+        const int64_t  kb   = kt * kRowBytes;
+        const bool     tail = kb + kRowBytes > p.Kb;             // uniform; true for a partial last tile only
+        const uint8_t* src0 = gbase + kb;
 #pragma unroll
         for(int d = 0; d < DPW; ++d)
         {
-            const uint8_t* src = gp[d] + kb;
-            if(tail && kb + gchunk[d] >= p.Kb) src -= gchunk[d];
+            uint32_t off = goff[d];
+            if(tail && kb + gchunk[d & 1] >= p.Kb) off -= gchunk[d & 1];
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(src),
+                (const __attribute__((address_space(1))) void*)(src0 + off),
                 (__attribute__((address_space(3))) void*)(lds + stage * STAGE_BYTES + (wave * DPW + d) * 1024),
                 16, 0, 0);   // address-space casts need the C form
         }
@@ -180,7 +188,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         {
 #pragma unroll
             for(int d = 0; d < DPW; ++d)
-                if(kb + gchunk[d] >= p.Kb)
+                if(kb + gchunk[d & 1] >= p.Kb)
                     *reinterpret_cast<uint4*>(lds + stage * STAGE_BYTES + (wave * DPW + d) * 1024 + lane * 16)
                         = make_uint4(0, 0, 0, 0);
         }
@@ -195,12 +203,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
 #pragma unroll
             for(int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    if(kt_begin < kt_end)
-    {
-        dma(0, kt_begin);
-        land(0, kt_begin);
-    }
-
     // Fragment reads: lane -> row lane%32 of a fragment, K chunk 2*ks + lane/32.  The swizzle term
     // (row/2)%8 is the same for every fragment of a lane because fragments start at multiples of 32.
     const int frag_row = lane & 31, khalf = lane >> 5;
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     for(int ks = 0; ks < 4; ++ks) roff[ks] = frag_row * kRowBytes + swizzle(frag_row, ks * 2 + khalf);
     const int a_base = (wm * WTM) * kRowBytes, b_base = BM * kRowBytes + (wn * WTN) * kRowBytes;
 
-    v4i32 af[3][FM], bf[3][FN];
+    v4i32 af[2][FM], bf[2][FN];
     auto  load_frags = [&](int buf, const uint8_t* st, int ks) {
 #pragma unroll
         for(int i = 0; i < FM; ++i)
@@ -218,81 +220,179 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         for(int j = 0; j < FN; ++j)
             bf[buf][j] = *reinterpret_cast<const v4i32*>(st + b_base + j * 32 * kRowBytes + roff[ks]);
     };
+    auto mma = [&](int buf) {
+        __builtin_amdgcn_sched_barrier(0);           // fences: keep the compiler from re-sinking the reads
+#pragma unroll
+        for(int i = 0; i < FM; ++i)
+#pragma unroll
+            for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(bf[buf][j], af[buf][i], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    for(int64_t kt = kt_begin; kt < kt_end; ++kt)
+    // K pipeline.  A tile has four 32-byte K chunks whose fragments alternate between two
+    // register sets: the reads for chunk ks+2 are issued right behind the matrix instructions of
+    // chunk ks (into the set those instructions have just consumed), so they complete while
+    // chunk ks+1 keeps the matrix cores busy.  At the tile boundary the wavefront (1) issues
+    // chunk 2, (2) joins the barrier that publishes the next stage, (3) issues chunk 3, whose
+    // operands are already in registers, and only then (4) requests the direct load of the tile
+    // after next into the stage just drained and reads the first two chunks of the next tile:
+    // barrier release and LDS latency hide behind chunk 3.
+    if(kt_begin < kt_end)
     {
-        const int      stage = static_cast<int>(kt - kt_begin) & 1;
-        const bool     more  = kt + 1 < kt_end;
-        const uint8_t* st    = lds + stage * STAGE_BYTES;
-        if(more) dma(stage ^ 1, kt + 1);                 // lands while this tile feeds the matrix cores
-        // Fragment pipeline over the four 32-byte K chunks of the tile, three register sets deep:
-        // the reads for chunk ks+2 are issued right after the matrix instructions of chunk ks, so
-        // the wait in front of chunk ks+1 falls into the time chunk ks keeps the matrix cores busy.
-        // The scheduling fences keep the compiler from sinking the reads back to their uses.
-        load_frags(0, st, 0);
-        load_frags(1, st, 1);
-#pragma unroll
-        for(int ks = 0; ks < 4; ++ks)
+        dma(0, kt_begin);
+        land(0, kt_begin);
+        if(kt_begin + 1 < kt_end) dma(1, kt_begin + 1);
+        load_frags(0, lds, 0);
+        load_frags(1, lds, 1);
+        for(int64_t kt = kt_begin; kt < kt_end; ++kt)
         {
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for(int i = 0; i < FM; ++i)
-#pragma unroll
-                for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(af[ks % 3][i], bf[ks % 3][j], acc[i][j]);
-            __builtin_amdgcn_sched_barrier(0);
-            if(ks + 2 < 4) load_frags((ks + 2) % 3, st, ks + 2);
+            const int      stage = static_cast<int>(kt - kt_begin) & 1;
+            const bool     more  = kt + 1 < kt_end;
+            const uint8_t* st    = lds + stage * STAGE_BYTES;
+            mma(0);
+            load_frags(0, st, 2);
+            mma(1);
+            load_frags(1, st, 3);
+            mma(0);
+            if(more) land(stage ^ 1, kt + 1);
+            mma(1);
+            if(more)
+            {
+                if(kt + 2 < kt_end) dma(stage, kt + 2);
+                const uint8_t* nst = lds + (stage ^ 1) * STAGE_BYTES;
+                load_frags(0, nst, 0);
+                load_frags(1, nst, 1);
+            }
         }
-        if(more) land(stage ^ 1, kt + 1);
     }
 
-    // ---- epilogue: 32x32 accumulator layout: lane -> column lane%32; register v -> row
-    //      8*(v/4) + 4*(lane/32) + v%4 of the fragment.
+    // ---- epilogue.  The B fragment is the matrix instruction's first operand, so a lane holds
+    //      C^T fragments: lane -> output row m = lane%32 of the fragment; register v -> output
+    //      column n = 8*(v/4) + 4*(lane/32) + v%4, i.e. four consecutive columns per register quad.
+    const int64_t wrow0 = m0 + wm * WTM, wcol0 = n0 + wn * WTN;
     if(SPLIT)
     {
         acc_t* part = static_cast<acc_t*>(p.partial) + static_cast<int64_t>(blockIdx.y) * p.M * p.N;
 #pragma unroll
         for(int i = 0; i < FM; ++i)
+        {
+            const int64_t row = wrow0 + i * 32 + frag_row;
 #pragma unroll
             for(int j = 0; j < FN; ++j)
-            {
-                const int64_t col = n0 + wn * WTN + j * 32 + frag_row;
 #pragma unroll
                 for(int v = 0; v < 16; ++v)
                 {
-                    const int64_t row = m0 + wm * WTM + i * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
+                    const int64_t col = wcol0 + j * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
                     if(row < p.M && col < p.N) part[row * p.N + col] = acc[i][j][v];
                 }
-            }
+        }
         return;
     }
 
     float alpha = 1.0f;
     if(p.s0) alpha *= *p.s0;
     if(p.s1) alpha *= *p.s1;
+    const int osize = p.c_is_f16 ? 2 : 4;
+    const bool fast = !p.acc_dump && (p.N * osize) % 16 == 0 && (reinterpret_cast<uintptr_t>(p.C) & 15) == 0;
+    if(!fast)
+    {   // element-wise stores: any N, any alignment, optional raw accumulator dump
 #pragma unroll
-    for(int j = 0; j < FN; ++j)
-    {
-        const int64_t col = n0 + wn * WTN + j * 32 + frag_row;
-        const bool    cok = col < p.N;
-        const float   f   = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
-        const float   b   = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
-#pragma unroll
-        for(int i = 0; i < FM; ++i)
+        for(int j = 0; j < FN; ++j)
 #pragma unroll
             for(int v = 0; v < 16; ++v)
             {
-                const int64_t row = m0 + wm * WTM + i * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
-                if(row < p.M && cok)
+                const int64_t col = wcol0 + j * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
+                const bool    cok = col < p.N;
+                const float   f   = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
+                const float   b   = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
+#pragma unroll
+                for(int i = 0; i < FM; ++i)
                 {
-                    const float y = static_cast<float>(acc[i][j][v]) * f + b;
-                    if(p.c_is_f16)
-                        static_cast<__half*>(p.C)[row * p.N + col] = __float2half_rn(y);
-                    else
-                        static_cast<float*>(p.C)[row * p.N + col] = y;
-                    if(sizeof(acc_t) == 4 && p.acc_dump) p.acc_dump[row * p.N + col] = static_cast<int32_t>(acc[i][j][v]);
+                    const int64_t row = wrow0 + i * 32 + frag_row;
+                    if(row < p.M && cok)
+                    {
+                        const float y = static_cast<float>(acc[i][j][v]) * f + b;
+                        if(p.c_is_f16)
+                            static_cast<__half*>(p.C)[row * p.N + col] = __float2half_rn(y);
+                        else
+                            static_cast<float*>(p.C)[row * p.N + col] = y;
+                        if(sizeof(acc_t) == 4 && p.acc_dump)
+                            p.acc_dump[row * p.N + col] = static_cast<int32_t>(acc[i][j][v]);
+                    }
                 }
             }
+        return;
     }
+
+    // Fast path: dequantize in registers, pass the wavefront's sub-tile through its private
+    // slice of LDS (the K pipeline is drained, so the stages are free) and leave with 16-byte
+    // stores whose lanes run along the rows of C: every store instruction writes whole
+    // 128-byte (or longer) row segments.
+    __syncthreads();                                  // all wavefronts are done reading the stages
+    constexpr int STG_BYTES = 2 * STAGE_BYTES / (WGM * WGN);
+    uint8_t*      stg       = lds + wave * STG_BYTES;
+    auto staged_store = [&](auto out_tag) {
+        typedef decltype(out_tag) out_t;
+        constexpr int OS    = sizeof(out_t);
+        constexpr int PITCH = WTN * OS + 16;                     // padded row pitch in the staging slice
+        constexpr int FPP   = (STG_BYTES / (32 * PITCH)) >= FM ? FM : ((STG_BYTES / (32 * PITCH)) >= 2 ? 2 : 1);
+        static_assert(32 * PITCH <= STG_BYTES && FM % FPP == 0, "staging slice too small");
+        constexpr int LPR   = WTN * OS / 16;                     // lanes per output row in the store phase
+        constexpr int RPI   = 64 / LPR;                          // rows per store instruction
+        float f[FN][16], b[FN][16];
+#pragma unroll
+        for(int j = 0; j < FN; ++j)
+#pragma unroll
+            for(int v = 0; v < 16; ++v)
+            {
+                const int64_t col = wcol0 + j * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
+                const bool    cok = col < p.N;
+                f[j][v] = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
+                b[j][v] = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
+            }
+#pragma unroll
+        for(int pass = 0; pass < FM / FPP; ++pass)
+        {
+#pragma unroll
+            for(int ii = 0; ii < FPP; ++ii)
+            {
+                const int i = pass * FPP + ii;
+#pragma unroll
+                for(int j = 0; j < FN; ++j)
+#pragma unroll
+                    for(int vq = 0; vq < 4; ++vq)
+                    {
+                        out_t o[4];
+#pragma unroll
+                        for(int e = 0; e < 4; ++e)
+                        {
+                            const float y = static_cast<float>(acc[i][j][vq * 4 + e]) * f[j][vq * 4 + e] + b[j][vq * 4 + e];
+                            o[e] = from_f32_out<out_t>(y);
+                        }
+                        uint8_t* dst = stg + (ii * 32 + frag_row) * PITCH + (j * 32 + 8 * vq + 4 * khalf) * OS;
+                        if(OS == 2)
+                            *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o);
+                        else
+                            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
+                    }
+            }
+            // the wavefront's own LDS writes are visible to its later LDS reads (same queue, in order)
+#pragma unroll
+            for(int r0 = 0; r0 < FPP * 32; r0 += RPI)
+            {
+                const int     lr  = r0 + lane / LPR, seg = lane % LPR;
+                const uint4   val = *reinterpret_cast<const uint4*>(stg + lr * PITCH + seg * 16);
+                const int64_t row = wrow0 + pass * FPP * 32 + lr;
+                const int64_t col = wcol0 + seg * (16 / OS);
+                if(row < p.M && col < p.N)
+                    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(p.C) + (row * p.N + col) * OS) = val;
+            }
+        }
+    };
+    if(p.c_is_f16)
+        staged_store(__half{});
+    else
+        staged_store(float{});
 }
 
 // Adds the split-K partials in split order and applies the epilogue.
