@@ -74,6 +74,10 @@ typedef enum {
  * x         [rows, ld] of xdt (QSYNC_F32 or QSYNC_F16), ld >= cols.
  * scale, inv_scale   out, 1 / rows / cols floats according to gran.  Both required.
  * amax_opt  out, same shape, may be NULL.
+ * colsum_opt out, cols floats or NULL; PER_TENSOR only (QSYNC_ERR_UNSUPPORTED otherwise).  When
+ *           given, the same pass over x also produces colsum[c] = sum_r x[r,c] in fp32: for x = dY
+ *           this is the bias gradient db (paper: Appendix, proof of Prop. 1, gradient of a linear
+ *           operator), obtained without reading dY a third time.
  * workspace scratch of at least qsync_absmax_workspace_bytes(rows, cols, gran) bytes, 16-byte aligned.
  * bits      2..8.
  * Any alignment of x and ld is accepted (vector loads are used when x and ld*sizeof(elem)
@@ -81,7 +85,7 @@ typedef enum {
  */
 int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld,
                        int gran, int bits, float* scale, float* inv_scale, float* amax_opt,
-                       void* workspace, size_t workspace_bytes, void* stream);
+                       float* colsum_opt, void* workspace, size_t workspace_bytes, void* stream);
 size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 
 /*

@@ -47,10 +47,14 @@ template <typename T> struct Vec16;
 template <> struct Vec16<float>
 {
     static constexpr int N = 4;
+    __device__ static __forceinline__ void decode(const uint4& r, float (&out)[4])
+    {
+        out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y);
+        out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
+    }
     __device__ static __forceinline__ void load(const float* p, float (&out)[4])
     {
-        const float4 v = *reinterpret_cast<const float4*>(p);
-        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+        decode(*reinterpret_cast<const uint4*>(p), out);
     }
 };
 template <> struct Vec16<__half>
@@ -58,7 +62,10 @@ template <> struct Vec16<__half>
     static constexpr int N = 8;
     __device__ static __forceinline__ void load(const __half* p, float (&out)[8])
     {
-        const uint4 raw = *reinterpret_cast<const uint4*>(p);
+        decode(*reinterpret_cast<const uint4*>(p), out);
+    }
+    __device__ static __forceinline__ void decode(const uint4& raw, float (&out)[8])
+    {
         const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for(int i = 0; i < 4; ++i)
@@ -114,23 +121,23 @@ __device__ __forceinline__ uint32_t philox_draw16(const uint4& blk, int slot)
 
 // Fixed-point code of one value: clamp(round(x * inv), -qmax, qmax).  RND is a qsync::Round.
 // The product is a single fp32 multiply; for stochastic rounding the residual x*inv - floor(.)
-// is exact in fp32 and the value rounds up iff u16 < floor(residual * 2^16).
+// is exact in fp32 and the value rounds up iff u16 < floor(residual * 2^16).  The rounded value
+// is integral and small, so the increment and the clamp run on integers.
 template <int RND>
-__device__ __forceinline__ int quantize_code(float x, float inv, float qmax, uint32_t u16)
+__device__ __forceinline__ int quantize_code(float x, float inv, int qmax, uint32_t u16)
 {
     const float v = __fmul_rn(x, inv);
-    float c;
-    if(RND == 0) c = rintf(v);
-    else if(RND == 2) c = floorf(v);
+    int         c;
+    if(RND == 0) c = static_cast<int>(rintf(v));
+    else if(RND == 2) c = static_cast<int>(floorf(v));
     else
     {
         const float    fl  = floorf(v);
         const float    fr  = __fsub_rn(v, fl);
         const uint32_t thr = static_cast<uint32_t>(__fmul_rn(fr, 65536.0f));
-        c = fl + (u16 < thr ? 1.0f : 0.0f);
+        c = static_cast<int>(fl) + (u16 < thr ? 1 : 0);
     }
-    c = fminf(fmaxf(c, -qmax), qmax);
-    return static_cast<int>(c);
+    return min(max(c, -qmax), qmax);
 }
 
 }  // namespace qsync

@@ -31,56 +31,87 @@ __device__ __forceinline__ void write_scale(float amax, float qmax, float* scale
     if(amax_opt) amax_opt[i] = amax;
 }
 
+// Running maximum of |x| over 16-byte vectors.  binary16 magnitudes order like their bit
+// patterns with the sign bit cleared, so for binary16 the maximum runs on packed 16-bit
+// integers (two elements per VALU operation) and is widened to fp32 once at the end.
+typedef unsigned short us2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_absmax_u16(uint32_t m, uint32_t w)
+{
+    const us2_t a = __builtin_bit_cast(us2_t, m), b = __builtin_bit_cast(us2_t, w & 0x7FFF7FFFu);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+}
+__device__ __forceinline__ float half_bits_to_f32(uint32_t h) { return __half2float(__ushort_as_half(static_cast<unsigned short>(h))); }
+
+template <typename T> struct RunMax;
+template <> struct RunMax<float>
+{
+    float m = 0.0f;
+    __device__ __forceinline__ void add(const uint4& r)
+    {
+        m = fmaxf(fmaxf(m, fmaxf(fabsf(__uint_as_float(r.x)), fabsf(__uint_as_float(r.y)))),
+                  fmaxf(fabsf(__uint_as_float(r.z)), fabsf(__uint_as_float(r.w))));
+    }
+    __device__ __forceinline__ void add_scalar(float v) { m = fmaxf(m, fabsf(v)); }
+    __device__ __forceinline__ float get() const { return m; }
+};
+template <> struct RunMax<__half>
+{
+    uint32_t pk = 0u;
+    float    s  = 0.0f;
+    __device__ __forceinline__ void add(const uint4& r)
+    {
+        pk = pk_absmax_u16(pk_absmax_u16(pk, r.x), r.y);
+        pk = pk_absmax_u16(pk_absmax_u16(pk, r.z), r.w);
+    }
+    __device__ __forceinline__ void add_scalar(__half v) { s = fmaxf(s, fabsf(__half2float(v))); }
+    __device__ __forceinline__ float get() const
+    {
+        return fmaxf(s, fmaxf(half_bits_to_f32(pk & 0xFFFFu), half_bits_to_f32(pk >> 16)));
+    }
+};
+
 // ------------------------------------------------------------------ absmax, per tensor
-// Stage 1: each block folds a strided share of the tensor into one partial maximum.
+// Stage 1: each block folds contiguous 32 KB pieces of the tensor into one partial maximum.
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kBlock) void absmax_tensor_kernel(const T* __restrict__ x, int64_t rows,
                                                                int64_t cols, int64_t ld,
                                                                float* __restrict__ partial)
 {
     __shared__ float lds[16];
-    float            m      = 0.0f;
-    const int64_t    n      = rows * cols;
-    const int64_t    stride = static_cast<int64_t>(gridDim.x) * kBlock;
-    int64_t          i      = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    RunMax<T>        rm;
+    const int64_t    n = rows * cols;
     if(VEC)
-    {   // contiguous tensor, 16-byte aligned base: every block streams contiguous 32 KB pieces
+    {   // contiguous tensor, 16-byte aligned base
         constexpr int E    = Vec16<T>::N;
         constexpr int U    = 8;                       // 16-byte loads in flight per lane
         const int64_t nvec = n / E;
         const int64_t step = static_cast<int64_t>(gridDim.x) * kBlock * U;
+        const uint4*  xv   = reinterpret_cast<const uint4*>(x);
         for(int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock * U + threadIdx.x; c < nvec; c += step)
         {
-            float v[U][E];
+            uint4 v[U];
 #pragma unroll
             for(int u = 0; u < U; ++u)
             {
                 const int64_t idx = c + static_cast<int64_t>(u) * kBlock;
-                if(idx < nvec)
-                    Vec16<T>::load(x + idx * E, v[u]);
-                else
-                {
-#pragma unroll
-                    for(int e = 0; e < E; ++e) v[u][e] = 0.0f;
-                }
+                v[u] = idx < nvec ? xv[idx] : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for(int u = 0; u < U; ++u)
-#pragma unroll
-                for(int e = 0; e < E; ++e) m = fmaxf(m, fabsf(v[u][e]));
+            for(int u = 0; u < U; ++u) rm.add(v[u]);
         }
         if(blockIdx.x == 0)
-            for(int64_t j = nvec * E + threadIdx.x; j < n; j += kBlock) m = fmaxf(m, fabsf(to_f32(x[j])));
+            for(int64_t j = nvec * E + threadIdx.x; j < n; j += kBlock) rm.add_scalar(x[j]);
     }
     else
     {
-        for(; i < n; i += stride)
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+        for(int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride)
         {
             const int64_t r = i / cols, c = i - r * cols;
-            m = fmaxf(m, fabsf(to_f32(x[r * ld + c])));
+            rm.add_scalar(x[r * ld + c]);
         }
     }
-    m = block_reduce_max(m, lds);
+    const float m = block_reduce_max(rm.get(), lds);
     if(threadIdx.x == 0) partial[blockIdx.x] = m;
 }
 
@@ -97,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void absmax_tensor_finalize_kernel(const fl
 }
 
 // ------------------------------------------------------------------ absmax, per row
-// One wavefront per row; the row maximum needs no second stage.
+// One wavefront per row, four 16-byte loads in flight per lane; no second stage.
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kBlock) void absmax_rows_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                              int64_t ld, float qmax, float* scale, float* inv_scale,
@@ -106,131 +137,219 @@ __global__ __launch_bounds__(kBlock) void absmax_rows_kernel(const T* __restrict
     const int     lane = threadIdx.x % kWaveSize;
     const int64_t r    = static_cast<int64_t>(blockIdx.x) * (kBlock / kWaveSize) + threadIdx.x / kWaveSize;
     if(r >= rows) return;
-    const T* row = x + r * ld;
-    float    m   = 0.0f;
-    int64_t  done = 0;
+    const T*  row  = x + r * ld;
+    RunMax<T> rm;
+    int64_t   done = 0;
     if(VEC)
     {
         constexpr int E    = Vec16<T>::N;
         const int64_t nvec = cols / E;
-        float         v[E];
-        for(int64_t i = lane; i < nvec; i += kWaveSize)
+        const uint4*  rv   = reinterpret_cast<const uint4*>(row);
+        for(int64_t i = lane; i < nvec; i += 4 * kWaveSize)
         {
-            Vec16<T>::load(row + i * E, v);
+            uint4 v[4];
 #pragma unroll
-            for(int e = 0; e < E; ++e) m = fmaxf(m, fabsf(v[e]));
+            for(int u = 0; u < 4; ++u) v[u] = i + u * kWaveSize < nvec ? rv[i + u * kWaveSize] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for(int u = 0; u < 4; ++u) rm.add(v[u]);
         }
         done = nvec * E;
     }
-    for(int64_t c = done + lane; c < cols; c += kWaveSize) m = fmaxf(m, fabsf(to_f32(row[c])));
-    m = wave_reduce_max(m);
+    for(int64_t c = done + lane; c < cols; c += kWaveSize) rm.add_scalar(row[c]);
+    const float m = wave_reduce_max(rm.get());
     if(lane == 0) write_scale(m, qmax, scale, inv_scale, amax_opt, r);
 }
 
-// ------------------------------------------------------------------ absmax, per column
-// Stage 1: lanes own adjacent columns (one 16-byte vector each when VEC), wavefronts own
-// interleaved row subsets; partial[s][c] holds the maximum of subset s.
-template <typename T, bool VEC>
-__global__ __launch_bounds__(kBlock) void absmax_cols_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
-                                                             int64_t ld, float* __restrict__ partial)
+// ------------------------------------------------------------------ per-column reductions
+// Shared by the per-column absmax (OP_MAX) and the column sums of the bias gradient (OP_SUM).
+// Stage 1: block (bx, by) reduces rows by*rpb + tr, + gridDim.y*rpb, ... of a strip of columns.
+// Lanes own adjacent columns (one 16-byte vector each when VEC); the block's row lanes are
+// folded through LDS, so partial[by][c] holds one value per block row.
+enum { OP_MAX = 0, OP_SUM = 1, OP_SUMMAX = 2 };   // SUMMAX: column sums plus the tensor-wide max |x| in one pass
+
+template <typename T, bool VEC, int OP>
+__global__ __launch_bounds__(kBlock) void colreduce_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                           int64_t ld, int tpr, float* __restrict__ partial,
+                                                           float* __restrict__ partial_max)
 {
-    constexpr int E    = VEC ? Vec16<T>::N : 1;
-    const int     lane = threadIdx.x % kWaveSize;
-    const int64_t c0   = (static_cast<int64_t>(blockIdx.x) * kWaveSize + lane) * E;
-    const int     s    = blockIdx.y * (kBlock / kWaveSize) + threadIdx.x / kWaveSize;
-    const int     S    = gridDim.y * (kBlock / kWaveSize);
-    if(c0 >= cols) return;
-    float m[E];
+    constexpr int E = VEC ? Vec16<T>::N : 1;
+    __shared__ float lds[kBlock * E];
+    __shared__ float lds_max[16];
+    RunMax<T>        rm;                                    // OP_SUMMAX only
+    const int     rpb = kBlock / tpr;                       // row lanes per block
+    const int     tc = threadIdx.x % tpr, tr = threadIdx.x / tpr;
+    const int64_t c0  = (static_cast<int64_t>(blockIdx.x) * tpr + tc) * E;
+    const int64_t S   = static_cast<int64_t>(gridDim.y) * rpb;
+    float    acc[E];
+    uint32_t pk[4] = {0u, 0u, 0u, 0u};                      // packed binary16 maxima (VEC, OP_MAX, binary16)
+    constexpr bool kPacked = VEC && OP == OP_MAX && sizeof(T) == 2;
 #pragma unroll
-    for(int e = 0; e < E; ++e) m[e] = 0.0f;
-    for(int64_t r = s; r < rows; r += S)
+    for(int e = 0; e < E; ++e) acc[e] = 0.0f;
+    if(c0 < cols)
     {
-        if(VEC)
+        for(int64_t r = static_cast<int64_t>(blockIdx.y) * rpb + tr; r < rows; r += S)
         {
-            float v[Vec16<T>::N];
-            Vec16<T>::load(x + r * ld + c0, v);
+            if(VEC)
+            {
+                const uint4 raw = *reinterpret_cast<const uint4*>(x + r * ld + c0);
+                if(kPacked)
+                {
+                    pk[0] = pk_absmax_u16(pk[0], raw.x); pk[1] = pk_absmax_u16(pk[1], raw.y);
+                    pk[2] = pk_absmax_u16(pk[2], raw.z); pk[3] = pk_absmax_u16(pk[3], raw.w);
+                }
+                else
+                {
+                    float v[Vec16<T>::N];
+                    Vec16<T>::decode(raw, v);
 #pragma unroll
-            for(int e = 0; e < E; ++e) m[e] = fmaxf(m[e], fabsf(v[e]));
+                    for(int e = 0; e < E; ++e) acc[e] = OP == OP_MAX ? fmaxf(acc[e], fabsf(v[e])) : fmaf(v[e], 1.0f, acc[e]);
+                    if(OP == OP_SUMMAX) rm.add(raw);
+                }
+            }
+            else
+            {
+                const T     xv = x[r * ld + c0];
+                const float v  = to_f32(xv);
+                acc[0] = OP == OP_MAX ? fmaxf(acc[0], fabsf(v)) : acc[0] + v;
+                if(OP == OP_SUMMAX) rm.add_scalar(xv);
+            }
         }
-        else
-            m[0] = fmaxf(m[0], fabsf(to_f32(x[r * ld + c0])));
+    }
+    if(kPacked)
+    {
+#pragma unroll
+        for(int e = 0; e < E; ++e) acc[e] = half_bits_to_f32((pk[e / 2] >> (16 * (e % 2))) & 0xFFFFu);
+    }
+    if(OP == OP_SUMMAX)
+    {   // every thread of the block takes part (threads beyond the last column carry 0)
+        const float bm = block_reduce_max(rm.get(), lds_max);
+        if(threadIdx.x == 0) partial_max[blockIdx.y * gridDim.x + blockIdx.x] = bm;
     }
 #pragma unroll
-    for(int e = 0; e < E; ++e) partial[static_cast<int64_t>(s) * cols + c0 + e] = m[e];
+    for(int e = 0; e < E; ++e) lds[(tr * tpr + tc) * E + e] = acc[e];
+    __syncthreads();
+    if(tr == 0 && c0 < cols)
+    {
+        for(int q = 1; q < rpb; ++q)
+#pragma unroll
+            for(int e = 0; e < E; ++e)
+            {
+                const float o = lds[(q * tpr + tc) * E + e];
+                acc[e] = OP == OP_MAX ? fmaxf(acc[e], o) : acc[e] + o;
+            }
+#pragma unroll
+        for(int e = 0; e < E; ++e) partial[static_cast<int64_t>(blockIdx.y) * cols + c0 + e] = acc[e];
+    }
 }
 
-__global__ __launch_bounds__(kBlock) void absmax_cols_finalize_kernel(const float* __restrict__ partial, int S,
-                                                                      int64_t cols, float qmax, float* scale,
-                                                                      float* inv_scale, float* amax_opt)
+// Stage 2: 16 columns per block; sixteen threads per column fold a sixteenth of the partials
+// each (fixed assignment, fixed order), then the sixteen are folded in order.
+template <int OP>
+__global__ __launch_bounds__(kBlock) void colreduce_finalize_kernel(const float* __restrict__ partial, int S,
+                                                                    int64_t cols, float qmax, float* out,
+                                                                    float* inv_scale, float* amax_opt)
 {
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if(c >= cols) return;
-    float m = 0.0f;
-    for(int s = 0; s < S; ++s) m = fmaxf(m, partial[static_cast<int64_t>(s) * cols + c]);
-    write_scale(m, qmax, scale, inv_scale, amax_opt, c);
+    __shared__ float lds[kBlock];
+    const int     tc = threadIdx.x % 16, q = threadIdx.x / 16;
+    const int64_t c  = static_cast<int64_t>(blockIdx.x) * 16 + tc;
+    float         acc = 0.0f;
+    if(c < cols)
+        for(int s = q; s < S; s += 16)
+        {
+            const float o = partial[static_cast<int64_t>(s) * cols + c];
+            acc = OP == OP_MAX ? fmaxf(acc, o) : acc + o;
+        }
+    lds[threadIdx.x] = acc;
+    __syncthreads();
+    if(q == 0 && c < cols)
+    {
+        float t = 0.0f;
+        for(int i = 0; i < 16; ++i) t = OP == OP_MAX ? fmaxf(t, lds[i * 16 + tc]) : t + lds[i * 16 + tc];
+        if(OP == OP_MAX)
+            write_scale(t, qmax, out, inv_scale, amax_opt, c);
+        else
+            out[c] = t;
+    }
 }
 
 // ------------------------------------------------------------------ INT8 quantize, vector path
-// Each lane owns a 16x16 patch of the tensor.  A wavefront is 8 patches wide and 8 tall, so
-// every load instruction covers 8 rows of 128 contiguous columns, the int8 codes of a row
-// leave as one 16-byte store (8 lanes = 128 contiguous bytes), and -- after a 16x16 byte
-// transpose held entirely in registers -- each column of the patch leaves as one 16-byte
-// store to the transposed copy (8 lanes = 128 contiguous bytes there, too).  No LDS, no
-// barrier.  Needs cols % 8 == 0 (Philox groups of 8 never straddle a row), rows % 16 == 0 when
-// the transposed copy is written, and 16-byte aligned rows.
-constexpr int kPatch      = 16;
-constexpr int kWaveTile   = 8 * kPatch;                       // 128 x 128 elements per wavefront
-constexpr int kBlockRows  = (kBlock / kWaveSize) * kWaveTile; // wavefronts stacked along rows
+// Each lane owns a patch of 16 rows x 32 input bytes (16 binary16 or 8 fp32 columns) and
+// requests the eight 16-byte loads of four rows together before it converts them.  A wavefront is 8 patches
+// wide and 8 tall, so every load instruction covers 8 rows of 256 contiguous bytes; the int8
+// codes of a patch row leave as one 16-byte (8-byte for fp32 input) store, and -- after a byte
+// transpose held entirely in registers -- each column of the patch leaves as one 16-byte store
+// to the transposed copy, 8 lanes side by side (128 contiguous bytes).  No LDS, no barrier.
+// Needs cols % 8 == 0 (Philox groups of 8 never straddle a row), rows % 16 == 0 when the
+// transposed copy is written, and 16-byte aligned rows.
+constexpr int kPatchRows = 16;
 
 __device__ __forceinline__ uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xFFu; }
 
 template <typename T, int RND, bool PERCOL>
-__global__ __launch_bounds__(kBlock) void quantize_patch_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
-                                                                int64_t ld, float qmax, int gran, uint64_t seed,
+__global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                                int64_t ld, int qmax, int gran, uint64_t seed,
                                                                 uint64_t offset, const float* __restrict__ inv_scale,
                                                                 int8_t* __restrict__ q, int8_t* __restrict__ qT,
                                                                 int64_t grid_x)
 {
-    constexpr int E    = Vec16<T>::N;        // elements per 16-byte load
-    constexpr int LPH  = 8 / E;              // loads per 8-column half-row (1 for binary16, 2 for fp32)
+    constexpr int E     = Vec16<T>::N;            // elements per 16-byte load (8 or 4)
+    constexpr int PCOLS = 2 * E;                  // patch width: 16 (binary16) or 8 (fp32) columns
+    constexpr int NH    = PCOLS / 8;              // 8-column halves per patch row (one Philox block each)
+    constexpr int CW    = PCOLS / 4;              // code dwords per patch row
+    constexpr int WTILE_R = 8 * kPatchRows, WTILE_C = 8 * PCOLS;
     const int     lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
     const int64_t by   = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
-    const int64_t r0   = by * kBlockRows + wave * kWaveTile + (lane / 8) * kPatch;
-    const int64_t c0   = bx * kWaveTile + (lane % 8) * kPatch;
+    const int64_t r0   = (by * (kBlock / kWaveSize) + wave) * WTILE_R + (lane / 8) * kPatchRows;
+    const int64_t c0   = bx * WTILE_C + (lane % 8) * PCOLS;
     if(r0 >= rows || c0 >= cols) return;
-    const bool half_ok[2] = {true, c0 + 8 < cols};
+    const bool second_ok = NH == 1 || c0 + 8 < cols;      // binary16: the patch's second 8 columns exist
 
-    float fcol[kPatch];
+    float fcol[PCOLS];
     if(PERCOL)
     {
 #pragma unroll
-        for(int j = 0; j < kPatch; ++j) fcol[j] = (j < 8 || half_ok[1]) ? inv_scale[c0 + j] : 1.0f;
+        for(int j = 0; j < PCOLS; ++j) fcol[j] = (j < 8 || second_ok) ? inv_scale[c0 + j] : 1.0f;
     }
     const float ftensor = (!PERCOL && gran == kPerTensor) ? inv_scale[0] : 1.0f;
 
-    uint32_t code[kPatch][4];   // row i, columns 4w..4w+3 in dword w
+    uint32_t code[kPatchRows][CW];   // row i, columns 4w..4w+3 in dword w
+    constexpr int RB = 4;                // rows per batch
 #pragma unroll
-    for(int i = 0; i < kPatch; ++i)
-    {
-        const int64_t r = r0 + i;
+    for(int batch = 0; batch < kPatchRows / RB; ++batch)
+    {   // four rows at a time: their 8 loads are requested together, then converted
+        uint4 raw[RB][2];
 #pragma unroll
-        for(int w = 0; w < 4; ++w) code[i][w] = 0u;
-        if(r < rows)
+        for(int ii = 0; ii < RB; ++ii)
         {
-            const float frow = PERCOL ? 1.0f : (gran == kPerRow ? inv_scale[r] : ftensor);
+            const int64_t r = r0 + batch * RB + ii;
 #pragma unroll
-            for(int h = 0; h < 2; ++h)
+            for(int l = 0; l < 2; ++l)
             {
-                if(!half_ok[h]) continue;
-                float v[8];
+                const bool ok = r < rows && (l == 0 || second_ok);
+                raw[ii][l] = ok ? *reinterpret_cast<const uint4*>(x + r * ld + c0 + l * E) : make_uint4(0, 0, 0, 0);
+            }
+        }
 #pragma unroll
-                for(int l = 0; l < LPH; ++l)
-                {
-                    float t[E];
-                    Vec16<T>::load(x + r * ld + c0 + 8 * h + l * E, t);
+        for(int ii = 0; ii < RB; ++ii)
+        {
+            const int     i    = batch * RB + ii;
+            const int64_t r    = r0 + i;
+            const float   frow = PERCOL ? 1.0f : ((gran == kPerRow && r < rows) ? inv_scale[r] : ftensor);
+            float         v[PCOLS];
+            float         t0[E], t1[E];
+            Vec16<T>::decode(raw[ii][0], t0);
+            Vec16<T>::decode(raw[ii][1], t1);
 #pragma unroll
-                    for(int e = 0; e < E; ++e) v[l * E + e] = t[e];
-                }
+            for(int e = 0; e < E; ++e)
+            {
+                v[e]     = t0[e];
+                v[E + e] = t1[e];
+            }
+#pragma unroll
+            for(int w = 0; w < CW; ++w) code[i][w] = 0u;
+#pragma unroll
+            for(int h = 0; h < NH; ++h)
+            {
                 uint4 blk = {0u, 0u, 0u, 0u};
                 if(RND == kStochastic)
                     blk = philox_group(seed, offset, static_cast<uint64_t>(r * cols + c0 + 8 * h) >> 3);
@@ -239,37 +358,44 @@ __global__ __launch_bounds__(kBlock) void quantize_patch_kernel(const T* __restr
                 {
                     const int   col = 8 * h + j;
                     const float f   = PERCOL ? fcol[col] : frow;
-                    const int   c   = quantize_code<RND>(v[j], f, qmax, philox_draw16(blk, j));
+                    const int   c   = quantize_code<RND>(v[col], f, qmax, philox_draw16(blk, j));
                     code[i][col / 4] |= (static_cast<uint32_t>(c) & 0xFFu) << (8 * (col % 4));
                 }
             }
         }
+        // Pin the batch's codes here: otherwise the compiler sinks all conversions behind the last
+        // batch's loads and keeps every raw vector of the patch alive (register budget).
+#pragma unroll
+        for(int ii = 0; ii < RB; ++ii)
+#pragma unroll
+            for(int w = 0; w < CW; ++w) asm volatile("" : "+v"(code[batch * RB + ii][w]));
     }
 
     if(q)
     {
-        const bool wide = (cols % 16 == 0);
 #pragma unroll
-        for(int i = 0; i < kPatch; ++i)
+        for(int i = 0; i < kPatchRows; ++i)
         {
             const int64_t r = r0 + i;
             if(r >= rows) continue;
             int8_t* dst = q + r * cols + c0;
-            if(wide)
-                *reinterpret_cast<uint4*>(dst) = make_uint4(code[i][0], code[i][1], code[i][2], code[i][3]);
+            if(NH == 1)
+                *reinterpret_cast<uint2*>(dst) = make_uint2(code[i][0], code[i][1]);
+            else if(cols % 16 == 0)
+                *reinterpret_cast<uint4*>(dst) = make_uint4(code[i][0], code[i][1], code[i][CW - 2], code[i][CW - 1]);
             else
             {
                 *reinterpret_cast<uint2*>(dst) = make_uint2(code[i][0], code[i][1]);
-                if(half_ok[1]) *reinterpret_cast<uint2*>(dst + 8) = make_uint2(code[i][2], code[i][3]);
+                if(second_ok) *reinterpret_cast<uint2*>(dst + 8) = make_uint2(code[i][CW - 2], code[i][CW - 1]);
             }
         }
     }
     if(qT)
     {   // rows % 16 == 0 here, so the patch's 16 rows all exist
 #pragma unroll
-        for(int col = 0; col < kPatch; ++col)
+        for(int col = 0; col < PCOLS; ++col)
         {
-            if(col >= 8 && !half_ok[1]) continue;
+            if(col >= 8 && !second_ok) continue;
             uint32_t t[4];
 #pragma unroll
             for(int g = 0; g < 4; ++g)
@@ -284,7 +410,7 @@ __global__ __launch_bounds__(kBlock) void quantize_patch_kernel(const T* __restr
 // Any shape, any alignment: one element per thread.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void quantize_generic_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
-                                                                  int64_t ld, float qmax, int gran, int rnd,
+                                                                  int64_t ld, int qmax, int gran, int rnd,
                                                                   uint64_t seed, uint64_t offset,
                                                                   const float* __restrict__ inv_scale,
                                                                   int8_t* __restrict__ q, int8_t* __restrict__ qT)
@@ -396,72 +522,6 @@ __global__ __launch_bounds__(kBlock) void dequantize_kernel(const Ti* __restrict
     }
 }
 
-// ------------------------------------------------------------------ column sums (bias gradient)
-// Stage 1: block (bx, by) sums rows by, by+gridDim.y, ... of a strip of columns.  Lanes own
-// adjacent columns (one 16-byte vector each when VEC); the block's row lanes are folded
-// through LDS, so partial[by][c] holds one value per block row.
-template <typename T, bool VEC>
-__global__ __launch_bounds__(kBlock) void colsum_kernel(const T* __restrict__ x, int64_t rows, int64_t cols, int tpr,
-                                                        float* __restrict__ partial)
-{
-    constexpr int E   = VEC ? Vec16<T>::N : 1;
-    __shared__ float lds[kBlock * E];
-    const int     rpb = kBlock / tpr;                       // row lanes per block
-    const int     tc = threadIdx.x % tpr, tr = threadIdx.x / tpr;
-    const int64_t c0  = (static_cast<int64_t>(blockIdx.x) * tpr + tc) * E;
-    const int64_t S   = static_cast<int64_t>(gridDim.y) * rpb;
-    float acc[E];
-#pragma unroll
-    for(int e = 0; e < E; ++e) acc[e] = 0.0f;
-    if(c0 < cols)
-    {
-        for(int64_t r = static_cast<int64_t>(blockIdx.y) * rpb + tr; r < rows; r += S)
-        {
-            if(VEC)
-            {
-                float v[Vec16<T>::N];
-                Vec16<T>::load(x + r * cols + c0, v);
-#pragma unroll
-                for(int e = 0; e < E; ++e) acc[e] += v[e];
-            }
-            else
-                acc[0] += to_f32(x[r * cols + c0]);
-        }
-    }
-#pragma unroll
-    for(int e = 0; e < E; ++e) lds[(tr * tpr + tc) * E + e] = acc[e];
-    __syncthreads();
-    if(tr == 0 && c0 < cols)
-    {
-        for(int q = 1; q < rpb; ++q)
-#pragma unroll
-            for(int e = 0; e < E; ++e) acc[e] += lds[(q * tpr + tc) * E + e];
-#pragma unroll
-        for(int e = 0; e < E; ++e) partial[static_cast<int64_t>(blockIdx.y) * cols + c0 + e] = acc[e];
-    }
-}
-
-// Stage 2: 16 columns per block; sixteen threads per column fold a sixteenth of the partials
-// each (fixed assignment, fixed order), then the sixteen are added in order.
-__global__ __launch_bounds__(kBlock) void colsum_finalize_kernel(const float* __restrict__ partial, int S, int64_t cols,
-                                                                 float* __restrict__ out)
-{
-    __shared__ float lds[kBlock];
-    const int     tc = threadIdx.x % 16, q = threadIdx.x / 16;
-    const int64_t c  = static_cast<int64_t>(blockIdx.x) * 16 + tc;
-    float         acc = 0.0f;
-    if(c < cols)
-        for(int s = q; s < S; s += 16) acc += partial[static_cast<int64_t>(s) * cols + c];
-    lds[threadIdx.x] = acc;
-    __syncthreads();
-    if(q == 0 && c < cols)
-    {
-        float t = 0.0f;
-        for(int i = 0; i < 16; ++i) t += lds[i * 16 + tc];
-        out[c] = t;
-    }
-}
-
 int next_pow2(int64_t v)
 {
     int p = 1;
@@ -469,9 +529,9 @@ int next_pow2(int64_t v)
     return p;
 }
 
-// Column-sum launch shape: threads per row (power of two) and block rows (gridDim.y, at most
-// kColsumSplits), aiming at about five hundred blocks.
-void colsum_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
+// Launch shape of a per-column reduction: threads per row (power of two) and block rows
+// (gridDim.y, at most kColParts), aiming at about five hundred blocks.
+void colreduce_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
 {
     const int64_t ncv = (cols + E - 1) / E;
     tpr               = ncv >= kBlock ? kBlock : (next_pow2(ncv) < 2 ? 2 : next_pow2(ncv));
@@ -480,9 +540,28 @@ void colsum_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
     int64_t       g   = (512 + gx - 1) / gx;
     const int64_t maxg = (rows + rpb - 1) / rpb;              // no more block rows than row groups
     if(g > maxg) g = maxg;
-    if(g > kColsumSplits) g = kColsumSplits;
+    if(g > kColParts) g = kColParts;
     if(g < 1) g = 1;
     gy = static_cast<int>(g);
+}
+
+template <typename T, int OP>
+hipError_t colreduce_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, float qmax, float* out,
+                            float* inv_scale, float* amax_opt, float* ws, hipStream_t st)
+{
+    constexpr int E   = Vec16<T>::N;
+    const bool    vec = aligned16(x) && (ld * sizeof(T)) % 16 == 0 && cols % E == 0;
+    int           tpr, gy;
+    colreduce_shape(rows, cols, vec ? E : 1, tpr, gy);
+    const int64_t ncv = (cols + (vec ? E : 1) - 1) / (vec ? E : 1);
+    const dim3    grid(static_cast<unsigned>((ncv + tpr - 1) / tpr), static_cast<unsigned>(gy));
+    if(vec)
+        colreduce_kernel<T, true, OP><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws, nullptr);
+    else
+        colreduce_kernel<T, false, OP><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws, nullptr);
+    colreduce_finalize_kernel<OP><<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(ws, gy, cols, qmax, out, inv_scale,
+                                                                               amax_opt);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -491,17 +570,47 @@ void colsum_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
 size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran)
 {
     (void)rows;
-    if(gran == kPerTensor) return sizeof(float) * kAbsmaxMaxBlocks;
-    if(gran == kPerCol) return sizeof(float) * kAbsmaxColSplits * static_cast<size_t>(cols > 0 ? cols : 0);
+    if(gran == kPerTensor)   // block maxima; with fused column sums also the per-column partial sums
+        return sizeof(float) * (kAbsmaxMaxBlocks + static_cast<size_t>(kColParts) * static_cast<size_t>(cols > 0 ? cols : 0));
+    if(gran == kPerCol) return sizeof(float) * kColParts * static_cast<size_t>(cols > 0 ? cols : 0);
     return 0;
+}
+
+// Per-tensor absmax fused with column sums: one pass over x.
+template <typename T>
+static hipError_t absmax_colsum_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, float qmax, float* scale,
+                                       float* inv_scale, float* amax_opt, float* colsum, float* ws, hipStream_t st)
+{
+    constexpr int E   = Vec16<T>::N;
+    const bool    vec = aligned16(x) && (ld * sizeof(T)) % 16 == 0 && cols % E == 0;
+    int           tpr, gy;
+    colreduce_shape(rows, cols, vec ? E : 1, tpr, gy);
+    const int64_t ncv = (cols + (vec ? E : 1) - 1) / (vec ? E : 1);
+    int64_t       gx  = (ncv + tpr - 1) / tpr;
+    while(gx * gy > kAbsmaxMaxBlocks && gy > 1) gy = (gy + 1) / 2;      // block maxima must fit their slots
+    float* ws_max = ws;                                                   // [kAbsmaxMaxBlocks]
+    float* ws_sum = ws + kAbsmaxMaxBlocks;                                // [gy][cols]
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy));
+    if(vec)
+        colreduce_kernel<T, true, OP_SUMMAX><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws_sum, ws_max);
+    else
+        colreduce_kernel<T, false, OP_SUMMAX><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws_sum, ws_max);
+    colreduce_finalize_kernel<OP_SUM><<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(ws_sum, gy, cols, 0.0f, colsum,
+                                                                                   nullptr, nullptr);
+    absmax_tensor_finalize_kernel<<<dim3(1), dim3(kBlock), 0, st>>>(ws_max, static_cast<int>(gx * gy), qmax, scale,
+                                                                    inv_scale, amax_opt);
+    return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax, float* scale,
-                               float* inv_scale, float* amax_opt, float* ws, hipStream_t st)
+                               float* inv_scale, float* amax_opt, float* colsum_opt, float* ws, hipStream_t st)
 {
+    if(gran == kPerTensor && colsum_opt)
+        return absmax_colsum_launch(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt, colsum_opt, ws, st);
     constexpr int E       = Vec16<T>::N;
     const bool    rows_ok = aligned16(x) && (ld * sizeof(T)) % 16 == 0;
+    (void)E;
     if(gran == kPerTensor)
     {
         const bool    vec  = aligned16(x) && ld == cols;
@@ -526,36 +635,34 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
                                                                            amax_opt);
     }
     else
-    {
-        const bool    vec = rows_ok && cols % E == 0;
-        const int64_t per = static_cast<int64_t>(kWaveSize) * (vec ? E : 1);
-        const dim3    grid(static_cast<unsigned>((cols + per - 1) / per), kAbsmaxColSplits / (kBlock / kWaveSize));
-        if(vec)
-            absmax_cols_kernel<T, true><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws);
-        else
-            absmax_cols_kernel<T, false><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws);
-        absmax_cols_finalize_kernel<<<dim3((cols + kBlock - 1) / kBlock), dim3(kBlock), 0, st>>>(
-            ws, kAbsmaxColSplits, cols, qmax, scale, inv_scale, amax_opt);
-    }
+        return colreduce_launch<T, OP_MAX>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt, ws, st);
     return hipGetLastError();
 }
 
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax,
-                               float* scale, float* inv_scale, float* amax_opt, float* workspace, hipStream_t stream)
+                               float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, float* workspace,
+                               hipStream_t stream)
 {
     if(xdt == kF32)
         return absmax_typed(static_cast<const float*>(x), rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt,
-                            workspace, stream);
+                            colsum_opt, workspace, stream);
     return absmax_typed(static_cast<const __half*>(x), rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt,
-                        workspace, stream);
+                        colsum_opt, workspace, stream);
 }
 
+template <typename T> struct PatchGeom
+{
+    static constexpr int kTileCols = 8 * 2 * Vec16<T>::N;                       // columns per wavefront tile
+    static constexpr int kTileRows = (kBlock / kWaveSize) * 8 * kPatchRows;     // rows per block (wavefronts stacked)
+};
+
 template <typename T, int RND>
-static void quantize_patch_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, float qmax, int gran,
+static void quantize_patch_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, int qmax, int gran,
                                   uint64_t seed, uint64_t offset, const float* inv, int8_t* q, int8_t* qT,
                                   hipStream_t st)
 {
-    const int64_t gx = (cols + kWaveTile - 1) / kWaveTile, gy = (rows + kBlockRows - 1) / kBlockRows;
+    const int64_t gx = (cols + PatchGeom<T>::kTileCols - 1) / PatchGeom<T>::kTileCols;
+    const int64_t gy = (rows + PatchGeom<T>::kTileRows - 1) / PatchGeom<T>::kTileRows;
     const dim3    grid(static_cast<unsigned>(gx * gy));
     if(gran == kPerCol)
         quantize_patch_kernel<T, RND, true><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, gran, seed, offset,
@@ -566,11 +673,12 @@ static void quantize_patch_launch(const T* x, int64_t rows, int64_t cols, int64_
 }
 
 template <typename T>
-static hipError_t quantize_typed(const T* x, int64_t rows, int64_t cols, int64_t ld, float qmax, int gran, int rnd,
+static hipError_t quantize_typed(const T* x, int64_t rows, int64_t cols, int64_t ld, int qmax, int gran, int rnd,
                                  uint64_t seed, uint64_t offset, const float* inv, int8_t* q, int8_t* qT,
                                  hipStream_t st)
 {
-    const int64_t gx   = (cols + kWaveTile - 1) / kWaveTile, gy = (rows + kBlockRows - 1) / kBlockRows;
+    const int64_t gx   = (cols + PatchGeom<T>::kTileCols - 1) / PatchGeom<T>::kTileCols;
+    const int64_t gy   = (rows + PatchGeom<T>::kTileRows - 1) / PatchGeom<T>::kTileRows;
     const bool    fast = cols % 8 == 0 && aligned16(x) && (ld * sizeof(T)) % 16 == 0 && (!q || aligned16(q))
                       && (!qT || (aligned16(qT) && rows % 16 == 0)) && gx * gy < (int64_t(1) << 31);
     if(fast)
@@ -592,7 +700,7 @@ static hipError_t quantize_typed(const T* x, int64_t rows, int64_t cols, int64_t
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, float qmax, int gran,
+hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int qmax, int gran,
                                 int rnd, uint64_t seed, uint64_t offset, const float* inv_scale, int8_t* q, int8_t* qT,
                                 hipStream_t stream)
 {
@@ -656,31 +764,17 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols)
 {
     (void)rows;
-    return sizeof(float) * static_cast<size_t>(kColsumSplits) * static_cast<size_t>(cols > 0 ? cols : 0);
-}
-
-template <typename T>
-static hipError_t colsum_typed(const T* x, int64_t rows, int64_t cols, float* out, float* ws, hipStream_t st)
-{
-    constexpr int E   = Vec16<T>::N;
-    const bool    vec = aligned16(x) && cols % E == 0;
-    int           tpr, gy;
-    colsum_shape(rows, cols, vec ? E : 1, tpr, gy);
-    const int64_t ncv = (cols + (vec ? E : 1) - 1) / (vec ? E : 1);
-    const dim3    grid(static_cast<unsigned>((ncv + tpr - 1) / tpr), static_cast<unsigned>(gy));
-    if(vec)
-        colsum_kernel<T, true><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, tpr, ws);
-    else
-        colsum_kernel<T, false><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, tpr, ws);
-    colsum_finalize_kernel<<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(ws, gy, cols, out);
-    return hipGetLastError();
+    return sizeof(float) * static_cast<size_t>(kColParts) * static_cast<size_t>(cols > 0 ? cols : 0);
 }
 
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream)
 {
-    if(xdt == kF32) return colsum_typed(static_cast<const float*>(x), rows, cols, out, workspace, stream);
-    return colsum_typed(static_cast<const __half*>(x), rows, cols, out, workspace, stream);
+    if(xdt == kF32)
+        return colreduce_launch<float, OP_SUM>(static_cast<const float*>(x), rows, cols, cols, 0.0f, out, nullptr, nullptr,
+                                               workspace, stream);
+    return colreduce_launch<__half, OP_SUM>(static_cast<const __half*>(x), rows, cols, cols, 0.0f, out, nullptr, nullptr,
+                                            workspace, stream);
 }
 
 }  // namespace qsync

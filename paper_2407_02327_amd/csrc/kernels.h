@@ -14,14 +14,15 @@ enum Round { kNearest = 0, kStochastic = 1, kFloor = 2 };
 
 // ---- absmax / scale -------------------------------------------------------------------
 constexpr int kAbsmaxMaxBlocks = 2048;  // per-tensor stage-1 partials
-constexpr int kAbsmaxColSplits = 64;    // per-column stage-1 row splits
+constexpr int kColParts = 512;          // most stage-1 partials per column of a per-column reduction
 size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran,
                                float qmax, float* scale, float* inv_scale, float* amax_opt,
-                               float* workspace, hipStream_t stream);
+                               float* colsum_opt /* per-tensor only: fused column sums */, float* workspace,
+                               hipStream_t stream);
 
 // ---- quantize / cast / copy (+ transpose) ---------------------------------------------
-hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, float qmax,
+hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int qmax,
                                 int gran, int rnd, uint64_t seed, uint64_t offset, const float* inv_scale,
                                 int8_t* q, int8_t* qT, hipStream_t stream);
 hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int outdt,
@@ -31,7 +32,6 @@ hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, in
 hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld,
                              const float* row_scale, const float* col_scale, float tensor_scale,
                              const float* col_bias, void* y, int ydt, hipStream_t stream);
-constexpr int kColsumSplits = 1024;  // most block rows (= partial sums per column) of the column-sum stage 1
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream);

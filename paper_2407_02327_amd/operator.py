@@ -70,7 +70,8 @@ class QLinear:
     def convert_x(self, x: torch.Tensor, stream=None) -> None:
         M, K = self.M, self.K
         if self.tag == Q.INT8:
-            Q.qsync_absmax_scale(x, M, K, K, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, self.ws_absmax, stream)
+            Q.qsync_absmax_scale(x, M, K, K, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None, self.ws_absmax,
+                                 stream)
             Q.qsync_quantize(x, M, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq,
                              self.xqT, stream)
         else:
@@ -81,7 +82,7 @@ class QLinear:
         if self.tag != Q.INT8:
             Q.qsync_quantize(w, N, K, K, self.tag, 0, 0, 0, 0, 0, None, self.wq, self.wqbT, stream)
             return
-        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, self.ws_absmax, stream)
+        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax, stream)
         if self.w_gran == Q.PER_TENSOR:       # one quantization serves the forward and dX
             Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq,
                              self.wqbT, stream)
@@ -89,15 +90,16 @@ class QLinear:
             return
         Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_ROW, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
         # dX contracts over the output channels, so its weight codes carry one scale per input feature
-        Q.qsync_absmax_scale(w, N, K, K, Q.PER_COL, self.bits, self.swb, self.iwb, None, self.ws_absmax, stream)
+        Q.qsync_absmax_scale(w, N, K, K, Q.PER_COL, self.bits, self.swb, self.iwb, None, None, self.ws_absmax, stream)
         Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_COL, Q.ROUND_NEAREST, 0, 0, self.iwb, None, self.wqbT,
                          stream)
 
     def convert_dy(self, dy: torch.Tensor, stream=None) -> None:
         M, N = self.M, self.N
         if self.tag == Q.INT8:
-            Q.qsync_absmax_scale(dy, M, N, N, Q.PER_TENSOR, self.bits, self.sdy, self.idy, self.ady, self.ws_absmax,
-                                 stream)
+            # the same pass over dY yields its absmax and the bias gradient db (column sums)
+            Q.qsync_absmax_scale(dy, M, N, N, Q.PER_TENSOR, self.bits, self.sdy, self.idy, self.ady, self.db,
+                                 self.ws_absmax, stream)
             Q.qsync_quantize(dy, M, N, N, Q.INT8, self.bits, Q.PER_TENSOR, self.dy_round, self.seed, self.offset,
                              self.idy, self.dyq, self.dyqT, stream)
             self.last_dy_offset = self.offset
@@ -111,10 +113,11 @@ class QLinear:
                             self.bias, self.y, self.acc, self.ws_fwd, stream)
 
     def gemm_bwd(self, dy: Optional[torch.Tensor], stream=None) -> None:
+        want_db = dy is not None and self.tag != Q.INT8      # INT8: db already came out of the absmax pass over dY
         Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
                             self.wqbT, self.swb, self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW,
-                            self.dx, self.dw, self.db if dy is not None else None, dy, self.acc_dx, self.acc_dw,
-                            self.ws_bwd, stream)
+                            self.dx, self.dw, self.db if want_db else None, dy if want_db else None, self.acc_dx,
+                            self.acc_dw, self.ws_bwd, stream)
 
     # ---- whole passes ----------------------------------------------------------------------
     def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None) -> torch.Tensor:

@@ -24,7 +24,7 @@ def _gpu_absmax(xd, rows, cols, ld, gran, bits=8):
     n = {"tensor": 1, "row": rows, "col": cols}[gran]
     s, iv, am = empty(n, torch.float32), empty(n, torch.float32), empty(n, torch.float32)
     w = ws(Q.qsync_absmax_workspace_bytes(rows, cols, GRAN[gran]))
-    Q.qsync_absmax_scale(xd, rows, cols, ld, GRAN[gran], bits, s, iv, am, w)
+    Q.qsync_absmax_scale(xd, rows, cols, ld, GRAN[gran], bits, s, iv, am, None, w)
     return s, iv, am
 
 
@@ -67,6 +67,29 @@ def test_absmax_strided_and_misaligned_and_zero():
     x[4095, 4095] = 77.0
     s, iv, am = _gpu_absmax(dev(x), 4096, 4096, 4096, "tensor")
     assert host(am)[0] == 77.0
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_absmax_fused_with_column_sums(dtype):
+    """One pass gives the per-tensor scale and the column sums (the bias gradient when x = dY)."""
+    rng = np.random.default_rng(7)
+    for rows, cols in [(1, 1), (3, 5), (64, 128), (257, 1000), (4096, 512), (2000, 24), (33, 8200), (16384, 64)]:
+        say("absmax+colsum", dtype.__name__, rows, cols)
+        x = _data(rng, (rows, cols), dtype, 1e-2)
+        xd = dev(x)
+        s, iv, am, cs = (empty(1, torch.float32), empty(1, torch.float32), empty(1, torch.float32),
+                         empty(cols, torch.float32))
+        w = ws(Q.qsync_absmax_workspace_bytes(rows, cols, Q.PER_TENSOR))
+        Q.qsync_absmax_scale(xd, rows, cols, cols, Q.PER_TENSOR, 8, s, iv, am, cs, w)
+        amax = orc.absmax(x, "tensor")
+        so, io = orc.scales_from_amax(amax)
+        assert_bits_equal(host(am), amax, "amax")
+        assert_bits_equal(host(s), so, "scale")
+        assert_bits_equal(host(iv), io, "inv_scale")
+        assert_close(host(cs), x.astype(np.float64).sum(axis=0), "column sums")
+    with pytest.raises(Q.QsyncError) as e:
+        Q.qsync_absmax_scale(xd, rows, cols, cols, Q.PER_ROW, 8, s, iv, am, cs, w)
+    assert e.value.status == Q.ERR_UNSUPPORTED
 
 
 def _gpu_quantize(xd, rows, cols, ld, tag, gran, rnd, seed, offset, inv, want_q=True, want_t=True, bits=8):
@@ -177,6 +200,6 @@ def test_dequantize(adt, ydt):
 def test_empty_tensors_are_noops():
     s = empty(1, torch.float32)
     a = empty(1, torch.int32)
-    Q.qsync_absmax_scale(s, 0, 16, 16, Q.PER_TENSOR, 8, s, s, None, None)
+    Q.qsync_absmax_scale(s, 0, 16, 16, Q.PER_TENSOR, 8, s, s, None, None, None)
     Q.qsync_quantize(s, 0, 16, 16, Q.INT8, 8, 0, 0, 0, 0, s, s, None)
     Q.qsync_dequantize(a, 16, 0, 0, None, None, 1.0, None, s)

@@ -81,6 +81,19 @@ def test_per_tensor_weights_share_codes_between_forward_and_backward():
     assert op.swb is op.sw
 
 
+def test_bias_gradient_from_the_backward_call():
+    """db requested from qsync_qlinear_bwd itself (not from the fused absmax pass)."""
+    case = wl.ragged_case(208, 144, 80, seed=31, dtype=np.float16)
+    say("db via qlinear_bwd")
+    M, N, K = case.mnk
+    for dy in (case.dy, case.dy.astype(np.float32)):
+        db = torch.empty(N, dtype=torch.float32, device="cuda")
+        w = torch.empty(Q.qsync_qlinear_bwd_workspace_bytes(Q.INT8, M, N, K), dtype=torch.uint8, device="cuda")
+        Q.qsync_qlinear_bwd(Q.INT8, M, N, K, None, None, None, None, None, None, None, Q.PER_TENSOR, None, None, db,
+                            dev(dy), None, None, w)
+        assert_close(host(db), dy.astype(np.float64).sum(axis=0), "db")
+
+
 def test_fp32_tag_equals_plain_matmul():
     case = wl.ragged_case(100, 60, 75, seed=5)               # K with no alignment at all
     say("fp32 plain matmul")
