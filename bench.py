@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--ydtype", default="f16", choices=["f16", "f32"], help="forward output type")
     ap.add_argument("--cpu-tokens", type=int, default=2048, help="rows per operator given to the CPU oracle")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 512 MiB device copy (known traffic) so that rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -134,6 +137,13 @@ def main():
             run("gemm_fwd", op.gemm_fwd)
             run("convert_dy", lambda: op.convert_dy(dy))
             run("gemm_bwd", lambda: op.gemm_bwd(dy))
+
+    if args.pmc_calibration:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step(False)

@@ -139,3 +139,83 @@ def test_int32_wraparound_matches_oracle():
     want, ovf = orc.int_gemm_nt(a, b)
     assert ovf
     assert_bits_equal(host(acc), want, "wrapped accumulators")
+
+
+def test_config4_mixed_precision_mlp_chain():
+    """12 linears (width -> hidden -> width, GELU in between), per-layer precision tags; fwd then bwd.
+
+    Parity is asserted per operator on identical input bits: each layer's actual GPU input and
+    incoming gradient are downloaded and given to the oracle.  GELU and its derivative are not part
+    of the operator path; the harness evaluates them with torch between the operators.
+    """
+    chain = wl.config4(tokens=2048)
+    M = chain.x.shape[0]
+    say("config4 chain, tags", chain.tags)
+    assert set(chain.tags) == {Q.INT8, Q.FP16, Q.FP32}
+    ops, acts, pre = [], [dev(chain.x)], []
+    wd = [dev(w) for w in chain.weights]
+    for l, (w, tag) in enumerate(zip(chain.weights, chain.tags)):
+        N, K = w.shape
+        op = QLinear(tag, M, N, K, x_dtype=torch.float32, y_dtype=torch.float32, dx_dtype=torch.float32,
+                     w_gran=Q.PER_ROW, dy_round=Q.ROUND_STOCHASTIC, philox_seed=chain.philox_seed, dump_acc=True)
+        y = op.forward(acts[-1], wd[l])
+        ops.append(op)
+        pre.append(y)
+        acts.append(torch.nn.functional.gelu(y) if l % 2 == 0 else y)
+    grads = [None] * len(ops)
+    g = dev(chain.dy_last)
+    offset = 0
+    offsets = [0] * len(ops)
+    for l in reversed(range(len(ops))):
+        if l % 2 == 0:                                       # through the GELU that follows layer l
+            t = pre[l].detach().clone().requires_grad_(True)
+            torch.nn.functional.gelu(t).backward(g)
+            g = t.grad
+        grads[l] = g
+        ops[l].offset = offsets[l] = offset
+        dx, dw, db = ops[l].backward(g)
+        if chain.tags[l] == Q.INT8:
+            offset += (M * chain.weights[l].shape[0] + 7) // 8
+        g = dx
+    torch.cuda.synchronize()
+    for l, op in enumerate(ops):
+        say("config4 layer", l, "tag", chain.tags[l])
+        x_l, g_l = host(acts[l]), host(grads[l])
+        ref = orc.operator_fwd_bwd(chain.tags[l], x_l, chain.weights[l], None, g_l, "row", "stochastic",
+                                   seed=chain.philox_seed, offset=offsets[l], y_dtype=np.float64,
+                                   dx_dtype=np.float64, dw_dtype=np.float64)
+        if chain.tags[l] == Q.INT8:
+            assert_bits_equal(host(op.xq), ref["xq"], "xq")
+            assert_bits_equal(host(op.dyq), ref["dyq"], "dyq")
+            assert_bits_equal(host(op.acc), ref["acc"], "fwd accumulators")
+            assert_bits_equal(host(op.acc_dx), ref["acc_dx"], "dX accumulators")
+            assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "dW accumulators")
+            assert not ref["overflow"]
+        assert_close(host(op.y), ref["y"], "Y")
+        assert_close(host(op.dx), ref["dx"], "dX")
+        assert_close(host(op.dw), ref["dw"], "dW")
+        assert_close(host(op.db), ref["db"], "db")
+    # the chain as a whole stays close to the unquantized fp64 network (sanity, not parity)
+    a = chain.x.astype(np.float64)
+    for l, w in enumerate(chain.weights):
+        a = a @ w.astype(np.float64).T
+        if l % 2 == 0:
+            a = orc.gelu(a)
+    out = host(acts[-1]).astype(np.float64)
+    assert np.abs(out - a).max() <= 0.1 * np.abs(a).max()
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config5_bert_large_full_size_int8(which):
+    """Full-size BERT-large-scale linears in the launch configuration the benchmark times."""
+    case = wl.config5()[which]
+    run_case(case, Q.INT8, y_dtype=np.float16)
+
+
+def test_config5_fp16_tag_full_size():
+    run_case(wl.config5()["up"], Q.FP16, y_dtype=np.float16, check_codes=False)
+
+
+def test_config3_resnet_conv_full_size_int8():
+    """M = 200704: split-K dW over a contraction of 200704, HBM-bound forward and dX."""
+    run_case(wl.config3(), Q.INT8, y_dtype=np.float16)
