@@ -478,15 +478,15 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
     const int64_t ktiles = (kb + kRowBytes - 1) / kRowBytes;
     auto ntiles = [&](int t) { return ((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn); };
     const int64_t cus = 256;
-    int tile = kNumTiles - 1;
+    int tile = 2;
     // largest tile that still yields at least ~one workgroup per CU
     for(int t = 0; t < kNumTiles; ++t)
         if(ntiles(t) >= (cus * 3) / 4) { tile = t; break; }
     if(ntiles(tile) < (cus * 3) / 4) tile = (M > 64 || N > 64) ? 1 : 2;
-    if(force_tile >= 0 && force_tile < kNumTiles) tile = force_tile;
     int splits = 1;
+    if(force_tile >= 0 && force_tile < kNumTiles) { tile = force_tile; splits = 1; }
     const int64_t nt = ntiles(tile);
-    if(nt * 2 <= cus && ktiles >= 8)
+    if(splits == 1 && nt * 2 <= cus && ktiles >= 8)
     {
         int64_t s = cus / nt;
         if(s > ktiles / 4) s = ktiles / 4;     // keep at least 4 K steps per split

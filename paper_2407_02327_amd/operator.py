@@ -60,9 +60,11 @@ class QLinear:
         if dump_acc and tag == Q.INT8:
             i32 = torch.int32
             self.acc, self.acc_dx, self.acc_dw = e(M, N, dt=i32), e(M, K, dt=i32), e(N, K, dt=i32)
-        nws = max(Q.qsync_absmax_workspace_bytes(M, K, Q.PER_TENSOR), Q.qsync_absmax_workspace_bytes(N, K, Q.PER_COL),
-                  Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR))
+        nws = max(Q.qsync_absmax_workspace_bytes(M, K, Q.PER_TENSOR), Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR))
         self.ws_absmax = _ws(nws, dev)
+        # the weight conversion may run on a second stream beside the activation conversion: own scratch
+        self.ws_absmax_w = _ws(max(Q.qsync_absmax_workspace_bytes(N, K, Q.PER_COL),
+                                   Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), dev)
         self.ws_fwd = _ws(Q.qsync_qlinear_workspace_bytes(tag, M, N, K), dev)
         self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K), dev)
 
@@ -82,7 +84,8 @@ class QLinear:
         if self.tag != Q.INT8:
             Q.qsync_quantize(w, N, K, K, self.tag, 0, 0, 0, 0, 0, None, self.wq, self.wqbT, stream)
             return
-        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax, stream)
+        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax_w,
+                             stream)
         if self.w_gran == Q.PER_TENSOR:       # one quantization serves the forward and dX
             Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq,
                              self.wqbT, stream)
@@ -90,7 +93,7 @@ class QLinear:
             return
         Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_ROW, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
         # dX contracts over the output channels, so its weight codes carry one scale per input feature
-        Q.qsync_absmax_scale(w, N, K, K, Q.PER_COL, self.bits, self.swb, self.iwb, None, None, self.ws_absmax, stream)
+        Q.qsync_absmax_scale(w, N, K, K, Q.PER_COL, self.bits, self.swb, self.iwb, None, None, self.ws_absmax_w, stream)
         Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_COL, Q.ROUND_NEAREST, 0, 0, self.iwb, None, self.wqbT,
                          stream)
 
@@ -120,9 +123,18 @@ class QLinear:
                             self.acc_dw, self.ws_bwd, stream)
 
     # ---- whole passes ----------------------------------------------------------------------
-    def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None) -> torch.Tensor:
-        self.convert_x(x, stream)
-        self.convert_w(w, stream)
+    def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None, side_stream=None) -> torch.Tensor:
+        """With `side_stream` (a torch stream of default priority) the small, latency-bound weight
+        conversion kernels run beside the HBM-bound activation conversion and join before the GEMM."""
+        if side_stream is None:
+            self.convert_x(x, stream)
+            self.convert_w(w, stream)
+        else:
+            main = stream if stream is not None else torch.cuda.current_stream()
+            side_stream.wait_stream(main)
+            self.convert_w(w, side_stream)
+            self.convert_x(x, main)
+            main.wait_stream(side_stream)
         self.gemm_fwd(stream)
         return self.y
 
