@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"int8": 5000.0, "fp16": 2500.0}          # dense MFMA peak of MI355X, TOP/s and TFLOP/s
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per forward-GEMM launch (mean of the two forward launches of config 5, INT8, fp16 output),
+# from rocprofv3 --pmc FETCH_SIZE (x2.0) and WRITE_SIZE (x1.0), scaled by a plain 512 MiB copy:
+# see profiles/config5_int8_hbm_traffic.md.  (96.4 + 128.0 + 96.3 + 32.0) MiB / 2.
+MEASURED_FWD_GEMM_TRAFFIC_BYTES = {("c5", "int8", "f16"): int((96.4 + 128.0 + 96.3 + 32.0) / 2 * 2**20)}
 
 
 def log(*a):
@@ -183,7 +187,11 @@ def main():
                    "w_scale": "per-output-channel", "dy_rounding": "stochastic (Philox4x32-10)"},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches)",
                      "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                     "frac": round(achieved / peak, 4), "traffic": None},
+                     "frac": round(achieved / peak, 4),
+                     "traffic": MEASURED_FWD_GEMM_TRAFFIC_BYTES.get((args.workload, args.tag, args.ydtype)),
+                     "algorithmic_bytes": int(sum((c.mnk[0] + c.mnk[1]) * c.mnk[2] * (1 if args.tag == "int8" else 2)
+                                                  + c.mnk[0] * c.mnk[1] * (2 if args.ydtype == "f16" else 4)
+                                                  for c in cases) / len(cases))},
         "breakdown_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
         "breakdown_note": "main-stream event times; the weight conversion runs on a second stream beside convert_x",
         "quantize_dy": {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),

@@ -42,6 +42,7 @@ typedef int      v4i32 __attribute__((ext_vector_type(4)));
 typedef int      v16i32 __attribute__((ext_vector_type(16)));
 typedef float    v16f32 __attribute__((ext_vector_type(16)));
 typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
+typedef unsigned v4u32 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowBytes   = 128;  // K bytes per tile row and per LDS row
 constexpr int kChunks     = 8;    // 16-byte chunks per LDS row
@@ -381,11 +382,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
             for(int r0 = 0; r0 < FPP * 32; r0 += RPI)
             {
                 const int     lr  = r0 + lane / LPR, seg = lane % LPR;
-                const uint4   val = *reinterpret_cast<const uint4*>(stg + lr * PITCH + seg * 16);
+                const v4u32   val = *reinterpret_cast<const v4u32*>(stg + lr * PITCH + seg * 16);
                 const int64_t row = wrow0 + pass * FPP * 32 + lr;
                 const int64_t col = wcol0 + seg * (16 / OS);
-                if(row < p.M && col < p.N)
-                    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(p.C) + (row * p.N + col) * OS) = val;
+                if(row < p.M && col < p.N)   // streaming store: C is not read again by this kernel, keep the operand panels in L2
+                    __builtin_nontemporal_store(val, reinterpret_cast<v4u32*>(static_cast<uint8_t*>(p.C) + (row * p.N + col) * OS));
             }
         }
     };
