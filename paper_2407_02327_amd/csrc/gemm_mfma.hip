@@ -289,9 +289,97 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     //      C^T fragments: lane -> output row m = lane%32 of the fragment; register v -> output
     //      column n = 8*(v/4) + 4*(lane/32) + v%4, i.e. four consecutive columns per register quad.
     const int64_t wrow0 = m0 + wm * WTM, wcol0 = n0 + wn * WTN;
+    // Staged stores: pass the wavefront's sub-tile through its private slice of LDS (the K
+    // pipeline is drained, so the stages are free) and leave with 16-byte stores whose lanes run
+    // along the rows of the destination: every store instruction writes whole 128-byte (or
+    // longer) row segments.  RAW writes the accumulators themselves (split-K partials); otherwise
+    // they are dequantized in registers first.
+    constexpr int STG_BYTES = 2 * STAGE_BYTES / (WGM * WGN);
+    uint8_t*      stg       = lds + wave * STG_BYTES;
+    float         alpha     = 1.0f;
+    auto staged_store = [&](auto out_tag, auto raw_tag, uint8_t* dst_base) {
+        typedef decltype(out_tag) out_t;
+        constexpr bool RAW   = decltype(raw_tag)::value;
+        constexpr int  OS    = sizeof(out_t);
+        constexpr int  PITCH = WTN * OS + 16;                     // padded row pitch in the staging slice
+        constexpr int  FPP   = (STG_BYTES / (32 * PITCH)) >= FM ? FM : ((STG_BYTES / (32 * PITCH)) >= 2 ? 2 : 1);
+        static_assert(32 * PITCH <= STG_BYTES && FM % FPP == 0, "staging slice too small");
+        constexpr int LPR   = WTN * OS / 16;                     // lanes per output row in the store phase
+        constexpr int RPI   = 64 / LPR;                          // rows per store instruction
+        float f[RAW ? 1 : FN][16], b[RAW ? 1 : FN][16];
+        if constexpr(!RAW)
+        {
+#pragma unroll
+            for(int j = 0; j < FN; ++j)
+#pragma unroll
+                for(int v = 0; v < 16; ++v)
+                {
+                    const int64_t col = wcol0 + j * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
+                    const bool    cok = col < p.N;
+                    f[j][v] = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
+                    b[j][v] = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
+                }
+        }
+        __syncthreads();                                  // all wavefronts are done reading the stages
+#pragma unroll
+        for(int pass = 0; pass < FM / FPP; ++pass)
+        {
+#pragma unroll
+            for(int ii = 0; ii < FPP; ++ii)
+            {
+                const int i = pass * FPP + ii;
+#pragma unroll
+                for(int j = 0; j < FN; ++j)
+#pragma unroll
+                    for(int vq = 0; vq < 4; ++vq)
+                    {
+                        out_t o[4];
+#pragma unroll
+                        for(int e = 0; e < 4; ++e)
+                        {
+                            if constexpr(RAW)
+                                o[e] = acc[i][j][vq * 4 + e];
+                            else
+                            {
+                                const float y = static_cast<float>(acc[i][j][vq * 4 + e]) * f[j][vq * 4 + e] + b[j][vq * 4 + e];
+                                o[e] = from_f32_out<out_t>(y);
+                            }
+                        }
+                        uint8_t* dst = stg + (ii * 32 + frag_row) * PITCH + (j * 32 + 8 * vq + 4 * khalf) * OS;
+                        if(OS == 2)
+                            *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o);
+                        else
+                            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
+                    }
+            }
+            // the wavefront's own LDS writes are visible to its later LDS reads (same queue, in order)
+#pragma unroll
+            for(int r0 = 0; r0 < FPP * 32; r0 += RPI)
+            {
+                const int     lr  = r0 + lane / LPR, seg = lane % LPR;
+                const v4u32   val = *reinterpret_cast<const v4u32*>(stg + lr * PITCH + seg * 16);
+                const int64_t row = wrow0 + pass * FPP * 32 + lr;
+                const int64_t col = wcol0 + seg * (16 / OS);
+                if(row < p.M && col < p.N)
+                {
+                    v4u32* dst = reinterpret_cast<v4u32*>(dst_base + (row * p.N + col) * OS);
+                    if constexpr(RAW)
+                        *dst = val;      // read back soon by the reduction: ordinary store
+                    else                 // streaming store: C is not read again here, keep the operand panels in L2
+                        __builtin_nontemporal_store(val, dst);
+                }
+            }
+        }
+    };
+
     if(SPLIT)
     {
         acc_t* part = static_cast<acc_t*>(p.partial) + static_cast<int64_t>(blockIdx.y) * p.M * p.N;
+        if((p.N * 4) % 16 == 0 && (reinterpret_cast<uintptr_t>(part) & 15) == 0)
+        {
+            staged_store(acc_t{}, std::true_type{}, reinterpret_cast<uint8_t*>(part));
+            return;
+        }
 #pragma unroll
         for(int i = 0; i < FM; ++i)
         {
@@ -308,7 +396,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         return;
     }
 
-    float alpha = 1.0f;
     if(p.s0) alpha *= *p.s0;
     if(p.s1) alpha *= *p.s1;
     const int osize = p.c_is_f16 ? 2 : 4;
@@ -343,104 +430,70 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         return;
     }
 
-    // Fast path: dequantize in registers, pass the wavefront's sub-tile through its private
-    // slice of LDS (the K pipeline is drained, so the stages are free) and leave with 16-byte
-    // stores whose lanes run along the rows of C: every store instruction writes whole
-    // 128-byte (or longer) row segments.
-    __syncthreads();                                  // all wavefronts are done reading the stages
-    constexpr int STG_BYTES = 2 * STAGE_BYTES / (WGM * WGN);
-    uint8_t*      stg       = lds + wave * STG_BYTES;
-    auto staged_store = [&](auto out_tag) {
-        typedef decltype(out_tag) out_t;
-        constexpr int OS    = sizeof(out_t);
-        constexpr int PITCH = WTN * OS + 16;                     // padded row pitch in the staging slice
-        constexpr int FPP   = (STG_BYTES / (32 * PITCH)) >= FM ? FM : ((STG_BYTES / (32 * PITCH)) >= 2 ? 2 : 1);
-        static_assert(32 * PITCH <= STG_BYTES && FM % FPP == 0, "staging slice too small");
-        constexpr int LPR   = WTN * OS / 16;                     // lanes per output row in the store phase
-        constexpr int RPI   = 64 / LPR;                          // rows per store instruction
-        float f[FN][16], b[FN][16];
-#pragma unroll
-        for(int j = 0; j < FN; ++j)
-#pragma unroll
-            for(int v = 0; v < 16; ++v)
-            {
-                const int64_t col = wcol0 + j * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
-                const bool    cok = col < p.N;
-                f[j][v] = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
-                b[j][v] = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
-            }
-#pragma unroll
-        for(int pass = 0; pass < FM / FPP; ++pass)
-        {
-#pragma unroll
-            for(int ii = 0; ii < FPP; ++ii)
-            {
-                const int i = pass * FPP + ii;
-#pragma unroll
-                for(int j = 0; j < FN; ++j)
-#pragma unroll
-                    for(int vq = 0; vq < 4; ++vq)
-                    {
-                        out_t o[4];
-#pragma unroll
-                        for(int e = 0; e < 4; ++e)
-                        {
-                            const float y = static_cast<float>(acc[i][j][vq * 4 + e]) * f[j][vq * 4 + e] + b[j][vq * 4 + e];
-                            o[e] = from_f32_out<out_t>(y);
-                        }
-                        uint8_t* dst = stg + (ii * 32 + frag_row) * PITCH + (j * 32 + 8 * vq + 4 * khalf) * OS;
-                        if(OS == 2)
-                            *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o);
-                        else
-                            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
-                    }
-            }
-            // the wavefront's own LDS writes are visible to its later LDS reads (same queue, in order)
-#pragma unroll
-            for(int r0 = 0; r0 < FPP * 32; r0 += RPI)
-            {
-                const int     lr  = r0 + lane / LPR, seg = lane % LPR;
-                const v4u32   val = *reinterpret_cast<const v4u32*>(stg + lr * PITCH + seg * 16);
-                const int64_t row = wrow0 + pass * FPP * 32 + lr;
-                const int64_t col = wcol0 + seg * (16 / OS);
-                if(row < p.M && col < p.N)   // streaming store: C is not read again by this kernel, keep the operand panels in L2
-                    __builtin_nontemporal_store(val, reinterpret_cast<v4u32*>(static_cast<uint8_t*>(p.C) + (row * p.N + col) * OS));
-            }
-        }
-    };
     if(p.c_is_f16)
-        staged_store(__half{});
+        staged_store(__half{}, std::false_type{}, static_cast<uint8_t*>(p.C));
     else
-        staged_store(float{});
+        staged_store(float{}, std::false_type{}, static_cast<uint8_t*>(p.C));
 }
 
 // Adds the split-K partials in split order and applies the epilogue.
 constexpr int kThreads = 256;   // split-K reduction
 
-template <typename ACC>
+template <typename ACC, bool VEC4>
 __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __restrict__ partial, int splits,
                                                                  int64_t M, int64_t N, void* C, int c_is_f16,
                                                                  const float* s0, const float* s1,
                                                                  const float* __restrict__ col_scale,
                                                                  const float* __restrict__ col_bias, int32_t* acc_dump)
 {
+    constexpr int V      = VEC4 ? 4 : 1;       // VEC4: N % 4 == 0 and 16-byte aligned buffers
     const int64_t n      = M * N;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * V;
     float         alpha  = 1.0f;
     if(s0) alpha *= *s0;
     if(s1) alpha *= *s1;
-    for(int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride)
+    for(int64_t i = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * V; i < n; i += stride)
     {
-        ACC acc = 0;
-        for(int s = 0; s < splits; ++s) acc += partial[static_cast<int64_t>(s) * n + i];
+        ACC acc[V];
+#pragma unroll
+        for(int e = 0; e < V; ++e) acc[e] = 0;
+        for(int s = 0; s < splits; ++s)
+        {
+            ACC part[V];
+            if(VEC4)
+                *reinterpret_cast<uint4*>(part) = *reinterpret_cast<const uint4*>(partial + static_cast<int64_t>(s) * n + i);
+            else
+                part[0] = partial[static_cast<int64_t>(s) * n + i];
+#pragma unroll
+            for(int e = 0; e < V; ++e) acc[e] += part[e];
+        }
         const int64_t col = i % N;
-        const float   f   = alpha * (col_scale ? col_scale[col] : 1.0f);
-        const float   y   = static_cast<float>(acc) * f + (col_bias ? col_bias[col] : 0.0f);
-        if(c_is_f16)
-            static_cast<__half*>(C)[i] = __float2half_rn(y);
+        float         y[V];
+#pragma unroll
+        for(int e = 0; e < V; ++e)
+        {
+            const float f = alpha * (col_scale ? col_scale[col + e] : 1.0f);
+            y[e] = static_cast<float>(acc[e]) * f + (col_bias ? col_bias[col + e] : 0.0f);
+        }
+        if(VEC4)
+        {
+            if(c_is_f16)
+            {
+                __half h[4];
+#pragma unroll
+                for(int e = 0; e < 4; ++e) h[e] = __float2half_rn(y[e]);
+                *reinterpret_cast<uint2*>(static_cast<__half*>(C) + i) = *reinterpret_cast<const uint2*>(h);
+            }
+            else
+                *reinterpret_cast<uint4*>(static_cast<float*>(C) + i) = *reinterpret_cast<const uint4*>(y);
+        }
+        else if(c_is_f16)
+            static_cast<__half*>(C)[i] = __float2half_rn(y[0]);
         else
-            static_cast<float*>(C)[i] = y;
-        if(acc_dump) acc_dump[i] = static_cast<int32_t>(acc);
+            static_cast<float*>(C)[i] = y[0];
+        if(acc_dump)
+#pragma unroll
+            for(int e = 0; e < V; ++e) acc_dump[i + e] = static_cast<int32_t>(acc[e]);
     }
 }
 
@@ -503,6 +556,14 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
         if(ntiles(t) >= (cus * 3) / 4) { tile = t; break; }
     if(ntiles(tile) < (cus * 3) / 4) tile = (M > 64 || N > 64) ? 1 : 2;
     int splits = 1;
+    // Too few large tiles for the chip but a long contraction (the weight-gradient shape): split K
+    // over the large tile rather than fall back to the smaller, less efficient one.
+    if(tile != 0 && ktiles >= 16)
+    {
+        int64_t s = cus / ntiles(0);
+        if(s > ktiles / 8) s = ktiles / 8;
+        if(s >= 2 && ntiles(0) * s >= (cus * 3) / 4) { tile = 0; splits = static_cast<int>(s); }
+    }
     if(force_tile >= 0 && force_tile < kNumTiles) { tile = force_tile; splits = 1; }
     const int64_t nt = ntiles(tile);
     if(splits == 1 && nt * 2 <= cus && ktiles >= 8)
@@ -543,16 +604,24 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     hipError_t e = p.prec == 8 ? launch_traits<I8Traits>(plan.tile, a, splits, stream)
                                : launch_traits<F16Traits>(plan.tile, a, splits, stream);
     if(e != hipSuccess || splits == 1) return e;
-    int64_t nb = (p.M * p.N + kThreads - 1) / kThreads;
-    nb         = nb > 65536 ? 65536 : nb;
+    const bool vec4 = p.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(p.C)) & 15) == 0;
+    int64_t    nb   = (p.M * p.N / (vec4 ? 4 : 1) + kThreads - 1) / kThreads;
+    nb              = nb > 65536 ? 65536 : nb;
+    auto reduce = [&](auto acc_tag, auto vec_tag, const void* ws, int32_t* dump) {
+        typedef decltype(acc_tag) acc_t;
+        splitk_reduce_kernel<acc_t, decltype(vec_tag)::value><<<dim3(nb), dim3(kThreads), 0, stream>>>(
+            static_cast<const acc_t*>(ws), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale, p.col_bias, dump);
+    };
     if(p.prec == 8)
-        splitk_reduce_kernel<int32_t><<<dim3(nb), dim3(kThreads), 0, stream>>>(
-            static_cast<const int32_t*>(workspace), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale,
-            p.col_bias, a.acc_dump);
+    {
+        if(vec4) reduce(int32_t{}, std::true_type{}, workspace, a.acc_dump);
+        else     reduce(int32_t{}, std::false_type{}, workspace, a.acc_dump);
+    }
     else
-        splitk_reduce_kernel<float><<<dim3(nb), dim3(kThreads), 0, stream>>>(
-            static_cast<const float*>(workspace), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale,
-            p.col_bias, nullptr);
+    {
+        if(vec4) reduce(float{}, std::true_type{}, workspace, nullptr);
+        else     reduce(float{}, std::false_type{}, workspace, nullptr);
+    }
     return hipGetLastError();
 }
 
