@@ -111,22 +111,44 @@ template <> __device__ __forceinline__ __half from_f32_out<__half>(float v) { re
 
 // One direct global->LDS load of 16 bytes per lane.  D selects the wavefront's D-th 1 KB slot
 // relative to the shared LDS base `lds_mid` (which points DPW/2 KB into the wavefront's slice).
+// The hardware adds the instruction's immediate offset to the LDS address and to the global
+// address alike.  The global address is formed as uniform base + 32-bit lane offset (scalar base
+// addressing), so the K loop spends no vector instructions on addresses: `sbase` is the
+// operand panel's address at this K tile minus kDmaBias, and `voff` already contains
+// + kDmaBias - IMM.
+constexpr int kDmaBias = 4096;
+template <int D, int DPW> constexpr int dma_imm() { return (D - DPW / 2) * 1024; }   // -4096 .. 3072
 template <int D, int DPW>
-__device__ __forceinline__ void dma_issue(const uint8_t* src, uint8_t* lds_mid)
+__device__ __forceinline__ void dma_issue(const uint8_t* sbase, uint32_t voff, uint8_t* lds_mid)
 {
-    constexpr int IMM = (D - DPW / 2) * 1024;      // 13-bit signed instruction offset: -4096 .. 3072
+    constexpr int IMM = dma_imm<D, DPW>();
     static_assert(IMM >= -4096 && IMM <= 4095, "immediate offset out of range");
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src - IMM),
+    asm volatile("" : "+v"(voff));      // keep the widening of the lane offset next to the load (scalar-base form)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(sbase + voff),
                                      (__attribute__((address_space(3))) void*)(lds_mid), 16, IMM, 0);
 }
 
 template <int DPW, int... Ds>
-__device__ __forceinline__ void dma_sequence(std::integer_sequence<int, Ds...>, const uint8_t* src0,
-                                             const uint32_t (&goff)[DPW], const int (&gchunk)[2], bool tail,
-                                             int64_t kb, int64_t Kb, uint8_t* lds_mid)
+__device__ __forceinline__ void dma_sequence(std::integer_sequence<int, Ds...>, const uint8_t* sbase,
+                                             const uint32_t (&voff)[DPW], uint8_t* lds_mid)
 {
-    // a chunk past the end of K (partial last tile) is fetched from the row's first chunk instead
-    (dma_issue<Ds, DPW>(src0 + (goff[Ds] - ((tail && kb + gchunk[Ds & 1] >= Kb) ? gchunk[Ds & 1] : 0)), lds_mid), ...);
+    (dma_issue<Ds, DPW>(sbase, voff[Ds], lds_mid), ...);
+}
+
+// Last, partial K tile: a chunk past the end of K is fetched from the row's first chunk instead
+// (and overwritten with zeros once landed).
+template <int DPW, int... Ds>
+__device__ __forceinline__ void dma_sequence_tail(std::integer_sequence<int, Ds...>, const uint8_t* sbase,
+                                                  const uint32_t (&voff)[DPW], const int (&gchunk)[2], int64_t kb,
+                                                  int64_t Kb, uint8_t* lds_mid)
+{
+    (dma_issue<Ds, DPW>(sbase, voff[Ds] - ((kb + gchunk[Ds & 1] >= Kb) ? gchunk[Ds & 1] : 0), lds_mid), ...);
+}
+
+template <int DPW, int... Ds>
+__device__ __forceinline__ void fill_dma_imms(int (&imm)[DPW], std::integer_sequence<int, Ds...>)
+{
+    ((imm[Ds] = dma_imm<Ds, DPW>()), ...);
 }
 
 __device__ __forceinline__ int swizzle(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) << 4; }
@@ -153,11 +175,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     const int     wave = __builtin_amdgcn_readfirstlane(tid / kWaveSize);     // wavefront index, held in an SGPR
     const int     wm = wave / WGN, wn = wave % WGN;
 
-    const int64_t ktiles_all = (p.Kb + kRowBytes - 1) / kRowBytes;
-    int64_t       kt_begin = 0, kt_end = ktiles_all;
+    // K-tile indices are 32-bit so that the loop control stays on the scalar unit
+    const int ktiles_all = static_cast<int>((p.Kb + kRowBytes - 1) / kRowBytes);
+    const int tail_kt    = (p.Kb % kRowBytes) ? ktiles_all - 1 : -1;     // index of a partial last tile, if any
+    int       kt_begin = 0, kt_end = ktiles_all;
     if(SPLIT)
     {
-        kt_begin = static_cast<int64_t>(blockIdx.y) * p.ktiles_per_split;
+        kt_begin = static_cast<int>(blockIdx.y) * p.ktiles_per_split;
         kt_end   = kt_begin + p.ktiles_per_split < ktiles_all ? kt_begin + p.ktiles_per_split : ktiles_all;
     }
 
@@ -175,36 +199,48 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     const bool     is_a      = wave * DPW < BM / 8;
     const uint8_t* gbase     = is_a ? p.A + m0 * p.Kb : p.B + n0 * p.Kb;
     const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
-    uint32_t       goff[DPW];
+    uint32_t       voff[DPW];                                         // lane offset + kDmaBias - immediate
     int            gchunk[2];                                         // the swizzle term depends on d%2 only
-#pragma unroll
-    for(int d = 0; d < DPW; ++d)
     {
-        const int srow  = (wave * DPW + d) * 8 + lane / 8;            // row inside the stage
-        const int chunk = (lane % 8) ^ ((srow >> 1) & 7);             // BM % 16 == 0: same term for A and B rows
-        int64_t   lrow  = srow - (is_a ? 0 : BM);
-        if(lrow >= rows_left) lrow = rows_left - 1;
-        goff[d] = static_cast<uint32_t>(lrow * p.Kb + chunk * 16);
-        if(d < 2) gchunk[d] = chunk * 16;
+        int imm[DPW];
+        fill_dma_imms<DPW>(imm, std::make_integer_sequence<int, DPW>{});
+#pragma unroll
+        for(int d = 0; d < DPW; ++d)
+        {
+            const int srow  = (wave * DPW + d) * 8 + lane / 8;            // row inside the stage
+            const int chunk = (lane % 8) ^ ((srow >> 1) & 7);             // BM % 16 == 0: same term for A and B rows
+            int64_t   lrow  = srow - (is_a ? 0 : BM);
+            if(lrow >= rows_left) lrow = rows_left - 1;
+            voff[d] = static_cast<uint32_t>(lrow * p.Kb + chunk * 16 + kDmaBias - imm[d]);
+            if(d < 2) gchunk[d] = chunk * 16;
+        }
     }
+    // the panel base as two scalar registers (the wavefront index is uniform, so is the choice of panel)
+    const uint64_t gbits = reinterpret_cast<uint64_t>(gbase) - kDmaBias;
+    // (the builtin returns a signed int: widen each half through uint32_t, never by sign extension)
+    const uint32_t glo    = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(gbits))));
+    const uint32_t ghi    = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(gbits >> 32))));
+    const uint8_t* sbase0 = reinterpret_cast<const uint8_t*>((static_cast<uint64_t>(ghi) << 32) | static_cast<uint64_t>(glo));
     // All DPW instructions of a wavefront share one LDS base (M0): instruction d reaches its 1 KB
-    // slot through the instruction's immediate offset (d - DPW/2) KB, which the hardware adds to
-    // the LDS address and to the global address alike, so the global address is biased by the
-    // opposite amount.  Rewriting M0 between direct loads would stall the wavefront until the
-    // previous load has left the issue queue (measured: +20 % GEMM throughput without it).
-    auto dma = [&](int stage, int64_t kt) {
-        const int64_t  kb    = kt * kRowBytes;
-        const bool     tail  = kb + kRowBytes > p.Kb;            // uniform; true for a partial last tile only
-        const uint8_t* src0  = gbase + kb;
+    // slot through the instruction's immediate offset (d - DPW/2) KB.  Rewriting M0 between direct
+    // loads would stall the wavefront until the previous load has left the issue queue
+    // (measured: +20 % GEMM throughput without it).
+    auto dma = [&](int stage, int kt) {
+        const int64_t  kb    = static_cast<int64_t>(kt) * kRowBytes;
         uint8_t*       lbase = lds + stage * STAGE_BYTES + wave * (DPW * 1024) + (DPW / 2) * 1024;
-        dma_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, src0, goff, gchunk, tail, kb, p.Kb, lbase);
+        const uint8_t* sb    = sbase0 + kb;
+        asm volatile("" : "+s"(sb));      // keep base + K offset a scalar pair: the lane offsets stay loop-invariant 32-bit values
+        if(kt == tail_kt)
+            dma_sequence_tail<DPW>(std::make_integer_sequence<int, DPW>{}, sb, voff, gchunk, kb, p.Kb, lbase);
+        else
+            dma_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, sb, voff, lbase);
     };
     // Waits for this wavefront's direct loads, zero-fills its out-of-K chunks, then joins the block.
-    auto land = [&](int stage, int64_t kt) {
+    auto land = [&](int stage, int kt) {
         __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
-        const int64_t kb = kt * kRowBytes;
-        if(kb + kRowBytes > p.Kb)
+        if(kt == tail_kt)
         {
+            const int64_t kb = static_cast<int64_t>(kt) * kRowBytes;
 #pragma unroll
             for(int d = 0; d < DPW; ++d)
                 if(kb + gchunk[d & 1] >= p.Kb)
@@ -263,9 +299,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         if(kt_begin + 1 < kt_end) dma(1, kt_begin + 1);
         load_frags(0, lds, 0);
         load_frags(1, lds, 1);
-        for(int64_t kt = kt_begin; kt < kt_end; ++kt)
+        for(int kt = kt_begin; kt < kt_end; ++kt)
         {
-            const int      stage = static_cast<int>(kt - kt_begin) & 1;
+            const int      stage = (kt - kt_begin) & 1;
             const bool     more  = kt + 1 < kt_end;
             const uint8_t* st    = lds + stage * STAGE_BYTES;
             mma(0);
