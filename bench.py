@@ -103,6 +103,9 @@ def main():
                     help="streams over which the workload's independent operators are spread in the timed region "
                          "(1 = one after the other, as a dependent training step would run them)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-overlap-pass", action="store_true",
+                    help="skip the extra pass with the operators on separate streams (keeps a profile of the run "
+                         "limited to the timed, serial region)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (known traffic) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled")
@@ -183,7 +186,7 @@ def main():
     # Extra (outside the timed region above): the same K steps with every operator on its own stream,
     # so that one operator's HBM-bound conversion kernels overlap the other's MFMA-bound GEMMs.
     overlapped = None
-    if len(ops_objs) > 1 and nstreams == 1:
+    if len(ops_objs) > 1 and nstreams == 1 and not args.no_overlap_pass:
         for _ in range(max(2, args.warmup)):
             step(False, len(ops_objs))
         torch.cuda.synchronize()

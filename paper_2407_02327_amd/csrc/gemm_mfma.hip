@@ -292,9 +292,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // operands are already in registers, and only then (4) requests the direct load of the tile
     // after next into the stage just drained and reads the first two chunks of the next tile:
     // barrier release and LDS latency hide behind chunk 3.
-    if(kt_begin < kt_end)
+    // Per-column epilogue parameters of this tile (alpha * column scale, column bias) are parked
+    // in LDS behind the stages while the first direct loads are in flight; the epilogue reads them
+    // back with a few 16-byte LDS reads instead of waiting on global memory.
+    float* colp = reinterpret_cast<float*>(lds + 2 * STAGE_BYTES);       // [2][BN]: scale, bias
+    float  alpha = 1.0f, cp_scale = 1.0f, cp_bias = 0.0f;
+    if(!SPLIT)
     {
-        dma(0, kt_begin);
+        if(p.s0) alpha *= *p.s0;
+        if(p.s1) alpha *= *p.s1;
+        const int64_t col = n0 + tid;
+        const bool    cok = tid < BN && col < p.N;
+        cp_scale = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
+        cp_bias  = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
+    }
+    const bool any_k = kt_begin < kt_end;
+    if(any_k) dma(0, kt_begin);
+    if(!SPLIT && tid < BN)
+    {
+        colp[tid]      = cp_scale;
+        colp[BN + tid] = cp_bias;
+    }
+    if(any_k)
+    {
         land(0, kt_begin);
         if(kt_begin + 1 < kt_end) dma(1, kt_begin + 1);
         load_frags(0, lds, 0);
@@ -332,7 +352,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // they are dequantized in registers first.
     constexpr int STG_BYTES = 2 * STAGE_BYTES / (WGM * WGN);
     uint8_t*      stg       = lds + wave * STG_BYTES;
-    float         alpha     = 1.0f;
     auto staged_store = [&](auto out_tag, auto raw_tag, uint8_t* dst_base) {
         typedef decltype(out_tag) out_t;
         constexpr bool RAW   = decltype(raw_tag)::value;
@@ -343,20 +362,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         constexpr int LPR   = WTN * OS / 16;                     // lanes per output row in the store phase
         constexpr int RPI   = 64 / LPR;                          // rows per store instruction
         float f[RAW ? 1 : FN][16], b[RAW ? 1 : FN][16];
+        __syncthreads();                                  // all wavefronts are done reading the stages
         if constexpr(!RAW)
         {
 #pragma unroll
             for(int j = 0; j < FN; ++j)
 #pragma unroll
-                for(int v = 0; v < 16; ++v)
+                for(int vq = 0; vq < 4; ++vq)
                 {
-                    const int64_t col = wcol0 + j * 32 + 8 * (v / 4) + 4 * khalf + (v % 4);
-                    const bool    cok = col < p.N;
-                    f[j][v] = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
-                    b[j][v] = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
+                    const int     c  = wn * WTN + j * 32 + 8 * vq + 4 * khalf;          // column inside the tile
+                    const float4  fs = *reinterpret_cast<const float4*>(colp + c);
+                    const float4  bs = *reinterpret_cast<const float4*>(colp + BN + c);
+                    f[j][vq * 4 + 0] = fs.x; f[j][vq * 4 + 1] = fs.y; f[j][vq * 4 + 2] = fs.z; f[j][vq * 4 + 3] = fs.w;
+                    b[j][vq * 4 + 0] = bs.x; b[j][vq * 4 + 1] = bs.y; b[j][vq * 4 + 2] = bs.z; b[j][vq * 4 + 3] = bs.w;
                 }
         }
-        __syncthreads();                                  // all wavefronts are done reading the stages
 #pragma unroll
         for(int pass = 0; pass < FM / FPP; ++pass)
         {
@@ -377,7 +397,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                                 o[e] = acc[i][j][vq * 4 + e];
                             else
                             {
-                                const float y = static_cast<float>(acc[i][j][vq * 4 + e]) * f[j][vq * 4 + e] + b[j][vq * 4 + e];
+                                const float y = fmaf(static_cast<float>(acc[i][j][vq * 4 + e]), f[j][vq * 4 + e], b[j][vq * 4 + e]);
                                 o[e] = from_f32_out<out_t>(y);
                             }
                         }
@@ -432,8 +452,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         return;
     }
 
-    if(p.s0) alpha *= *p.s0;
-    if(p.s1) alpha *= *p.s1;
     const int osize = p.c_is_f16 ? 2 : 4;
     const bool fast = !p.acc_dump && (p.N * osize) % 16 == 0 && (reinterpret_cast<uintptr_t>(p.C) & 15) == 0;
     if(!fast)
@@ -542,7 +560,7 @@ constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 template <typename TR, int BM, int BN, int WGM, int WGN>
 hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
 {
-    constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes;
+    constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float);
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
     const dim3       block(64 * WGM * WGN);
     static bool      attr_set[2] = {false, false};   // per instantiation; benign if set twice
