@@ -65,7 +65,8 @@ typedef enum {
 /*
  * qsync_absmax_scale - absolute maximum and symmetric fixed-point scale.
  * Paper: Backend section, "Minmax Optimization" (two-step reduction: block partials, then a
- * small second kernel); scale of the fixed-point quantizer x_bar = (x - z)/q with z = 0.
+ * small second step; here the last block to finish performs that step inside the same launch);
+ * scale of the fixed-point quantizer x_bar = (x - z)/q with z = 0.
  *
  *   amax  = max |x| over the tensor (PER_TENSOR), each row (PER_ROW) or each column (PER_COL)
  *   scale = amax / qmax,  inv_scale = qmax / amax,   qmax = 2^(bits-1) - 1   (one fp32 division each)
@@ -74,11 +75,16 @@ typedef enum {
  * x         [rows, ld] of xdt (QSYNC_F32 or QSYNC_F16), ld >= cols.
  * scale, inv_scale   out, 1 / rows / cols floats according to gran.  Both required.
  * amax_opt  out, same shape, may be NULL.
- * colsum_opt out, cols floats or NULL; PER_TENSOR only (QSYNC_ERR_UNSUPPORTED otherwise).  When
+ * colsum_opt out, cols floats or NULL; PER_TENSOR only and cols <= 2^19 (QSYNC_ERR_UNSUPPORTED otherwise).  When
  *           given, the same pass over x also produces colsum[c] = sum_r x[r,c] in fp32: for x = dY
  *           this is the bias gradient db (paper: Appendix, proof of Prop. 1, gradient of a linear
  *           operator), obtained without reading dY a third time.
  * workspace scratch of at least qsync_absmax_workspace_bytes(rows, cols, gran) bytes, 16-byte aligned.
+ *           PER_TENSOR: its first 256 bytes hold a block arrival counter: ZERO THEM ONCE after
+ *           allocating the buffer (hipMemset); every call that completes leaves them zero again, so
+ *           the buffer can be reused by later calls without clearing.  The rest needs no
+ *           initialisation.  Two calls that may run concurrently (different streams) need separate
+ *           workspaces.  A counter that is not zero yields an undefined scale (no fault).
  * bits      2..8.
  * Any alignment of x and ld is accepted (vector loads are used when x and ld*sizeof(elem)
  * are multiples of 16 bytes).

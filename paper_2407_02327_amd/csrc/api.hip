@@ -75,6 +75,7 @@ int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64
     if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
     if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
     if(colsum_opt && gran != QSYNC_PER_TENSOR) return QSYNC_ERR_UNSUPPORTED;
+    if(colsum_opt && cols > (int64_t(1) << 19)) return QSYNC_ERR_UNSUPPORTED;   // one block-maximum slot per column strip
     if(rows == 0 || cols == 0) return QSYNC_OK;
     const size_t need = qsync_absmax_workspace_bytes(rows, cols, gran);
     if(need > 0)
@@ -84,7 +85,7 @@ int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64
     }
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     return hip_status(launch_absmax_scale(x, xdt, rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt, colsum_opt,
-                                          static_cast<float*>(workspace), static_cast<hipStream_t>(stream)));
+                                          workspace, static_cast<hipStream_t>(stream)));
 }
 
 int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int tag, int bits, int gran,

@@ -70,14 +70,50 @@ template <> struct RunMax<__half>
     }
 };
 
+// ------------------------------------------------------------------ arrival counter
+// The per-tensor maximum finishes inside one launch: every block publishes its partial maximum,
+// then takes a ticket from an arrival counter; the block that draws the last ticket folds the
+// partials (a maximum: the result does not depend on which block that is) and resets the counter
+// to zero for the next launch.  The counter lives at the start of the caller's workspace, which
+// must be zero before its first use.  Tickets to one address cost about 10 ns each on this
+// part, so these kernels run few, large blocks (at most a few hundred).
+// Partials are written and read with device-scope atomic accesses (write-through stores, loads
+// that bypass the non-coherent cache levels), so no cache-wide flush is needed: a block waits
+// until its own partial store has completed, joins its barrier, and only then draws its ticket;
+// the last block reads the partials after its ticket has returned.
+__device__ __forceinline__ void st_partial(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_partial(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool last_arrival(unsigned int* ctr, unsigned int expected, bool* flag_lds)
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wavefront's partial stores have completed
+    __syncthreads();
+    if(threadIdx.x == 0)
+    {
+        const unsigned int t = atomicAdd(ctr, 1u);
+        *flag_lds            = (t == expected - 1u);
+    }
+    __syncthreads();
+    return *flag_lds;
+}
+
 // ------------------------------------------------------------------ absmax, per tensor
-// Stage 1: each block folds contiguous 32 KB pieces of the tensor into one partial maximum.
-template <typename T, bool VEC>
-__global__ __launch_bounds__(kBlock) void absmax_tensor_kernel(const T* __restrict__ x, int64_t rows,
-                                                               int64_t cols, int64_t ld,
-                                                               float* __restrict__ partial)
+// Each block folds contiguous pieces of the tensor (BLOCK * 8 sixteen-byte vectors each) into one
+// partial maximum; the last block to arrive folds the partials and writes amax, scale and
+// inverse scale.  With ctr == nullptr only the partials are written (a second launch folds them).
+template <typename T, bool VEC, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void absmax_tensor_kernel(const T* __restrict__ x, int64_t rows,
+                                                              int64_t cols, int64_t ld, float* partial,
+                                                              unsigned int* ctr, float qmax, float* scale,
+                                                              float* inv_scale, float* amax_opt)
 {
     __shared__ float lds[16];
+    __shared__ bool  flag;
     RunMax<T>        rm;
     const int64_t    n = rows * cols;
     if(VEC)
@@ -85,37 +121,47 @@ __global__ __launch_bounds__(kBlock) void absmax_tensor_kernel(const T* __restri
         constexpr int E    = Vec16<T>::N;
         constexpr int U    = 8;                       // 16-byte loads in flight per lane
         const int64_t nvec = n / E;
-        const int64_t step = static_cast<int64_t>(gridDim.x) * kBlock * U;
+        const int64_t step = static_cast<int64_t>(gridDim.x) * BLOCK * U;
         const uint4*  xv   = reinterpret_cast<const uint4*>(x);
-        for(int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock * U + threadIdx.x; c < nvec; c += step)
+        for(int64_t c = static_cast<int64_t>(blockIdx.x) * BLOCK * U + threadIdx.x; c < nvec; c += step)
         {
             uint4 v[U];
 #pragma unroll
             for(int u = 0; u < U; ++u)
             {
-                const int64_t idx = c + static_cast<int64_t>(u) * kBlock;
+                const int64_t idx = c + static_cast<int64_t>(u) * BLOCK;
                 v[u] = idx < nvec ? xv[idx] : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for(int u = 0; u < U; ++u) rm.add(v[u]);
         }
         if(blockIdx.x == 0)
-            for(int64_t j = nvec * E + threadIdx.x; j < n; j += kBlock) rm.add_scalar(x[j]);
+            for(int64_t j = nvec * E + threadIdx.x; j < n; j += BLOCK) rm.add_scalar(x[j]);
     }
     else
     {
-        const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
-        for(int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride)
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * BLOCK;
+        for(int64_t i = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x; i < n; i += stride)
         {
             const int64_t r = i / cols, c = i - r * cols;
             rm.add_scalar(x[r * ld + c]);
         }
     }
     const float m = block_reduce_max(rm.get(), lds);
-    if(threadIdx.x == 0) partial[blockIdx.x] = m;
+    if(threadIdx.x == 0) st_partial(partial + blockIdx.x, m);
+    if(!ctr) return;
+    if(!last_arrival(ctr, gridDim.x, &flag)) return;
+    float mm = 0.0f;
+    for(int i = threadIdx.x; i < static_cast<int>(gridDim.x); i += BLOCK) mm = fmaxf(mm, ld_partial(partial + i));
+    mm = block_reduce_max(mm, lds);
+    if(threadIdx.x == 0)
+    {
+        write_scale(mm, qmax, scale, inv_scale, amax_opt, 0);
+        *ctr = 0u;
+    }
 }
 
-// Stage 2: one block folds the partials and writes amax, scale and inverse scale.
+// Second launch of the two-launch form: one block folds the partials.
 __global__ __launch_bounds__(kBlock) void absmax_tensor_finalize_kernel(const float* __restrict__ partial, int n,
                                                                         float qmax, float* scale, float* inv_scale,
                                                                         float* amax_opt)
@@ -128,55 +174,85 @@ __global__ __launch_bounds__(kBlock) void absmax_tensor_finalize_kernel(const fl
 }
 
 // ------------------------------------------------------------------ absmax, per row
-// One wavefront per row, four 16-byte loads in flight per lane; no second stage.
-template <typename T, bool VEC>
+// WPR wavefronts per row (1 when there are many rows, 4 = the whole block when there are few),
+// four 16-byte loads in flight per lane; no second stage.
+template <typename T, bool VEC, int WPR>
 __global__ __launch_bounds__(kBlock) void absmax_rows_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                              int64_t ld, float qmax, float* scale, float* inv_scale,
                                                              float* amax_opt)
 {
-    const int     lane = threadIdx.x % kWaveSize;
-    const int64_t r    = static_cast<int64_t>(blockIdx.x) * (kBlock / kWaveSize) + threadIdx.x / kWaveSize;
-    if(r >= rows) return;
-    const T*  row  = x + r * ld;
-    RunMax<T> rm;
-    int64_t   done = 0;
-    if(VEC)
+    constexpr int RPB = kBlock / kWaveSize / WPR;       // rows per block
+    constexpr int TPR = WPR * kWaveSize;                // threads per row
+    __shared__ float lds[kBlock / kWaveSize];
+    const int     lane = threadIdx.x % kWaveSize, t = threadIdx.x % TPR;
+    const int64_t r    = static_cast<int64_t>(blockIdx.x) * RPB + threadIdx.x / TPR;
+    RunMax<T>     rm;
+    if(r < rows)
     {
-        constexpr int E    = Vec16<T>::N;
-        const int64_t nvec = cols / E;
-        const uint4*  rv   = reinterpret_cast<const uint4*>(row);
-        for(int64_t i = lane; i < nvec; i += 4 * kWaveSize)
+        const T* row  = x + r * ld;
+        int64_t  done = 0;
+        if(VEC)
         {
-            uint4 v[4];
+            constexpr int E    = Vec16<T>::N;
+            const int64_t nvec = cols / E;
+            const uint4*  rv   = reinterpret_cast<const uint4*>(row);
+            for(int64_t i = t; i < nvec; i += 4 * TPR)
+            {
+                uint4 v[4];
 #pragma unroll
-            for(int u = 0; u < 4; ++u) v[u] = i + u * kWaveSize < nvec ? rv[i + u * kWaveSize] : make_uint4(0, 0, 0, 0);
+                for(int u = 0; u < 4; ++u) v[u] = i + u * TPR < nvec ? rv[i + u * TPR] : make_uint4(0, 0, 0, 0);
 #pragma unroll
-            for(int u = 0; u < 4; ++u) rm.add(v[u]);
+                for(int u = 0; u < 4; ++u) rm.add(v[u]);
+            }
+            done = nvec * E;
         }
-        done = nvec * E;
+        for(int64_t c = done + t; c < cols; c += TPR) rm.add_scalar(row[c]);
     }
-    for(int64_t c = done + lane; c < cols; c += kWaveSize) rm.add_scalar(row[c]);
-    const float m = wave_reduce_max(rm.get());
-    if(lane == 0) write_scale(m, qmax, scale, inv_scale, amax_opt, r);
+    float m = wave_reduce_max(rm.get());
+    if(WPR > 1)
+    {
+        if(lane == 0) lds[threadIdx.x / kWaveSize] = m;
+        __syncthreads();
+        if(t == 0)
+        {
+            const int w0 = (threadIdx.x / TPR) * WPR;
+            for(int w = 1; w < WPR; ++w) m = fmaxf(m, lds[w0 + w]);
+        }
+    }
+    if(t == 0 && r < rows) write_scale(m, qmax, scale, inv_scale, amax_opt, r);
 }
 
 // ------------------------------------------------------------------ per-column reductions
-// Shared by the per-column absmax (OP_MAX) and the column sums of the bias gradient (OP_SUM).
-// Stage 1: block (bx, by) reduces rows by*rpb + tr, + gridDim.y*rpb, ... of a strip of columns.
-// Lanes own adjacent columns (one 16-byte vector each when VEC); the block's row lanes are
-// folded through LDS, so partial[by][c] holds one value per block row.
-enum { OP_MAX = 0, OP_SUM = 1, OP_SUMMAX = 2 };   // SUMMAX: column sums plus the tensor-wide max |x| in one pass
+// Shared by the per-column absmax (OP_MAX), the column sums of the bias gradient (OP_SUM) and
+// their fusion with the tensor-wide absmax (OP_SUMMAX: one pass yields both).
+// Stage 1: block (bx, by) reduces rows by*rpb + tr, + gridDim.y*rpb, ... of a strip of tpr*E
+// columns, four rows in flight per lane.  Lanes own adjacent columns (one 16-byte vector each
+// when VEC); the block's row lanes are folded through LDS, so partial[by][c] holds one value
+// per block row; a second launch folds those.  The tensor-wide maximum of OP_SUMMAX is folded
+// by the last block of the grid to arrive (ctr != nullptr).
+enum { OP_MAX = 0, OP_SUM = 1, OP_SUMMAX = 2 };
 
-template <typename T, bool VEC, int OP>
-__global__ __launch_bounds__(kBlock) void colreduce_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
-                                                           int64_t ld, int tpr, float* __restrict__ partial,
-                                                           float* __restrict__ partial_max)
+struct TensorFinal          // OP_SUMMAX: where the tensor-wide result goes
+{
+    unsigned int* ctr;      // arrival counter; nullptr: a second launch folds the block maxima
+    float         qmax;
+    float*        scale;
+    float*        inv_scale;
+    float*        amax_opt;
+};
+
+template <typename T, bool VEC, int OP, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void colreduce_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                          int64_t ld, int tpr, float* partial, float* partial_max,
+                                                          const TensorFinal fin)
 {
     constexpr int E = VEC ? Vec16<T>::N : 1;
-    __shared__ float lds[kBlock * E];
+    constexpr int U = 4;                                    // rows in flight per lane
+    __shared__ float lds[BLOCK * E];
     __shared__ float lds_max[16];
+    __shared__ bool  flag;
     RunMax<T>        rm;                                    // OP_SUMMAX only
-    const int     rpb = kBlock / tpr;                       // row lanes per block
+    const int     rpb = BLOCK / tpr;                       // row lanes per block
     const int     tc = threadIdx.x % tpr, tr = threadIdx.x / tpr;
     const int64_t c0  = (static_cast<int64_t>(blockIdx.x) * tpr + tc) * E;
     const int64_t S   = static_cast<int64_t>(gridDim.y) * rpb;
@@ -187,31 +263,49 @@ __global__ __launch_bounds__(kBlock) void colreduce_kernel(const T* __restrict__
     for(int e = 0; e < E; ++e) acc[e] = 0.0f;
     if(c0 < cols)
     {
-        for(int64_t r = static_cast<int64_t>(blockIdx.y) * rpb + tr; r < rows; r += S)
+        for(int64_t r = static_cast<int64_t>(blockIdx.y) * rpb + tr; r < rows; r += S * U)
         {
             if(VEC)
             {
-                const uint4 raw = *reinterpret_cast<const uint4*>(x + r * ld + c0);
-                if(kPacked)
-                {
-                    pk[0] = pk_absmax_u16(pk[0], raw.x); pk[1] = pk_absmax_u16(pk[1], raw.y);
-                    pk[2] = pk_absmax_u16(pk[2], raw.z); pk[3] = pk_absmax_u16(pk[3], raw.w);
-                }
-                else
-                {
-                    float v[Vec16<T>::N];
-                    Vec16<T>::decode(raw, v);
+                uint4 raw[U];
 #pragma unroll
-                    for(int e = 0; e < E; ++e) acc[e] = OP == OP_MAX ? fmaxf(acc[e], fabsf(v[e])) : fmaf(v[e], 1.0f, acc[e]);
-                    if(OP == OP_SUMMAX) rm.add(raw);
+                for(int u = 0; u < U; ++u)
+                {
+                    const int64_t rr = r + u * S;        // rows past the end contribute zeros (neutral for sum and max)
+                    raw[u] = rr < rows ? *reinterpret_cast<const uint4*>(x + rr * ld + c0) : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for(int u = 0; u < U; ++u)
+                {
+                    if(kPacked)
+                    {
+                        pk[0] = pk_absmax_u16(pk[0], raw[u].x); pk[1] = pk_absmax_u16(pk[1], raw[u].y);
+                        pk[2] = pk_absmax_u16(pk[2], raw[u].z); pk[3] = pk_absmax_u16(pk[3], raw[u].w);
+                    }
+                    else
+                    {
+                        float v[Vec16<T>::N];
+                        Vec16<T>::decode(raw[u], v);
+#pragma unroll
+                        for(int e = 0; e < E; ++e) acc[e] = OP == OP_MAX ? fmaxf(acc[e], fabsf(v[e])) : acc[e] + v[e];
+                        if(OP == OP_SUMMAX) rm.add(raw[u]);
+                    }
                 }
             }
             else
             {
-                const T     xv = x[r * ld + c0];
-                const float v  = to_f32(xv);
-                acc[0] = OP == OP_MAX ? fmaxf(acc[0], fabsf(v)) : acc[0] + v;
-                if(OP == OP_SUMMAX) rm.add_scalar(xv);
+#pragma unroll
+                for(int u = 0; u < U; ++u)
+                {
+                    const int64_t rr = r + u * S;
+                    if(rr < rows)
+                    {
+                        const T     xv = x[rr * ld + c0];
+                        const float v  = to_f32(xv);
+                        acc[0] = OP == OP_MAX ? fmaxf(acc[0], fabsf(v)) : acc[0] + v;
+                        if(OP == OP_SUMMAX) rm.add_scalar(xv);
+                    }
+                }
             }
         }
     }
@@ -223,27 +317,47 @@ __global__ __launch_bounds__(kBlock) void colreduce_kernel(const T* __restrict__
     if(OP == OP_SUMMAX)
     {   // every thread of the block takes part (threads beyond the last column carry 0)
         const float bm = block_reduce_max(rm.get(), lds_max);
-        if(threadIdx.x == 0) partial_max[blockIdx.y * gridDim.x + blockIdx.x] = bm;
+        if(threadIdx.x == 0) st_partial(partial_max + blockIdx.y * gridDim.x + blockIdx.x, bm);
     }
+    // fold the block's row lanes in order 0, 1, ... through LDS
+    auto fold_rows = [&]() {
 #pragma unroll
-    for(int e = 0; e < E; ++e) lds[(tr * tpr + tc) * E + e] = acc[e];
-    __syncthreads();
+        for(int e = 0; e < E; ++e) lds[(tr * tpr + tc) * E + e] = acc[e];
+        __syncthreads();
+        if(tr == 0)
+            for(int q = 1; q < rpb; ++q)
+#pragma unroll
+                for(int e = 0; e < E; ++e)
+                {
+                    const float o = lds[(q * tpr + tc) * E + e];
+                    acc[e] = OP == OP_MAX ? fmaxf(acc[e], o) : acc[e] + o;
+                }
+    };
+    fold_rows();
     if(tr == 0 && c0 < cols)
     {
-        for(int q = 1; q < rpb; ++q)
-#pragma unroll
-            for(int e = 0; e < E; ++e)
-            {
-                const float o = lds[(q * tpr + tc) * E + e];
-                acc[e] = OP == OP_MAX ? fmaxf(acc[e], o) : acc[e] + o;
-            }
 #pragma unroll
         for(int e = 0; e < E; ++e) partial[static_cast<int64_t>(blockIdx.y) * cols + c0 + e] = acc[e];
     }
+    if(OP != OP_SUMMAX || !fin.ctr) return;
+
+    // ---- tensor-wide maximum: the last block of the whole grid
+    const unsigned int nblocks = gridDim.x * gridDim.y;
+    if(last_arrival(fin.ctr, nblocks, &flag))
+    {
+        float mm = 0.0f;
+        for(unsigned int i = threadIdx.x; i < nblocks; i += BLOCK) mm = fmaxf(mm, ld_partial(partial_max + i));
+        mm = block_reduce_max(mm, lds_max);
+        if(threadIdx.x == 0)
+        {
+            write_scale(mm, fin.qmax, fin.scale, fin.inv_scale, fin.amax_opt, 0);
+            *fin.ctr = 0u;
+        }
+    }
 }
 
-// Stage 2: 16 columns per block; sixteen threads per column fold a sixteenth of the partials
-// each (fixed assignment, fixed order), then the sixteen are folded in order.
+// Second launch of the two-launch form: 16 columns per block; sixteen threads per column fold a
+// sixteenth of the partials each (fixed assignment, fixed order), then the sixteen are folded in order.
 template <int OP>
 __global__ __launch_bounds__(kBlock) void colreduce_finalize_kernel(const float* __restrict__ partial, int S,
                                                                     int64_t cols, float qmax, float* out,
@@ -529,15 +643,20 @@ int next_pow2(int64_t v)
     return p;
 }
 
-// Launch shape of a per-column reduction: threads per row (power of two) and block rows
-// (gridDim.y, at most kColParts), aiming at about five hundred blocks.
-void colreduce_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
+// Launch shape of a per-column reduction with `block` threads per block: threads per row (a power
+// of two, at most one wavefront so that a wavefront reads 1 KB of a row) and block rows
+// (gridDim.y, at most kColParts).  Large inputs run 1024-thread blocks, about one per compute
+// unit: sixteen wavefronts with four loads in flight each keep the memory pipeline full, and a
+// strip then has few enough partials for one block to fold them.
+void colreduce_shape(int64_t rows, int64_t cols, int E, int block, int& tpr, int& gy)
 {
     const int64_t ncv = (cols + E - 1) / E;
-    tpr               = ncv >= kBlock ? kBlock : (next_pow2(ncv) < 2 ? 2 : next_pow2(ncv));
+    tpr               = ncv >= kWaveSize ? kWaveSize : (next_pow2(ncv) < 2 ? 2 : next_pow2(ncv));
+    if(ncv > static_cast<int64_t>(kWaveSize) * 1000) tpr = kBlock;     // very wide: keep the strip count small
     const int64_t gx  = (ncv + tpr - 1) / tpr;
-    const int     rpb = kBlock / tpr;
-    int64_t       g   = (512 + gx - 1) / gx;
+    const int     rpb = block / tpr;
+    const int64_t target = block >= 1024 ? 256 : 1024;
+    int64_t       g   = (target + gx - 1) / gx;
     const int64_t maxg = (rows + rpb - 1) / rpb;              // no more block rows than row groups
     if(g > maxg) g = maxg;
     if(g > kColParts) g = kColParts;
@@ -545,22 +664,44 @@ void colreduce_shape(int64_t rows, int64_t cols, int E, int& tpr, int& gy)
     gy = static_cast<int>(g);
 }
 
+// Workspace of the per-tensor reductions: the arrival counter first (a 256-byte slot), partials behind it.
+constexpr size_t kCtrBytes = 256;
+
 template <typename T, int OP>
 hipError_t colreduce_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, float qmax, float* out,
-                            float* inv_scale, float* amax_opt, float* ws, hipStream_t st)
+                            float* inv_scale, float* amax_opt, float* partial, float* partial_max, TensorFinal tfin,
+                            hipStream_t st)
 {
-    constexpr int E   = Vec16<T>::N;
-    const bool    vec = aligned16(x) && (ld * sizeof(T)) % 16 == 0 && cols % E == 0;
+    constexpr int E     = Vec16<T>::N;
+    const bool    vec   = aligned16(x) && (ld * sizeof(T)) % 16 == 0 && cols % E == 0;
+    const int     block = rows * cols >= (int64_t(1) << 20) ? 1024 : kBlock;
     int           tpr, gy;
-    colreduce_shape(rows, cols, vec ? E : 1, tpr, gy);
+    colreduce_shape(rows, cols, vec ? E : 1, block, tpr, gy);
     const int64_t ncv = (cols + (vec ? E : 1) - 1) / (vec ? E : 1);
-    const dim3    grid(static_cast<unsigned>((ncv + tpr - 1) / tpr), static_cast<unsigned>(gy));
+    const int64_t gx  = (ncv + tpr - 1) / tpr;
+    if(partial_max)
+        while(gx * gy > kAbsmaxMaxBlocks && gy > 1) gy = (gy + 1) / 2;  // block maxima must fit their slots
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy));
     if(vec)
-        colreduce_kernel<T, true, OP><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws, nullptr);
+    {
+        if(block == 1024)
+            colreduce_kernel<T, true, OP, 1024><<<grid, dim3(1024), 0, st>>>(x, rows, cols, ld, tpr, partial, partial_max, tfin);
+        else
+            colreduce_kernel<T, true, OP, kBlock><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, partial, partial_max, tfin);
+    }
     else
-        colreduce_kernel<T, false, OP><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws, nullptr);
-    colreduce_finalize_kernel<OP><<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(ws, gy, cols, qmax, out, inv_scale,
-                                                                               amax_opt);
+    {
+        if(block == 1024)
+            colreduce_kernel<T, false, OP, 1024><<<grid, dim3(1024), 0, st>>>(x, rows, cols, ld, tpr, partial, partial_max, tfin);
+        else
+            colreduce_kernel<T, false, OP, kBlock><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, partial, partial_max, tfin);
+    }
+    constexpr int FOP = OP == OP_MAX ? OP_MAX : OP_SUM;
+    colreduce_finalize_kernel<FOP><<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy, cols, qmax, out, inv_scale,
+                                                                                amax_opt);
+    if(OP == OP_SUMMAX && !tfin.ctr)
+        absmax_tensor_finalize_kernel<<<dim3(1), dim3(kBlock), 0, st>>>(partial_max, static_cast<int>(gx * gy), tfin.qmax,
+                                                                        tfin.scale, tfin.inv_scale, tfin.amax_opt);
     return hipGetLastError();
 }
 
@@ -570,77 +711,82 @@ hipError_t colreduce_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, 
 size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran)
 {
     (void)rows;
-    if(gran == kPerTensor)   // block maxima; with fused column sums also the per-column partial sums
-        return sizeof(float) * (kAbsmaxMaxBlocks + static_cast<size_t>(kColParts) * static_cast<size_t>(cols > 0 ? cols : 0));
-    if(gran == kPerCol) return sizeof(float) * kColParts * static_cast<size_t>(cols > 0 ? cols : 0);
+    const size_t c = static_cast<size_t>(cols > 0 ? cols : 0);
+    if(gran == kPerTensor)   // counter, block maxima; with fused column sums also the per-column partial sums
+        return kCtrBytes + sizeof(float) * (kAbsmaxMaxBlocks + static_cast<size_t>(kColParts) * c);
+    if(gran == kPerCol) return kCtrBytes + sizeof(float) * kColParts * c;   // same layout: the counter slot stays untouched
     return 0;
-}
-
-// Per-tensor absmax fused with column sums: one pass over x.
-template <typename T>
-static hipError_t absmax_colsum_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, float qmax, float* scale,
-                                       float* inv_scale, float* amax_opt, float* colsum, float* ws, hipStream_t st)
-{
-    constexpr int E   = Vec16<T>::N;
-    const bool    vec = aligned16(x) && (ld * sizeof(T)) % 16 == 0 && cols % E == 0;
-    int           tpr, gy;
-    colreduce_shape(rows, cols, vec ? E : 1, tpr, gy);
-    const int64_t ncv = (cols + (vec ? E : 1) - 1) / (vec ? E : 1);
-    int64_t       gx  = (ncv + tpr - 1) / tpr;
-    while(gx * gy > kAbsmaxMaxBlocks && gy > 1) gy = (gy + 1) / 2;      // block maxima must fit their slots
-    float* ws_max = ws;                                                   // [kAbsmaxMaxBlocks]
-    float* ws_sum = ws + kAbsmaxMaxBlocks;                                // [gy][cols]
-    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy));
-    if(vec)
-        colreduce_kernel<T, true, OP_SUMMAX><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws_sum, ws_max);
-    else
-        colreduce_kernel<T, false, OP_SUMMAX><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, tpr, ws_sum, ws_max);
-    colreduce_finalize_kernel<OP_SUM><<<dim3((cols + 15) / 16), dim3(kBlock), 0, st>>>(ws_sum, gy, cols, 0.0f, colsum,
-                                                                                   nullptr, nullptr);
-    absmax_tensor_finalize_kernel<<<dim3(1), dim3(kBlock), 0, st>>>(ws_max, static_cast<int>(gx * gy), qmax, scale,
-                                                                    inv_scale, amax_opt);
-    return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax, float* scale,
-                               float* inv_scale, float* amax_opt, float* colsum_opt, float* ws, hipStream_t st)
+                               float* inv_scale, float* amax_opt, float* colsum_opt, void* workspace, hipStream_t st)
 {
-    if(gran == kPerTensor && colsum_opt)
-        return absmax_colsum_launch(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt, colsum_opt, ws, st);
     constexpr int E       = Vec16<T>::N;
     const bool    rows_ok = aligned16(x) && (ld * sizeof(T)) % 16 == 0;
     (void)E;
     if(gran == kPerTensor)
     {
+        unsigned int* ctr = static_cast<unsigned int*>(workspace);
+        float*        ws  = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes);
+        if(colsum_opt)
+        {   // per-tensor absmax fused with column sums: one pass over x
+            TensorFinal tfin{ctr, qmax, scale, inv_scale, amax_opt};
+            return colreduce_launch<T, OP_SUMMAX>(x, rows, cols, ld, 0.0f, colsum_opt, nullptr, nullptr,
+                                                  ws + kAbsmaxMaxBlocks, ws, tfin, st);
+        }
         const bool    vec  = aligned16(x) && ld == cols;
         const int64_t work = vec ? (rows * cols) / E : rows * cols;
-        int64_t       nb   = (work + kBlock * 8 - 1) / (kBlock * 8);
-        nb                 = nb < 1 ? 1 : (nb > kAbsmaxMaxBlocks ? kAbsmaxMaxBlocks : nb);
+        const bool    big  = work >= (int64_t(1) << 19);
+        const int     blk  = big ? 1024 : kBlock;
+        int64_t       nb   = (work + blk * 8 - 1) / (blk * 8);
+        nb                 = nb < 1 ? 1 : (nb > 256 ? 256 : nb);       // few blocks: the tickets are serialised
         if(vec)
-            absmax_tensor_kernel<T, true><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws);
+        {
+            if(big)
+                absmax_tensor_kernel<T, true, 1024><<<dim3(nb), dim3(1024), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+            else
+                absmax_tensor_kernel<T, true, kBlock><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+        }
         else
-            absmax_tensor_kernel<T, false><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws);
-        absmax_tensor_finalize_kernel<<<dim3(1), dim3(kBlock), 0, st>>>(ws, static_cast<int>(nb), qmax, scale,
-                                                                        inv_scale, amax_opt);
+        {
+            if(big)
+                absmax_tensor_kernel<T, false, 1024><<<dim3(nb), dim3(1024), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+            else
+                absmax_tensor_kernel<T, false, kBlock><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+        }
     }
     else if(gran == kPerRow)
     {
-        const int64_t nb = (rows + 3) / 4;
+        const bool few = rows < 4096;         // too few rows to fill the chip with one wavefront per row
+        const int64_t nb = few ? rows : (rows + 3) / 4;
         if(rows_ok)
-            absmax_rows_kernel<T, true><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, scale, inv_scale,
-                                                                          amax_opt);
+        {
+            if(few)
+                absmax_rows_kernel<T, true, 4><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt);
+            else
+                absmax_rows_kernel<T, true, 1><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt);
+        }
         else
-            absmax_rows_kernel<T, false><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, scale, inv_scale,
-                                                                           amax_opt);
+        {
+            if(few)
+                absmax_rows_kernel<T, false, 4><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt);
+            else
+                absmax_rows_kernel<T, false, 1><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt);
+        }
     }
     else
-        return colreduce_launch<T, OP_MAX>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt, ws, st);
+    {
+        TensorFinal none{nullptr, qmax, nullptr, nullptr, nullptr};
+        return colreduce_launch<T, OP_MAX>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt,
+                                           reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes), nullptr,
+                                           none, st);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax,
-                               float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, float* workspace,
+                               float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, void* workspace,
                                hipStream_t stream)
 {
     if(xdt == kF32)
@@ -770,11 +916,12 @@ size_t colsum_workspace_bytes(int64_t rows, int64_t cols)
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream)
 {
+    TensorFinal none{nullptr, 0.0f, nullptr, nullptr, nullptr};
     if(xdt == kF32)
         return colreduce_launch<float, OP_SUM>(static_cast<const float*>(x), rows, cols, cols, 0.0f, out, nullptr, nullptr,
-                                               workspace, stream);
+                                               workspace, nullptr, none, stream);
     return colreduce_launch<__half, OP_SUM>(static_cast<const __half*>(x), rows, cols, cols, 0.0f, out, nullptr, nullptr,
-                                            workspace, stream);
+                                            workspace, nullptr, none, stream);
 }
 
 }  // namespace qsync

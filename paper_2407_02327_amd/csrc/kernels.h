@@ -18,7 +18,8 @@ constexpr int kColParts = 512;          // most stage-1 partials per column of a
 size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran,
                                float qmax, float* scale, float* inv_scale, float* amax_opt,
-                               float* colsum_opt /* per-tensor only: fused column sums */, float* workspace,
+                               float* colsum_opt /* per-tensor only: fused column sums */,
+                               void* workspace /* zero before first use; left zero where it must be */,
                                hipStream_t stream);
 
 // ---- quantize / cast / copy (+ transpose) ---------------------------------------------

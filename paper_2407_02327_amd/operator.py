@@ -26,7 +26,8 @@ _TORCH_OF_TAG = {Q.INT8: torch.int8, Q.FP16: torch.float16, Q.FP32: torch.float3
 
 
 def _ws(nbytes: int, device) -> Optional[torch.Tensor]:
-    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    # zero-filled once: qsync_absmax_scale keeps block arrival counters at the start of its workspace
+    return torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
 class QLinear:

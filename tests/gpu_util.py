@@ -30,7 +30,8 @@ def empty(shape, dtype):
 
 
 def ws(nbytes: int):
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+    """Workspace for a C-ABI call: zero-filled once, as qsync_absmax_scale requires of its counters."""
+    return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
 
 
 def assert_bits_equal(got: np.ndarray, want: np.ndarray, what: str):

@@ -92,6 +92,51 @@ def test_absmax_fused_with_column_sums(dtype):
     assert e.value.status == Q.ERR_UNSUPPORTED
 
 
+def test_absmax_workspace_is_reusable_without_clearing():
+    """The arrival counters at the start of the workspace are zeroed once by the caller and left zero
+    by every call: one buffer serves a sequence of different reductions, each checked against the oracle."""
+    rng = np.random.default_rng(11)
+    shapes = [(4096, 4096), (64, 128), (16384, 1024), (257, 1000), (8192, 72), (33, 8200), (3, 5), (4096, 4096)]
+    nbytes = max(max(Q.qsync_absmax_workspace_bytes(r, c, Q.PER_TENSOR), Q.qsync_absmax_workspace_bytes(r, c, Q.PER_COL))
+                 for r, c in shapes)
+    w = ws(nbytes)
+    for rep, (rows, cols) in enumerate(shapes):
+        dtype = np.float16 if rep % 2 == 0 else np.float32
+        x = _data(rng, (rows, cols), dtype, 0.5)
+        xd = dev(x)
+        for gran, with_sums in (("tensor", False), ("col", False), ("tensor", True)):
+            say("absmax reuse", rows, cols, dtype.__name__, gran, with_sums)
+            n = 1 if gran == "tensor" else cols
+            sc, iv, am = empty(n, torch.float32), empty(n, torch.float32), empty(n, torch.float32)
+            cs = empty(cols, torch.float32) if with_sums else None
+            Q.qsync_absmax_scale(xd, rows, cols, cols, GRAN[gran], 8, sc, iv, am, cs, w)
+            amax = orc.absmax(x, gran)
+            so, io = orc.scales_from_amax(amax)
+            assert_bits_equal(host(am), amax, "amax")
+            assert_bits_equal(host(sc), so, "scale")
+            assert_bits_equal(host(iv), io, "inv_scale")
+            if with_sums:
+                assert_close(host(cs), x.astype(np.float64).sum(axis=0), "column sums")
+    assert int(w[:256].to(torch.int32).abs().sum().item()) == 0, "the arrival counter must be left at zero"
+
+
+def test_absmax_column_sums_are_reproducible():
+    """The in-kernel fold uses a fixed assignment and order: two runs give identical bits."""
+    rng = np.random.default_rng(12)
+    rows, cols = 16384, 4096
+    xd = dev(_data(rng, (rows, cols), np.float16, 1e-2))
+    w = ws(Q.qsync_absmax_workspace_bytes(rows, cols, Q.PER_TENSOR))
+    outs = []
+    for _ in range(3):
+        sc, iv, am, cs = (empty(1, torch.float32), empty(1, torch.float32), empty(1, torch.float32),
+                          empty(cols, torch.float32))
+        Q.qsync_absmax_scale(xd, rows, cols, cols, Q.PER_TENSOR, 8, sc, iv, am, cs, w)
+        outs.append((host(cs).copy(), host(sc).copy()))
+    for cs, sc in outs[1:]:
+        assert_bits_equal(cs, outs[0][0], "column sums, repeated run")
+        assert_bits_equal(sc, outs[0][1], "scale, repeated run")
+
+
 def _gpu_quantize(xd, rows, cols, ld, tag, gran, rnd, seed, offset, inv, want_q=True, want_t=True, bits=8):
     dt = {Q.INT8: torch.int8, Q.FP16: torch.float16, Q.FP32: torch.float32}[tag]
     q = empty((rows, cols), dt) if want_q else None
