@@ -103,9 +103,12 @@ def main():
                     help="streams over which the workload's independent operators are spread in the timed region "
                          "(1 = one after the other, as a dependent training step would run them)")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--no-overlap-pass", action="store_true",
-                    help="skip the extra pass with the operators on separate streams (keeps a profile of the run "
-                         "limited to the timed, serial region)")
+    ap.add_argument("--no-extra-passes", action="store_true",
+                    help="skip the passes that follow the timed region (per-phase breakdown, operators on separate "
+                         "streams): keeps a profile of the run limited to the timed, serial region")
+    ap.add_argument("--w-side-stream", type=int, default=0,
+                    help="1: an operator's weight conversion runs on a side stream beside its activation conversion "
+                         "(measured: the cross-stream join costs about what the overlap saves)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (known traffic) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled")
@@ -147,16 +150,24 @@ def main():
     op_streams = [main] + [torch.cuda.Stream() for _ in range(len(ops_objs) - 1)]
     side_streams = [torch.cuda.Stream() for _ in ops_objs]
 
-    def step(record: bool, nstreams=nstreams):
-        run = ev.run if record else (lambda name, fn, st: fn())
+    def step(record: str, nstreams=nstreams):
+        """record: "none", "gemm_fwd" (events around the forward GEMM only: the timed region) or "all"."""
+        def run(name, fn, st):
+            if record == "all" or record == name:
+                ev.run(name, fn, st)
+            else:
+                fn()
         for st in op_streams[1:nstreams]:
             st.wait_stream(main)
         for i, (op, (x, w, dy)) in enumerate(zip(ops_objs, dev_in)):
             st, side = op_streams[i % nstreams], side_streams[i]
-            side.wait_stream(st)
-            op.convert_w(w, side)
-            run("convert_x", lambda: op.convert_x(x, st), st)
-            st.wait_stream(side)
+            if args.w_side_stream:
+                side.wait_stream(st)
+                op.convert_w(w, side)
+                run("convert_x", lambda: op.convert_x(x, st), st)
+                st.wait_stream(side)
+            else:
+                run("convert_x", lambda: (op.convert_w(w, st), op.convert_x(x, st)), st)
             run("gemm_fwd", lambda: op.gemm_fwd(st), st)
             run("convert_dy", lambda: op.convert_dy(dy, st), st)
             run("gemm_bwd", lambda: op.gemm_bwd(dy, st), st)
@@ -170,15 +181,18 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Timed region: K whole steps; HIP events bracket only the forward GEMM launches (the dominant
+    # kernel of the roofline figure), because every event pair costs the stream a few microseconds.
     for _ in range(args.warmup):
-        step(False)
+        step("none")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(True)
+        step("gemm_fwd")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
+    fwd_ms = ev.totals()["gemm_fwd"][0] / args.steps
 
     gemm_ops = sum(6 * c.mnk[0] * c.mnk[1] * c.mnk[2] for c in cases)          # three GEMMs, 2MNK each
     value = gemm_ops / (ms_per_step * 1e-3) / 1e12
@@ -186,29 +200,36 @@ def main():
     # Extra (outside the timed region above): the same K steps with every operator on its own stream,
     # so that one operator's HBM-bound conversion kernels overlap the other's MFMA-bound GEMMs.
     overlapped = None
-    if len(ops_objs) > 1 and nstreams == 1 and not args.no_overlap_pass:
+    if len(ops_objs) > 1 and nstreams == 1 and not args.no_extra_passes:
         for _ in range(max(2, args.warmup)):
-            step(False, len(ops_objs))
+            step("none", len(ops_objs))
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for _ in range(args.steps):
-            step(False, len(ops_objs))
+            step("none", len(ops_objs))
         torch.cuda.synchronize()
         ms2 = (time.perf_counter() - t1) * 1e3 / args.steps
         overlapped = {"operator_streams": len(ops_objs), "ms_per_step": round(ms2, 4),
                       "value": round(gemm_ops / (ms2 * 1e-3) / 1e12, 3), "unit": "TOPS"}
-    tot = ev.totals()
-    per_step = {k: v[0] / args.steps for k, v in tot.items()}                     # ms per step per class
+    # Extra (outside the timed region): a fully instrumented pass for the per-phase breakdown.
+    per_step = {"gemm_fwd": fwd_ms}
+    if not args.no_extra_passes:
+        ev2 = EventLog()
+        ev, ev_timed = ev2, ev
+        for _ in range(args.steps):
+            step("all")
+        torch.cuda.synchronize()
+        per_step = {k: v[0] / args.steps for k, v in ev2.totals().items()}        # ms per step per class
+        ev = ev_timed
     # dominant kernel: the MFMA GEMM.  gemm_bwd also holds the bias-gradient column sum, so the
     # roofline figure uses the forward GEMM launches alone (one launch per operator per step).
     fwd_ops = sum(2 * c.mnk[0] * c.mnk[1] * c.mnk[2] for c in cases)
-    fwd_ms = per_step["gemm_fwd"]
     achieved = fwd_ops / (fwd_ms * 1e-3) / 1e12
     peak = PEAK[args.tag]
     # HBM-bound side: absmax + quantize of dY (read twice, write codes + transposed codes)
     esz = cases[0].dy.dtype.itemsize
     dy_bytes = sum(c.dy.size * (2 * esz + 2) for c in cases)
-    quant_gbs = dy_bytes / (per_step["convert_dy"] * 1e-3) / 1e9
+    quant_gbs = dy_bytes / (per_step["convert_dy"] * 1e-3) / 1e9 if "convert_dy" in per_step else None
 
     out = {
         "metric": "qlinear fwd+bwd TOPS (whole step incl. absmax/quantize/dequantize)",
@@ -226,13 +247,15 @@ def main():
                                                   + c.mnk[0] * c.mnk[1] * (2 if args.ydtype == "f16" else 4)
                                                   for c in cases) / len(cases))},
         "breakdown_ms_per_step": {k: round(v, 4) for k, v in per_step.items()},
-        "breakdown_note": f"event times on each operator's stream, {nstreams} operator stream(s) run concurrently; "
-                          "the weight conversion runs on a side stream beside convert_x",
-        "quantize_dy": {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
+        "breakdown_note": "separate pass after the timed region with events around every phase (the events "
+                          "themselves lengthen that pass); convert_x includes the weight conversion",
+        "quantize_dy": None if quant_gbs is None else
+                       {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
                         "bytes": "absmax read + quantize read + codes + transposed codes"},
         "operators_on_separate_streams": overlapped,
-        "gemm_only_TOPS": round(gemm_ops / ((per_step["gemm_fwd"] + per_step["gemm_bwd"]) * 1e-3) / 1e12, 2),
     }
+    if "gemm_bwd" in per_step:
+        out["gemm_only_TOPS"] = round(gemm_ops / ((per_step["gemm_fwd"] + per_step["gemm_bwd"]) * 1e-3) / 1e12, 2)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(cases, tag, args.cpu_tokens)
