@@ -24,8 +24,8 @@ PEAK = {"int8": 5000.0, "fp16": 2500.0}          # dense MFMA peak of MI355X, TO
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per forward-GEMM launch (mean of the two forward launches of config 5, INT8, fp16 output),
 # from rocprofv3 --pmc FETCH_SIZE (x2.0) and WRITE_SIZE (x1.0), scaled by a plain 512 MiB copy:
-# see profiles/config5_int8_hbm_traffic.md.  (96.4 + 128.0 + 96.3 + 32.0) MiB / 2.
-MEASURED_FWD_GEMM_TRAFFIC_BYTES = {("c5", "int8", "f16"): int((96.4 + 128.0 + 96.3 + 32.0) / 2 * 2**20)}
+# see profiles/config5_int8_hbm_traffic.md.  (54.4 + 128.4 + 96.2 + 32.0) MiB / 2.
+MEASURED_FWD_GEMM_TRAFFIC_BYTES = {("c5", "int8", "f16"): int((54.4 + 128.4 + 96.2 + 32.0) / 2 * 2**20)}
 
 
 def log(*a):

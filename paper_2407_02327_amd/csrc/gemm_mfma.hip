@@ -90,13 +90,19 @@ struct GemmKernelArgs
     int            tiles_m, tiles_n;
 };
 
-// Logical tile index for a workgroup id: contiguous ranges per XCD, then grouped row-major.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+// Work item (K split, tile) of a workgroup.  Workgroups are dealt round-robin to the eight XCDs
+// in launch order, each with its own L2, so XCD x takes the x-th contiguous eighth of the item
+// list (split-major, tiles in grouped row-major order inside a split): the workgroups that share
+// an L2 then read neighbouring operand panels, and with split K also the same K range.
+__device__ __forceinline__ void item_of_block(int lin, int tiles_m, int tiles_n, int splits, int& split, int& tm,
+                                              int& tn)
 {
-    const int total = tiles_m * tiles_n;
+    const int tiles = tiles_m * tiles_n, total = tiles * splits;
     const int per = total / kNumXcd, rem = total % kNumXcd;
-    const int xcd = bid % kNumXcd, loc = bid / kNumXcd;
-    const int L     = xcd * per + (xcd < rem ? xcd : rem) + loc;
+    const int xcd = lin % kNumXcd, loc = lin / kNumXcd;
+    const int item  = xcd * per + (xcd < rem ? xcd : rem) + loc;
+    split           = item / tiles;
+    const int L     = item - split * tiles;
     const int width = kGroupM * tiles_n;
     const int group = L / width, first = group * kGroupM;
     const int gsz   = (tiles_m - first) < kGroupM ? (tiles_m - first) : kGroupM;
@@ -168,8 +174,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
-    int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    int split, tm, tn;
+    item_of_block(static_cast<int>(blockIdx.y * gridDim.x + blockIdx.x), p.tiles_m, p.tiles_n, SPLIT ? static_cast<int>(gridDim.y) : 1,
+                  split, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
     const int     tid = threadIdx.x, lane = tid % kWaveSize;
     const int     wave = __builtin_amdgcn_readfirstlane(tid / kWaveSize);     // wavefront index, held in an SGPR
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     int       kt_begin = 0, kt_end = ktiles_all;
     if(SPLIT)
     {
-        kt_begin = static_cast<int>(blockIdx.y) * p.ktiles_per_split;
+        kt_begin = split * p.ktiles_per_split;
         kt_end   = kt_begin + p.ktiles_per_split < ktiles_all ? kt_begin + p.ktiles_per_split : ktiles_all;
     }
 
@@ -430,7 +437,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
 
     if(SPLIT)
     {
-        acc_t* part = static_cast<acc_t*>(p.partial) + static_cast<int64_t>(blockIdx.y) * p.M * p.N;
+        acc_t* part = static_cast<acc_t*>(p.partial) + static_cast<int64_t>(split) * p.M * p.N;
         if((p.N * 4) % 16 == 0 && (reinterpret_cast<uintptr_t>(part) & 15) == 0)
         {
             staged_store(acc_t{}, std::true_type{}, reinterpret_cast<uint8_t*>(part));
