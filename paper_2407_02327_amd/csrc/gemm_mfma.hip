@@ -107,8 +107,10 @@ __device__ __forceinline__ void item_of_block(int lin, int tiles_m, int tiles_n,
     const int group = L / width, first = group * kGroupM;
     const int gsz   = (tiles_m - first) < kGroupM ? (tiles_m - first) : kGroupM;
     const int in    = L - group * width;
-    tm = first + in % gsz;
-    tn = in / gsz;
+    // the divisions run on the vector unit; hand the (uniform) results back as scalars
+    split = __builtin_amdgcn_readfirstlane(split);
+    tm    = __builtin_amdgcn_readfirstlane(first + in % gsz);
+    tn    = __builtin_amdgcn_readfirstlane(in / gsz);
 }
 
 template <typename T> __device__ __forceinline__ T from_f32_out(float v);
