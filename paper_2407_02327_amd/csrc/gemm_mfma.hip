@@ -417,7 +417,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                             *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
                     }
             }
-            // the wavefront's own LDS writes are visible to its later LDS reads (same queue, in order)
+            // Lanes read what other lanes of the wavefront have just written: the hardware keeps a
+            // wavefront's LDS operations in order, and the wavefront-scope fence tells the compiler
+            // that these loads may not be satisfied from values a lane has seen before.
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
 #pragma unroll
             for(int r0 = 0; r0 < FPP * 32; r0 += RPI)
             {
