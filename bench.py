@@ -13,6 +13,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -211,6 +212,52 @@ def main():
         ms2 = (time.perf_counter() - t1) * 1e3 / args.steps
         overlapped = {"operator_streams": len(ops_objs), "ms_per_step": round(ms2, 4),
                       "value": round(gemm_ops / (ms2 * 1e-3) / 1e12, 3), "unit": "TOPS"}
+    # Extra (outside the timed region): the quantize kernel alone on the largest gradient tensor of the
+    # workload, 20 back-to-back launches each; "cold" rotates through enough input/output sets to exceed
+    # 512 MB (nothing is left in the memory-side cache), "warm" reuses one set.
+    quant_iso = None
+    if tag == Q.INT8 and not args.no_extra_passes:
+        big = max(range(len(cases)), key=lambda i: cases[i].dy.size)
+        op, dy = ops_objs[big], dev_in[big][2]
+        Mq, Nq = op.M, op.N
+        bytes_per = dy.numel() * (dy.element_size() + 2)           # read once, write codes + transposed codes
+        nset = max(2, int(math.ceil((512 << 20) / bytes_per)) + 1)
+        sets = [(dy.clone(), torch.empty_like(op.dyq), torch.empty_like(op.dyqT)) for _ in range(nset)]
+        quant_iso = {"tensor": f"dY [{Mq},{Nq}] {str(dy.dtype).replace('torch.', '')}", "bytes": "read + codes + transposed codes",
+                     "sets_rotated_cold": nset}
+        for rname, rnd in (("rtn", Q.ROUND_NEAREST), ("sr", Q.ROUND_STOCHASTIC)):
+            for mode in ("cold", "warm"):
+                def one(i):
+                    x_, q_, qt_ = sets[i % nset] if mode == "cold" else sets[0]
+                    Q.qsync_quantize(x_, Mq, Nq, Nq, Q.INT8, 8, Q.PER_TENSOR, rnd, 1, 0, op.idy, q_, qt_, main)
+                for i in range(5):
+                    one(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(main)
+                for i in range(20):
+                    one(i)
+                e1.record(main)
+                torch.cuda.synchronize()
+                gbs = bytes_per / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
+                quant_iso[f"{rname}_{mode}"] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+        # reference on the same machine: a plain device copy moving the same bytes (read 2 B, write 2 B per element)
+        csets = [(s_[0], torch.empty_like(s_[0])) for s_ in sets]
+        for mode in ("cold", "warm"):
+            def onec(i):
+                a_, b_ = csets[i % nset] if mode == "cold" else csets[0]
+                b_.copy_(a_)
+            for i in range(5):
+                onec(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            for i in range(20):
+                onec(i)
+            e1.record(main)
+            torch.cuda.synchronize()
+            gbs = bytes_per / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
+            quant_iso[f"plain_copy_{mode}"] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+        del sets, csets
+
     # Extra (outside the timed region): a fully instrumented pass for the per-phase breakdown.
     per_step = {"gemm_fwd": fwd_ms}
     if not args.no_extra_passes:
@@ -252,6 +299,7 @@ def main():
         "quantize_dy": None if quant_gbs is None else
                        {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
                         "bytes": "absmax read + quantize read + codes + transposed codes"},
+        "quantize_alone": quant_iso,
         "operators_on_separate_streams": overlapped,
     }
     if "gemm_bwd" in per_step:
