@@ -195,16 +195,20 @@ size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t 
  * Paper: Indicator section (x_hat = code * q), Cost Mapper (layer-wise / channel-wise
  * dequantizers as element-wise kernels).
  *
- *   y[r,c] = float(a[r,c]) * tensor_scale * row_scale[r] * col_scale[c] + col_bias[c]
+ *   y[r,c] = float(a[r,c]) * (tensor_scale * tensor_scale_dev[0]) * row_scale[r] * col_scale[c] + col_bias[c]
  *   (absent factors are 1, absent bias is 0; evaluated in fp32 in that order)
  *
- * a  [rows, ld] of adt (QSYNC_I32 or QSYNC_I8).  tensor_scale is a HOST float.
+ * a  [rows, ld] of adt (QSYNC_I32 or QSYNC_I8).  tensor_scale is a HOST float;
+ * tensor_scale_dev_opt is a DEVICE pointer to one float or NULL (the per-tensor scale that
+ * qsync_absmax_scale left on the device: no host round trip is needed to dequantize saved
+ * codes, e.g. for the FP16 backward of an INT8 forward, paper: footnote in the Cost Mapper paragraph).
  * row_scale_opt rows floats, col_scale_opt / col_bias_opt cols floats, or NULL.
  * y  out, packed [rows, cols] of ydt (QSYNC_F32 or QSYNC_F16).
  */
 int qsync_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld,
                      const float* row_scale_opt, const float* col_scale_opt, float tensor_scale,
-                     const float* col_bias_opt, void* y, int ydt, void* stream);
+                     const float* tensor_scale_dev_opt, const float* col_bias_opt, void* y, int ydt,
+                     void* stream);
 
 /* hipError_t (as int) of the last failing HIP call made by this thread, 0 if none. */
 int qsync_last_hip_error(void);

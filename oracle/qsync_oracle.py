@@ -311,16 +311,49 @@ def gelu_grad(x: np.ndarray) -> np.ndarray:
 
 
 # ------------------------------------------------------------ whole-operator drivers
+def fp16_backward_of_int8_forward(xq: np.ndarray, sx, wq: np.ndarray, sw, w_gran: str, dy: np.ndarray,
+                                  dx_dtype=np.float16, dw_dtype=np.float32) -> dict:
+    """Backward of a fixed-point operator the way the paper runs it (footnote in the Cost Mapper
+    paragraph: the backward of fixed-point kernels is executed in FP16).
+
+    The saved forward codes are dequantized (x_hat = code * q, Indicator section) and narrowed to
+    binary16, the incoming gradient is narrowed to binary16, and the two contractions of the
+    Prop. 1 proof run on those operands:  dX = dY16 W16,  dW = dY16^T X16,  db = sum_m dY.
+    Returns dict(xh, wh, dyh, dx, dw, db).
+    """
+    sxv = float(_F32(np.asarray(sx).reshape(-1)[0]))
+    xh = cast_fp16(dequantize(xq, tensor_scale=sxv))
+    swv = np.asarray(sw, _F32).reshape(-1)
+    if w_gran == "row":
+        wh = cast_fp16(dequantize(wq, row_scale=swv))
+    else:
+        wh = cast_fp16(dequantize(wq, tensor_scale=float(swv[0])))
+    dyh = cast_fp16(dy)
+    b = qlinear_bwd(FP16, dyh, None, xh, None, wh, None, dy, dx_dtype, dw_dtype)
+    return dict(xh=xh, wh=wh, dyh=dyh, dx=b["dx"], dw=b["dw"], db=b["db"])
+
+
 def operator_fwd_bwd(tag: int, x: np.ndarray, w: np.ndarray, bias, dy: np.ndarray, w_gran: str = "row",
                      dy_round: str = "stochastic", seed: int = 0, offset: int = 0,
-                     y_dtype=np.float32, dx_dtype=np.float16, dw_dtype=np.float32) -> dict:
+                     y_dtype=np.float32, dx_dtype=np.float16, dw_dtype=np.float32, bwd_tag: Optional[int] = None) -> dict:
     """absmax -> quantize/cast -> forward -> quantize dY -> backward, for one linear operator.
 
     Returns every intermediate (codes, scales, accumulators, outputs) so a test can
     compare each stage.  For INT8 with per-output-channel weights the backward uses a
     second quantization of W with one scale per input feature k (see qlinear_bwd).
+    bwd_tag = FP16 with tag = INT8 selects the paper's own pairing: INT8 forward, FP16 backward
+    on the dequantized saved codes (fp16_backward_of_int8_forward).
     """
     r = {}
+    if tag == INT8 and bwd_tag == FP16:
+        ax = absmax(x, "tensor"); sx, ix = scales_from_amax(ax)
+        aw = absmax(w, w_gran); sw, iw = scales_from_amax(aw)
+        xq = quantize_int(x, ix, "tensor", "nearest")
+        wq = quantize_int(w, iw, w_gran, "nearest")
+        y, acc, ovf = qlinear_fwd(INT8, xq, sx, wq, sw, bias, y_dtype)
+        b = fp16_backward_of_int8_forward(xq, sx, wq, sw, w_gran, dy, dx_dtype, dw_dtype)
+        r.update(sx=sx, sw=sw, xq=xq, wq=wq, y=y, acc=acc, overflow=ovf, **b)
+        return r
     if tag == INT8:
         ax = absmax(x, "tensor"); sx, ix = scales_from_amax(ax)
         aw = absmax(w, w_gran); sw, iw = scales_from_amax(aw)

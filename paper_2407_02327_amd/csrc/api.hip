@@ -244,15 +244,16 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
 }
 
 int qsync_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld, const float* row_scale_opt,
-                     const float* col_scale_opt, float tensor_scale, const float* col_bias_opt, void* y, int ydt,
-                     void* stream)
+                     const float* col_scale_opt, float tensor_scale, const float* tensor_scale_dev_opt,
+                     const float* col_bias_opt, void* y, int ydt, void* stream)
 {
     if(!a || !y) return QSYNC_ERR_NULL;
     if((adt != QSYNC_I32 && adt != QSYNC_I8) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
     if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
     if(rows == 0 || cols == 0) return QSYNC_OK;
     return hip_status(launch_dequantize(a, adt == QSYNC_I32 ? kI32 : kI8, rows, cols, ld, row_scale_opt, col_scale_opt,
-                                        tensor_scale, col_bias_opt, y, ydt, static_cast<hipStream_t>(stream)));
+                                        tensor_scale, tensor_scale_dev_opt, col_bias_opt, y, ydt,
+                                        static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -599,9 +599,11 @@ template <> __device__ __forceinline__ __half from_f32<__half>(float v) { return
 template <typename Ti, typename To, int V>
 __global__ __launch_bounds__(kBlock) void dequantize_kernel(const Ti* __restrict__ a, int64_t rows, int64_t cols,
                                                             int64_t ld, const float* __restrict__ rs,
-                                                            const float* __restrict__ cs, float ts,
+                                                            const float* __restrict__ cs, float ts_host,
+                                                            const float* __restrict__ ts_dev,
                                                             const float* __restrict__ cb, To* __restrict__ y)
 {
+    const float   ts     = ts_dev ? ts_host * ts_dev[0] : ts_host;      // one fp32 product (exact when ts_host is 1)
     const int64_t cv     = cols / V;          // V divides cols on this path (V == 1 otherwise)
     const int64_t n      = rows * cv;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
@@ -878,7 +880,7 @@ hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, in
 
 template <typename Ti, typename To>
 static hipError_t dequantize_typed(const void* a, int64_t rows, int64_t cols, int64_t ld, const float* rs,
-                                   const float* cs, float ts, const float* cb, void* y, hipStream_t st)
+                                   const float* cs, float ts, const float* tsd, const float* cb, void* y, hipStream_t st)
 {
     const bool vec = cols % 4 == 0 && ld % 4 == 0 && (reinterpret_cast<uintptr_t>(a) % (4 * sizeof(Ti))) == 0
                   && (reinterpret_cast<uintptr_t>(y) % (4 * sizeof(To))) == 0;
@@ -887,24 +889,24 @@ static hipError_t dequantize_typed(const void* a, int64_t rows, int64_t cols, in
     nb                 = nb > (1 << 20) ? (1 << 20) : nb;
     if(vec)
         dequantize_kernel<Ti, To, 4><<<dim3(nb), dim3(kBlock), 0, st>>>(static_cast<const Ti*>(a), rows, cols, ld, rs,
-                                                                       cs, ts, cb, static_cast<To*>(y));
+                                                                       cs, ts, tsd, cb, static_cast<To*>(y));
     else
         dequantize_kernel<Ti, To, 1><<<dim3(nb), dim3(kBlock), 0, st>>>(static_cast<const Ti*>(a), rows, cols, ld, rs,
-                                                                       cs, ts, cb, static_cast<To*>(y));
+                                                                       cs, ts, tsd, cb, static_cast<To*>(y));
     return hipGetLastError();
 }
 
 hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld, const float* row_scale,
-                             const float* col_scale, float tensor_scale, const float* col_bias, void* y, int ydt,
-                             hipStream_t stream)
+                             const float* col_scale, float tensor_scale, const float* tensor_scale_dev,
+                             const float* col_bias, void* y, int ydt, hipStream_t stream)
 {
     if(adt == kI32 && ydt == kF32)
-        return dequantize_typed<int32_t, float>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, col_bias, y, stream);
+        return dequantize_typed<int32_t, float>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
     if(adt == kI32 && ydt == kF16)
-        return dequantize_typed<int32_t, __half>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, col_bias, y, stream);
+        return dequantize_typed<int32_t, __half>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
     if(adt == kI8 && ydt == kF32)
-        return dequantize_typed<int8_t, float>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, col_bias, y, stream);
-    return dequantize_typed<int8_t, __half>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, col_bias, y, stream);
+        return dequantize_typed<int8_t, float>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
+    return dequantize_typed<int8_t, __half>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
 }
 
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols)

@@ -32,7 +32,8 @@ hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, in
 // ---- standalone dequantize, column sums -----------------------------------------------
 hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld,
                              const float* row_scale, const float* col_scale, float tensor_scale,
-                             const float* col_bias, void* y, int ydt, hipStream_t stream);
+                             const float* tensor_scale_dev, const float* col_bias, void* y, int ydt,
+                             hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream);

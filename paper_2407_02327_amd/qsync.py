@@ -36,7 +36,7 @@ SIGNATURES = {
                                _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
-    "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _i, _vp]),
+    "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _vp, _i, _vp]),
     "qsync_last_hip_error": (_i, []),
     "qsync_strerror": (ctypes.c_char_p, [_i]),
     "qsync_version": (_i, []),
@@ -124,6 +124,7 @@ def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, 
 
 
 def qsync_dequantize(a, rows, cols, ld, row_scale_opt, col_scale_opt, tensor_scale, col_bias_opt, y,
-                     stream=None) -> None:
+                     stream=None, tensor_scale_dev_opt=None) -> None:
     _check(lib.qsync_dequantize(_ptr(a), dtype_code(a), rows, cols, ld, _ptr(row_scale_opt), _ptr(col_scale_opt),
-                                float(tensor_scale), _ptr(col_bias_opt), _ptr(y), dtype_code(y), _stream(stream)))
+                                float(tensor_scale), _ptr(tensor_scale_dev_opt), _ptr(col_bias_opt), _ptr(y),
+                                dtype_code(y), _stream(stream)))

@@ -117,16 +117,16 @@ def test_qlinear_validation():
 
 def test_dequantize_validation():
     f = lib.qsync_dequantize
-    assert f(None, 3, 4, 4, 4, None, None, 1.0, None, A, 0, None) == qsync.ERR_NULL
-    assert f(A, 0, 4, 4, 4, None, None, 1.0, None, A, 0, None) == qsync.ERR_BAD_ENUM     # float input
-    assert f(A, 3, 4, 4, 4, None, None, 1.0, None, A, 2, None) == qsync.ERR_BAD_ENUM     # int output
-    assert f(A, 3, 4, 4, 2, None, None, 1.0, None, A, 0, None) == qsync.ERR_BAD_SHAPE
-    assert f(A, 3, 4, 0, 0, None, None, 1.0, None, A, 0, None) == qsync.OK
+    assert f(None, 3, 4, 4, 4, None, None, 1.0, None, None, A, 0, None) == qsync.ERR_NULL
+    assert f(A, 0, 4, 4, 4, None, None, 1.0, None, None, A, 0, None) == qsync.ERR_BAD_ENUM     # float input
+    assert f(A, 3, 4, 4, 4, None, None, 1.0, None, None, A, 2, None) == qsync.ERR_BAD_ENUM     # int output
+    assert f(A, 3, 4, 4, 2, None, None, 1.0, None, None, A, 0, None) == qsync.ERR_BAD_SHAPE
+    assert f(A, 3, 4, 0, 0, None, None, 1.0, None, None, A, 0, None) == qsync.OK
 
 
 def test_no_gpu_gives_hip_error_not_a_crash():
     import torch
     if torch.cuda.is_available():
         pytest.skip("GPU present")
-    rc = lib.qsync_dequantize(A, 3, 4, 4, 4, None, None, 1.0, None, A, 0, None)
+    rc = lib.qsync_dequantize(A, 3, 4, 4, 4, None, None, 1.0, None, None, A, 0, None)
     assert rc == qsync.ERR_HIP and lib.qsync_last_hip_error() != 0

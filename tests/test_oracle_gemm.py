@@ -155,6 +155,48 @@ def test_operator_driver_close_to_float_operator(tag):
         assert r["wqb"].shape == (n, k) and np.abs(r["wqb"]).max(axis=0).min() == 127
 
 
+def test_fp16_backward_of_int8_forward_reduces_to_exact_integer_products():
+    """Pin for the paper's INT8-forward / FP16-backward pairing.  With power-of-two scales and small codes
+    every dequantized operand and every product is exact in binary16/double, so dX and dW must equal the
+    integer matrix products scaled by the (exact) scales: a transposed operand, a missing dequantize
+    factor or the wrong scale granularity cannot pass."""
+    rng = np.random.default_rng(21)
+    m, n, k = 7, 5, 11
+    xq = rng.integers(-8, 9, (m, k)).astype(np.int8)
+    wq = rng.integers(-8, 9, (n, k)).astype(np.int8)
+    dy = (rng.integers(-16, 17, (m, n)) / 64.0).astype(np.float32)      # exact in binary16
+    sx = np.float32([0.25])
+    sw_row = (2.0 ** rng.integers(-4, 1, n)).astype(np.float32)
+    for w_gran, sw in (("row", sw_row), ("tensor", np.float32([0.125]))):
+        out = orc.fp16_backward_of_int8_forward(xq, sx, wq, sw, w_gran, dy, np.float64, np.float64)
+        swn = sw if w_gran == "row" else np.repeat(sw, n)
+        W = [[int(wq[j, t]) * float(swn[j]) for t in range(k)] for j in range(n)]
+        X = [[int(xq[i, t]) * 0.25 for t in range(k)] for i in range(m)]
+        dx = [[math.fsum(float(dy[i, j]) * W[j][t] for j in range(n)) for t in range(k)] for i in range(m)]
+        dw = [[math.fsum(float(dy[i, j]) * X[i][t] for i in range(m)) for t in range(k)] for j in range(n)]
+        assert out["dx"].tolist() == dx and out["dw"].tolist() == dw
+        assert out["xh"].dtype == np.float16 and out["wh"].dtype == np.float16 and out["dyh"].dtype == np.float16
+        np.testing.assert_allclose(out["db"], dy.astype(np.float64).sum(0), rtol=1e-6)
+
+
+def test_fp16_backward_of_int8_forward_error_against_float_operator():
+    """On Gaussian data the paper's pairing tracks the unquantized backward within the quantization noise
+    of the saved codes (rounding of x and w to 8 bits, then to binary16), and is closer to it than the
+    INT8 backward, whose gradient is also quantized."""
+    rng = np.random.default_rng(22)
+    m, n, k = 64, 48, 80
+    x = rng.standard_normal((m, k)).astype(np.float32)
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    dy = (rng.standard_normal((m, n)) * 1e-2).astype(np.float32)
+    r16 = orc.operator_fwd_bwd(INT8, x, w, None, dy, "row", "stochastic", seed=3, dx_dtype=np.float32, bwd_tag=FP16)
+    r8 = orc.operator_fwd_bwd(INT8, x, w, None, dy, "row", "stochastic", seed=3, dx_dtype=np.float32)
+    dx0, dw0 = dy.astype(np.float64) @ w, dy.astype(np.float64).T @ x
+    e16 = max(np.abs(r16["dx"] - dx0).max() / np.abs(dx0).max(), np.abs(r16["dw"] - dw0).max() / np.abs(dw0).max())
+    e8 = max(np.abs(r8["dx"] - dx0).max() / np.abs(dx0).max(), np.abs(r8["dw"] - dw0).max() / np.abs(dw0).max())
+    assert e16 < 0.02 and e16 < e8
+    assert np.array_equal(r16["y"], r8["y"]) and np.array_equal(r16["xq"], r8["xq"])     # same forward
+
+
 def test_gelu_and_its_derivative():
     x = np.linspace(-6, 6, 241)
     g = orc.gelu(x)
