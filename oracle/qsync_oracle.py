@@ -316,18 +316,20 @@ def fp16_backward_of_int8_forward(xq: np.ndarray, sx, wq: np.ndarray, sw, w_gran
     """Backward of a fixed-point operator the way the paper runs it (footnote in the Cost Mapper
     paragraph: the backward of fixed-point kernels is executed in FP16).
 
-    The saved forward codes are dequantized (x_hat = code * q, Indicator section) and narrowed to
-    binary16, the incoming gradient is narrowed to binary16, and the two contractions of the
+    The saved forward codes are dequantized (x_hat = code * q, Indicator section; one binary32
+    multiply, the precision the dequantizer kernel works in) and narrowed to binary16 with round to
+    nearest even, the incoming gradient is narrowed to binary16, and the two contractions of the
     Prop. 1 proof run on those operands:  dX = dY16 W16,  dW = dY16^T X16,  db = sum_m dY.
     Returns dict(xh, wh, dyh, dx, dw, db).
     """
-    sxv = float(_F32(np.asarray(sx).reshape(-1)[0]))
-    xh = cast_fp16(dequantize(xq, tensor_scale=sxv))
+    # x_hat = code * q is one binary32 product (codes and scales are binary32-exact), then narrowed
+    sxv = _F32(np.asarray(sx).reshape(-1)[0])
+    xh = cast_fp16(xq.astype(_F32) * sxv)
     swv = np.asarray(sw, _F32).reshape(-1)
     if w_gran == "row":
-        wh = cast_fp16(dequantize(wq, row_scale=swv))
+        wh = cast_fp16(wq.astype(_F32) * swv.reshape(-1, 1))
     else:
-        wh = cast_fp16(dequantize(wq, tensor_scale=float(swv[0])))
+        wh = cast_fp16(wq.astype(_F32) * swv[0])
     dyh = cast_fp16(dy)
     b = qlinear_bwd(FP16, dyh, None, xh, None, wh, None, dy, dx_dtype, dw_dtype)
     return dict(xh=xh, wh=wh, dyh=dyh, dx=b["dx"], dw=b["dw"], db=b["db"])

@@ -13,6 +13,8 @@ inputs and weights, extra casting in the backward pass; Backend section):
             GEMM with fused dequantize + bias
   backward: absmax+quantize dY (stochastic rounding; codes and transposed codes),
             dX GEMM, dW GEMM, bias gradient
+  backward, bwd_tag = FP16 on an INT8 operator (the pairing the paper itself runs, footnote in the
+            Cost Mapper paragraph): dequantize the saved codes to binary16, cast dY, FP16 GEMMs
 """
 from __future__ import annotations
 
@@ -34,8 +36,12 @@ class QLinear:
     def __init__(self, tag: int, M: int, N: int, K: int, x_dtype=torch.float16, w_dtype=torch.float32,
                  dy_dtype=None, y_dtype=torch.float32, dx_dtype=torch.float16, dw_dtype=torch.float32,
                  w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
-                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda"):
+                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda",
+                 bwd_tag: Optional[int] = None):
         self.tag, self.M, self.N, self.K = tag, M, N, K
+        self.bwd_tag = tag if bwd_tag is None else bwd_tag
+        if self.bwd_tag != tag and not (tag == Q.INT8 and self.bwd_tag == Q.FP16):
+            raise ValueError("bwd_tag: only the FP16 backward of an INT8 forward differs from the forward tag")
         self.w_gran, self.dy_round, self.seed, self.bits = w_gran, dy_round, philox_seed, bits
         self.offset = 0
         dy_dtype = dy_dtype or x_dtype
@@ -67,7 +73,12 @@ class QLinear:
         self.ws_absmax_w = _ws(max(Q.qsync_absmax_workspace_bytes(N, K, Q.PER_COL),
                                    Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), dev)
         self.ws_fwd = _ws(Q.qsync_qlinear_workspace_bytes(tag, M, N, K), dev)
-        self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K), dev)
+        self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(self.bwd_tag, M, N, K), dev)
+        if self.bwd_tag != tag:
+            h = torch.float16
+            # binary16 operands of the FP16 backward: dequantized X^T, dequantized W and its transpose, cast dY
+            self.xhT, self.wh, self.whT = e(K, M, dt=h), e(N, K, dt=h), e(K, N, dt=h)
+            self.dyh, self.dyhT = e(M, N, dt=h), e(N, M, dt=h)
 
     # ---- precision conversion -----------------------------------------------------------
     def convert_x(self, x: torch.Tensor, stream=None) -> None:
@@ -99,7 +110,18 @@ class QLinear:
                          stream)
 
     def convert_dy(self, dy: torch.Tensor, stream=None) -> None:
-        M, N = self.M, self.N
+        M, N, K = self.M, self.N, self.K
+        if self.bwd_tag != self.tag:
+            # FP16 backward of the INT8 forward: x_hat = code * q narrowed to binary16 (straight from the saved
+            # transposed codes), w_hat likewise and then transposed, dY narrowed and transposed
+            Q.qsync_dequantize(self.xqT, K, M, M, None, None, 1.0, None, self.xhT, stream, tensor_scale_dev_opt=self.sx)
+            if self.w_gran == Q.PER_ROW:
+                Q.qsync_dequantize(self.wq, N, K, K, self.sw, None, 1.0, None, self.wh, stream)
+            else:
+                Q.qsync_dequantize(self.wq, N, K, K, None, None, 1.0, None, self.wh, stream, tensor_scale_dev_opt=self.sw)
+            Q.qsync_quantize(self.wh, N, K, K, Q.FP16, 0, 0, 0, 0, 0, None, None, self.whT, stream)
+            Q.qsync_quantize(dy, M, N, N, Q.FP16, 0, 0, 0, 0, 0, None, self.dyh, self.dyhT, stream)
+            return
         if self.tag == Q.INT8:
             # the same pass over dY yields its absmax and the bias gradient db (column sums)
             Q.qsync_absmax_scale(dy, M, N, N, Q.PER_TENSOR, self.bits, self.sdy, self.idy, self.ady, self.db,
@@ -117,6 +139,11 @@ class QLinear:
                             self.bias, self.y, self.acc, self.ws_fwd, stream)
 
     def gemm_bwd(self, dy: Optional[torch.Tensor], stream=None) -> None:
+        if self.bwd_tag != self.tag:
+            Q.qsync_qlinear_bwd(Q.FP16, self.M, self.N, self.K, self.dyh, self.dyhT, None, self.xhT, None, self.whT, None,
+                                Q.PER_TENSOR, self.dx, self.dw, self.db if dy is not None else None, dy, None, None,
+                                self.ws_bwd, stream)
+            return
         want_db = dy is not None and self.tag != Q.INT8      # INT8: db already came out of the absmax pass over dY
         Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
                             self.wqbT, self.swb, self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW,

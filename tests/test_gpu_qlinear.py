@@ -219,3 +219,42 @@ def test_config5_fp16_tag_full_size():
 def test_config3_resnet_conv_full_size_int8():
     """M = 200704: split-K dW over a contraction of 200704, HBM-bound forward and dX."""
     run_case(wl.config3(), Q.INT8, y_dtype=np.float16)
+
+
+def run_case_fp16_backward(case: wl.LinearCase, y_dtype=np.float32):
+    """INT8 forward with the paper's FP16 backward on the dequantized saved codes, stage by stage."""
+    M, N, K = case.mnk
+    say(case.name, "INT8 forward / FP16 backward", "MNK", M, N, K, "w_gran", case.w_gran)
+    op = QLinear(Q.INT8, M, N, K, x_dtype=TORCH[case.x.dtype], w_dtype=TORCH[case.w.dtype],
+                 dy_dtype=TORCH[case.dy.dtype], y_dtype=TORCH[np.dtype(y_dtype)], dx_dtype=torch.float16,
+                 dw_dtype=torch.float32, w_gran=GRAN[case.w_gran], philox_seed=case.philox_seed, bwd_tag=Q.FP16)
+    op.bias.copy_(dev(case.bias))
+    op.forward(dev(case.x), dev(case.w))
+    op.backward(dev(case.dy))
+    ref = orc.operator_fwd_bwd(Q.INT8, case.x, case.w, case.bias, case.dy, case.w_gran, y_dtype=np.float64,
+                               dx_dtype=np.float64, dw_dtype=np.float64, bwd_tag=Q.FP16)
+    assert_bits_equal(host(op.xq), ref["xq"], "xq")
+    assert_bits_equal(host(op.wq), ref["wq"], "wq")
+    # dequantized binary16 operands: one fp32 product rounded to binary16 on both sides
+    assert_bits_equal(host(op.xhT), ref["xh"].T, "x_hat transposed")
+    assert_bits_equal(host(op.wh), ref["wh"], "w_hat")
+    assert_bits_equal(host(op.whT), ref["wh"].T, "w_hat transposed")
+    assert_bits_equal(host(op.dyh), ref["dyh"], "dY cast")
+    assert_bits_equal(host(op.dyhT), ref["dyh"].T, "dY cast transposed")
+    assert_close(host(op.y), ref["y"], "Y")
+    assert_close(host(op.dx), ref["dx"], "dX (FP16 backward)")
+    assert_close(host(op.dw), ref["dw"], "dW (FP16 backward)")
+    assert_close(host(op.db), ref["db"], "db", rtol=1e-3, atol_rel=1e-3)
+    return op, ref
+
+
+@pytest.mark.parametrize("w_gran", ["row", "tensor"])
+def test_int8_forward_fp16_backward_small_and_ragged(w_gran):
+    for shape in [(64, 128, 128), (208, 144, 272), (528, 272, 400)]:
+        case = wl.ragged_case(*shape, seed=sum(shape) + 1)
+        case.w_gran = w_gran
+        run_case_fp16_backward(case)
+
+
+def test_int8_forward_fp16_backward_config2_full_size():
+    run_case_fp16_backward(wl.config2(), y_dtype=np.float16)
