@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c5", choices=["c5", "c2", "c3"])
     ap.add_argument("--tag", default="int8", choices=["int8", "fp16"])
+    ap.add_argument("--bwd-tag", default=None, choices=[None, "fp16"],
+                    help="fp16 with --tag int8: the paper's pairing, FP16 backward on the dequantized saved codes")
     ap.add_argument("--ydtype", default="f16", choices=["f16", "f32"], help="forward output type")
     ap.add_argument("--cpu-tokens", type=int, default=2048, help="rows per operator given to the CPU oracle")
     ap.add_argument("--streams", type=int, default=1,
@@ -136,7 +138,7 @@ def main():
                      dx_dtype=torch.float16, dw_dtype=torch.float32,
                      w_gran=Q.PER_ROW if c.w_gran == "row" else Q.PER_TENSOR,
                      dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
-                     philox_seed=c.philox_seed)
+                     philox_seed=c.philox_seed, bwd_tag=(Q.FP16 if args.bwd_tag == "fp16" and tag == Q.INT8 else None))
         ops_objs.append(op)
         dev_in.append((torch.from_numpy(c.x).cuda(), torch.from_numpy(c.w).cuda(), torch.from_numpy(c.dy).cuda()))
     torch.cuda.synchronize()
@@ -216,7 +218,7 @@ def main():
     # workload, 20 back-to-back launches each; "cold" rotates through enough input/output sets to exceed
     # 512 MB (nothing is left in the memory-side cache), "warm" reuses one set.
     quant_iso = None
-    if tag == Q.INT8 and not args.no_extra_passes:
+    if tag == Q.INT8 and args.bwd_tag is None and not args.no_extra_passes:
         big = max(range(len(cases)), key=lambda i: cases[i].dy.size)
         op, dy = ops_objs[big], dev_in[big][2]
         Mq, Nq = op.M, op.N
@@ -284,7 +286,9 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.tag if args.tag == "int8" else "f16", "data": "synthetic",
         "config": {"workload": desc, "tag": args.tag, "y_dtype": args.ydtype, "dx_dtype": "f16", "dw_dtype": "f32",
-                   "w_scale": "per-output-channel", "dy_rounding": "stochastic (Philox4x32-10)",
+                   "w_scale": "per-output-channel",
+                   "dy_rounding": "stochastic (Philox4x32-10)" if args.bwd_tag is None else "none (FP16 backward)",
+                   "bwd_tag": args.bwd_tag or args.tag,
                    "operator_streams": nstreams},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches)",
                      "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
