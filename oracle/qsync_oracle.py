@@ -310,6 +310,44 @@ def gelu_grad(x: np.ndarray) -> np.ndarray:
     return cdf + xd * pdf
 
 
+# ------------------------------------------------------------ indicator statistics
+def effective_exponent(amax: float) -> int:
+    """Exponent e of the largest magnitude, 2^e <= amax < 2^(e+1) (the "effective bits" the Indicator
+    section derives from the data's magnitude); -126 for an all-zero tensor."""
+    if not amax > 0:
+        return -126
+    return int(math.floor(math.log2(float(amax))))
+
+
+def tensor_stats(x: np.ndarray) -> dict:
+    """The per-tensor quantities the variance indicator needs (Indicator section, Prop. 3): squared
+    Euclidean norm (double sum), absmax, effective exponent and dimensionality."""
+    xd = x.astype(np.float64).reshape(-1)
+    am = float(absmax(x, "tensor")[0]) if x.size else 0.0
+    return dict(sumsq=float(np.dot(xd, xd)), amax=am, e=effective_exponent(am), D=int(x.size))
+
+
+def variance_increment(kind: str, x: dict, v: dict, gv: dict, q_x: float = 0.0, q_v: float = 0.0,
+                       eps: float = 2.0 ** -9, gamma: float = 1.0, d_o: int = 1, d_L: int = 1) -> dict:
+    """Omega = gamma^2 d_o sigma_fp + (d_L - d_o) sigma_bp of one unary operator (Prop. 3 and the two
+    case equations below it).  x, v, gv are tensor_stats of the parameter, the (dequantized) activation
+    and the activation gradient; q_x, q_v the fixed-point scales; eps = 2^-k of the float format.
+      fixed:  sigma_fp = (|x|^2 q_v^2 D_v + |v|^2 q_x^2 D_x) / 6
+              sigma_bp = (|gv|^2 q_v^2 D_v + |v|^2 2^(2 e_gv) eps^2 D_gv) / 6
+      float:  sigma_fp = eps^2 (|x|^2 2^(2 e_v) D_v + |v|^2 2^(2 e_x) D_x) / 6
+              sigma_bp = eps^2 (|gv|^2 2^(2 e_v) D_v + |v|^2 2^(2 e_gv) D_gv) / 6
+    """
+    if kind == "fixed":
+        s_fp = (x["sumsq"] * q_v ** 2 * v["D"] + v["sumsq"] * q_x ** 2 * x["D"]) / 6.0
+        s_bp = (gv["sumsq"] * q_v ** 2 * v["D"] + v["sumsq"] * 4.0 ** gv["e"] * eps ** 2 * gv["D"]) / 6.0
+    elif kind == "float":
+        s_fp = eps ** 2 * (x["sumsq"] * 4.0 ** v["e"] * v["D"] + v["sumsq"] * 4.0 ** x["e"] * x["D"]) / 6.0
+        s_bp = eps ** 2 * (gv["sumsq"] * 4.0 ** v["e"] * v["D"] + v["sumsq"] * 4.0 ** gv["e"] * gv["D"]) / 6.0
+    else:
+        raise ValueError(kind)
+    return dict(sigma_fp=s_fp, sigma_bp=s_bp, omega=gamma ** 2 * d_o * s_fp + (d_L - d_o) * s_bp)
+
+
 # ------------------------------------------------------------ whole-operator drivers
 def fp16_backward_of_int8_forward(xq: np.ndarray, sx, wq: np.ndarray, sw, w_gran: str, dy: np.ndarray,
                                   dx_dtype=np.float16, dw_dtype=np.float32) -> dict:
