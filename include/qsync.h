@@ -79,6 +79,10 @@ typedef enum {
  *           given, the same pass over x also produces colsum[c] = sum_r x[r,c] in fp32: for x = dY
  *           this is the bias gradient db (paper: Appendix, proof of Prop. 1, gradient of a linear
  *           operator), obtained without reading dY a third time.
+ * sumsq_opt out, one float or NULL; PER_TENSOR only.  When given, the same pass also yields the squared
+ *           Euclidean norm sum x[r,c]^2 (fp32 per lane and block, block results folded in double in block
+ *           order): with amax it is what the variance indicator needs from a tensor (paper: Indicator
+ *           section, Prop. 3: norms, scaling factors and effective bits "collected through profiling").
  * workspace scratch of at least qsync_absmax_workspace_bytes(rows, cols, gran) bytes, 16-byte aligned.
  *           PER_TENSOR: its first 256 bytes hold a block arrival counter: ZERO THEM ONCE after
  *           allocating the buffer (hipMemset); every call that completes leaves them zero again, so
@@ -91,7 +95,8 @@ typedef enum {
  */
 int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld,
                        int gran, int bits, float* scale, float* inv_scale, float* amax_opt,
-                       float* colsum_opt, void* workspace, size_t workspace_bytes, void* stream);
+                       float* colsum_opt, float* sumsq_opt, void* workspace, size_t workspace_bytes,
+                       void* stream);
 size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 
 /*

@@ -67,14 +67,14 @@ size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran)
 }
 
 int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran, int bits,
-                       float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, void* workspace,
-                       size_t workspace_bytes, void* stream)
+                       float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, float* sumsq_opt,
+                       void* workspace, size_t workspace_bytes, void* stream)
 {
     if(!x || !scale || !inv_scale) return QSYNC_ERR_NULL;
     if(!is_float_dtype(xdt) || !is_gran(gran)) return QSYNC_ERR_BAD_ENUM;
     if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
     if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
-    if(colsum_opt && gran != QSYNC_PER_TENSOR) return QSYNC_ERR_UNSUPPORTED;
+    if((colsum_opt || sumsq_opt) && gran != QSYNC_PER_TENSOR) return QSYNC_ERR_UNSUPPORTED;
     if(colsum_opt && cols > (int64_t(1) << 19)) return QSYNC_ERR_UNSUPPORTED;   // one block-maximum slot per column strip
     if(rows == 0 || cols == 0) return QSYNC_OK;
     const size_t need = qsync_absmax_workspace_bytes(rows, cols, gran);
@@ -85,7 +85,7 @@ int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64
     }
     const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
     return hip_status(launch_absmax_scale(x, xdt, rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt, colsum_opt,
-                                          workspace, static_cast<hipStream_t>(stream)));
+                                          sumsq_opt, workspace, static_cast<hipStream_t>(stream)));
 }
 
 int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int tag, int bits, int gran,

@@ -38,6 +38,21 @@ __device__ __forceinline__ float block_reduce_max(float v, float* lds /* >= 16 f
     return v;
 }
 
+// Block-wide sum in a fixed order (wave shuffles, then the wave sums in order); valid in thread 0.
+__device__ __forceinline__ float block_reduce_sum(float v, float* lds /* >= 16 floats */)
+{
+    v = wave_reduce_sum(v);
+    const int lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
+    if(lane == 0) lds[wave] = v;
+    __syncthreads();
+    if(threadIdx.x == 0)
+    {
+        const int nw = (blockDim.x + kWaveSize - 1) / kWaveSize;
+        for(int i = 1; i < nw; ++i) v += lds[i];
+    }
+    return v;
+}
+
 // Element access that widens to fp32 (binary16 -> fp32 is exact).
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(__half v) { return __half2float(v); }

@@ -70,6 +70,38 @@ template <> struct RunMax<__half>
     }
 };
 
+// Running sum of squares in fp32 (the squared norm of the indicator statistics).
+template <typename T> struct RunSq
+{
+    float s = 0.0f;
+    __device__ __forceinline__ void add(const uint4& r)
+    {
+        float v[Vec16<T>::N];
+        Vec16<T>::decode(r, v);
+#pragma unroll
+        for(int e = 0; e < Vec16<T>::N; ++e) s = fmaf(v[e], v[e], s);
+    }
+    __device__ __forceinline__ void add_scalar(T x) { const float v = to_f32(x); s = fmaf(v, v, s); }
+};
+
+// The last block folds the per-block sums of squares in block order, in double.  The first `cap`
+// partials are fetched by the whole block into LDS, any further ones straight from memory.
+__device__ __forceinline__ void fold_sumsq(const float* partial_sq, unsigned int nblocks, float* sumsq, double* lds_d,
+                                           unsigned int cap)
+{
+    for(unsigned int i = threadIdx.x; i < nblocks && i < cap; i += blockDim.x)
+        lds_d[i] = static_cast<double>(__hip_atomic_load(partial_sq + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    __syncthreads();
+    if(threadIdx.x == 0)
+    {
+        double t = 0.0;
+        for(unsigned int i = 0; i < nblocks; ++i)
+            t += i < cap ? lds_d[i]
+                         : static_cast<double>(__hip_atomic_load(partial_sq + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        *sumsq = static_cast<float>(t);
+    }
+}
+
 // ------------------------------------------------------------------ arrival counter
 // The per-tensor maximum finishes inside one launch: every block publishes its partial maximum,
 // then takes a ticket from an arrival counter; the block that draws the last ticket folds the
@@ -110,12 +142,16 @@ template <typename T, bool VEC, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void absmax_tensor_kernel(const T* __restrict__ x, int64_t rows,
                                                               int64_t cols, int64_t ld, float* partial,
                                                               unsigned int* ctr, float qmax, float* scale,
-                                                              float* inv_scale, float* amax_opt)
+                                                              float* inv_scale, float* amax_opt, float* partial_sq,
+                                                              float* sumsq_opt)
 {
-    __shared__ float lds[16];
-    __shared__ bool  flag;
-    RunMax<T>        rm;
-    const int64_t    n = rows * cols;
+    __shared__ float  lds[16];
+    __shared__ double lds_d[1024];
+    __shared__ bool   flag;
+    RunMax<T>         rm;
+    RunSq<T>          sq;                 // only when sumsq_opt is given
+    const bool        want_sq = sumsq_opt != nullptr;
+    const int64_t     n = rows * cols;
     if(VEC)
     {   // contiguous tensor, 16-byte aligned base
         constexpr int E    = Vec16<T>::N;
@@ -134,9 +170,18 @@ __global__ __launch_bounds__(BLOCK) void absmax_tensor_kernel(const T* __restric
             }
 #pragma unroll
             for(int u = 0; u < U; ++u) rm.add(v[u]);
+            if(want_sq)
+            {
+#pragma unroll
+                for(int u = 0; u < U; ++u) sq.add(v[u]);
+            }
         }
         if(blockIdx.x == 0)
-            for(int64_t j = nvec * E + threadIdx.x; j < n; j += BLOCK) rm.add_scalar(x[j]);
+            for(int64_t j = nvec * E + threadIdx.x; j < n; j += BLOCK)
+            {
+                rm.add_scalar(x[j]);
+                if(want_sq) sq.add_scalar(x[j]);
+            }
     }
     else
     {
@@ -145,12 +190,24 @@ __global__ __launch_bounds__(BLOCK) void absmax_tensor_kernel(const T* __restric
         {
             const int64_t r = i / cols, c = i - r * cols;
             rm.add_scalar(x[r * ld + c]);
+            if(want_sq) sq.add_scalar(x[r * ld + c]);
         }
     }
     const float m = block_reduce_max(rm.get(), lds);
     if(threadIdx.x == 0) st_partial(partial + blockIdx.x, m);
+    if(want_sq)
+    {
+        __syncthreads();
+        const float bs = block_reduce_sum(sq.s, lds);
+        if(threadIdx.x == 0) st_partial(partial_sq + blockIdx.x, bs);
+    }
     if(!ctr) return;
     if(!last_arrival(ctr, gridDim.x, &flag)) return;
+    if(want_sq)
+    {
+        fold_sumsq(partial_sq, gridDim.x, sumsq_opt, lds_d, 1024u);
+        __syncthreads();
+    }
     float mm = 0.0f;
     for(int i = threadIdx.x; i < static_cast<int>(gridDim.x); i += BLOCK) mm = fmaxf(mm, ld_partial(partial + i));
     mm = block_reduce_max(mm, lds);
@@ -239,6 +296,8 @@ struct TensorFinal          // OP_SUMMAX: where the tensor-wide result goes
     float*        scale;
     float*        inv_scale;
     float*        amax_opt;
+    float*        partial_sq;   // per-block sums of squares and their total (indicator statistics), or nullptr
+    float*        sumsq_opt;
 };
 
 template <typename T, bool VEC, int OP, int BLOCK>
@@ -252,6 +311,8 @@ __global__ __launch_bounds__(BLOCK) void colreduce_kernel(const T* __restrict__ 
     __shared__ float lds_max[16];
     __shared__ bool  flag;
     RunMax<T>        rm;                                    // OP_SUMMAX only
+    float            sqv     = 0.0f;                        // OP_SUMMAX with fin.sumsq_opt: sum of squares
+    const bool       want_sq = OP == OP_SUMMAX && fin.sumsq_opt != nullptr;
     const int     rpb = BLOCK / tpr;                       // row lanes per block
     const int     tc = threadIdx.x % tpr, tr = threadIdx.x / tpr;
     const int64_t c0  = (static_cast<int64_t>(blockIdx.x) * tpr + tc) * E;
@@ -289,6 +350,11 @@ __global__ __launch_bounds__(BLOCK) void colreduce_kernel(const T* __restrict__ 
 #pragma unroll
                         for(int e = 0; e < E; ++e) acc[e] = OP == OP_MAX ? fmaxf(acc[e], fabsf(v[e])) : acc[e] + v[e];
                         if(OP == OP_SUMMAX) rm.add(raw[u]);
+                        if(want_sq)
+                        {
+#pragma unroll
+                            for(int e = 0; e < E; ++e) sqv = fmaf(v[e], v[e], sqv);
+                        }
                     }
                 }
             }
@@ -304,6 +370,7 @@ __global__ __launch_bounds__(BLOCK) void colreduce_kernel(const T* __restrict__ 
                         const float v  = to_f32(xv);
                         acc[0] = OP == OP_MAX ? fmaxf(acc[0], fabsf(v)) : acc[0] + v;
                         if(OP == OP_SUMMAX) rm.add_scalar(xv);
+                        if(want_sq) sqv = fmaf(v, v, sqv);
                     }
                 }
             }
@@ -318,6 +385,12 @@ __global__ __launch_bounds__(BLOCK) void colreduce_kernel(const T* __restrict__ 
     {   // every thread of the block takes part (threads beyond the last column carry 0)
         const float bm = block_reduce_max(rm.get(), lds_max);
         if(threadIdx.x == 0) st_partial(partial_max + blockIdx.y * gridDim.x + blockIdx.x, bm);
+        if(want_sq)
+        {
+            __syncthreads();
+            const float bs = block_reduce_sum(sqv, lds_max);
+            if(threadIdx.x == 0) st_partial(fin.partial_sq + blockIdx.y * gridDim.x + blockIdx.x, bs);
+        }
     }
     // fold the block's row lanes in order 0, 1, ... through LDS
     auto fold_rows = [&]() {
@@ -345,6 +418,11 @@ __global__ __launch_bounds__(BLOCK) void colreduce_kernel(const T* __restrict__ 
     const unsigned int nblocks = gridDim.x * gridDim.y;
     if(last_arrival(fin.ctr, nblocks, &flag))
     {
+        if(want_sq)
+        {   // the strip buffer is free by now: borrow it for the fold
+            fold_sumsq(fin.partial_sq, nblocks, fin.sumsq_opt, reinterpret_cast<double*>(lds), BLOCK * E / 2);
+            __syncthreads();
+        }
         float mm = 0.0f;
         for(unsigned int i = threadIdx.x; i < nblocks; i += BLOCK) mm = fmaxf(mm, ld_partial(partial_max + i));
         mm = block_reduce_max(mm, lds_max);
@@ -714,15 +792,16 @@ size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran)
 {
     (void)rows;
     const size_t c = static_cast<size_t>(cols > 0 ? cols : 0);
-    if(gran == kPerTensor)   // counter, block maxima; with fused column sums also the per-column partial sums
-        return kCtrBytes + sizeof(float) * (kAbsmaxMaxBlocks + static_cast<size_t>(kColParts) * c);
+    if(gran == kPerTensor)   // counter, block maxima, block sums of squares; with fused column sums also their partials
+        return kCtrBytes + sizeof(float) * (2 * kAbsmaxMaxBlocks + static_cast<size_t>(kColParts) * c);
     if(gran == kPerCol) return kCtrBytes + sizeof(float) * kColParts * c;   // same layout: the counter slot stays untouched
     return 0;
 }
 
 template <typename T>
 static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax, float* scale,
-                               float* inv_scale, float* amax_opt, float* colsum_opt, void* workspace, hipStream_t st)
+                               float* inv_scale, float* amax_opt, float* colsum_opt, float* sumsq_opt, void* workspace,
+                               hipStream_t st)
 {
     constexpr int E       = Vec16<T>::N;
     const bool    rows_ok = aligned16(x) && (ld * sizeof(T)) % 16 == 0;
@@ -731,11 +810,12 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
     {
         unsigned int* ctr = static_cast<unsigned int*>(workspace);
         float*        ws  = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes);
+        float*        wsq = ws + kAbsmaxMaxBlocks;          // block sums of squares
         if(colsum_opt)
         {   // per-tensor absmax fused with column sums: one pass over x
-            TensorFinal tfin{ctr, qmax, scale, inv_scale, amax_opt};
+            TensorFinal tfin{ctr, qmax, scale, inv_scale, amax_opt, wsq, sumsq_opt};
             return colreduce_launch<T, OP_SUMMAX>(x, rows, cols, ld, 0.0f, colsum_opt, nullptr, nullptr,
-                                                  ws + kAbsmaxMaxBlocks, ws, tfin, st);
+                                                  ws + 2 * kAbsmaxMaxBlocks, ws, tfin, st);
         }
         const bool    vec  = aligned16(x) && ld == cols;
         const int64_t work = vec ? (rows * cols) / E : rows * cols;
@@ -746,16 +826,16 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
         if(vec)
         {
             if(big)
-                absmax_tensor_kernel<T, true, 1024><<<dim3(nb), dim3(1024), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+                absmax_tensor_kernel<T, true, 1024><<<dim3(nb), dim3(1024), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt, wsq, sumsq_opt);
             else
-                absmax_tensor_kernel<T, true, kBlock><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+                absmax_tensor_kernel<T, true, kBlock><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt, wsq, sumsq_opt);
         }
         else
         {
             if(big)
-                absmax_tensor_kernel<T, false, 1024><<<dim3(nb), dim3(1024), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+                absmax_tensor_kernel<T, false, 1024><<<dim3(nb), dim3(1024), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt, wsq, sumsq_opt);
             else
-                absmax_tensor_kernel<T, false, kBlock><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt);
+                absmax_tensor_kernel<T, false, kBlock><<<dim3(nb), dim3(kBlock), 0, st>>>(x, rows, cols, ld, ws, ctr, qmax, scale, inv_scale, amax_opt, wsq, sumsq_opt);
         }
     }
     else if(gran == kPerRow)
@@ -779,7 +859,7 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
     }
     else
     {
-        TensorFinal none{nullptr, qmax, nullptr, nullptr, nullptr};
+        TensorFinal none{nullptr, qmax, nullptr, nullptr, nullptr, nullptr, nullptr};
         return colreduce_launch<T, OP_MAX>(x, rows, cols, ld, qmax, scale, inv_scale, amax_opt,
                                            reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes), nullptr,
                                            none, st);
@@ -788,14 +868,14 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
 }
 
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax,
-                               float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, void* workspace,
-                               hipStream_t stream)
+                               float* scale, float* inv_scale, float* amax_opt, float* colsum_opt, float* sumsq_opt,
+                               void* workspace, hipStream_t stream)
 {
     if(xdt == kF32)
         return absmax_typed(static_cast<const float*>(x), rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt,
-                            colsum_opt, workspace, stream);
+                            colsum_opt, sumsq_opt, workspace, stream);
     return absmax_typed(static_cast<const __half*>(x), rows, cols, ld, gran, qmax, scale, inv_scale, amax_opt,
-                        colsum_opt, workspace, stream);
+                        colsum_opt, sumsq_opt, workspace, stream);
 }
 
 template <typename T> struct PatchGeom
@@ -918,7 +998,7 @@ size_t colsum_workspace_bytes(int64_t rows, int64_t cols)
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream)
 {
-    TensorFinal none{nullptr, 0.0f, nullptr, nullptr, nullptr};
+    TensorFinal none{nullptr, 0.0f, nullptr, nullptr, nullptr, nullptr, nullptr};
     if(xdt == kF32)
         return colreduce_launch<float, OP_SUM>(static_cast<const float*>(x), rows, cols, cols, 0.0f, out, nullptr, nullptr,
                                                workspace, nullptr, none, stream);

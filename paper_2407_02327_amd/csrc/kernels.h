@@ -19,6 +19,7 @@ size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran,
                                float qmax, float* scale, float* inv_scale, float* amax_opt,
                                float* colsum_opt /* per-tensor only: fused column sums */,
+                               float* sumsq_opt /* per-tensor only: squared norm */,
                                void* workspace /* zero before first use; left zero where it must be */,
                                hipStream_t stream);
 

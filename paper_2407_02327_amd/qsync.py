@@ -28,7 +28,7 @@ lib = ctypes.CDLL(LIB_PATH)
 _vp, _i, _i64, _u64, _sz, _f = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64,
                                  ctypes.c_size_t, ctypes.c_float)
 SIGNATURES = {
-    "qsync_absmax_scale": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "qsync_absmax_scale": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qsync_absmax_workspace_bytes": (_sz, [_i64, _i64, _i]),
     "qsync_quantize": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _i, _i, _u64, _u64, _vp, _vp, _vp, _vp]),
     "qsync_qlinear_fwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
@@ -93,10 +93,10 @@ def qsync_qlinear_bwd_workspace_bytes(tag: int, M: int, N: int, K: int) -> int:
 
 
 def qsync_absmax_scale(x, rows, cols, ld, gran, bits, scale, inv_scale, amax_opt, colsum_opt, workspace,
-                       stream=None) -> None:
+                       stream=None, sumsq_opt=None) -> None:
     _check(lib.qsync_absmax_scale(_ptr(x), dtype_code(x), rows, cols, ld, gran, bits, _ptr(scale), _ptr(inv_scale),
-                                  _ptr(amax_opt), _ptr(colsum_opt), _ptr(workspace), _bytes(workspace),
-                                  _stream(stream)))
+                                  _ptr(amax_opt), _ptr(colsum_opt), _ptr(sumsq_opt), _ptr(workspace),
+                                  _bytes(workspace), _stream(stream)))
 
 
 def qsync_quantize(x, rows, cols, ld, tag, bits, gran, rnd, philox_seed, philox_offset, inv_scale, q_opt, qT_opt,

@@ -33,7 +33,7 @@ def test_strerror_and_version():
 
 def test_absmax_validation():
     g = lib.qsync_absmax_scale
-    f = lambda *a: g(*a[:10], None, *a[10:])        # colsum_opt absent
+    f = lambda *a: g(*a[:10], None, None, *a[10:])        # colsum_opt and sumsq_opt absent
     assert f(None, 0, 4, 4, 4, 0, 8, A, A, None, A, 1 << 20, None) == qsync.ERR_NULL
     assert f(A, 0, 4, 4, 4, 0, 8, None, A, None, A, 1 << 20, None) == qsync.ERR_NULL
     assert f(A, 7, 4, 4, 4, 0, 8, A, A, None, A, 1 << 20, None) == qsync.ERR_BAD_ENUM
@@ -49,7 +49,8 @@ def test_absmax_validation():
     assert f(A, 0, 4, 4, 4, 0, 8, A, A, None, U, 1 << 20, None) == qsync.ERR_ALIGN
     assert f(A, 0, 0, 4, 4, 0, 8, A, A, None, None, 0, None) == qsync.OK          # empty tensor: no-op
     assert f(A, 0, 4, 4, 4, qsync.PER_ROW, 8, A, A, None, None, 0, None) in (qsync.OK, qsync.ERR_HIP)
-    assert g(A, 0, 4, 4, 4, qsync.PER_ROW, 8, A, A, None, A, A, 1 << 20, None) == qsync.ERR_UNSUPPORTED  # colsum needs PER_TENSOR
+    assert g(A, 0, 4, 4, 4, qsync.PER_ROW, 8, A, A, None, A, None, A, 1 << 20, None) == qsync.ERR_UNSUPPORTED  # colsum needs PER_TENSOR
+    assert g(A, 0, 4, 4, 4, qsync.PER_COL, 8, A, A, None, None, A, A, 1 << 20, None) == qsync.ERR_UNSUPPORTED  # so does sumsq
     assert lib.qsync_absmax_workspace_bytes(4, 4, qsync.PER_ROW) == 0
     assert lib.qsync_absmax_workspace_bytes(4, 4, qsync.PER_TENSOR) > 0
     assert lib.qsync_absmax_workspace_bytes(4, 1000, qsync.PER_COL) >= 4 * 1000

@@ -137,6 +137,46 @@ def test_absmax_column_sums_are_reproducible():
         assert_bits_equal(sc, outs[0][1], "scale, repeated run")
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_absmax_with_squared_norm(dtype):
+    """The indicator statistics: one pass yields the scale, the squared norm and (optionally) the column sums."""
+    rng = np.random.default_rng(13)
+    for rows, cols in [(1, 1), (3, 5), (64, 128), (257, 1000), (4096, 512), (33, 8200), (16384, 1024)]:
+        for with_sums in (False, True):
+            say("absmax+sumsq", dtype.__name__, rows, cols, with_sums)
+            x = _data(rng, (rows, cols), dtype, 0.7)
+            xd = dev(x)
+            sc, iv, am, sq = (empty(1, torch.float32) for _ in range(4))
+            cs = empty(cols, torch.float32) if with_sums else None
+            w = ws(Q.qsync_absmax_workspace_bytes(rows, cols, Q.PER_TENSOR))
+            Q.qsync_absmax_scale(xd, rows, cols, cols, Q.PER_TENSOR, 8, sc, iv, am, cs, w, sumsq_opt=sq)
+            st = orc.tensor_stats(x)
+            assert_bits_equal(host(am), orc.absmax(x, "tensor"), "amax")
+            assert_bits_equal(host(sc), orc.scales_from_amax(orc.absmax(x, "tensor"))[0], "scale")
+            assert abs(float(host(sq)[0]) - st["sumsq"]) <= 1e-4 * st["sumsq"] + 1e-30, (float(host(sq)[0]), st["sumsq"])
+            if with_sums:
+                assert_close(host(cs), x.astype(np.float64).sum(axis=0), "column sums")
+
+
+def test_indicator_from_device_statistics_matches_oracle():
+    from paper_2407_02327_amd import indicator as ind
+    rng = np.random.default_rng(14)
+    w = (rng.standard_normal((768, 512)) * 0.02).astype(np.float32)
+    v = rng.standard_normal((2048, 512)).astype(np.float16)
+    g = (rng.standard_normal((2048, 768)) * 1e-3).astype(np.float16)
+    sw, sv, sg = ind.tensor_stats(dev(w)), ind.tensor_stats(dev(v)), ind.tensor_stats(dev(g))
+    ow, ov, og = orc.tensor_stats(w), orc.tensor_stats(v), orc.tensor_stats(g)
+    for got, want in ((sw, ow), (sv, ov), (sg, og)):
+        assert got.amax == want["amax"] and got.e == want["e"] and got.D == want["D"]
+        assert abs(got.sumsq - want["sumsq"]) <= 1e-4 * want["sumsq"]
+    q_x, q_v = ow["amax"] / 127, ov["amax"] / 127
+    for kind in ("fixed", "float"):
+        a = ind.variance_increment(kind, sw, sv, sg, q_x=q_x, q_v=q_v, eps=2.0 ** -9, gamma=1.5, d_o=3, d_L=24)
+        b = orc.variance_increment(kind, ow, ov, og, q_x=q_x, q_v=q_v, eps=2.0 ** -9, gamma=1.5, d_o=3, d_L=24)
+        for k in ("sigma_fp", "sigma_bp", "omega"):
+            assert a[k] == pytest.approx(b[k], rel=2e-4), (kind, k)
+
+
 def _gpu_quantize(xd, rows, cols, ld, tag, gran, rnd, seed, offset, inv, want_q=True, want_t=True, bits=8):
     dt = {Q.INT8: torch.int8, Q.FP16: torch.float16, Q.FP32: torch.float32}[tag]
     q = empty((rows, cols), dt) if want_q else None
