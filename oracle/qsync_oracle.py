@@ -167,6 +167,44 @@ def cast_fp16(x: np.ndarray) -> np.ndarray:
     return x.astype(np.float16)
 
 
+def cast_fp16_stochastic(x: np.ndarray, seed: int = 0, offset: int = 0, k: int = 10) -> np.ndarray:
+    """Floating-point stochastic quantization to binary16 (Appendix, Proposition 2, the two-case rule
+    for the rounded value): with x = s 2^e (1 + m), the mantissa is truncated to k bits and the value moves
+    up by eps = 2^-k (in units of 2^e) with probability (m - floor_k(m)) / eps.
+
+    Worked out on the binary32 significand as integers.  sig * 2^(e-23) is |x| (sig carries the implicit
+    one); D = (23 - k) + max(0, -14 - e) low bits are dropped, so that below the binary16 normal range
+    the spacing stays that of the target format (2^(-14-k)); the dropped part rem gives the threshold
+    floor(rem * 2^16 / 2^D) and the element's 16-bit draw u (same Philox mapping as the fixed-point
+    quantizer) rounds up iff u < threshold.  The result is exactly representable in binary16 unless it
+    reaches 2^16, which becomes infinity as in IEEE narrowing.  binary16 input is returned unchanged.
+    k = 10 is the full binary16 mantissa; the paper quotes k = 9.
+    """
+    if x.dtype == np.float16:
+        return x.copy()
+    if not 7 <= k <= 10:
+        raise ValueError("k must be 7..10")
+    xf = np.ascontiguousarray(x, dtype=_F32)
+    bits = xf.view(np.uint32).astype(np.uint64)
+    neg = (bits >> np.uint64(31)) & np.uint64(1)
+    eb = ((bits >> np.uint64(23)) & np.uint64(0xFF)).astype(np.int64)
+    mant = bits & np.uint64(0x7FFFFF)
+    sig = np.where(eb == 0, mant, mant | np.uint64(1 << 23)).astype(np.uint64)
+    e = np.where(eb == 0, -126, eb - 127)
+    D = (23 - k) + np.maximum(0, -14 - e)
+    D = np.minimum(D, 40).astype(np.uint64)
+    kept = sig >> D
+    rem = sig & ((np.uint64(1) << D) - np.uint64(1))
+    thr = np.where(D >= 16, rem >> np.maximum(D, np.uint64(16)) - np.uint64(16),
+                   rem << (np.uint64(16) - np.minimum(D, np.uint64(16))))
+    u = sr_draws(seed, offset, x.size).reshape(x.shape).astype(np.uint64)
+    res = kept + (u < thr).astype(np.uint64)
+    val = np.ldexp(res.astype(np.float64), (e - 23 + D.astype(np.int64)).astype(np.int64))
+    val = np.where(neg == 1, -val, val)
+    with np.errstate(over="ignore"):
+        return val.astype(np.float16)
+
+
 def dequantize(a: np.ndarray, tensor_scale: float = 1.0, row_scale: Optional[np.ndarray] = None,
                col_scale: Optional[np.ndarray] = None, col_bias: Optional[np.ndarray] = None,
                out_dtype=np.float32) -> np.ndarray:
