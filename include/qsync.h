@@ -112,6 +112,12 @@ size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
  *             cut into eight 16-bit draws, element takes draw i%8 (word (i%8)/2, low half
  *             first).  A call consumes ceil(rows*cols/8) counters.
  *   tag FP16: IEEE round-to-nearest-even narrowing to binary16 (copy if x is binary16).
+ *             With rnd = QSYNC_ROUND_STOCHASTIC and fp32 input: the floating-point stochastic
+ *             quantizer of the paper (Appendix, Proposition 2): the mantissa is truncated to k bits
+ *             (k = bits, 7..10; bits = 0 means 10, the full binary16 mantissa; the paper quotes 9) and
+ *             the value moves up by one spacing 2^(max(e,-14)-k) with probability dropped/spacing,
+ *             decided as u < floor(p * 2^16) with the same per-element Philox draw u as tag INT8.
+ *             Values that reach 2^16 become infinity, as in IEEE narrowing.
  *   tag FP32: copy as fp32 (widening from binary16 is exact).
  *
  * x         [rows, ld] of xdt (QSYNC_F32 or QSYNC_F16).
@@ -121,7 +127,7 @@ size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
  * qT_opt    out, packed [cols, rows], the transpose of q (identical codes), or NULL.
  *           At least one of q_opt, qT_opt is required.  The GEMM entry points take some
  *           operands in transposed form; this is where those copies are made.
- * bits, gran, rnd, seed, offset are ignored for FP16 / FP32.
+ * bits, gran, rnd, seed, offset are ignored for FP16 / FP32 (except the stochastic FP16 case above).
  * Any shape and alignment is accepted; the vectorised path needs cols % 8 == 0, x and ld*sizeof(elem)
  * multiples of 16 bytes, q 16-byte aligned (and rows % 16 == 0 for qT).
  */

@@ -101,8 +101,13 @@ int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t l
     }
     if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
     if(tag == QSYNC_INT8 && (bits < 2 || bits > 8)) return QSYNC_ERR_UNSUPPORTED;
+    const bool fp_sr = tag == QSYNC_FP16 && rnd == QSYNC_ROUND_STOCHASTIC && xdt == QSYNC_F32;
+    if(fp_sr && bits != 0 && (bits < 7 || bits > 10)) return QSYNC_ERR_UNSUPPORTED;
     if(rows == 0 || cols == 0) return QSYNC_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if(fp_sr)
+        return hip_status(launch_convert_sr(static_cast<const float*>(x), rows, cols, ld, bits == 0 ? 10 : bits,
+                                            philox_seed, philox_offset, q_opt, qT_opt, st));
     if(tag == QSYNC_INT8)
     {
         const int qmax = (1 << (bits - 1)) - 1;

@@ -636,12 +636,36 @@ template <> __device__ __forceinline__ float  convert_elem<float, __half>(__half
 template <> __device__ __forceinline__ __half convert_elem<__half, float>(float v) { return __float2half_rn(v); }
 template <> __device__ __forceinline__ __half convert_elem<__half, __half>(__half v) { return v; }
 
+// Floating-point stochastic quantization of one binary32 value to binary16 (Appendix, Proposition 2:
+// truncate the mantissa to k bits, move up by one spacing with probability dropped / spacing).
+// Integer arithmetic on the significand: sig * 2^(e-23) = |x|; D = (23-k) + max(0, -14-e) low bits are
+// dropped (below the binary16 normal range the spacing stays 2^(-14-k)); up iff u16 < floor(rem * 2^16 / 2^D).
+// The result is exact in binary16 (or reaches 2^16 and narrows to infinity).
+__device__ __forceinline__ __half sr_narrow(float xv, int k, uint32_t u16)
+{
+    const uint32_t bits = __float_as_uint(xv);
+    const uint32_t eb   = (bits >> 23) & 0xFFu;
+    const uint32_t mant = bits & 0x7FFFFFu;
+    const uint64_t sig  = eb == 0 ? mant : (mant | 0x800000u);
+    const int      e    = eb == 0 ? -126 : static_cast<int>(eb) - 127;
+    int            D    = (23 - k) + (e < -14 ? -14 - e : 0);
+    D                   = D > 40 ? 40 : D;
+    const uint64_t kept = sig >> D;
+    const uint64_t rem  = sig & ((uint64_t(1) << D) - 1);
+    const uint64_t thr  = D >= 16 ? (rem >> (D - 16)) : (rem << (16 - D));
+    const uint32_t res  = static_cast<uint32_t>(kept) + (u16 < thr ? 1u : 0u);       // <= 2^(k+1)
+    float          val  = ldexpf(static_cast<float>(res), e - 23 + D);                // exact
+    val                 = (bits >> 31) ? -val : val;
+    return __float2half_rn(val);                                                     // exact, or overflow to infinity
+}
+
 // 64x64 tile; the transposed copy goes through a padded LDS tile so that both copies are
-// written with lanes along the contiguous axis.
-template <typename Ti, typename To>
+// written with lanes along the contiguous axis.  SR (binary32 -> binary16 only) draws the element's
+// 16-bit number from the Philox block of its row-major index, as the fixed-point quantizer does.
+template <typename Ti, typename To, bool SR>
 __global__ __launch_bounds__(kBlock) void convert_kernel(const Ti* __restrict__ x, int64_t rows, int64_t cols,
                                                          int64_t ld, To* __restrict__ q, To* __restrict__ qT,
-                                                         int64_t grid_x)
+                                                         int64_t grid_x, uint64_t seed, uint64_t offset, int k)
 {
     __shared__ To tile[64][65];
     const int64_t by = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
@@ -653,7 +677,15 @@ __global__ __launch_bounds__(kBlock) void convert_kernel(const Ti* __restrict__ 
         const int64_t r = by * 64 + lr, c = bx * 64 + tx;
         if(r < rows && c < cols)
         {
-            const To v = convert_elem<To, Ti>(x[r * ld + c]);
+            To v;
+            if constexpr(SR)
+            {
+                const uint64_t idx = static_cast<uint64_t>(r) * static_cast<uint64_t>(cols) + static_cast<uint64_t>(c);
+                const uint4    blk = philox_group(seed, offset, idx >> 3);
+                v = sr_narrow(x[r * ld + c], k, philox_draw16(blk, static_cast<int>(idx & 7)));
+            }
+            else
+                v = convert_elem<To, Ti>(x[r * ld + c]);
             if(q) q[r * cols + c] = v;
             tile[lr][tx] = v;
         }
@@ -944,8 +976,8 @@ static hipError_t convert_typed(const void* x, int64_t rows, int64_t cols, int64
                                 hipStream_t st)
 {
     const int64_t gx = (cols + 63) / 64, gy = (rows + 63) / 64;
-    convert_kernel<Ti, To><<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, st>>>(
-        static_cast<const Ti*>(x), rows, cols, ld, static_cast<To*>(q), static_cast<To*>(qT), gx);
+    convert_kernel<Ti, To, false><<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, st>>>(
+        static_cast<const Ti*>(x), rows, cols, ld, static_cast<To*>(q), static_cast<To*>(qT), gx, 0, 0, 0);
     return hipGetLastError();
 }
 
@@ -956,6 +988,15 @@ hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, in
     if(xdt == kF32 && outdt == kF32) return convert_typed<float, float>(x, rows, cols, ld, q, qT, stream);
     if(xdt == kF16 && outdt == kF16) return convert_typed<__half, __half>(x, rows, cols, ld, q, qT, stream);
     return convert_typed<__half, float>(x, rows, cols, ld, q, qT, stream);
+}
+
+hipError_t launch_convert_sr(const float* x, int64_t rows, int64_t cols, int64_t ld, int mantissa_bits, uint64_t seed,
+                             uint64_t offset, void* q, void* qT, hipStream_t stream)
+{
+    const int64_t gx = (cols + 63) / 64, gy = (rows + 63) / 64;
+    convert_kernel<float, __half, true><<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, stream>>>(
+        x, rows, cols, ld, static_cast<__half*>(q), static_cast<__half*>(qT), gx, seed, offset, mantissa_bits);
+    return hipGetLastError();
 }
 
 template <typename Ti, typename To>

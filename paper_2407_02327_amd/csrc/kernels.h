@@ -29,6 +29,9 @@ hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t co
                                 int8_t* q, int8_t* qT, hipStream_t stream);
 hipError_t launch_convert(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int outdt,
                           void* q, void* qT, hipStream_t stream);
+// binary32 -> binary16 with stochastic rounding of the mantissa to `mantissa_bits` (7..10) bits
+hipError_t launch_convert_sr(const float* x, int64_t rows, int64_t cols, int64_t ld, int mantissa_bits,
+                             uint64_t seed, uint64_t offset, void* q, void* qT, hipStream_t stream);
 
 // ---- standalone dequantize, column sums -----------------------------------------------
 hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld,

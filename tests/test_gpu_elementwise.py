@@ -92,6 +92,30 @@ def test_absmax_fused_with_column_sums(dtype):
     assert e.value.status == Q.ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("k", [10, 9, 7])
+def test_fp16_stochastic_cast_bit_exact(k):
+    """Floating-point stochastic quantization to binary16: same draws, same integer decision, same bits."""
+    rng = np.random.default_rng(31)
+    for rows, cols in [(1, 1), (5, 7), (64, 64), (130, 72), (257, 1000), (1024, 768)]:
+        say("fp16 SR cast", k, rows, cols)
+        x = (rng.standard_normal((rows, cols)) * np.exp(rng.uniform(-14, 9, (rows, cols)))).astype(np.float32)
+        if rows * cols > 16:
+            x.reshape(-1)[:8] = [0.0, -0.0, 65504.0, 65530.0, 2.0 ** -24, -2.0 ** -26, 1.0, 2.0 - 2.0 ** -12]
+        xd = dev(x)
+        q, qt = empty((rows, cols), torch.float16), empty((cols, rows), torch.float16)
+        Q.qsync_quantize(xd, rows, cols, cols, Q.FP16, k, 0, Q.ROUND_STOCHASTIC, 99, 4242, None, q, qt)
+        want = orc.cast_fp16_stochastic(x, seed=99, offset=4242, k=k)
+        assert_bits_equal(host(q).view(np.uint16), want.view(np.uint16), "fp16 SR")
+        assert_bits_equal(host(qt).view(np.uint16), np.ascontiguousarray(want.T).view(np.uint16), "fp16 SR transposed")
+    with pytest.raises(Q.QsyncError) as e:
+        Q.qsync_quantize(xd, rows, cols, cols, Q.FP16, 5, 0, Q.ROUND_STOCHASTIC, 1, 0, None, q, qt)
+    assert e.value.status == Q.ERR_UNSUPPORTED
+    # binary16 input: a copy whatever the rounding mode
+    h = x.astype(np.float16)
+    Q.qsync_quantize(dev(h), rows, cols, cols, Q.FP16, 0, 0, Q.ROUND_STOCHASTIC, 1, 0, None, q, None)
+    assert_bits_equal(host(q).view(np.uint16), h.view(np.uint16), "fp16 copy")
+
+
 def test_absmax_workspace_is_reusable_without_clearing():
     """The arrival counters at the start of the workspace are zeroed once by the caller and left zero
     by every call: one buffer serves a sequence of different reductions, each checked against the oracle."""
