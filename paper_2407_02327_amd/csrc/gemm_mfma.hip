@@ -617,10 +617,18 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
     auto ntiles = [&](int t) { return ((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn); };
     const int64_t cus = 256;
     int tile = 2;
-    // largest tile that still yields at least ~one workgroup per CU
+    // Among the tiles that yield at least ~one workgroup per CU, the one with the least padded work per
+    // unit of measured efficiency (relative MFMA rates of the three tiles at saturation): a 64-wide
+    // output wastes three quarters of a 256-wide tile.
+    const double eff[kNumTiles] = {1.0, 0.62, 0.30};
+    double       best = -1.0;
     for(int t = 0; t < kNumTiles; ++t)
-        if(ntiles(t) >= (cus * 3) / 4) { tile = t; break; }
-    if(ntiles(tile) < (cus * 3) / 4) tile = (M > 64 || N > 64) ? 1 : 2;
+        if(ntiles(t) >= (cus * 3) / 4)
+        {
+            const double cost = static_cast<double>(ntiles(t)) * kTiles[t].bm * kTiles[t].bn / eff[t];
+            if(best < 0.0 || cost < best) { best = cost; tile = t; }
+        }
+    if(best < 0.0) tile = (M > 64 || N > 64) ? 1 : 2;
     int splits = 1;
     // Too few large tiles for the chip but a long contraction (the weight-gradient shape): split K
     // over the large tile rather than fall back to the smaller, less efficient one.
