@@ -32,6 +32,7 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <cmath>
 #include <type_traits>
 #include <utility>
 
@@ -615,37 +616,42 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
     const int64_t kb     = K * (prec == 8 ? 1 : 2);
     const int64_t ktiles = (kb + kRowBytes - 1) / kRowBytes;
     auto ntiles = [&](int t) { return ((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn); };
-    const int64_t cus = 256;
-    int tile = 2;
-    // Among the tiles that yield at least ~one workgroup per CU, the one with the least padded work per
-    // unit of measured efficiency (relative MFMA rates of the three tiles at saturation): a 64-wide
-    // output wastes three quarters of a 256-wide tile.
-    const double eff[kNumTiles] = {1.0, 0.62, 0.30};
-    double       best = -1.0;
+    // Plan = (tile, K splits) with the smallest estimated time.  The estimate is a small model
+    // calibrated on gfx950 measurements of this kernel (int8, random codes; binary16 scales alike):
+    //   a compute unit retires `rate` Mop/us of a tile's work (it grows with the workgroups that share
+    //   the unit, up to `rate_max`), every workgroup costs `ovh` us of launch, first-load latency and
+    //   epilogue (overlapped among co-resident workgroups), split K adds its reduction pass.
+    struct TileModel { double rate1, rate_max, ovh; int occ; int fill; };
+    const TileModel model[kNumTiles] = {{8.6, 8.6, 8.0, 1, 256}, {5.4, 6.5, 5.0, 2, 512}, {2.6, 6.0, 5.0, 4, 512}};
+    const double    cus = 256.0;
+    auto estimate = [&](int t, int64_t s) {
+        const TileModel& m     = model[t];
+        const double     wgs   = static_cast<double>(ntiles(t)) * static_cast<double>(s);
+        const double     per   = std::ceil(wgs / cus);                                   // workgroups per unit
+        const double     share = per < m.occ ? per : m.occ;                              // co-resident ones
+        const double     rate  = m.rate1 * share < m.rate_max ? m.rate1 * share : m.rate_max;
+        const double     kt    = std::ceil(static_cast<double>(ktiles) / static_cast<double>(s));
+        const double     mop   = 2.0 * kTiles[t].bm * kTiles[t].bn * kRowBytes * 1e-6;   // per K tile (int8 ops)
+        double           us    = per * kt * mop / rate + m.ovh * std::ceil(per / m.occ);
+        if(s > 1) us += 3.0 + static_cast<double>(s + 1) * static_cast<double>(M) * static_cast<double>(N) * 4.0 / 5e6;
+        return us;
+    };
+    int     tile = 0, splits = 1;
+    double  best = -1.0;
     for(int t = 0; t < kNumTiles; ++t)
-        if(ntiles(t) >= (cus * 3) / 4)
+    {
+        if(force_tile >= 0 && force_tile < kNumTiles && t != force_tile) continue;
+        int64_t cand[2] = {1, 1};
+        int64_t s       = model[t].fill / ntiles(t);
+        if(s > ktiles / 8) s = ktiles / 8;                    // keep at least 8 K tiles per split
+        if(s > 128) s = 128;
+        if(s >= 2 && !(force_tile >= 0 && force_splits < 0)) cand[1] = s;
+        for(int c = 0; c < 2; ++c)
         {
-            const double cost = static_cast<double>(ntiles(t)) * kTiles[t].bm * kTiles[t].bn / eff[t];
-            if(best < 0.0 || cost < best) { best = cost; tile = t; }
+            if(c == 1 && cand[1] == 1) break;
+            const double us = estimate(t, cand[c]);
+            if(best < 0.0 || us < best) { best = us; tile = t; splits = static_cast<int>(cand[c]); }
         }
-    if(best < 0.0) tile = (M > 64 || N > 64) ? 1 : 2;
-    int splits = 1;
-    // Too few large tiles for the chip but a long contraction (the weight-gradient shape): split K
-    // over the large tile rather than fall back to the smaller, less efficient one.
-    if(tile != 0 && ktiles >= 16)
-    {
-        int64_t s = cus / ntiles(0);
-        if(s > ktiles / 8) s = ktiles / 8;
-        if(s >= 2 && ntiles(0) * s >= (cus * 3) / 4) { tile = 0; splits = static_cast<int>(s); }
-    }
-    if(force_tile >= 0 && force_tile < kNumTiles) { tile = force_tile; splits = 1; }
-    const int64_t nt = ntiles(tile);
-    if(splits == 1 && nt * 2 <= cus && ktiles >= 8)
-    {
-        int64_t s = cus / nt;
-        if(s > ktiles / 4) s = ktiles / 4;     // keep at least 4 K steps per split
-        if(s > 64) s = 64;
-        splits = static_cast<int>(s < 1 ? 1 : s);
     }
     if(force_splits >= 1) splits = force_splits;
     if(splits > ktiles) splits = static_cast<int>(ktiles < 1 ? 1 : ktiles);
