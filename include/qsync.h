@@ -202,6 +202,23 @@ size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 
 /*
+ * qsync_im2col3x3_i8 - patches of a 3x3, stride-1, pad-1 convolution, built from int8 codes.
+ * Paper: Backend section (low-precision convolution runs on NHWC tensors; the convolution is
+ * lowered to the GEMM of the linear operator).  The activation is quantized once as an NHWC
+ * tensor (qsync_absmax_scale + qsync_quantize on [nimg*H*W, C]) and expanded afterwards; the
+ * codes equal those of quantizing the fp16 patch matrix with the same per-tensor scale.
+ *
+ *   a [m, (kh*3+kw)*C + c] = xq[n, h+kh-1, w+kw-1, c]   (0 outside the image),  m = (n*H + h)*W + w
+ *   aT[k, m]               = a[m, k]
+ *
+ * xq      [nimg, H, W, C] int8, 16-byte aligned.  C % 16 == 0 (QSYNC_ERR_UNSUPPORTED otherwise).
+ * a_opt   out, [nimg*H*W, 9*C] int8, 16-byte aligned, or NULL.
+ * aT_opt  out, [9*C, nimg*H*W] int8, 16-byte aligned, or NULL; needs nimg*H*W % 16 == 0 (QSYNC_ERR_ALIGN).
+ */
+int qsync_im2col3x3_i8(const void* xq, int64_t nimg, int64_t H, int64_t W, int64_t C,
+                       void* a_opt, void* aT_opt, void* stream);
+
+/*
  * qsync_dequantize - standalone dequantizer (used when it is not fused into a GEMM).
  * Paper: Indicator section (x_hat = code * q), Cost Mapper (layer-wise / channel-wise
  * dequantizers as element-wise kernels).

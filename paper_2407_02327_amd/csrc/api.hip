@@ -248,6 +248,22 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
     return QSYNC_OK;
 }
 
+int qsync_im2col3x3_i8(const void* xq, int64_t nimg, int64_t H, int64_t W, int64_t C, void* a_opt, void* aT_opt,
+                       void* stream)
+{
+    if(!xq || (!a_opt && !aT_opt)) return QSYNC_ERR_NULL;
+    if(nimg < 0 || H < 0 || W < 0 || C < 0 || H > (1 << 15) || W > (1 << 15) || C > (1 << 15)) return QSYNC_ERR_BAD_SHAPE;
+    if(nimg > 0 && H > 0 && W > 0 && nimg > (int64_t(1) << 40) / (H * W)) return QSYNC_ERR_BAD_SHAPE;
+    const int64_t M = nimg * H * W;
+    if(M == 0 || C == 0) return QSYNC_OK;
+    if(C % 16 != 0) return QSYNC_ERR_UNSUPPORTED;
+    if(((M + 511) / 512) * ((9 * C / 16 + 7) / 8) >= (int64_t(1) << 31)) return QSYNC_ERR_BAD_SHAPE;
+    if(!aligned16(xq) || (a_opt && !aligned16(a_opt)) || (aT_opt && (!aligned16(aT_opt) || M % 16 != 0))) return QSYNC_ERR_ALIGN;
+    return hip_status(launch_im2col3x3_i8(static_cast<const int8_t*>(xq), nimg, static_cast<int>(H), static_cast<int>(W),
+                                          static_cast<int>(C), static_cast<int8_t*>(a_opt), static_cast<int8_t*>(aT_opt),
+                                          static_cast<hipStream_t>(stream)));
+}
+
 int qsync_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t ld, const float* row_scale_opt,
                      const float* col_scale_opt, float tensor_scale, const float* tensor_scale_dev_opt,
                      const float* col_bias_opt, void* y, int ydt, void* stream)

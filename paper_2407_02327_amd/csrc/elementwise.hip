@@ -629,6 +629,66 @@ __global__ __launch_bounds__(kBlock) void quantize_generic_kernel(const T* __res
     }
 }
 
+// ------------------------------------------------------------------ 3x3 im2col on int8 codes
+// Patches of a 3x3, stride-1, pad-1 convolution built from the already quantized NHWC activation:
+// A[m, (kh*3+kw)*C + c] = xq[n, h+kh-1, w+kw-1, c] (0 outside the image), m = (n*H + h)*W + w.
+// The codes of the patch matrix equal the codes of the quantized fp16 patch matrix (per-tensor
+// scale, zeros map to zero), but the activation is read and quantized once instead of nine times.
+// Same lane geometry as the quantizer: a lane owns 16 output pixels x 16 K bytes (one tap, 16
+// channels; needs C % 16 == 0), a wavefront 128 pixels x 128 K bytes; row-major rows leave as
+// 16-byte stores, the transposed copy after a byte transpose in registers (needs M % 16 == 0).
+__global__ __launch_bounds__(kBlock) void im2col3x3_i8_kernel(const int8_t* __restrict__ xq, int64_t nimg, int H, int W,
+                                                              int C, int8_t* __restrict__ a, int8_t* __restrict__ aT,
+                                                              int64_t grid_x)
+{
+    const int64_t M  = nimg * H * W;
+    const int     K  = 9 * C, nchunk = K / 16;
+    const int     lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
+    const int64_t by = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
+    const int64_t m0 = (by * (kBlock / kWaveSize) + wave) * 128 + (lane / 8) * 16;
+    const int     ch = static_cast<int>(bx) * 8 + (lane % 8);             // 16-byte chunk of the K axis
+    if(m0 >= M || ch >= nchunk) return;
+    const int k0  = ch * 16;
+    const int tap = k0 / C, c0 = k0 - tap * C;
+    const int dh  = tap / 3 - 1, dw = tap % 3 - 1;
+    uint32_t  code[16][4];
+#pragma unroll
+    for(int i = 0; i < 16; ++i)
+    {
+        const int64_t m = m0 + i;
+        uint4         v = make_uint4(0, 0, 0, 0);
+        if(m < M)
+        {
+            const int64_t hw = m % (static_cast<int64_t>(H) * W), n = m / (static_cast<int64_t>(H) * W);
+            const int     h = static_cast<int>(hw / W) + dh, w = static_cast<int>(hw % W) + dw;
+            if(h >= 0 && h < H && w >= 0 && w < W)
+                v = *reinterpret_cast<const uint4*>(xq + ((n * H + h) * W + w) * C + c0);
+        }
+        code[i][0] = v.x; code[i][1] = v.y; code[i][2] = v.z; code[i][3] = v.w;
+    }
+    if(a)
+    {
+#pragma unroll
+        for(int i = 0; i < 16; ++i)
+            if(m0 + i < M)
+                *reinterpret_cast<uint4*>(a + (m0 + i) * K + k0) = make_uint4(code[i][0], code[i][1], code[i][2], code[i][3]);
+    }
+    if(aT)
+    {   // M % 16 == 0 here, so the 16 pixels all exist
+#pragma unroll
+        for(int col = 0; col < 16; ++col)
+        {
+            uint32_t t[4];
+#pragma unroll
+            for(int g = 0; g < 4; ++g)
+                t[g] = byte_of(code[4 * g + 0][col / 4], col % 4) | (byte_of(code[4 * g + 1][col / 4], col % 4) << 8)
+                     | (byte_of(code[4 * g + 2][col / 4], col % 4) << 16)
+                     | (byte_of(code[4 * g + 3][col / 4], col % 4) << 24);
+            *reinterpret_cast<uint4*>(aT + (static_cast<int64_t>(k0) + col) * M + m0) = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ cast / copy (+ transpose)
 template <typename To, typename Ti> __device__ __forceinline__ To convert_elem(Ti v);
 template <> __device__ __forceinline__ float  convert_elem<float, float>(float v) { return v; }
@@ -1028,6 +1088,15 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
     if(adt == kI8 && ydt == kF32)
         return dequantize_typed<int8_t, float>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
     return dequantize_typed<int8_t, __half>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
+}
+
+hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
+                               hipStream_t stream)
+{
+    const int64_t M  = nimg * H * W;
+    const int64_t gx = (9 * C / 16 + 7) / 8, gy = (M + 511) / 512;
+    im2col3x3_i8_kernel<<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, stream>>>(xq, nimg, H, W, C, a, aT, gx);
+    return hipGetLastError();
 }
 
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols)

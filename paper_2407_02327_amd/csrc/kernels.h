@@ -38,6 +38,9 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
                              const float* row_scale, const float* col_scale, float tensor_scale,
                              const float* tensor_scale_dev, const float* col_bias, void* y, int ydt,
                              hipStream_t stream);
+// 3x3 / stride 1 / pad 1 patches of an int8 NHWC tensor: a [M, 9C] and/or aT [9C, M], M = nimg*H*W
+hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
+                               hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream);

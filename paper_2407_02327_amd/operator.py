@@ -91,6 +91,20 @@ class QLinear:
         else:
             Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, self.xq, self.xqT, stream)
 
+    def convert_x_nhwc(self, act: torch.Tensor, stream=None) -> None:
+        """3x3 / stride 1 / pad 1 convolution lowered to this operator (K = 9*C): the NHWC activation is
+        quantized once and its codes are expanded into the patch matrix and its transpose, instead of
+        quantizing a nine times larger fp16 patch matrix (INT8 tag only)."""
+        b, h, w, c = act.shape
+        assert self.tag == Q.INT8 and b * h * w == self.M and 9 * c == self.K
+        if not hasattr(self, "xq_nhwc"):
+            self.xq_nhwc = torch.empty(b * h * w, c, dtype=torch.int8, device=act.device)
+        Q.qsync_absmax_scale(act, self.M, c, c, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None, self.ws_absmax,
+                             stream)
+        Q.qsync_quantize(act, self.M, c, c, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq_nhwc,
+                         None, stream)
+        Q.qsync_im2col3x3_i8(self.xq_nhwc, b, h, w, c, self.xq, self.xqT, stream)
+
     def convert_w(self, w: torch.Tensor, stream=None) -> None:
         N, K = self.N, self.K
         if self.tag != Q.INT8:

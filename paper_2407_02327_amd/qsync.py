@@ -36,6 +36,7 @@ SIGNATURES = {
                                _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
+    "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _vp, _i, _vp]),
     "qsync_last_hip_error": (_i, []),
     "qsync_strerror": (ctypes.c_char_p, [_i]),
@@ -121,6 +122,10 @@ def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, 
                                  F32 if dy_float_opt is None else dtype_code(dy_float_opt),
                                  _ptr(acc_dx_dump_opt), _ptr(acc_dw_dump_opt), _ptr(workspace), _bytes(workspace),
                                  _stream(stream)))
+
+
+def qsync_im2col3x3_i8(xq, nimg, H, W, C, a_opt, aT_opt, stream=None) -> None:
+    _check(lib.qsync_im2col3x3_i8(_ptr(xq), nimg, H, W, C, _ptr(a_opt), _ptr(aT_opt), _stream(stream)))
 
 
 def qsync_dequantize(a, rows, cols, ld, row_scale_opt, col_scale_opt, tensor_scale, col_bias_opt, y,

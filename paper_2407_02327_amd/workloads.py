@@ -12,7 +12,7 @@ fixed order, so that the oracle and the GPU always see identical bits.
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import Dict, List
+from typing import Dict, List, Optional
 
 import numpy as np
 
@@ -31,6 +31,7 @@ class LinearCase:
     dy_round: str = "nearest"          # "nearest" | "stochastic"
     philox_seed: int = 0
     tags: List[int] = field(default_factory=lambda: [INT8])
+    nhwc: Optional[np.ndarray] = None  # convolution cases: the [B,H,W,C] activation whose 3x3 im2col is x
 
     @property
     def mnk(self):
@@ -89,7 +90,7 @@ def config3(batch: int = 64) -> LinearCase:
     dy = _normal(rng, (batch * 56 * 56, 64), 1e-3, np.float16)
     x = im2col_nhwc_3x3(act)
     return LinearCase("c3_resnet50_conv3x3", x, w, np.zeros(64, np.float32), dy,
-                      w_gran="row", dy_round="stochastic", philox_seed=3, tags=[INT8, FP16])
+                      w_gran="row", dy_round="stochastic", philox_seed=3, tags=[INT8, FP16], nhwc=act)
 
 
 @dataclass

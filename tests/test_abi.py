@@ -125,6 +125,17 @@ def test_dequantize_validation():
     assert f(A, 3, 4, 0, 0, None, None, 1.0, None, None, A, 0, None) == qsync.OK
 
 
+def test_im2col_validation():
+    f = lib.qsync_im2col3x3_i8
+    assert f(None, 1, 4, 4, 16, A, None, None) == qsync.ERR_NULL
+    assert f(A, 1, 4, 4, 16, None, None, None) == qsync.ERR_NULL
+    assert f(A, -1, 4, 4, 16, A, None, None) == qsync.ERR_BAD_SHAPE
+    assert f(A, 1, 4, 4, 24, A, None, None) == qsync.ERR_UNSUPPORTED          # C % 16
+    assert f(A, 1, 3, 3, 16, None, A, None) == qsync.ERR_ALIGN                # M % 16 for the transposed copy
+    assert f(U, 1, 4, 4, 16, A, None, None) == qsync.ERR_ALIGN
+    assert f(A, 0, 4, 4, 16, A, None, None) == qsync.OK
+
+
 def test_no_gpu_gives_hip_error_not_a_crash():
     import torch
     if torch.cuda.is_available():

@@ -116,6 +116,27 @@ def test_fp16_stochastic_cast_bit_exact(k):
     assert_bits_equal(host(q).view(np.uint16), h.view(np.uint16), "fp16 copy")
 
 
+def test_im2col_on_codes_bit_exact():
+    from paper_2407_02327_amd import workloads as wl
+    rng = np.random.default_rng(41)
+    for (b, h, w, c) in [(1, 4, 4, 16), (2, 7, 5, 16), (3, 8, 8, 64), (2, 56, 56, 64), (1, 13, 16, 48)]:
+        say("im2col codes", b, h, w, c)
+        xq = rng.integers(-127, 128, (b, h, w, c)).astype(np.int8)
+        M, K = b * h * w, 9 * c
+        want = wl.im2col_nhwc_3x3(xq)
+        a = empty((M, K), torch.int8); a.fill_(5)
+        aT = None
+        if M % 16 == 0:
+            aT = empty((K, M), torch.int8); aT.fill_(5)
+        Q.qsync_im2col3x3_i8(dev(xq), b, h, w, c, a, aT)
+        assert_bits_equal(host(a), want, "patch matrix")
+        if aT is not None:
+            assert_bits_equal(host(aT), np.ascontiguousarray(want.T), "transposed patch matrix")
+            a2 = empty((K, M), torch.int8)
+            Q.qsync_im2col3x3_i8(dev(xq), b, h, w, c, None, a2)            # transposed copy alone
+            assert_bits_equal(host(a2), np.ascontiguousarray(want.T), "transposed patch matrix alone")
+
+
 def test_absmax_workspace_is_reusable_without_clearing():
     """The arrival counters at the start of the workspace are zeroed once by the caller and left zero
     by every call: one buffer serves a sequence of different reductions, each checked against the oracle."""

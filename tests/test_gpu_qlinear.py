@@ -258,3 +258,28 @@ def test_int8_forward_fp16_backward_small_and_ragged(w_gran):
 
 def test_int8_forward_fp16_backward_config2_full_size():
     run_case_fp16_backward(wl.config2(), y_dtype=np.float16)
+
+
+def test_conv_activation_quantized_once_then_expanded():
+    """Config 3 through the NHWC path: absmax + quantize of the activation, int8 im2col, then the same GEMMs;
+    codes, scales and accumulators equal those of quantizing the fp16 patch matrix (the oracle's operator)."""
+    case = wl.config3(batch=4)
+    M, N, K = case.mnk
+    op = QLinear(Q.INT8, M, N, K, x_dtype=torch.float16, w_dtype=torch.float32, dy_dtype=torch.float16,
+                 y_dtype=torch.float16, w_gran=GRAN[case.w_gran], dy_round=RND[case.dy_round],
+                 philox_seed=case.philox_seed, dump_acc=True)
+    op.bias.copy_(dev(case.bias))
+    op.convert_w(dev(case.w))
+    op.convert_x_nhwc(dev(case.nhwc))
+    op.gemm_fwd()
+    op.backward(dev(case.dy))
+    ref = orc.operator_fwd_bwd(Q.INT8, case.x, case.w, case.bias, case.dy, case.w_gran, case.dy_round,
+                               seed=case.philox_seed, offset=0, y_dtype=np.float64, dx_dtype=np.float64,
+                               dw_dtype=np.float64)
+    assert_bits_equal(host(op.sx), ref["sx"], "sx")
+    assert_bits_equal(host(op.xq), ref["xq"], "xq")
+    assert_bits_equal(host(op.xqT), ref["xq"].T, "xqT")
+    assert_bits_equal(host(op.acc), ref["acc"], "fwd accumulators")
+    assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "dW accumulators")
+    assert_close(host(op.y), ref["y"], "Y")
+    assert_close(host(op.dw), ref["dw"], "dW")

@@ -148,3 +148,25 @@ def test_fp16_cast_is_ieee_nearest_even():
     assert h[0] == np.float16(1.0) and h[1] == np.float16(1.0 + 2 * 2.0**-10) and h[2] == np.float16(1.0 + 2.0**-10)
     assert h[3] == np.float16(65504.0) and np.isinf(h[4])
     assert h[5] == 0 and h[6] == np.float16(2.0**-23)
+
+
+def test_quantizing_the_patch_matrix_equals_expanding_the_quantized_activation():
+    """A 3x3 im2col only copies activation values and inserts zeros, every activation value appears in it,
+    and zero quantizes to zero: with a per-tensor scale the codes of the patch matrix are the patches of
+    the codes.  This is what lets the GPU path quantize the NHWC activation once and expand int8 codes."""
+    from paper_2407_02327_amd import workloads as wl
+    rng = np.random.default_rng(40)
+    act = np.abs(rng.standard_normal((2, 7, 5, 16))).astype(np.float16)
+    x = wl.im2col_nhwc_3x3(act)
+    a_act, a_x = orc.absmax(act.reshape(-1, 16), "tensor"), orc.absmax(x, "tensor")
+    assert a_act.tobytes() == a_x.tobytes()
+    _, inv = orc.scales_from_amax(a_x)
+    q_of_patches = orc.quantize_int(x, inv, "tensor", "nearest")
+    patches_of_q = wl.im2col_nhwc_3x3(orc.quantize_int(act.reshape(-1, 16), inv, "tensor", "nearest").reshape(act.shape))
+    assert np.array_equal(q_of_patches, patches_of_q)
+    # hand check of one row: output pixel (n=1, h=0, w=4) is a corner: taps with h-1 or w+1 are zero
+    m = (1 * 7 + 0) * 5 + 4
+    row = patches_of_q[m].reshape(3, 3, 16)
+    assert not row[0].any() and not row[:, 2].any()
+    centre = orc.quantize_int(act[1, 0, 4].reshape(1, 16), inv, "tensor", "nearest")[0]
+    assert np.array_equal(row[1, 1], centre)
