@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c5", choices=["c5", "c2", "c3"])
+    ap.add_argument("--conv-input", default="nhwc", choices=["nhwc", "patches"],
+                    help="workload c3 with tag int8: start each step from the NHWC activation (quantize it once, "
+                         "expand int8 codes into the patch matrix) or from the fp16 patch matrix")
     ap.add_argument("--tag", default="int8", choices=["int8", "fp16"])
     ap.add_argument("--bwd-tag", default=None, choices=[None, "fp16"],
                     help="fp16 with --tag int8: the paper's pairing, FP16 backward on the dequantized saved codes")
@@ -140,7 +143,10 @@ def main():
                      dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
                      philox_seed=c.philox_seed, bwd_tag=(Q.FP16 if args.bwd_tag == "fp16" and tag == Q.INT8 else None))
         ops_objs.append(op)
-        dev_in.append((torch.from_numpy(c.x).cuda(), torch.from_numpy(c.w).cuda(), torch.from_numpy(c.dy).cuda()))
+        nhwc = c.nhwc is not None and tag == Q.INT8 and args.conv_input == "nhwc"
+        x_in = torch.from_numpy(c.nhwc if nhwc else c.x).cuda()
+        op.convert_act = op.convert_x_nhwc if nhwc else op.convert_x
+        dev_in.append((x_in, torch.from_numpy(c.w).cuda(), torch.from_numpy(c.dy).cuda()))
     torch.cuda.synchronize()
 
     ev = EventLog()
@@ -167,10 +173,10 @@ def main():
             if args.w_side_stream:
                 side.wait_stream(st)
                 op.convert_w(w, side)
-                run("convert_x", lambda: op.convert_x(x, st), st)
+                run("convert_x", lambda: op.convert_act(x, st), st)
                 st.wait_stream(side)
             else:
-                run("convert_x", lambda: (op.convert_w(w, st), op.convert_x(x, st)), st)
+                run("convert_x", lambda: (op.convert_w(w, st), op.convert_act(x, st)), st)
             run("gemm_fwd", lambda: op.gemm_fwd(st), st)
             run("convert_dy", lambda: op.convert_dy(dy, st), st)
             run("gemm_bwd", lambda: op.gemm_bwd(dy, st), st)
@@ -289,7 +295,8 @@ def main():
                    "w_scale": "per-output-channel",
                    "dy_rounding": "stochastic (Philox4x32-10)" if args.bwd_tag is None else "none (FP16 backward)",
                    "bwd_tag": args.bwd_tag or args.tag,
-                   "operator_streams": nstreams},
+                   "operator_streams": nstreams,
+                   **({"conv_input": args.conv_input} if any(c.nhwc is not None for c in cases) and tag == Q.INT8 else {})},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches)",
                      "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4),
