@@ -15,7 +15,9 @@ inputs, the <= scale/2 error bound of nearest rounding, unbiasedness and the
 D/6 variance law of stochastic rounding (Prop. 2), code range, the forward
 identity of the Prop. 2 proof (integer GEMM times scales == GEMM of dequantized
 tensors), rocRAND's host Philox4x32-10 engine for the generator, and math.fsum
-triple loops for the floating-point contractions.
+triple loops for the floating-point contractions; for the 3x3 convolution scipy's
+2-D correlation, six-deep loops, single-tap shifts, a hand-worked example and the
+adjoint identities.
 Parity unpinned: nothing in this file.
 """
 from __future__ import annotations
@@ -458,4 +460,129 @@ def operator_fwd_bwd(tag: int, x: np.ndarray, w: np.ndarray, bias, dy: np.ndarra
     y, _, _ = qlinear_fwd(tag, xh, None, wh, None, bias, y_dtype)
     b = qlinear_bwd(tag, dyh, None, xh, None, wh, None, dy, dx_dtype, dw_dtype)
     r.update(xq=xh, wq=wh, dyq=dyh, y=y, overflow=False, **{k: b[k] for k in ("dx", "dw", "db")})
+    return r
+
+
+# ------------------------------------------------ 3x3 convolution (NHWC, stride 1, pad 1)
+# The paper's convolution models run NHWC low-precision kernels (Experiment setup: "only the
+# NHWC format is supported" below 16 bit); its forward/backward flow is the linear operator's
+# (Appendix, proofs of Prop. 1 and Prop. 2) with the contraction running over the 3x3 window and
+# the input channels.  The functions below are the definition written out tap by tap:
+#   Y[b,h,w,n]  = sum_{kh,kw,c} X[b, h+kh-1, w+kw-1, c] * W[n,kh,kw,c]        (zero outside the image)
+#   dX[b,h,w,c] = sum_{kh,kw,n} dY[b, h-(kh-1), w-(kw-1), n] * W[n,kh,kw,c]
+#   dW[n,kh,kw,c] = sum_{b,h,w} dY[b,h,w,n] * X[b, h+kh-1, w+kw-1, c]
+def _pad_hw(a: np.ndarray) -> np.ndarray:
+    b, h, w, c = a.shape
+    p = np.zeros((b, h + 2, w + 2, c), dtype=np.float64)
+    p[:, 1:h + 1, 1:w + 1, :] = a
+    return p
+
+
+def conv3x3_fwd_f64(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """x [B,H,W,C], w [N,3,3,C] -> [B,H,W,N] in double (exact for integer codes: every partial sum < 2^53)."""
+    b, h, wd, c = x.shape
+    assert w.shape[1:] == (3, 3, c)
+    xp, wf = _pad_hw(x), w.astype(np.float64)
+    y = np.zeros((b, h, wd, w.shape[0]), dtype=np.float64)
+    for kh in range(3):
+        for kw in range(3):
+            y += xp[:, kh:kh + h, kw:kw + wd, :] @ wf[:, kh, kw, :].T
+    return y
+
+
+def conv3x3_dgrad_f64(dy: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """dy [B,H,W,N], w [N,3,3,C] -> dX [B,H,W,C]: every output pixel scatters its gradient over its window."""
+    b, h, wd, n = dy.shape
+    assert w.shape[0] == n and w.shape[1:3] == (3, 3)
+    c = w.shape[3]
+    dxp = np.zeros((b, h + 2, wd + 2, c), dtype=np.float64)
+    dyf, wf = dy.astype(np.float64), w.astype(np.float64)
+    for kh in range(3):
+        for kw in range(3):
+            dxp[:, kh:kh + h, kw:kw + wd, :] += dyf @ wf[:, kh, kw, :]
+    return dxp[:, 1:h + 1, 1:wd + 1, :]
+
+
+def conv3x3_wgrad_f64(dy: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """dy [B,H,W,N], x [B,H,W,C] -> dW [N,3,3,C]."""
+    b, h, wd, n = dy.shape
+    c = x.shape[3]
+    xp = _pad_hw(x)
+    dyf = dy.astype(np.float64).reshape(-1, n)
+    dw = np.zeros((n, 3, 3, c), dtype=np.float64)
+    for kh in range(3):
+        for kw in range(3):
+            dw[:, kh, kw, :] = dyf.T @ xp[:, kh:kh + h, kw:kw + wd, :].reshape(-1, c)
+    return dw
+
+
+def _wrap_i32(exact: np.ndarray) -> Tuple[np.ndarray, bool]:
+    acc64 = exact.astype(np.int64)
+    ovf = bool(acc64.size and (acc64.max() > 2**31 - 1 or acc64.min() < -2**31))
+    return (acc64 & np.int64(0xFFFFFFFF)).astype(np.uint32).view(np.int32), ovf
+
+
+def conv3x3_operator_fwd_bwd(tag: int, act: np.ndarray, w: np.ndarray, bias, dy: np.ndarray, w_gran: str = "row",
+                             dy_round: str = "stochastic", seed: int = 0, offset: int = 0,
+                             y_dtype=np.float32, dx_dtype=np.float16, dw_dtype=np.float32) -> dict:
+    """absmax -> quantize/cast -> forward -> quantize dY -> dgrad, wgrad for one 3x3 convolution.
+
+    act [B,H,W,C]; w [N, 9*C] with k = (kh, kw, c); dy [B*H*W, N] (or [B,H,W,N]); outputs Y [B*H*W, N],
+    dX [B*H*W, C], dW [N, 9*C].  The quantizers are the linear operator's (operator_fwd_bwd): activation
+    and gradient per tensor, weights per tensor or per output channel ("row").  Reading for the data
+    gradient with per-output-channel weights: the output channel n sits on dgrad's contraction axis, so
+    dgrad uses a second quantization of W with one scale per input channel c (absmax over n, kh, kw) -- the
+    convolution's counterpart of the per-input-feature scales of the linear backward (see qlinear_bwd).
+    """
+    b, h, wd, c = act.shape
+    n = w.shape[0]
+    assert w.shape == (n, 9 * c)
+    m = b * h * wd
+    dy2 = dy.reshape(m, n)
+    r = {}
+    if tag == INT8:
+        ax = absmax(act.reshape(m, c), "tensor"); sx, ix = scales_from_amax(ax)
+        aw = absmax(w, w_gran); sw, iw = scales_from_amax(aw)
+        xq = quantize_int(act.reshape(m, c), ix, "tensor", "nearest")
+        wq = quantize_int(w, iw, w_gran, "nearest")
+        acc, o0 = _wrap_i32(conv3x3_fwd_f64(xq.reshape(b, h, wd, c), wq.reshape(n, 3, 3, c)).reshape(m, n))
+        swv = np.asarray(sw, _F32).reshape(-1)
+        sxv = float(_F32(np.asarray(sx).reshape(-1)[0]))
+        y = acc.astype(np.float64) * (sxv if swv.size > 1 else sxv * float(swv[0]))
+        if swv.size > 1:
+            y = y * swv.astype(np.float64).reshape(1, -1)
+        if bias is not None:
+            y = y + np.asarray(bias, _F32).astype(np.float64).reshape(1, -1)
+        ady = absmax(dy2, "tensor"); sdy, idy = scales_from_amax(ady)
+        dyq = quantize_int(dy2, idy, "tensor", dy_round, seed, offset)
+        if w_gran == "row":
+            w9 = w.reshape(n * 9, c)                           # rows (n, kh, kw), columns c
+            awb = absmax(w9, "col"); swb, iwb = scales_from_amax(awb)
+            wqb = quantize_int(w9, iwb, "col", "nearest").reshape(n, 9 * c)
+        else:
+            swb, wqb = sw, wq
+        acc_dx, o1 = _wrap_i32(conv3x3_dgrad_f64(dyq.reshape(b, h, wd, n), wqb.reshape(n, 3, 3, c)).reshape(m, c))
+        acc_dw, o2 = _wrap_i32(conv3x3_wgrad_f64(dyq.reshape(b, h, wd, n), xq.reshape(b, h, wd, c)).reshape(n, 9 * c))
+        sdyv = float(_F32(np.asarray(sdy).reshape(-1)[0]))
+        swbv = np.asarray(swb, _F32).reshape(-1)
+        dx = acc_dx.astype(np.float64) * sdyv
+        dx = dx * (swbv.astype(np.float64).reshape(1, -1) if swbv.size > 1 else float(swbv[0]))
+        dw = acc_dw.astype(np.float64) * (sdyv * sxv)
+        r.update(sx=sx, sw=sw, xq=xq, wq=wq, y=y.astype(y_dtype), acc=acc, sdy=sdy, dyq=dyq, swb=swb, wqb=wqb,
+                 dx=dx.astype(dx_dtype), dw=dw.astype(dw_dtype), acc_dx=acc_dx, acc_dw=acc_dw,
+                 db=dy2.astype(np.float64).sum(axis=0).astype(_F32), overflow=o0 or o1 or o2)
+        return r
+    if tag == FP16:
+        xh, wh, dyh = cast_fp16(act), cast_fp16(w), cast_fp16(dy2)
+    elif tag == FP32:
+        xh, wh, dyh = act.astype(_F32), w.astype(_F32), dy2.astype(_F32)
+    else:
+        raise ValueError(tag)
+    y = conv3x3_fwd_f64(xh, wh.reshape(n, 3, 3, c)).reshape(m, n)
+    if bias is not None:
+        y = y + np.asarray(bias, _F32).astype(np.float64).reshape(1, -1)
+    dx = conv3x3_dgrad_f64(dyh.reshape(b, h, wd, n), wh.reshape(n, 3, 3, c)).reshape(m, c)
+    dw = conv3x3_wgrad_f64(dyh.reshape(b, h, wd, n), xh).reshape(n, 9 * c)
+    r.update(xq=xh.reshape(m, c), wq=wh, dyq=dyh, y=y.astype(y_dtype), dx=dx.astype(dx_dtype), dw=dw.astype(dw_dtype),
+             db=dy2.astype(np.float64).sum(axis=0).astype(_F32), overflow=False)
     return r

@@ -524,6 +524,7 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
         ACC acc[V];
 #pragma unroll
         for(int e = 0; e < V; ++e) acc[e] = 0;
+#pragma unroll 8                                  // eight independent partial loads in flight; the sum keeps its order
         for(int s = 0; s < splits; ++s)
         {
             ACC part[V];
