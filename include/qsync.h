@@ -202,6 +202,47 @@ size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 
 /*
+ * qsync_debug_set_gemm_tile - for tests and tuning runs: pin the tile shape of the MFMA GEMM
+ * (0: 256x256, 1: 128x128, 2: 64x64) for every later call of this process, -1 (or any other value)
+ * returns the choice to the planner.  Workspace sizes reported afterwards follow the pinned tile.
+ * Process-wide and not synchronized: do not call it while another thread is inside the library.
+ */
+void qsync_debug_set_gemm_tile(int tile);
+
+/*
+ * qsync_conv3x3_fwd - 3x3 / stride 1 / pad 1 convolution over an NHWC tensor as an implicit GEMM.
+ * Paper: Backend section (low-precision convolution kernels run on NHWC tensors; dequantization is
+ * fused into the kernel's epilogue); Appendix, proof of Prop. 2 (forward flow of a fixed-point
+ * kernel).  The patch matrix is never stored: the GEMM's loads gather it from the NHWC codes.
+ *
+ *   y[m, n] = sx * sw[n] * sum_{kh,kw,c} xq[b, h+kh-1, w+kw-1, c] * wq[n, (kh*3+kw)*C + c] + bias[n]
+ *   m = (b*H + h)*W + w; terms outside the image are zero.  FP16: the same sum over binary16 operands
+ *   with fp32 accumulation, no scales.
+ *
+ * tag     QSYNC_INT8 or QSYNC_FP16 (QSYNC_FP32: QSYNC_ERR_UNSUPPORTED).
+ * xq      [nimg, H, W, C] codes (int8) or binary16, device, 16-byte aligned; C * element size must be a
+ *         multiple of 16 bytes (QSYNC_ERR_ALIGN) and nimg*H*W*C*element size < 2^31 (QSYNC_ERR_BAD_SHAPE).
+ * wq      [N, 9*C], k = (kh, kw, c), same element type, 16-byte aligned.
+ * sx, sw, wgran, bias_opt, y [nimg*H*W, N], ydt, acc_dump_opt: as in qsync_qlinear_fwd.
+ *
+ * The data gradient of the convolution is this same entry point with the roles of the channels
+ * swapped: dX[m, c] = conv3x3(dyq [nimg,H,W,N], wflip [C, 9*N]) with wflip from qsync_conv3x3_wflip
+ * (C and N exchanged in the call).  The weight gradient is qsync_qlinear_bwd (dx_opt = NULL) on the
+ * transposed patch matrix of qsync_im2col3x3_i8.
+ */
+int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N,
+                      const void* xq, const float* sx, const void* wq, const float* sw, int wgran,
+                      const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt, void* stream);
+
+/*
+ * qsync_conv3x3_wflip - weights of the data-gradient convolution:
+ *   wflip[c, ((2-kh)*3 + (2-kw))*N + n] = w[n, (kh*3+kw)*C + c]
+ * (window mirrored, channel roles exchanged), so that dX = conv3x3(dY, wflip).
+ * w [N, 9*C] and wflip [C, 9*N] of wdt (QSYNC_I8 or QSYNC_F16), device, distinct buffers.
+ */
+int qsync_conv3x3_wflip(const void* w, int wdt, int64_t N, int64_t C, void* wflip, void* stream);
+
+/*
  * qsync_im2col3x3_i8 - patches of a 3x3, stride-1, pad-1 convolution, built from int8 codes.
  * Paper: Backend section (low-precision convolution runs on NHWC tensors; the convolution is
  * lowered to the GEMM of the linear operator).  The activation is quantized once as an NHWC

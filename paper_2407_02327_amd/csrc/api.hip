@@ -248,6 +248,54 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
     return QSYNC_OK;
 }
 
+void qsync_debug_set_gemm_tile(int tile) { set_gemm_tile_override(tile); }
+
+int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,
+                      const float* sx, const void* wq, const float* sw, int wgran, const float* bias_opt, void* y,
+                      int ydt, int32_t* acc_dump_opt, void* stream)
+{
+    if(!xq || !wq || !y) return QSYNC_ERR_NULL;
+    if(!is_tag(tag) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
+    if(tag == QSYNC_INT8)
+    {
+        if(!sx || !sw) return QSYNC_ERR_NULL;
+        if(!is_gran(wgran)) return QSYNC_ERR_BAD_ENUM;
+    }
+    if(nimg < 0 || H < 0 || W < 0 || C < 0 || N < 0 || H > 65535 || W > 65535 || C > (1 << 20) || N > (int64_t(1) << 31))
+        return QSYNC_ERR_BAD_SHAPE;
+    if(tag == QSYNC_FP32) return QSYNC_ERR_UNSUPPORTED;
+    if(tag == QSYNC_INT8 && wgran == QSYNC_PER_COL) return QSYNC_ERR_UNSUPPORTED;
+    if(tag != QSYNC_INT8 && acc_dump_opt) return QSYNC_ERR_UNSUPPORTED;
+    const int64_t esz = tag == QSYNC_INT8 ? 1 : 2;
+    if(H > 0 && W > 0 && C > 0 && nimg > ((int64_t(1) << 31) - 1) / (H * W * C * esz)) return QSYNC_ERR_BAD_SHAPE;
+    const int64_t M = nimg * H * W;
+    if(!count_ok(M, N) || !count_ok(N, 9 * C)) return QSYNC_ERR_BAD_SHAPE;
+    if((C * esz) % 16 != 0 || !aligned16(xq) || !aligned16(wq)) return QSYNC_ERR_ALIGN;
+    if(M == 0 || N == 0) return QSYNC_OK;
+    const GemmPlan plan = plan_gemm(tag, M, N, 9 * C, -1, -1, /*allow_split=*/false);
+    GemmProblem p{};
+    p.prec = tag; p.M = M; p.N = N; p.K = 9 * C;
+    p.A = xq; p.B = wq; p.C = y; p.c_dtype = ydt;
+    p.conv_H = static_cast<int>(H); p.conv_W = static_cast<int>(W); p.conv_C = C;
+    if(tag == QSYNC_INT8)
+    {
+        p.s0 = sx;
+        if(wgran == QSYNC_PER_TENSOR) p.s1 = sw; else p.col_scale = sw;
+        p.acc_dump = acc_dump_opt;
+    }
+    p.col_bias = bias_opt;
+    return hip_status(launch_gemm(p, plan, nullptr, static_cast<hipStream_t>(stream)));
+}
+
+int qsync_conv3x3_wflip(const void* w, int wdt, int64_t N, int64_t C, void* wflip, void* stream)
+{
+    if(!w || !wflip) return QSYNC_ERR_NULL;
+    if(wdt != QSYNC_I8 && wdt != QSYNC_F16) return QSYNC_ERR_BAD_ENUM;
+    if(N < 0 || C < 0 || !count_ok(N, 9 * C)) return QSYNC_ERR_BAD_SHAPE;
+    if(w == wflip) return QSYNC_ERR_UNSUPPORTED;
+    return hip_status(launch_conv3x3_wflip(w, wdt == QSYNC_I8 ? 1 : 2, N, C, wflip, static_cast<hipStream_t>(stream)));
+}
+
 int qsync_im2col3x3_i8(const void* xq, int64_t nimg, int64_t H, int64_t W, int64_t C, void* a_opt, void* aT_opt,
                        void* stream)
 {

@@ -1090,6 +1090,33 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
     return dequantize_typed<int8_t, __half>(a, rows, cols, ld, row_scale, col_scale, tensor_scale, tensor_scale_dev, col_bias, y, stream);
 }
 
+// wflip[c, (8 - tap)*N + n] = w[n, tap*C + c]: a few kilobytes of weights, one element per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void conv3x3_wflip_kernel(const T* __restrict__ w, int64_t N, int64_t C, T* __restrict__ wflip)
+{
+    const int64_t total = 9 * N * C;
+    for(int64_t o = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; o < total; o += static_cast<int64_t>(gridDim.x) * 256)
+    {
+        const int64_t c = o / (9 * N), r = o - c * 9 * N, tap = r / N, n = r - tap * N;
+        wflip[o] = w[n * 9 * C + (8 - tap) * C + c];
+    }
+}
+
+hipError_t launch_conv3x3_wflip(const void* w, int elem_bytes, int64_t N, int64_t C, void* wflip, hipStream_t stream)
+{
+    const int64_t total = 9 * N * C;
+    if(total <= 0) return hipSuccess;
+    int64_t nb = (total + 255) / 256;
+    nb         = nb > 4096 ? 4096 : nb;
+    if(elem_bytes == 1)
+        conv3x3_wflip_kernel<int8_t><<<dim3(static_cast<unsigned>(nb)), dim3(256), 0, stream>>>(
+            static_cast<const int8_t*>(w), N, C, static_cast<int8_t*>(wflip));
+    else
+        conv3x3_wflip_kernel<uint16_t><<<dim3(static_cast<unsigned>(nb)), dim3(256), 0, stream>>>(
+            static_cast<const uint16_t*>(w), N, C, static_cast<uint16_t*>(wflip));
+    return hipGetLastError();
+}
+
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream)
 {

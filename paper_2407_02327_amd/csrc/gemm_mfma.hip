@@ -89,6 +89,7 @@ struct GemmKernelArgs
     void*          partial;      // split-K: [splits][M][N] raw accumulators
     int            ktiles_per_split;
     int            tiles_m, tiles_n;
+    int            conv_H, conv_W, conv_Cb;   // implicit 3x3 patch matrix: image height, width, bytes per pixel
 };
 
 // Work item (K split, tile) of a workgroup.  Workgroups are dealt round-robin to the eight XCDs
@@ -154,6 +155,37 @@ __device__ __forceinline__ void dma_sequence_tail(std::integer_sequence<int, Ds.
     (dma_issue<Ds, DPW>(sbase, voff[Ds] - ((kb + gchunk[Ds & 1] >= Kb) ? gchunk[Ds & 1] : 0), lds_mid), ...);
 }
 
+// Implicit patch matrix of a 3x3 / stride 1 / pad 1 convolution over an NHWC tensor: row m of A is
+// output pixel m, its K axis runs (kh, kw, c).  A 16-byte chunk lies inside one tap because the
+// pixel size is a multiple of 16 bytes, so the direct load of a lane either reads 16 bytes of the
+// neighbouring pixel (same image, inside the border) or, for padding and for chunks past the end
+// of K, 16 zero bytes from a constant block.
+__device__ uint4 g_zero_chunk;     // never written: static storage starts at zero
+
+struct ConvTap { int delta[2]; int dh[2]; int dw[2]; bool valid[2]; };     // per chunk parity of the lane
+
+template <int D, int DPW>
+__device__ __forceinline__ void conv_issue(const uint8_t* a, const uint8_t* zero, uint32_t pix_off, uint32_t hw,
+                                           const ConvTap& t, int H, int W, uint8_t* lds_mid)
+{
+    constexpr int IMM = dma_imm<D, DPW>();
+    constexpr int par = D & 1;
+    const int  hh  = static_cast<int>(hw >> 16) + t.dh[par], ww = static_cast<int>(hw & 0xffffu) + t.dw[par];
+    const bool inb = t.valid[par] && static_cast<unsigned>(hh) < static_cast<unsigned>(H)
+                     && static_cast<unsigned>(ww) < static_cast<unsigned>(W);
+    const uint8_t* src = inb ? a + static_cast<int64_t>(static_cast<int32_t>(pix_off) + t.delta[par]) : zero;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src - IMM),
+                                     (__attribute__((address_space(3))) void*)(lds_mid), 16, IMM, 0);
+}
+
+template <int DPW, int... Ds>
+__device__ __forceinline__ void conv_sequence(std::integer_sequence<int, Ds...>, const uint8_t* a, const uint8_t* zero,
+                                              const uint32_t (&pix_off)[DPW], const uint32_t (&hw)[DPW],
+                                              const ConvTap& t, int H, int W, uint8_t* lds_mid)
+{
+    (conv_issue<Ds, DPW>(a, zero, pix_off[Ds], hw[Ds], t, H, W, lds_mid), ...);
+}
+
 template <int DPW, int... Ds>
 __device__ __forceinline__ void fill_dma_imms(int (&imm)[DPW], std::integer_sequence<int, Ds...>)
 {
@@ -162,9 +194,10 @@ __device__ __forceinline__ void fill_dma_imms(int (&imm)[DPW], std::integer_sequ
 
 __device__ __forceinline__ int swizzle(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) << 4; }
 
-template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT>
+template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT, bool CONV = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKernelArgs p)
 {
+    static_assert(!(SPLIT && CONV), "the implicit patch matrix is not combined with split K");
     typedef typename TR::accv_t accv_t;
     typedef typename TR::acc_t  acc_t;
     constexpr int kThreads = 64 * WGM * WGN;
@@ -210,6 +243,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     const uint8_t* gbase     = is_a ? p.A + m0 * p.Kb : p.B + n0 * p.Kb;
     const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
     uint32_t       voff[DPW];                                         // lane offset + kDmaBias - immediate
+    uint32_t       hw[CONV ? DPW : 1];                                // CONV, A side: (h << 16) | w of the lane's pixels
     int            gchunk[2];                                         // the swizzle term depends on d%2 only
     {
         int imm[DPW];
@@ -222,6 +256,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
             int64_t   lrow  = srow - (is_a ? 0 : BM);
             if(lrow >= rows_left) lrow = rows_left - 1;
             voff[d] = static_cast<uint32_t>(lrow * p.Kb + chunk * 16 + kDmaBias - imm[d]);
+            if constexpr(CONV)
+                if(is_a)
+                {   // A side: voff holds the byte offset of output pixel m in the NHWC tensor instead
+                    const uint32_t m = static_cast<uint32_t>(m0 + lrow), q = m / static_cast<uint32_t>(p.conv_W);
+                    voff[d] = m * static_cast<uint32_t>(p.conv_Cb);
+                    hw[d]   = ((q % static_cast<uint32_t>(p.conv_H)) << 16) | (m - q * static_cast<uint32_t>(p.conv_W));
+                }
             if(d < 2) gchunk[d] = chunk * 16;
         }
     }
@@ -238,6 +279,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     auto dma = [&](int stage, int kt) {
         const int64_t  kb    = static_cast<int64_t>(kt) * kRowBytes;
         uint8_t*       lbase = lds + stage * STAGE_BYTES + wave * (DPW * 1024) + (DPW / 2) * 1024;
+        if constexpr(CONV)
+            if(is_a)
+            {
+                ConvTap t;
+#pragma unroll
+                for(int par = 0; par < 2; ++par)
+                {
+                    const uint32_t koff = static_cast<uint32_t>(kb) + static_cast<uint32_t>(gchunk[par]);
+                    const uint32_t tap  = koff / static_cast<uint32_t>(p.conv_Cb);
+                    const int      c0   = static_cast<int>(koff - tap * static_cast<uint32_t>(p.conv_Cb));
+                    const int      kh   = static_cast<int>((tap * 11u) >> 5);         // tap / 3 for tap < 12
+                    const int      kw   = static_cast<int>(tap) - 3 * kh;
+                    t.dh[par]    = kh - 1;
+                    t.dw[par]    = kw - 1;
+                    t.delta[par] = ((kh - 1) * p.conv_W + (kw - 1)) * p.conv_Cb + c0;
+                    t.valid[par] = static_cast<int64_t>(koff) < p.Kb;
+                }
+                conv_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, p.A,
+                                   reinterpret_cast<const uint8_t*>(&g_zero_chunk), voff, hw, t, p.conv_H, p.conv_W, lbase);
+                return;
+            }
         const uint8_t* sb    = sbase0 + kb;
         asm volatile("" : "+s"(sb));      // keep base + K offset a scalar pair: the lane offsets stay loop-invariant 32-bit values
         if(kt == tail_kt)
@@ -577,18 +639,23 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
     constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float);
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
     const dim3       block(64 * WGM * WGN);
-    static bool      attr_set[2] = {false, false};   // per instantiation; benign if set twice
-    const int        which = splits > 1 ? 1 : 0;
+    static bool      attr_set[3] = {false, false, false};   // per instantiation; benign if set twice
+    const bool       conv  = a.conv_H > 0;
+    const int        which = conv ? 2 : (splits > 1 ? 1 : 0);
+    if(conv && splits > 1) return hipErrorInvalidValue;
     if(!attr_set[which])
     {
-        const void* fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
+        const void* fn = conv ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true>)
+                       : splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
                                     : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false>);
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  static_cast<int>(lds_bytes));
         if(e != hipSuccess) return e;
         attr_set[which] = true;
     }
-    if(splits > 1)
+    if(conv)
+        gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true><<<grid, block, lds_bytes, st>>>(a);
+    else if(splits > 1)
         gemm_nt_kernel<TR, BM, BN, WGM, WGN, true><<<grid, block, lds_bytes, st>>>(a);
     else
         gemm_nt_kernel<TR, BM, BN, WGM, WGN, false><<<grid, block, lds_bytes, st>>>(a);
@@ -610,8 +677,16 @@ hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStrea
 
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t stream);   // gemm_f32.hip
 
-GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits)
+static int g_tile_override = -1;     // set by tests and tuning runs only (not synchronized)
+void set_gemm_tile_override(int tile) { g_tile_override = (tile >= 0 && tile < kNumTiles) ? tile : -1; }
+
+GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits, bool allow_split)
 {
+    if(force_tile < 0 && g_tile_override >= 0)
+    {   // a forced tile keeps the planner's split choice for that tile
+        GemmPlan forced = plan_gemm(prec, M, N, K, g_tile_override, force_splits >= 1 ? force_splits : 0, allow_split);
+        return forced;
+    }
     GemmPlan plan{1, 1, 0};
     if(prec == 32 || M <= 0 || N <= 0) return plan;
     const int64_t kb     = K * (prec == 8 ? 1 : 2);
@@ -646,7 +721,7 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
         int64_t s       = model[t].fill / ntiles(t);
         if(s > ktiles / 8) s = ktiles / 8;                    // keep at least 8 K tiles per split
         if(s > 128) s = 128;
-        if(s >= 2 && !(force_tile >= 0 && force_splits < 0)) cand[1] = s;
+        if(s >= 2 && allow_split && !(force_tile >= 0 && force_splits < 0)) cand[1] = s;
         for(int c = 0; c < 2; ++c)
         {
             if(c == 1 && cand[1] == 1) break;
@@ -654,7 +729,7 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
             if(best < 0.0 || us < best) { best = us; tile = t; splits = static_cast<int>(cand[c]); }
         }
     }
-    if(force_splits >= 1) splits = force_splits;
+    if(force_splits >= 1 && allow_split) splits = force_splits;
     if(splits > ktiles) splits = static_cast<int>(ktiles < 1 ? 1 : ktiles);
     plan.tile      = tile;
     plan.splits    = splits;
@@ -665,7 +740,7 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
 hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream)
 {
     if(p.M <= 0 || p.N <= 0) return hipSuccess;
-    if(p.prec == 32) return launch_gemm_f32(p, stream);
+    if(p.prec == 32) return p.conv_H > 0 ? hipErrorInvalidValue : launch_gemm_f32(p, stream);
     const int      esz = p.prec == 8 ? 1 : 2;
     GemmKernelArgs a;
     a.A = static_cast<const uint8_t*>(p.A);
@@ -675,6 +750,15 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.s0 = p.s0; a.s1 = p.s1; a.col_scale = p.col_scale; a.col_bias = p.col_bias;
     a.acc_dump = p.prec == 8 ? p.acc_dump : nullptr;
     a.partial  = workspace;
+    a.conv_H = a.conv_W = a.conv_Cb = 0;
+    if(p.conv_H > 0)
+    {   // A is the NHWC tensor [M = images*H*W, C]; its 3x3 patch matrix [M, 9*C] is formed by the loads
+        if(p.K != 9 * p.conv_C || plan.splits > 1 || p.M * p.conv_C * esz >= (int64_t(1) << 31)
+           || p.conv_H > 65535 || p.conv_W > 65535 || (p.conv_C * esz) % 16 != 0
+           || p.M % (static_cast<int64_t>(p.conv_H) * p.conv_W) != 0)
+            return hipErrorInvalidValue;
+        a.conv_H = p.conv_H; a.conv_W = p.conv_W; a.conv_Cb = static_cast<int>(p.conv_C * esz);
+    }
     const int64_t ktiles = (a.Kb + kRowBytes - 1) / kRowBytes;
     int splits = plan.splits < 1 ? 1 : plan.splits;
     a.ktiles_per_split = static_cast<int>((ktiles + splits - 1) / splits);

@@ -39,6 +39,7 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
                              const float* tensor_scale_dev, const float* col_bias, void* y, int ydt,
                              hipStream_t stream);
 // 3x3 / stride 1 / pad 1 patches of an int8 NHWC tensor: a [M, 9C] and/or aT [9C, M], M = nimg*H*W
+hipError_t launch_conv3x3_wflip(const void* w, int elem_bytes, int64_t N, int64_t C, void* wflip, hipStream_t stream);
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
@@ -59,6 +60,10 @@ struct GemmProblem {
     const float* col_scale; // [N] or nullptr
     const float* col_bias;  // [N] or nullptr
     int32_t*    acc_dump;   // [M,N] raw int32 accumulators (prec 8 only) or nullptr
+    // conv_H > 0: A is an NHWC tensor [M = images*conv_H*conv_W, conv_C] and the GEMM runs over its
+    // 3x3 / stride 1 / pad 1 patch matrix [M, K = 9*conv_C] (k = (kh, kw, c)), formed on the fly.
+    int         conv_H = 0, conv_W = 0;
+    int64_t     conv_C = 0;
 };
 
 struct GemmPlan {
@@ -67,7 +72,10 @@ struct GemmPlan {
     size_t  workspace;     // bytes needed for split-K partials
 };
 // force_tile / force_splits < 0 leave the choice to the heuristic.
-GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile = -1, int force_splits = -1);
+GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile = -1, int force_splits = -1,
+                   bool allow_split = true);
+// tile >= 0 pins the tile shape of every later plan (tests, tuning); -1 returns the choice to the planner.
+void set_gemm_tile_override(int tile);
 hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream);
 
 }  // namespace qsync

@@ -184,3 +184,112 @@ class QLinear:
         self.convert_dy(dy, stream)
         self.gemm_bwd(dy, stream)
         return self.dx, self.dw, self.db
+
+
+class QConv3x3:
+    """One 3x3 / stride 1 / pad 1 NHWC convolution as quantized operator (paper: Backend section, low-precision
+    convolution on NHWC tensors).  Forward and data gradient run as implicit GEMMs over the codes (the patch
+    matrix is never stored); the weight gradient contracts over the pixels and reads the transposed patch
+    matrix, expanded from the int8 codes.  Buffers are allocated once; nothing here computes.
+
+    INT8: all three passes.  FP16: forward and data gradient (no binary16 patch expansion is provided).
+    """
+
+    def __init__(self, tag: int, nimg: int, H: int, W: int, C: int, N: int, x_dtype=torch.float16, w_dtype=torch.float32,
+                 dy_dtype=None, y_dtype=torch.float32, dx_dtype=torch.float16, dw_dtype=torch.float32,
+                 w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
+                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda"):
+        if tag not in (Q.INT8, Q.FP16):
+            raise ValueError("QConv3x3: tag INT8 or FP16")
+        self.tag, self.nimg, self.H, self.W, self.C, self.N = tag, nimg, H, W, C, N
+        M, K = nimg * H * W, 9 * C
+        self.M, self.K = M, K
+        self.w_gran, self.dy_round, self.seed, self.bits, self.offset = w_gran, dy_round, philox_seed, bits, 0
+        e = lambda *s, dt: torch.empty(*s, dtype=dt, device=device)
+        qd, f32 = _TORCH_OF_TAG[tag], torch.float32
+        self.xq = e(M, C, dt=qd)
+        self.xqTp = e(K, M, dt=qd) if tag == Q.INT8 else None        # transposed patch matrix (weight gradient)
+        self.wq, self.wqb, self.wflip = e(N, K, dt=qd), e(N, K, dt=qd), e(C, 9 * N, dt=qd)
+        self.dyq, self.dyqT = e(M, N, dt=qd), e(N, M, dt=qd)
+        self.sx, self.ix, self.ax = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
+        nsw, nswb = (N, C) if w_gran == Q.PER_ROW else (1, 1)
+        self.sw, self.iw, self.aw = e(nsw, dt=f32), e(nsw, dt=f32), e(nsw, dt=f32)
+        self.swb, self.iwb = e(nswb, dt=f32), e(nswb, dt=f32)
+        self.sdy, self.idy, self.ady = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
+        self.bias = torch.zeros(N, dtype=f32, device=device) if bias else None
+        self.y, self.dx, self.dw = e(M, N, dt=y_dtype), e(M, C, dt=dx_dtype), e(N, K, dt=dw_dtype)
+        self.db = e(N, dt=f32)
+        self.acc = self.acc_dx = self.acc_dw = None
+        if dump_acc and tag == Q.INT8:
+            i32 = torch.int32
+            self.acc, self.acc_dx, self.acc_dw = e(M, N, dt=i32), e(M, C, dt=i32), e(N, K, dt=i32)
+        self.ws_absmax = _ws(max(Q.qsync_absmax_workspace_bytes(M, C, Q.PER_TENSOR),
+                                 Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR)), device)
+        self.ws_absmax_w = _ws(max(Q.qsync_absmax_workspace_bytes(9 * N, C, Q.PER_COL),
+                                   Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), device)
+        self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K), device)
+
+    def convert_x(self, act: torch.Tensor, stream=None) -> None:
+        M, C = self.M, self.C
+        if self.tag == Q.INT8:
+            Q.qsync_absmax_scale(act, M, C, C, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None, self.ws_absmax, stream)
+            Q.qsync_quantize(act, M, C, C, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq, None, stream)
+        else:
+            Q.qsync_quantize(act, M, C, C, self.tag, 0, 0, 0, 0, 0, None, self.xq, None, stream)
+
+    def convert_w(self, w: torch.Tensor, stream=None) -> None:
+        N, K, C = self.N, self.K, self.C
+        if self.tag != Q.INT8:
+            Q.qsync_quantize(w, N, K, K, self.tag, 0, 0, 0, 0, 0, None, self.wq, None, stream)
+            Q.qsync_conv3x3_wflip(self.wq, N, C, self.wflip, stream)
+            return
+        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax_w, stream)
+        Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, self.w_gran, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
+        if self.w_gran == Q.PER_TENSOR:
+            self.swb, src = self.sw, self.wq
+        else:
+            # the output channel is the data gradient's contraction axis: second set of codes with one scale per
+            # input channel c, i.e. per column of the weights viewed as [9*N, C]
+            Q.qsync_absmax_scale(w, 9 * N, C, C, Q.PER_COL, self.bits, self.swb, self.iwb, None, None, self.ws_absmax_w, stream)
+            Q.qsync_quantize(w, 9 * N, C, C, Q.INT8, self.bits, Q.PER_COL, Q.ROUND_NEAREST, 0, 0, self.iwb, self.wqb, None, stream)
+            src = self.wqb
+        Q.qsync_conv3x3_wflip(src, N, C, self.wflip, stream)
+
+    def conv_fwd(self, stream=None) -> None:
+        Q.qsync_conv3x3_fwd(self.tag, self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.wq, self.sw,
+                            self.w_gran, self.bias, self.y, self.acc, stream)
+
+    def convert_dy(self, dy: torch.Tensor, stream=None) -> None:
+        M, N = self.M, self.N
+        if self.tag == Q.INT8:
+            Q.qsync_absmax_scale(dy, M, N, N, Q.PER_TENSOR, self.bits, self.sdy, self.idy, self.ady, self.db, self.ws_absmax, stream)
+            Q.qsync_quantize(dy, M, N, N, Q.INT8, self.bits, Q.PER_TENSOR, self.dy_round, self.seed, self.offset,
+                             self.idy, self.dyq, self.dyqT, stream)
+            self.offset += (M * N + 7) // 8
+        else:
+            Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, self.dyq, None, stream)
+
+    def conv_dgrad(self, stream=None) -> None:
+        # dX = conv3x3(dY, mirrored weights with the channel roles exchanged)
+        Q.qsync_conv3x3_fwd(self.tag, self.nimg, self.H, self.W, self.N, self.C, self.dyq, self.sdy, self.wflip, self.swb,
+                            self.w_gran, None, self.dx, self.acc_dx, stream)
+
+    def conv_wgrad(self, stream=None) -> None:
+        if self.tag != Q.INT8:
+            raise NotImplementedError("weight gradient: INT8 tag only")
+        Q.qsync_im2col3x3_i8(self.xq, self.nimg, self.H, self.W, self.C, None, self.xqTp, stream)
+        Q.qsync_qlinear_bwd(Q.INT8, self.M, self.N, self.K, None, self.dyqT, self.sdy, self.xqTp, self.sx, None, None,
+                            Q.PER_TENSOR, None, self.dw, None, None, None, self.acc_dw, self.ws_bwd, stream)
+
+    def forward(self, act: torch.Tensor, w: torch.Tensor, stream=None) -> torch.Tensor:
+        self.convert_w(w, stream)
+        self.convert_x(act, stream)
+        self.conv_fwd(stream)
+        return self.y
+
+    def backward(self, dy: torch.Tensor, stream=None):
+        self.convert_dy(dy, stream)
+        self.conv_dgrad(stream)
+        if self.tag == Q.INT8:
+            self.conv_wgrad(stream)
+        return self.dx, self.dw, self.db

@@ -37,6 +37,9 @@ SIGNATURES = {
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
+    "qsync_debug_set_gemm_tile": (None, [_i]),
+    "qsync_conv3x3_wflip": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
     "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _vp, _i, _vp]),
     "qsync_last_hip_error": (_i, []),
     "qsync_strerror": (ctypes.c_char_p, [_i]),
@@ -122,6 +125,19 @@ def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, 
                                  F32 if dy_float_opt is None else dtype_code(dy_float_opt),
                                  _ptr(acc_dx_dump_opt), _ptr(acc_dw_dump_opt), _ptr(workspace), _bytes(workspace),
                                  _stream(stream)))
+
+
+def qsync_conv3x3_fwd(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt=None, stream=None) -> None:
+    _check(lib.qsync_conv3x3_fwd(tag, nimg, H, W, C, N, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
+                                 _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _stream(stream)))
+
+
+def qsync_debug_set_gemm_tile(tile: int) -> None:
+    lib.qsync_debug_set_gemm_tile(tile)
+
+
+def qsync_conv3x3_wflip(w, N, C, wflip, stream=None) -> None:
+    _check(lib.qsync_conv3x3_wflip(_ptr(w), dtype_code(w), N, C, _ptr(wflip), _stream(stream)))
 
 
 def qsync_im2col3x3_i8(xq, nimg, H, W, C, a_opt, aT_opt, stream=None) -> None:

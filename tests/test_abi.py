@@ -136,6 +136,41 @@ def test_im2col_validation():
     assert f(A, 0, 4, 4, 16, A, None, None) == qsync.OK
 
 
+def test_conv_validation():
+    f = lib.qsync_conv3x3_fwd
+    ok = [8, 1, 4, 4, 16, 8, A, A, A, A, qsync.PER_ROW, None, A, 0, None, None]
+    names = ["tag", "nimg", "H", "W", "C", "N", "xq", "sx", "wq", "sw", "wgran", "bias", "y", "ydt", "dump", "st"]
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return f(*a)
+
+    assert call(xq=None) == qsync.ERR_NULL
+    assert call(sw=None) == qsync.ERR_NULL
+    assert call(tag=5) == qsync.ERR_BAD_ENUM
+    assert call(ydt=qsync.I8) == qsync.ERR_BAD_ENUM
+    assert call(H=-1) == qsync.ERR_BAD_SHAPE
+    assert call(W=70000) == qsync.ERR_BAD_SHAPE
+    assert call(nimg=1 << 20, H=64, W=64, C=64) == qsync.ERR_BAD_SHAPE        # activation beyond 2^31 bytes
+    assert call(tag=32) == qsync.ERR_UNSUPPORTED
+    assert call(wgran=qsync.PER_COL) == qsync.ERR_UNSUPPORTED
+    assert call(tag=16, dump=A) == qsync.ERR_UNSUPPORTED
+    assert call(C=24) == qsync.ERR_ALIGN
+    assert call(tag=16, C=12) == qsync.ERR_ALIGN
+    assert call(xq=U) == qsync.ERR_ALIGN
+    assert call(nimg=0) == qsync.OK
+    g = lib.qsync_conv3x3_wflip
+    assert g(None, qsync.I8, 4, 4, A, None) == qsync.ERR_NULL
+    assert g(A, qsync.F32, 4, 4, P(8192), None) == qsync.ERR_BAD_ENUM
+    assert g(A, qsync.I8, -1, 4, P(8192), None) == qsync.ERR_BAD_SHAPE
+    assert g(A, qsync.I8, 4, 4, A, None) == qsync.ERR_UNSUPPORTED             # in place
+    assert g(A, qsync.I8, 0, 4, P(8192), None) == qsync.OK
+    lib.qsync_debug_set_gemm_tile(1)
+    lib.qsync_debug_set_gemm_tile(-1)
+
+
 def test_no_gpu_gives_hip_error_not_a_crash():
     import torch
     if torch.cuda.is_available():
