@@ -97,9 +97,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c5", choices=["c5", "c2", "c3"])
-    ap.add_argument("--conv-input", default="nhwc", choices=["nhwc", "patches"],
+    ap.add_argument("--conv-input", default="nhwc", choices=["nhwc", "patches", "implicit"],
                     help="workload c3 with tag int8: start each step from the NHWC activation (quantize it once, "
-                         "expand int8 codes into the patch matrix) or from the fp16 patch matrix")
+                         "expand int8 codes into the patch matrix), from the fp16 patch matrix, or run the convolution "
+                         "itself (implicit: forward and data gradient gather patches inside the GEMM, dX is the NHWC "
+                         "gradient [M,C] instead of the patch gradient [M,9C])")
     ap.add_argument("--tag", default="int8", choices=["int8", "fp16"])
     ap.add_argument("--bwd-tag", default=None, choices=[None, "fp16"],
                     help="fp16 with --tag int8: the paper's pairing, FP16 backward on the dequantized saved codes")
@@ -142,8 +144,17 @@ def main():
                      w_gran=Q.PER_ROW if c.w_gran == "row" else Q.PER_TENSOR,
                      dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
                      philox_seed=c.philox_seed, bwd_tag=(Q.FP16 if args.bwd_tag == "fp16" and tag == Q.INT8 else None))
+        if c.nhwc is not None and tag == Q.INT8 and args.conv_input == "implicit":
+            from paper_2407_02327_amd.operator import QConv3x3
+            b_, h_, w_, c_ = c.nhwc.shape
+            op = QConv3x3(tag, b_, h_, w_, c_, N, x_dtype=tdt[str(c.nhwc.dtype)], y_dtype=ydt, dx_dtype=torch.float16,
+                          dw_dtype=torch.float32, w_gran=Q.PER_ROW if c.w_gran == "row" else Q.PER_TENSOR,
+                          dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
+                          philox_seed=c.philox_seed)
+            op.convert_x_nhwc, op.gemm_fwd = op.convert_x, op.conv_fwd
+            op.gemm_bwd = (lambda o: lambda dy, st=None: (o.conv_dgrad(st), o.conv_wgrad(st)))(op)
         ops_objs.append(op)
-        nhwc = c.nhwc is not None and tag == Q.INT8 and args.conv_input == "nhwc"
+        nhwc = c.nhwc is not None and tag == Q.INT8 and args.conv_input in ("nhwc", "implicit")
         x_in = torch.from_numpy(c.nhwc if nhwc else c.x).cuda()
         op.convert_act = op.convert_x_nhwc if nhwc else op.convert_x
         dev_in.append((x_in, torch.from_numpy(c.w).cuda(), torch.from_numpy(c.dy).cuda()))

@@ -9,6 +9,8 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace qsync {
 
 namespace {
@@ -465,34 +467,37 @@ __global__ __launch_bounds__(kBlock) void colreduce_finalize_kernel(const float*
 }
 
 // ------------------------------------------------------------------ INT8 quantize, vector path
-// Each lane owns a patch of 16 rows x 32 input bytes (16 binary16 or 8 fp32 columns) and
-// requests the eight 16-byte loads of four rows together before it converts them.  A wavefront is 8 patches
-// wide and 8 tall, so every load instruction covers 8 rows of 256 contiguous bytes; the int8
+// Each lane owns a patch of 16 (or 8) rows x 32 input bytes (16 binary16 or 8 fp32 columns) and
+// requests the eight 16-byte loads of four rows together before it converts them.  A wavefront is up
+// to 8 patches wide (fewer for narrow matrices, so that no lane idles) and the rest of its lanes
+// stack patches downwards, so every load instruction covers whole 256-byte row segments; the int8
 // codes of a patch row leave as one 16-byte (8-byte for fp32 input) store, and -- after a byte
-// transpose held entirely in registers -- each column of the patch leaves as one 16-byte store
-// to the transposed copy, 8 lanes side by side (128 contiguous bytes).  No LDS, no barrier.
+// transpose held entirely in registers -- each column of the patch leaves as one 16-byte (8-byte)
+// store to the transposed copy, lanes side by side.  No LDS, no barrier.
 // Needs cols % 8 == 0 (Philox groups of 8 never straddle a row), rows % 16 == 0 when the
 // transposed copy is written, and 16-byte aligned rows.
-constexpr int kPatchRows = 16;
 
 __device__ __forceinline__ uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xFFu; }
 
-template <typename T, int RND, bool PERCOL>
+template <typename T, int RND, bool PERCOL, int PR>
 __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                                 int64_t ld, int qmax, int gran, uint64_t seed,
                                                                 uint64_t offset, const float* __restrict__ inv_scale,
                                                                 int8_t* __restrict__ q, int8_t* __restrict__ qT,
-                                                                int64_t grid_x)
+                                                                int64_t grid_x, int lpr_log2)
 {
+    // A lane converts a patch of PR rows x PCOLS columns; the 2^lpr_log2 lanes of a wavefront that share
+    // rows cover a contiguous row segment, the other lane bits stack patches downwards.  Narrow matrices
+    // use fewer lanes per row (no idle lanes), small ones shorter patches (more wavefronts in flight).
     constexpr int E     = Vec16<T>::N;            // elements per 16-byte load (8 or 4)
     constexpr int PCOLS = 2 * E;                  // patch width: 16 (binary16) or 8 (fp32) columns
     constexpr int NH    = PCOLS / 8;              // 8-column halves per patch row (one Philox block each)
     constexpr int CW    = PCOLS / 4;              // code dwords per patch row
-    constexpr int WTILE_R = 8 * kPatchRows, WTILE_C = 8 * PCOLS;
+    const int     wtile_r = (kWaveSize >> lpr_log2) * PR, wtile_c = PCOLS << lpr_log2;
     const int     lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
     const int64_t by   = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
-    const int64_t r0   = (by * (kBlock / kWaveSize) + wave) * WTILE_R + (lane / 8) * kPatchRows;
-    const int64_t c0   = bx * WTILE_C + (lane % 8) * PCOLS;
+    const int64_t r0   = (by * (kBlock / kWaveSize) + wave) * wtile_r + (lane >> lpr_log2) * PR;
+    const int64_t c0   = bx * wtile_c + (lane & ((1 << lpr_log2) - 1)) * PCOLS;
     if(r0 >= rows || c0 >= cols) return;
     const bool second_ok = NH == 1 || c0 + 8 < cols;      // binary16: the patch's second 8 columns exist
 
@@ -504,10 +509,10 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
     }
     const float ftensor = (!PERCOL && gran == kPerTensor) ? inv_scale[0] : 1.0f;
 
-    uint32_t code[kPatchRows][CW];   // row i, columns 4w..4w+3 in dword w
+    uint32_t code[PR][CW];   // row i, columns 4w..4w+3 in dword w
     constexpr int RB = 4;                // rows per batch
 #pragma unroll
-    for(int batch = 0; batch < kPatchRows / RB; ++batch)
+    for(int batch = 0; batch < PR / RB; ++batch)
     {   // four rows at a time: their 8 loads are requested together, then converted
         uint4 raw[RB][2];
 #pragma unroll
@@ -566,7 +571,7 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
     if(q)
     {
 #pragma unroll
-        for(int i = 0; i < kPatchRows; ++i)
+        for(int i = 0; i < PR; ++i)
         {
             const int64_t r = r0 + i;
             if(r >= rows) continue;
@@ -583,18 +588,22 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
         }
     }
     if(qT)
-    {   // rows % 16 == 0 here, so the patch's 16 rows all exist
+    {   // rows % 16 == 0 here, so every row of the patch exists
 #pragma unroll
         for(int col = 0; col < PCOLS; ++col)
         {
             if(col >= 8 && !second_ok) continue;
-            uint32_t t[4];
+            uint32_t t[PR / 4];
 #pragma unroll
-            for(int g = 0; g < 4; ++g)
+            for(int g = 0; g < PR / 4; ++g)
                 t[g] = byte_of(code[4 * g + 0][col / 4], col % 4) | (byte_of(code[4 * g + 1][col / 4], col % 4) << 8)
                      | (byte_of(code[4 * g + 2][col / 4], col % 4) << 16)
                      | (byte_of(code[4 * g + 3][col / 4], col % 4) << 24);
-            *reinterpret_cast<uint4*>(qT + (c0 + col) * rows + r0) = make_uint4(t[0], t[1], t[2], t[3]);
+            int8_t* dst = qT + (c0 + col) * rows + r0;
+            if constexpr(PR == 16)
+                *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
+            else
+                *reinterpret_cast<uint2*>(dst) = make_uint2(t[0], t[1]);
         }
     }
 }
@@ -970,26 +979,39 @@ hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t col
                         colsum_opt, sumsq_opt, workspace, stream);
 }
 
-template <typename T> struct PatchGeom
+// Launch shape of the patch kernel: lanes per row (as a power of two) and patch height.
+struct PatchShape { int lpr_log2, pr; int64_t gx, gy; };
+template <typename T> static PatchShape patch_shape(int64_t rows, int64_t cols, bool transposed_copy)
 {
-    static constexpr int kTileCols = 8 * 2 * Vec16<T>::N;                       // columns per wavefront tile
-    static constexpr int kTileRows = (kBlock / kWaveSize) * 8 * kPatchRows;     // rows per block (wavefronts stacked)
-};
+    constexpr int PCOLS = 2 * Vec16<T>::N;
+    PatchShape    p{3, 16, 0, 0};
+    const int64_t pc = (cols + PCOLS - 1) / PCOLS;                 // patches per row
+    while(p.lpr_log2 > 0 && (int64_t(1) << (p.lpr_log2 - 1)) >= pc) --p.lpr_log2;
+    // 8-row patches put twice the wavefronts in flight (measured: faster whenever no transposed copy is
+    // written, and below about eight wavefronts of 16-row patches per compute unit); the transposed copy
+    // of a large tensor prefers 16-byte stores
+    if(!transposed_copy || (rows / 16) * pc < int64_t(kWaveSize) * 2048) p.pr = 8;
+    p.gx = (pc + (int64_t(1) << p.lpr_log2) - 1) >> p.lpr_log2;
+    const int64_t rows_per_block = static_cast<int64_t>(kBlock / kWaveSize) * (kWaveSize >> p.lpr_log2) * p.pr;
+    p.gy = (rows + rows_per_block - 1) / rows_per_block;
+    return p;
+}
 
 template <typename T, int RND>
 static void quantize_patch_launch(const T* x, int64_t rows, int64_t cols, int64_t ld, int qmax, int gran,
                                   uint64_t seed, uint64_t offset, const float* inv, int8_t* q, int8_t* qT,
                                   hipStream_t st)
 {
-    const int64_t gx = (cols + PatchGeom<T>::kTileCols - 1) / PatchGeom<T>::kTileCols;
-    const int64_t gy = (rows + PatchGeom<T>::kTileRows - 1) / PatchGeom<T>::kTileRows;
-    const dim3    grid(static_cast<unsigned>(gx * gy));
-    if(gran == kPerCol)
-        quantize_patch_kernel<T, RND, true><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, gran, seed, offset,
-                                                                          inv, q, qT, gx);
-    else
-        quantize_patch_kernel<T, RND, false><<<grid, dim3(kBlock), 0, st>>>(x, rows, cols, ld, qmax, gran, seed,
-                                                                           offset, inv, q, qT, gx);
+    const PatchShape ps = patch_shape<T>(rows, cols, qT != nullptr);
+    const dim3       grid(static_cast<unsigned>(ps.gx * ps.gy));
+    auto go = [&](auto percol, auto pr) {
+        quantize_patch_kernel<T, RND, decltype(percol)::value, decltype(pr)::value><<<grid, dim3(kBlock), 0, st>>>(
+            x, rows, cols, ld, qmax, gran, seed, offset, inv, q, qT, ps.gx, ps.lpr_log2);
+    };
+    typedef std::integral_constant<int, 16> P16;
+    typedef std::integral_constant<int, 8>  P8;
+    if(gran == kPerCol) { if(ps.pr == 16) go(std::true_type{}, P16{}); else go(std::true_type{}, P8{}); }
+    else                { if(ps.pr == 16) go(std::false_type{}, P16{}); else go(std::false_type{}, P8{}); }
 }
 
 template <typename T>
@@ -997,8 +1019,8 @@ static hipError_t quantize_typed(const T* x, int64_t rows, int64_t cols, int64_t
                                  uint64_t seed, uint64_t offset, const float* inv, int8_t* q, int8_t* qT,
                                  hipStream_t st)
 {
-    const int64_t gx   = (cols + PatchGeom<T>::kTileCols - 1) / PatchGeom<T>::kTileCols;
-    const int64_t gy   = (rows + PatchGeom<T>::kTileRows - 1) / PatchGeom<T>::kTileRows;
+    const PatchShape ps = patch_shape<T>(rows, cols, qT != nullptr);
+    const int64_t    gx = ps.gx, gy = ps.gy;
     const bool    fast = cols % 8 == 0 && aligned16(x) && (ld * sizeof(T)) % 16 == 0 && (!q || aligned16(q))
                       && (!qT || (aligned16(qT) && rows % 16 == 0)) && gx * gy < (int64_t(1) << 31);
     if(fast)
