@@ -770,6 +770,67 @@ __global__ __launch_bounds__(kBlock) void convert_kernel(const Ti* __restrict__ 
     }
 }
 
+// Vector path of the cast to binary16 (and of the plain binary16 copy/transpose): each lane owns an
+// 8 x 8 patch (8 rows x 16 bytes of binary16 output), a wavefront is 8 x 8 patches, so every load and
+// every store instruction covers 128-byte (binary16) or 256-byte (fp32 input) row segments.  The patch
+// is transposed in registers by pairing 16-bit halves; no LDS, no barrier.  Needs cols % 8 == 0, 16-byte
+// aligned rows, and rows % 8 == 0 when the transposed copy is written.
+template <typename Ti>
+__global__ __launch_bounds__(kBlock) void cast_f16_patch_kernel(const Ti* __restrict__ x, int64_t rows, int64_t cols,
+                                                                int64_t ld, __half* __restrict__ q,
+                                                                __half* __restrict__ qT, int64_t grid_x)
+{
+    const int     lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
+    const int64_t by = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
+    const int64_t r0 = (by * (kBlock / kWaveSize) + wave) * 64 + (lane / 8) * 8;
+    const int64_t c0 = bx * 64 + (lane % 8) * 8;
+    if(r0 >= rows || c0 >= cols) return;
+    uint32_t w[8][4];                           // row i of the patch as four pairs of binary16
+#pragma unroll
+    for(int i = 0; i < 8; ++i)
+    {
+        const int64_t r  = r0 + i;
+        const bool    ok = r < rows;
+        if constexpr(sizeof(Ti) == 2)
+        {
+            const uint4 v = ok ? *reinterpret_cast<const uint4*>(x + r * ld + c0) : make_uint4(0, 0, 0, 0);
+            w[i][0] = v.x; w[i][1] = v.y; w[i][2] = v.z; w[i][3] = v.w;
+        }
+        else
+        {
+            const uint4 a = ok ? *reinterpret_cast<const uint4*>(x + r * ld + c0) : make_uint4(0, 0, 0, 0);
+            const uint4 b = ok ? *reinterpret_cast<const uint4*>(x + r * ld + c0 + 4) : make_uint4(0, 0, 0, 0);
+            const uint32_t f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for(int j = 0; j < 4; ++j)
+                w[i][j] = static_cast<uint32_t>(__half_as_ushort(__float2half_rn(__uint_as_float(f[2 * j]))))
+                        | (static_cast<uint32_t>(__half_as_ushort(__float2half_rn(__uint_as_float(f[2 * j + 1])))) << 16);
+        }
+    }
+    if(q)
+    {
+#pragma unroll
+        for(int i = 0; i < 8; ++i)
+            if(r0 + i < rows)
+                *reinterpret_cast<uint4*>(q + (r0 + i) * cols + c0) = make_uint4(w[i][0], w[i][1], w[i][2], w[i][3]);
+    }
+    if(qT)
+    {   // rows % 8 == 0 here: all eight rows exist.  Column c of the patch = halves c%2 of pair c/2 of every row.
+#pragma unroll
+        for(int c = 0; c < 8; ++c)
+        {
+            uint32_t t[4];
+#pragma unroll
+            for(int g = 0; g < 4; ++g)
+            {
+                const uint32_t lo = w[2 * g][c / 2], hi = w[2 * g + 1][c / 2];
+                t[g] = (c % 2 == 0) ? ((lo & 0xFFFFu) | (hi << 16)) : ((lo >> 16) | (hi & 0xFFFF0000u));
+            }
+            *reinterpret_cast<uint4*>(qT + (c0 + c) * rows + r0) = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ standalone dequantize
 template <typename To> __device__ __forceinline__ To from_f32(float v);
 template <> __device__ __forceinline__ float  from_f32<float>(float v) { return v; }
@@ -1057,6 +1118,17 @@ template <typename Ti, typename To>
 static hipError_t convert_typed(const void* x, int64_t rows, int64_t cols, int64_t ld, void* q, void* qT,
                                 hipStream_t st)
 {
+    if constexpr(std::is_same<To, __half>::value)
+    {
+        const int64_t bx = (cols + 63) / 64, by = (rows + 255) / 256;
+        if(cols % 8 == 0 && aligned16(x) && (ld * sizeof(Ti)) % 16 == 0 && (!q || aligned16(q))
+           && (!qT || (aligned16(qT) && rows % 8 == 0)) && bx * by < (int64_t(1) << 31))
+        {
+            cast_f16_patch_kernel<Ti><<<dim3(static_cast<unsigned>(bx * by)), dim3(kBlock), 0, st>>>(
+                static_cast<const Ti*>(x), rows, cols, ld, static_cast<__half*>(q), static_cast<__half*>(qT), bx);
+            return hipGetLastError();
+        }
+    }
     const int64_t gx = (cols + 63) / 64, gy = (rows + 63) / 64;
     convert_kernel<Ti, To, false><<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, st>>>(
         static_cast<const Ti*>(x), rows, cols, ld, static_cast<To*>(q), static_cast<To*>(qT), gx, 0, 0, 0);

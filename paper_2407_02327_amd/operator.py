@@ -88,6 +88,10 @@ class QLinear:
                                  stream)
             Q.qsync_quantize(x, M, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq,
                              self.xqT, stream)
+        elif x.dtype == _TORCH_OF_TAG[self.tag] and x.is_contiguous():
+            # already in the operand type: the tensor itself is the saved operand, only its transpose is written
+            self.xq = x
+            Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, None, self.xqT, stream)
         else:
             Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, self.xq, self.xqT, stream)
 
@@ -134,7 +138,11 @@ class QLinear:
             else:
                 Q.qsync_dequantize(self.wq, N, K, K, None, None, 1.0, None, self.wh, stream, tensor_scale_dev_opt=self.sw)
             Q.qsync_quantize(self.wh, N, K, K, Q.FP16, 0, 0, 0, 0, 0, None, None, self.whT, stream)
-            Q.qsync_quantize(dy, M, N, N, Q.FP16, 0, 0, 0, 0, 0, None, self.dyh, self.dyhT, stream)
+            if dy.dtype == torch.float16 and dy.is_contiguous():
+                self.dyh = dy
+                Q.qsync_quantize(dy, M, N, N, Q.FP16, 0, 0, 0, 0, 0, None, None, self.dyhT, stream)
+            else:
+                Q.qsync_quantize(dy, M, N, N, Q.FP16, 0, 0, 0, 0, 0, None, self.dyh, self.dyhT, stream)
             return
         if self.tag == Q.INT8:
             # the same pass over dY yields its absmax and the bias gradient db (column sums)
@@ -144,6 +152,9 @@ class QLinear:
                              self.idy, self.dyq, self.dyqT, stream)
             self.last_dy_offset = self.offset
             self.offset += (M * N + 7) // 8
+        elif dy.dtype == _TORCH_OF_TAG[self.tag] and dy.is_contiguous():
+            self.dyq = dy
+            Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, None, self.dyqT, stream)
         else:
             Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, self.dyq, self.dyqT, stream)
 
