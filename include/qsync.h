@@ -202,6 +202,26 @@ size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 
 /*
+ * qsync_prepare_weights - every weight operand of one INT8 linear operator with per-output-channel
+ * scales, from one call (paper: Cost Mapper paragraph, casting cost of the weights in the forward pass;
+ * channel-wise weight quantization).  Equivalent to, and bit-identical with, the sequence
+ *   qsync_absmax_scale(w, PER_ROW) -> sw, iw;   qsync_quantize(w, PER_ROW, nearest) -> wq [N,K]
+ *   qsync_absmax_scale(w, PER_COL) -> swb, iwb; qsync_quantize(w, PER_COL, nearest) -> wqbT [K,N] (transposed only)
+ * but reads w twice instead of four times (row and column maxima come from one pass, both sets of codes
+ * from another).  wqbT / swb are the operand and scales qsync_qlinear_bwd takes for dX.
+ *
+ * w        [N,K] packed, wdt QSYNC_F32 or QSYNC_F16, device.
+ * sw, iw   out, N floats each (scale, inverse scale per output channel); aw_opt out, N raw maxima or NULL.
+ * swb, iwb out, K floats each (per input feature).
+ * wq       out, [N,K] int8;  wqbT out, [K,N] int8.
+ * workspace  at least qsync_absmax_workspace_bytes(N, K, QSYNC_PER_COL) bytes, 16-byte aligned.
+ */
+int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits,
+                          float* sw, float* iw, float* aw_opt, void* wq,
+                          float* swb, float* iwb, void* wqbT,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * qsync_debug_set_gemm_tile - for tests and tuning runs: pin the tile shape of the MFMA GEMM
  * (0: 256x256, 1: 128x128, 2: 64x64) for every later call of this process, -1 (or any other value)
  * returns the choice to the planner.  Workspace sizes reported afterwards follow the pinned tile.

@@ -248,6 +248,23 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
     return QSYNC_OK;
 }
 
+int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits, float* sw, float* iw, float* aw_opt,
+                          void* wq, float* swb, float* iwb, void* wqbT, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    if(!w || !sw || !iw || !wq || !swb || !iwb || !wqbT) return QSYNC_ERR_NULL;
+    if(!is_float_dtype(wdt)) return QSYNC_ERR_BAD_ENUM;
+    if(!count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    if(N == 0 || K == 0) return QSYNC_OK;
+    if(!workspace || workspace_bytes < absmax_workspace_bytes(N, K, kPerCol)) return QSYNC_ERR_WORKSPACE;
+    if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    return hip_status(launch_prepare_weights(w, wdt == QSYNC_F32 ? kF32 : kF16, N, K, qmax, sw, iw, aw_opt,
+                                             static_cast<int8_t*>(wq), swb, iwb, static_cast<int8_t*>(wqbT), workspace,
+                                             static_cast<hipStream_t>(stream)));
+}
+
 void qsync_debug_set_gemm_tile(int tile) { set_gemm_tile_override(tile); }
 
 int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,

@@ -466,6 +466,82 @@ __global__ __launch_bounds__(kBlock) void colreduce_finalize_kernel(const float*
     }
 }
 
+// ------------------------------------------------------------------ weights: row and column maxima in one pass
+// Block b owns rows b*R .. b*R+R-1 in full: a thread sweeps its 16-byte column vectors with the R
+// row loads of a vector in flight together, keeps the running maximum of every row in registers and
+// writes the column maxima of its row group to partial[b][c] (folded by colreduce_finalize_kernel).
+// Row maxima are complete inside the block: wave shuffles, one LDS exchange, then scale and inverse.
+// Maxima are order independent, so the results equal those of the separate per-row and per-column passes.
+template <typename T, int R, int U>
+__global__ __launch_bounds__(kBlock) void absmax_rowcol_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                               int64_t ld, float qmax, float* row_scale, float* row_inv,
+                                                               float* row_amax_opt, float* __restrict__ col_partial)
+{
+    constexpr int E = Vec16<T>::N;
+    __shared__ float lds[R][kBlock / kWaveSize];
+    const int64_t r0  = static_cast<int64_t>(blockIdx.x) * R;
+    const int64_t ncv = cols / E;                    // cols % E == 0 on this path
+    float         rowm[R];
+#pragma unroll
+    for(int i = 0; i < R; ++i) rowm[i] = 0.0f;
+    for(int64_t cv0 = threadIdx.x; cv0 < ncv; cv0 += static_cast<int64_t>(kBlock) * U)
+    {
+        uint4 raw[U][R];                             // R x U loads in flight
+#pragma unroll
+        for(int u = 0; u < U; ++u)
+#pragma unroll
+            for(int i = 0; i < R; ++i)
+            {
+                const int64_t cv = cv0 + u * kBlock;
+                raw[u][i] = (r0 + i < rows && cv < ncv) ? *reinterpret_cast<const uint4*>(x + (r0 + i) * ld + cv * E)
+                                                         : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+        for(int u = 0; u < U; ++u)
+        {
+            const int64_t cv = cv0 + u * kBlock;
+            float         cm[E];
+#pragma unroll
+            for(int e = 0; e < E; ++e) cm[e] = 0.0f;
+#pragma unroll
+            for(int i = 0; i < R; ++i)
+            {
+                float v[E];
+                Vec16<T>::decode(raw[u][i], v);
+#pragma unroll
+                for(int e = 0; e < E; ++e)
+                {
+                    const float a = fabsf(v[e]);
+                    cm[e]   = fmaxf(cm[e], a);
+                    rowm[i] = fmaxf(rowm[i], a);
+                }
+            }
+            if(cv < ncv)
+            {
+                float* dst = col_partial + static_cast<int64_t>(blockIdx.x) * cols + cv * E;
+#pragma unroll
+                for(int e = 0; e < E; e += 4)
+                    *reinterpret_cast<float4*>(dst + e) = make_float4(cm[e], cm[e + 1], cm[e + 2], cm[e + 3]);
+            }
+        }
+    }
+    const int lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
+#pragma unroll
+    for(int i = 0; i < R; ++i)
+    {
+        const float m = wave_reduce_max(rowm[i]);
+        if(lane == 0) lds[i][wave] = m;
+    }
+    __syncthreads();
+    if(threadIdx.x < R && r0 + threadIdx.x < rows)
+    {
+        float m = lds[threadIdx.x][0];
+#pragma unroll
+        for(int w = 1; w < kBlock / kWaveSize; ++w) m = fmaxf(m, lds[threadIdx.x][w]);
+        write_scale(m, qmax, row_scale, row_inv, row_amax_opt, r0 + threadIdx.x);
+    }
+}
+
 // ------------------------------------------------------------------ INT8 quantize, vector path
 // Each lane owns a patch of 16 (or 8) rows x 32 input bytes (16 binary16 or 8 fp32 columns) and
 // requests the eight 16-byte loads of four rows together before it converts them.  A wavefront is up
@@ -479,13 +555,17 @@ __global__ __launch_bounds__(kBlock) void colreduce_finalize_kernel(const float*
 
 __device__ __forceinline__ uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xFFu; }
 
-template <typename T, int RND, bool PERCOL, int PR>
+template <typename T, int RND, bool PERCOL, int PR, bool DUAL = false>
 __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                                 int64_t ld, int qmax, int gran, uint64_t seed,
                                                                 uint64_t offset, const float* __restrict__ inv_scale,
                                                                 int8_t* __restrict__ q, int8_t* __restrict__ qT,
-                                                                int64_t grid_x, int lpr_log2)
+                                                                int64_t grid_x, int lpr_log2,
+                                                                const float* __restrict__ inv_scale_T = nullptr)
 {
+    // DUAL (weights): q takes the scales of `gran` (per row), the transposed copy takes one scale per column
+    // from inv_scale_T -- two quantizations of the same values from one read.
+    static_assert(!DUAL || (!PERCOL && RND != kStochastic), "dual scales: nearest/floor, row scales for q");
     // A lane converts a patch of PR rows x PCOLS columns; the 2^lpr_log2 lanes of a wavefront that share
     // rows cover a contiguous row segment, the other lane bits stack patches downwards.  Narrow matrices
     // use fewer lanes per row (no idle lanes), small ones shorter patches (more wavefronts in flight).
@@ -502,14 +582,16 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
     const bool second_ok = NH == 1 || c0 + 8 < cols;      // binary16: the patch's second 8 columns exist
 
     float fcol[PCOLS];
-    if(PERCOL)
+    if(PERCOL || DUAL)
     {
+        const float* cs = DUAL ? inv_scale_T : inv_scale;
 #pragma unroll
-        for(int j = 0; j < PCOLS; ++j) fcol[j] = (j < 8 || second_ok) ? inv_scale[c0 + j] : 1.0f;
+        for(int j = 0; j < PCOLS; ++j) fcol[j] = (j < 8 || second_ok) ? cs[c0 + j] : 1.0f;
     }
     const float ftensor = (!PERCOL && gran == kPerTensor) ? inv_scale[0] : 1.0f;
 
     uint32_t code[PR][CW];   // row i, columns 4w..4w+3 in dword w
+    uint32_t codeT[DUAL ? PR : 1][CW];   // DUAL: the codes of the transposed copy
     constexpr int RB = 4;                // rows per batch
 #pragma unroll
     for(int batch = 0; batch < PR / RB; ++batch)
@@ -544,6 +626,17 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
             }
 #pragma unroll
             for(int w = 0; w < CW; ++w) code[i][w] = 0u;
+            if constexpr(DUAL)
+            {
+#pragma unroll
+                for(int w = 0; w < CW; ++w) codeT[i][w] = 0u;
+#pragma unroll
+                for(int col = 0; col < PCOLS; ++col)
+                {
+                    const int c = quantize_code<RND>(v[col], fcol[col], qmax, 0u);
+                    codeT[i][col / 4] |= (static_cast<uint32_t>(c) & 0xFFu) << (8 * (col % 4));
+                }
+            }
 #pragma unroll
             for(int h = 0; h < NH; ++h)
             {
@@ -596,9 +689,14 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
             uint32_t t[PR / 4];
 #pragma unroll
             for(int g = 0; g < PR / 4; ++g)
-                t[g] = byte_of(code[4 * g + 0][col / 4], col % 4) | (byte_of(code[4 * g + 1][col / 4], col % 4) << 8)
-                     | (byte_of(code[4 * g + 2][col / 4], col % 4) << 16)
-                     | (byte_of(code[4 * g + 3][col / 4], col % 4) << 24);
+            {
+                auto pick = [&](int r, int w) -> uint32_t {
+                    if constexpr(DUAL) return codeT[r][w]; else return code[r][w];
+                };
+                t[g] = byte_of(pick(4 * g + 0, col / 4), col % 4) | (byte_of(pick(4 * g + 1, col / 4), col % 4) << 8)
+                     | (byte_of(pick(4 * g + 2, col / 4), col % 4) << 16)
+                     | (byte_of(pick(4 * g + 3, col / 4), col % 4) << 24);
+            }
             int8_t* dst = qT + (c0 + col) * rows + r0;
             if constexpr(PR == 16)
                 *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
@@ -1112,6 +1210,60 @@ hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t co
                               q, qT, stream);
     return quantize_typed(static_cast<const __half*>(x), rows, cols, ld, qmax, gran, rnd, seed, offset, inv_scale, q,
                           qT, stream);
+}
+
+// Weights of one linear operator in one go: per-row scales and codes for the forward, per-column scales
+// and transposed codes for dX.  Fused form: row + column maxima in one pass, the column fold, one dual
+// quantize (3 launches, W read twice); otherwise the five separate launches.  Same results either way.
+template <typename T>
+static hipError_t prepare_weights_typed(const T* w, int64_t N, int64_t K, float qmax, float* sw, float* iw,
+                                        float* aw_opt, int8_t* wq, float* swb, float* iwb, int8_t* wqbT,
+                                        void* workspace, hipStream_t st)
+{
+    constexpr int E = Vec16<T>::N;
+    float*        partial = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes);
+    const bool    fused = aligned16(w) && K % (2 * E) == 0 && K % 8 == 0 && N % 16 == 0 && N <= 16 * kColParts
+                       && aligned16(wq) && aligned16(wqbT) && aligned16(partial);
+    if(!fused)
+    {
+        hipError_t e = absmax_typed(w, N, K, K, kPerRow, qmax, sw, iw, aw_opt, nullptr, nullptr, workspace, st);
+        if(e != hipSuccess) return e;
+        e = quantize_typed(w, N, K, K, static_cast<int>(qmax), kPerRow, kNearest, 0, 0, iw, wq, nullptr, st);
+        if(e != hipSuccess) return e;
+        e = absmax_typed(w, N, K, K, kPerCol, qmax, swb, iwb, nullptr, nullptr, nullptr, workspace, st);
+        if(e != hipSuccess) return e;
+        return quantize_typed(w, N, K, K, static_cast<int>(qmax), kPerCol, kNearest, 0, 0, iwb, nullptr, wqbT, st);
+    }
+    int gy;          // row groups = partial rows per column (at most kColParts); 16 loads in flight per thread
+    if(N <= 4 * kColParts)
+    {
+        gy = static_cast<int>((N + 3) / 4);
+        absmax_rowcol_kernel<T, 4, 4><<<dim3(gy), dim3(kBlock), 0, st>>>(w, N, K, K, qmax, sw, iw, aw_opt, partial);
+    }
+    else if(N <= 8 * kColParts)
+    {
+        gy = static_cast<int>((N + 7) / 8);
+        absmax_rowcol_kernel<T, 8, 2><<<dim3(gy), dim3(kBlock), 0, st>>>(w, N, K, K, qmax, sw, iw, aw_opt, partial);
+    }
+    else
+    {
+        gy = static_cast<int>((N + 15) / 16);
+        absmax_rowcol_kernel<T, 16, 1><<<dim3(gy), dim3(kBlock), 0, st>>>(w, N, K, K, qmax, sw, iw, aw_opt, partial);
+    }
+    colreduce_finalize_kernel<OP_MAX><<<dim3((K + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy, K, qmax, swb, iwb, nullptr);
+    PatchShape ps = patch_shape<T>(N, K, false);          // 8-row patches
+    quantize_patch_kernel<T, kNearest, false, 8, true><<<dim3(static_cast<unsigned>(ps.gx * ps.gy)), dim3(kBlock), 0, st>>>(
+        w, N, K, K, static_cast<int>(qmax), kPerRow, 0, 0, iw, wq, wqbT, ps.gx, ps.lpr_log2, iwb);
+    return hipGetLastError();
+}
+
+hipError_t launch_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, float qmax, float* sw, float* iw,
+                                  float* aw_opt, int8_t* wq, float* swb, float* iwb, int8_t* wqbT, void* workspace,
+                                  hipStream_t stream)
+{
+    if(wdt == kF32)
+        return prepare_weights_typed(static_cast<const float*>(w), N, K, qmax, sw, iw, aw_opt, wq, swb, iwb, wqbT, workspace, stream);
+    return prepare_weights_typed(static_cast<const __half*>(w), N, K, qmax, sw, iw, aw_opt, wq, swb, iwb, wqbT, workspace, stream);
 }
 
 template <typename Ti, typename To>

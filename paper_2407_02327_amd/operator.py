@@ -114,18 +114,17 @@ class QLinear:
         if self.tag != Q.INT8:
             Q.qsync_quantize(w, N, K, K, self.tag, 0, 0, 0, 0, 0, None, self.wq, self.wqbT, stream)
             return
-        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax_w,
-                             stream)
         if self.w_gran == Q.PER_TENSOR:       # one quantization serves the forward and dX
+            Q.qsync_absmax_scale(w, N, K, K, Q.PER_TENSOR, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax_w,
+                                 stream)
             Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq,
                              self.wqbT, stream)
             self.swb = self.sw
             return
-        Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_ROW, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
-        # dX contracts over the output channels, so its weight codes carry one scale per input feature
-        Q.qsync_absmax_scale(w, N, K, K, Q.PER_COL, self.bits, self.swb, self.iwb, None, None, self.ws_absmax_w, stream)
-        Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_COL, Q.ROUND_NEAREST, 0, 0, self.iwb, None, self.wqbT,
-                         stream)
+        # per-output-channel codes for the forward; dX contracts over the output channels, so its weight codes
+        # carry one scale per input feature (second quantization, stored transposed): one fused call
+        Q.qsync_prepare_weights(w, N, K, self.bits, self.sw, self.iw, self.aw, self.wq, self.swb, self.iwb, self.wqbT,
+                                self.ws_absmax_w, stream)
 
     def convert_dy(self, dy: torch.Tensor, stream=None) -> None:
         M, N, K = self.M, self.N, self.K

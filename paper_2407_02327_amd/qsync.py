@@ -39,6 +39,7 @@ SIGNATURES = {
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
     "qsync_debug_set_gemm_tile": (None, [_i]),
+    "qsync_prepare_weights": (_i, [_vp, _i, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qsync_conv3x3_wflip": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
     "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _vp, _i, _vp]),
     "qsync_last_hip_error": (_i, []),
@@ -130,6 +131,11 @@ def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, 
 def qsync_conv3x3_fwd(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt=None, stream=None) -> None:
     _check(lib.qsync_conv3x3_fwd(tag, nimg, H, W, C, N, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
                                  _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _stream(stream)))
+
+
+def qsync_prepare_weights(w, N, K, bits, sw, iw, aw_opt, wq, swb, iwb, wqbT, workspace, stream=None) -> None:
+    _check(lib.qsync_prepare_weights(_ptr(w), dtype_code(w), N, K, bits, _ptr(sw), _ptr(iw), _ptr(aw_opt), _ptr(wq),
+                                     _ptr(swb), _ptr(iwb), _ptr(wqbT), _ptr(workspace), _bytes(workspace), _stream(stream)))
 
 
 def qsync_debug_set_gemm_tile(tile: int) -> None:

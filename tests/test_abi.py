@@ -136,6 +136,27 @@ def test_im2col_validation():
     assert f(A, 0, 4, 4, 16, A, None, None) == qsync.OK
 
 
+def test_prepare_weights_validation():
+    f = lib.qsync_prepare_weights
+    ok = [A, qsync.F32, 64, 64, 8, A, A, None, A, A, A, A, A, 1 << 24, None]
+    assert f(*ok) in (qsync.OK, qsync.ERR_HIP)
+    for i in (0, 5, 6, 8, 9, 10, 11):
+        a = list(ok); a[i] = None
+        assert f(*a) == qsync.ERR_NULL
+    a = list(ok); a[1] = qsync.I8
+    assert f(*a) == qsync.ERR_BAD_ENUM
+    a = list(ok); a[2] = -1
+    assert f(*a) == qsync.ERR_BAD_SHAPE
+    a = list(ok); a[4] = 9
+    assert f(*a) == qsync.ERR_UNSUPPORTED
+    a = list(ok); a[13] = 16
+    assert f(*a) == qsync.ERR_WORKSPACE
+    a = list(ok); a[12] = U
+    assert f(*a) == qsync.ERR_ALIGN
+    a = list(ok); a[2] = 0
+    assert f(*a) == qsync.OK
+
+
 def test_conv_validation():
     f = lib.qsync_conv3x3_fwd
     ok = [8, 1, 4, 4, 16, 8, A, A, A, A, qsync.PER_ROW, None, A, 0, None, None]

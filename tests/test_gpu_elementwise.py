@@ -116,6 +116,31 @@ def test_fp16_stochastic_cast_bit_exact(k):
     assert_bits_equal(host(q).view(np.uint16), h.view(np.uint16), "fp16 copy")
 
 
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+def test_prepare_weights_equals_the_separate_calls(dt):
+    """Fused weight preparation (row and column maxima in one pass, both sets of codes in another) against the
+    oracle's per-row and per-column quantizations; shapes on the fused path (both row-group sizes) and off it."""
+    rng = np.random.default_rng(42)
+    for (n, k) in [(64, 576), (1024, 4096), (4096, 1024), (3072, 768), (48, 40), (20, 24), (16, 8), (8208, 64)]:
+        say("prepare weights", dt.__name__, n, k)
+        w = (rng.standard_normal((n, k)) * 0.02).astype(dt)
+        w[rng.integers(0, n), :] = 0                       # an all-zero row: scale 1
+        sw, iw, aw = empty((n,), torch.float32), empty((n,), torch.float32), empty((n,), torch.float32)
+        swb, iwb = empty((k,), torch.float32), empty((k,), torch.float32)
+        wq, wqbT = empty((n, k), torch.int8), empty((k, n), torch.int8)
+        Q.qsync_prepare_weights(dev(w), n, k, 8, sw, iw, aw, wq, swb, iwb, wqbT, ws(Q.qsync_absmax_workspace_bytes(n, k, Q.PER_COL)))
+        ar, ac = orc.absmax(w, "row"), orc.absmax(w, "col")
+        sr, ir = orc.scales_from_amax(ar)
+        sc, ic = orc.scales_from_amax(ac)
+        assert_bits_equal(host(aw), ar, "row maxima")
+        assert_bits_equal(host(sw), sr, "row scales")
+        assert_bits_equal(host(iw), ir, "row inverse scales")
+        assert_bits_equal(host(swb), sc, "column scales")
+        assert_bits_equal(host(iwb), ic, "column inverse scales")
+        assert_bits_equal(host(wq), orc.quantize_int(w, ir, "row", "nearest"), "row-scaled codes")
+        assert_bits_equal(host(wqbT), orc.quantize_int(w, ic, "col", "nearest").T, "column-scaled codes, transposed")
+
+
 def test_im2col_on_codes_bit_exact():
     from paper_2407_02327_amd import workloads as wl
     rng = np.random.default_rng(41)
