@@ -231,6 +231,25 @@ def main():
         ms2 = (time.perf_counter() - t1) * 1e3 / args.steps
         overlapped = {"operator_streams": len(ops_objs), "ms_per_step": round(ms2, 4),
                       "value": round(gemm_ops / (ms2 * 1e-3) / 1e12, 3), "unit": "TOPS"}
+    # Extra (outside the timed region): the matrix-instruction rate the GPU sustains with no memory traffic
+    # (register operands), with constant and with pseudo-random operand values: context for roofline.frac.
+    mfma_probe = None
+    if not args.no_extra_passes:
+        scratch = torch.empty(512 * 256, dtype=torch.int32, device="cuda")
+        mfma_probe = {"unit": "TOPS" if tag == Q.INT8 else "TFLOP/s", "kernel": "qsync_probe_mfma (512 x 4 wavefronts, "
+                      "back-to-back 32x32 matrix instructions on register operands)"}
+        modes = [("constant_operands", 0), ("random_operands", 1)]
+        if tag == Q.FP16:
+            modes.append(("random_operands_second_subnormal", 2))
+        for key, rnd_ops in modes:
+            Q.qsync_probe_mfma(tag, rnd_ops, 2000, scratch, main)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            ops = Q.qsync_probe_mfma(tag, rnd_ops, 50000, scratch, main)
+            e1.record(main)
+            torch.cuda.synchronize()
+            mfma_probe[key] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        del scratch
     # Extra (outside the timed region): the quantize kernel alone on the largest gradient tensor of the
     # workload, 20 back-to-back launches each; "cold" rotates through enough input/output sets to exceed
     # 512 MB (nothing is left in the memory-side cache), "warm" reuses one set.
@@ -292,6 +311,8 @@ def main():
     fwd_ops = sum(2 * c.mnk[0] * c.mnk[1] * c.mnk[2] for c in cases)
     achieved = fwd_ops / (fwd_ms * 1e-3) / 1e12
     peak = PEAK[args.tag]
+    if mfma_probe is not None:
+        mfma_probe["forward_gemm_frac_of_random_operand_rate"] = round(achieved / mfma_probe["random_operands"], 4)
     # HBM-bound side: absmax + quantize of dY (read twice, write codes + transposed codes)
     esz = cases[0].dy.dtype.itemsize
     dy_bytes = sum(c.dy.size * (2 * esz + 2) for c in cases)
@@ -322,6 +343,7 @@ def main():
                        {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
                         "bytes": "absmax read + quantize read + codes + transposed codes"},
         "quantize_alone": quant_iso,
+        "mfma_probe": mfma_probe,
         "operators_on_separate_streams": overlapped,
     }
     if "gemm_bwd" in per_step:

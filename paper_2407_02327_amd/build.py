@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libqsync.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm_mfma.hip", "gemm_f32.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm_mfma.hip", "gemm_f32.hip", "probe.hip"]
 
 # -ffp-contract=off: the quantizer's multiply and subtract must stay separately rounded.
 # packed fp32 VALU ops are disabled for the device pass (hipcc's host pass warns that it

@@ -265,6 +265,18 @@ int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits
                                              static_cast<hipStream_t>(stream)));
 }
 
+int qsync_probe_mfma(int tag, int random_operands, int iters, void* out, double* ops_out, void* stream)
+{
+    if(!out) return QSYNC_ERR_NULL;
+    if(tag != QSYNC_INT8 && tag != QSYNC_FP16) return QSYNC_ERR_BAD_ENUM;
+    if(iters < 1 || iters > (1 << 24)) return QSYNC_ERR_BAD_SHAPE;
+    iters = (iters + 3) / 4 * 4;               // the kernel runs whole groups of four iterations
+    if(random_operands < 0 || random_operands > 2) return QSYNC_ERR_BAD_ENUM;
+    if(ops_out)   // a 32x32x32 int8 instruction is 2*32*32*32 operations, the 32x32x16 binary16 one half of that
+        *ops_out = static_cast<double>(kProbeBlocks) * 4.0 * 4.0 * iters * (tag == QSYNC_INT8 ? 65536.0 : 32768.0);
+    return hip_status(launch_probe_mfma(tag, random_operands, iters, out, static_cast<hipStream_t>(stream)));
+}
+
 void qsync_debug_set_gemm_tile(int tile) { set_gemm_tile_override(tile); }
 
 int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,

@@ -81,4 +81,8 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile = -
 void set_gemm_tile_override(int tile);
 hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream);
 
+// ---- measurement probe (probe.hip): matrix instructions on register operands, no memory traffic
+constexpr int kProbeBlocks = 512;       // workgroups of 4 wavefronts, 4 matrix instructions per wavefront and iteration
+hipError_t launch_probe_mfma(int prec, int operand_mode, int iters, void* out, hipStream_t stream);
+
 }  // namespace qsync

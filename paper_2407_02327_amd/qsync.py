@@ -39,6 +39,7 @@ SIGNATURES = {
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
     "qsync_debug_set_gemm_tile": (None, [_i]),
+    "qsync_probe_mfma": (_i, [_i, _i, _i, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "qsync_prepare_weights": (_i, [_vp, _i, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qsync_conv3x3_wflip": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
     "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _vp, _i, _vp]),
@@ -136,6 +137,13 @@ def qsync_conv3x3_fwd(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y,
 def qsync_prepare_weights(w, N, K, bits, sw, iw, aw_opt, wq, swb, iwb, wqbT, workspace, stream=None) -> None:
     _check(lib.qsync_prepare_weights(_ptr(w), dtype_code(w), N, K, bits, _ptr(sw), _ptr(iw), _ptr(aw_opt), _ptr(wq),
                                      _ptr(swb), _ptr(iwb), _ptr(wqbT), _ptr(workspace), _bytes(workspace), _stream(stream)))
+
+
+def qsync_probe_mfma(tag: int, random_operands: int, iters: int, out, stream=None) -> float:
+    """Launches the probe on `stream` and returns the operation count of the launch (the caller times it)."""
+    ops = ctypes.c_double(0.0)
+    _check(lib.qsync_probe_mfma(tag, int(random_operands), iters, _ptr(out), ctypes.byref(ops), _stream(stream)))
+    return ops.value
 
 
 def qsync_debug_set_gemm_tile(tile: int) -> None:

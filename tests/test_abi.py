@@ -157,6 +157,17 @@ def test_prepare_weights_validation():
     assert f(*a) == qsync.OK
 
 
+def test_probe_validation():
+    f = lib.qsync_probe_mfma
+    assert f(8, 0, 10, None, None, None) == qsync.ERR_NULL
+    assert f(32, 0, 10, A, None, None) == qsync.ERR_BAD_ENUM
+    assert f(8, 0, 0, A, None, None) == qsync.ERR_BAD_SHAPE
+    ops = ctypes.c_double(0.0)
+    assert f(16, 1, 10, A, ctypes.byref(ops), None) in (qsync.OK, qsync.ERR_HIP)
+    assert ops.value == 512 * 16 * 12 * 32768.0          # iterations rounded up to a multiple of four
+    assert f(16, 3, 10, A, None, None) == qsync.ERR_BAD_ENUM
+
+
 def test_conv_validation():
     f = lib.qsync_conv3x3_fwd
     ok = [8, 1, 4, 4, 16, 8, A, A, A, A, qsync.PER_ROW, None, A, 0, None, None]
