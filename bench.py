@@ -254,6 +254,7 @@ def main():
     # workload, 20 back-to-back launches each; "cold" rotates through enough input/output sets to exceed
     # 512 MB (nothing is left in the memory-side cache), "warm" reuses one set.
     quant_iso = None
+    dequant_iso = None
     if tag == Q.INT8 and args.bwd_tag is None and not args.no_extra_passes:
         big = max(range(len(cases)), key=lambda i: cases[i].dy.size)
         op, dy = ops_objs[big], dev_in[big][2]
@@ -295,6 +296,29 @@ def main():
             gbs = bytes_per / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
             quant_iso[f"plain_copy_{mode}"] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
         del sets, csets
+        # the standalone dequantizer on raw accumulators of the same shape: int32 -> fp16 with the per-column
+        # scale and bias of a per-output-channel operator (read 4 B, write 2 B per element)
+        dq_bytes = Mq * Nq * 6
+        nset = max(2, int(math.ceil((512 << 20) / dq_bytes)) + 1)
+        dsets = [(torch.randint(-2**20, 2**20, (Mq, Nq), dtype=torch.int32, device="cuda"),
+                  torch.empty(Mq, Nq, dtype=torch.float16, device="cuda")) for _ in range(nset)]
+        csv_, cbv_ = torch.rand(Nq, device="cuda"), torch.rand(Nq, device="cuda")
+        dequant_iso = {"tensor": f"int32 accumulators [{Mq},{Nq}] -> float16, per-column scale + bias", "sets_rotated_cold": nset}
+        for mode in ("cold", "warm"):
+            def oned(i):
+                a_, y_ = dsets[i % nset] if mode == "cold" else dsets[0]
+                Q.qsync_dequantize(a_, Mq, Nq, Nq, None, csv_, 1e-6, cbv_, y_, main)
+            for i in range(5):
+                oned(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            for i in range(20):
+                oned(i)
+            e1.record(main)
+            torch.cuda.synchronize()
+            gbs = dq_bytes / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
+            dequant_iso[mode] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+        del dsets
 
     # Extra (outside the timed region): a fully instrumented pass for the per-phase breakdown.
     per_step = {"gemm_fwd": fwd_ms}
@@ -343,6 +367,7 @@ def main():
                        {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
                         "bytes": "absmax read + quantize read + codes + transposed codes"},
         "quantize_alone": quant_iso,
+        "dequantize_alone": dequant_iso,
         "mfma_probe": mfma_probe,
         "operators_on_separate_streams": overlapped,
     }
