@@ -222,6 +222,25 @@ int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qsync_conv3x3_prepare_weights - every weight operand of one INT8 3x3 convolution with per-output-channel
+ * scales (paper: channel-wise weight quantization; casting cost of the weights in the forward pass).
+ * Bit-identical with the sequence
+ *   qsync_absmax_scale(w [N,9C], PER_ROW) -> sw, iw;          qsync_quantize(PER_ROW, nearest) -> wq [N,9C]
+ *   qsync_absmax_scale(w as [9N,C], PER_COL) -> swb, iwb;     qsync_quantize(PER_COL, nearest) -> codes [N,9C]
+ *   qsync_conv3x3_wflip(codes) -> wflip [C,9N]
+ * wflip with swb (QSYNC_PER_ROW of wflip) is the weight operand of the data gradient, see qsync_conv3x3_fwd.
+ * Three launches and two reads of w when N % 16 == 0 (row and column maxima in one pass, both sets of codes
+ * from one read, written straight to their final places), the five separate passes otherwise.
+ * w [N, 9*C] packed (k = (kh, kw, c)), wdt QSYNC_F32 or QSYNC_F16; sw, iw: N floats; swb, iwb: C floats.
+ * workspace  at least qsync_conv3x3_prepare_weights_workspace_bytes(N, C) bytes, 16-byte aligned, its first
+ *            256 bytes zeroed once by the caller (as for qsync_absmax_scale).
+ */
+int qsync_conv3x3_prepare_weights(const void* w, int wdt, int64_t N, int64_t C, int bits,
+                                  float* sw, float* iw, void* wq, float* swb, float* iwb, void* wflip,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+size_t qsync_conv3x3_prepare_weights_workspace_bytes(int64_t N, int64_t C);
+
+/*
  * qsync_probe_mfma - measurement probe, not part of the operator path: launches a kernel that issues
  * `iters` x 4 back-to-back 32x32 matrix instructions per wavefront on register operands (512 workgroups
  * of 4 wavefronts, no memory traffic), so that a caller can time the matrix-instruction rate this GPU

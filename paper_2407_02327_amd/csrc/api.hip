@@ -265,6 +265,29 @@ int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits
                                              static_cast<hipStream_t>(stream)));
 }
 
+size_t qsync_conv3x3_prepare_weights_workspace_bytes(int64_t N, int64_t C)
+{
+    if(N <= 0 || C <= 0) return 0;
+    return absmax_workspace_bytes(N, 9 * C, kPerCol) + static_cast<size_t>(9 * N * C);
+}
+
+int qsync_conv3x3_prepare_weights(const void* w, int wdt, int64_t N, int64_t C, int bits, float* sw, float* iw, void* wq,
+                                  float* swb, float* iwb, void* wflip, void* workspace, size_t workspace_bytes,
+                                  void* stream)
+{
+    if(!w || !sw || !iw || !wq || !swb || !iwb || !wflip) return QSYNC_ERR_NULL;
+    if(!is_float_dtype(wdt)) return QSYNC_ERR_BAD_ENUM;
+    if(N < 0 || C < 0 || C > (1 << 20) || !count_ok(N, 9 * C)) return QSYNC_ERR_BAD_SHAPE;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    if(N == 0 || C == 0) return QSYNC_OK;
+    if(!workspace || workspace_bytes < qsync_conv3x3_prepare_weights_workspace_bytes(N, C)) return QSYNC_ERR_WORKSPACE;
+    if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    return hip_status(launch_conv3x3_prepare_weights(w, wdt == QSYNC_F32 ? kF32 : kF16, N, C, qmax, sw, iw, swb, iwb,
+                                                     static_cast<int8_t*>(wq), static_cast<int8_t*>(wflip), workspace,
+                                                     static_cast<hipStream_t>(stream)));
+}
+
 int qsync_probe_mfma(int tag, int random_operands, int iters, void* out, double* ops_out, void* stream)
 {
     if(!out) return QSYNC_ERR_NULL;

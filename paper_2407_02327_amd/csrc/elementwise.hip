@@ -561,10 +561,13 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
                                                                 uint64_t offset, const float* __restrict__ inv_scale,
                                                                 int8_t* __restrict__ q, int8_t* __restrict__ qT,
                                                                 int64_t grid_x, int lpr_log2,
-                                                                const float* __restrict__ inv_scale_T = nullptr)
+                                                                const float* __restrict__ inv_scale_T = nullptr,
+                                                                int flip_C = 0)
 {
     // DUAL (weights): q takes the scales of `gran` (per row), the transposed copy takes one scale per column
-    // from inv_scale_T -- two quantizations of the same values from one read.
+    // from inv_scale_T -- two quantizations of the same values from one read.  flip_C > 0 (3x3 convolution
+    // weights [N, 9*C]): the column scale belongs to the input channel c = column % C and column (tap, c)
+    // lands in row c*9 + (8 - tap) of the transposed copy, i.e. the mirrored, channel-exchanged weights.
     static_assert(!DUAL || (!PERCOL && RND != kStochastic), "dual scales: nearest/floor, row scales for q");
     // A lane converts a patch of PR rows x PCOLS columns; the 2^lpr_log2 lanes of a wavefront that share
     // rows cover a contiguous row segment, the other lane bits stack patches downwards.  Narrow matrices
@@ -586,7 +589,8 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
     {
         const float* cs = DUAL ? inv_scale_T : inv_scale;
 #pragma unroll
-        for(int j = 0; j < PCOLS; ++j) fcol[j] = (j < 8 || second_ok) ? cs[c0 + j] : 1.0f;
+        for(int j = 0; j < PCOLS; ++j)
+            fcol[j] = (j < 8 || second_ok) ? cs[(DUAL && flip_C > 0) ? (c0 + j) % flip_C : (c0 + j)] : 1.0f;
     }
     const float ftensor = (!PERCOL && gran == kPerTensor) ? inv_scale[0] : 1.0f;
 
@@ -697,7 +701,13 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
                      | (byte_of(pick(4 * g + 2, col / 4), col % 4) << 16)
                      | (byte_of(pick(4 * g + 3, col / 4), col % 4) << 24);
             }
-            int8_t* dst = qT + (c0 + col) * rows + r0;
+            int64_t trow = c0 + col;
+            if(DUAL && flip_C > 0)
+            {
+                const int64_t tap = trow / flip_C;
+                trow = (trow - tap * flip_C) * 9 + (8 - tap);
+            }
+            int8_t* dst = qT + trow * rows + r0;
             if constexpr(PR == 16)
                 *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
             else
@@ -1282,12 +1292,15 @@ hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t co
 template <typename T>
 static hipError_t prepare_weights_typed(const T* w, int64_t N, int64_t K, float qmax, float* sw, float* iw,
                                         float* aw_opt, int8_t* wq, float* swb, float* iwb, int8_t* wqbT,
-                                        void* workspace, hipStream_t st)
+                                        void* workspace, hipStream_t st, int64_t conv_C = 0)
 {
+    // conv_C > 0: w is [N, 9*conv_C]; the second scales are per input channel (conv_C of them) and wqbT is the
+    // mirrored, channel-exchanged copy [conv_C, 9*N]; only the fused form serves this case.
     constexpr int E = Vec16<T>::N;
     float*        partial = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes);
     const bool    fused = aligned16(w) && K % (2 * E) == 0 && K % 8 == 0 && N % 16 == 0 && N <= 16 * kColParts
                        && aligned16(wq) && aligned16(wqbT) && aligned16(partial);
+    if(!fused && conv_C > 0) return hipErrorInvalidValue;      // the caller tests the same conditions before choosing this form
     if(!fused)
     {
         hipError_t e = absmax_typed(w, N, K, K, kPerRow, qmax, sw, iw, aw_opt, nullptr, nullptr, workspace, st);
@@ -1314,10 +1327,13 @@ static hipError_t prepare_weights_typed(const T* w, int64_t N, int64_t K, float 
         gy = static_cast<int>((N + 15) / 16);
         absmax_rowcol_kernel<T, 16, 1><<<dim3(gy), dim3(kBlock), 0, st>>>(w, N, K, K, qmax, sw, iw, aw_opt, partial);
     }
-    colreduce_finalize_kernel<OP_MAX><<<dim3((K + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy, K, qmax, swb, iwb, nullptr);
+    if(conv_C > 0)      // partial[gy][9][C] read as gy*9 rows of C columns: maxima per input channel
+        colreduce_finalize_kernel<OP_MAX><<<dim3((conv_C + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy * 9, conv_C, qmax, swb, iwb, nullptr);
+    else
+        colreduce_finalize_kernel<OP_MAX><<<dim3((K + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy, K, qmax, swb, iwb, nullptr);
     PatchShape ps = patch_shape<T>(N, K, false);          // 8-row patches
     quantize_patch_kernel<T, kNearest, false, 8, true><<<dim3(static_cast<unsigned>(ps.gx * ps.gy)), dim3(kBlock), 0, st>>>(
-        w, N, K, K, static_cast<int>(qmax), kPerRow, 0, 0, iw, wq, wqbT, ps.gx, ps.lpr_log2, iwb);
+        w, N, K, K, static_cast<int>(qmax), kPerRow, 0, 0, iw, wq, wqbT, ps.gx, ps.lpr_log2, iwb, static_cast<int>(conv_C));
     return hipGetLastError();
 }
 
@@ -1447,6 +1463,35 @@ hipError_t launch_conv3x3_wflip(const void* w, int elem_bytes, int64_t N, int64_
             static_cast<const uint16_t*>(w), N, C, static_cast<uint16_t*>(wflip));
     return hipGetLastError();
 }
+
+hipError_t launch_conv3x3_prepare_weights(const void* w, int wdt, int64_t N, int64_t C, float qmax, float* sw, float* iw,
+                                          float* swb, float* iwb, int8_t* wq, int8_t* wflip, void* workspace,
+                                          hipStream_t st)
+{
+    const int64_t K = 9 * C;
+    const int64_t e2 = wdt == kF32 ? 8 : 16;
+    float*        partial = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes);
+    const bool    fused = aligned16(w) && K % e2 == 0 && N % 16 == 0 && N <= 16 * kColParts && C <= (1 << 20)
+                       && aligned16(wq) && aligned16(wflip) && aligned16(partial);
+    if(fused)
+    {
+        if(wdt == kF32)
+            return prepare_weights_typed(static_cast<const float*>(w), N, K, qmax, sw, iw, nullptr, wq, swb, iwb, wflip, workspace, st, C);
+        return prepare_weights_typed(static_cast<const __half*>(w), N, K, qmax, sw, iw, nullptr, wq, swb, iwb, wflip, workspace, st, C);
+    }
+    // large weights: the separate passes; the per-c codes go through the workspace (behind the absmax scratch)
+    int8_t*    wqb = static_cast<int8_t*>(workspace) + absmax_workspace_bytes(N, K, kPerCol);
+    hipError_t e   = launch_absmax_scale(w, wdt, N, K, K, kPerRow, qmax, sw, iw, nullptr, nullptr, nullptr, workspace, st);
+    if(e != hipSuccess) return e;
+    e = launch_quantize_int8(w, wdt, N, K, K, static_cast<int>(qmax), kPerRow, kNearest, 0, 0, iw, wq, nullptr, st);
+    if(e != hipSuccess) return e;
+    e = launch_absmax_scale(w, wdt, 9 * N, C, C, kPerCol, qmax, swb, iwb, nullptr, nullptr, nullptr, workspace, st);
+    if(e != hipSuccess) return e;
+    e = launch_quantize_int8(w, wdt, 9 * N, C, C, static_cast<int>(qmax), kPerCol, kNearest, 0, 0, iwb, wqb, nullptr, st);
+    if(e != hipSuccess) return e;
+    return launch_conv3x3_wflip(wqb, 1, N, C, wflip, st);
+}
+
 
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream)

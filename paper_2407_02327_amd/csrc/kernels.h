@@ -42,6 +42,9 @@ hipError_t launch_dequantize(const void* a, int adt, int64_t rows, int64_t cols,
 hipError_t launch_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, float qmax, float* sw, float* iw,
                                   float* aw_opt, int8_t* wq, float* swb, float* iwb, int8_t* wqbT, void* workspace,
                                   hipStream_t stream);
+hipError_t launch_conv3x3_prepare_weights(const void* w, int wdt, int64_t N, int64_t C, float qmax, float* sw, float* iw,
+                                          float* swb, float* iwb, int8_t* wq, int8_t* wflip, void* workspace,
+                                          hipStream_t stream);
 hipError_t launch_conv3x3_wflip(const void* w, int elem_bytes, int64_t N, int64_t C, void* wflip, hipStream_t stream);
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream);

@@ -219,7 +219,7 @@ class QConv3x3:
         qd, f32 = _TORCH_OF_TAG[tag], torch.float32
         self.xq = e(M, C, dt=qd)
         self.xqTp = e(K, M, dt=qd) if tag == Q.INT8 else None        # transposed patch matrix (weight gradient)
-        self.wq, self.wqb, self.wflip = e(N, K, dt=qd), e(N, K, dt=qd), e(C, 9 * N, dt=qd)
+        self.wq, self.wflip = e(N, K, dt=qd), e(C, 9 * N, dt=qd)
         self.dyq, self.dyqT = e(M, N, dt=qd), e(N, M, dt=qd)
         self.sx, self.ix, self.ax = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
         nsw, nswb = (N, C) if w_gran == Q.PER_ROW else (1, 1)
@@ -235,7 +235,7 @@ class QConv3x3:
             self.acc, self.acc_dx, self.acc_dw = e(M, N, dt=i32), e(M, C, dt=i32), e(N, K, dt=i32)
         self.ws_absmax = _ws(max(Q.qsync_absmax_workspace_bytes(M, C, Q.PER_TENSOR),
                                  Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR)), device)
-        self.ws_absmax_w = _ws(max(Q.qsync_absmax_workspace_bytes(9 * N, C, Q.PER_COL),
+        self.ws_absmax_w = _ws(max(Q.qsync_conv3x3_prepare_weights_workspace_bytes(N, C),
                                    Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), device)
         self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K), device)
 
@@ -253,17 +253,16 @@ class QConv3x3:
             Q.qsync_quantize(w, N, K, K, self.tag, 0, 0, 0, 0, 0, None, self.wq, None, stream)
             Q.qsync_conv3x3_wflip(self.wq, N, C, self.wflip, stream)
             return
-        Q.qsync_absmax_scale(w, N, K, K, self.w_gran, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax_w, stream)
-        Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, self.w_gran, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
         if self.w_gran == Q.PER_TENSOR:
-            self.swb, src = self.sw, self.wq
-        else:
-            # the output channel is the data gradient's contraction axis: second set of codes with one scale per
-            # input channel c, i.e. per column of the weights viewed as [9*N, C]
-            Q.qsync_absmax_scale(w, 9 * N, C, C, Q.PER_COL, self.bits, self.swb, self.iwb, None, None, self.ws_absmax_w, stream)
-            Q.qsync_quantize(w, 9 * N, C, C, Q.INT8, self.bits, Q.PER_COL, Q.ROUND_NEAREST, 0, 0, self.iwb, self.wqb, None, stream)
-            src = self.wqb
-        Q.qsync_conv3x3_wflip(src, N, C, self.wflip, stream)
+            Q.qsync_absmax_scale(w, N, K, K, Q.PER_TENSOR, self.bits, self.sw, self.iw, self.aw, None, self.ws_absmax_w, stream)
+            Q.qsync_quantize(w, N, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.iw, self.wq, None, stream)
+            self.swb = self.sw
+            Q.qsync_conv3x3_wflip(self.wq, N, C, self.wflip, stream)
+            return
+        # the output channel is the data gradient's contraction axis: second set of codes with one scale per
+        # input channel c (per column of the weights viewed as [9*N, C]), mirrored and channel-exchanged
+        Q.qsync_conv3x3_prepare_weights(w, N, C, self.bits, self.sw, self.iw, self.wq, self.swb, self.iwb, self.wflip,
+                                        self.ws_absmax_w, stream)
 
     def conv_fwd(self, stream=None) -> None:
         Q.qsync_conv3x3_fwd(self.tag, self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.wq, self.sw,

@@ -157,6 +157,28 @@ def test_prepare_weights_validation():
     assert f(*a) == qsync.OK
 
 
+def test_conv_prepare_weights_validation():
+    f = lib.qsync_conv3x3_prepare_weights
+    ok = [A, qsync.F32, 8, 16, 8, A, A, A, A, A, A, A, 1 << 24, None]
+    assert f(*ok) in (qsync.OK, qsync.ERR_HIP)
+    for i in (0, 5, 6, 7, 8, 9, 10):
+        a = list(ok); a[i] = None
+        assert f(*a) == qsync.ERR_NULL
+    a = list(ok); a[1] = qsync.I32
+    assert f(*a) == qsync.ERR_BAD_ENUM
+    a = list(ok); a[3] = -2
+    assert f(*a) == qsync.ERR_BAD_SHAPE
+    a = list(ok); a[4] = 1
+    assert f(*a) == qsync.ERR_UNSUPPORTED
+    a = list(ok); a[12] = 8
+    assert f(*a) == qsync.ERR_WORKSPACE
+    a = list(ok); a[11] = U
+    assert f(*a) == qsync.ERR_ALIGN
+    a = list(ok); a[2] = 0
+    assert f(*a) == qsync.OK
+    assert lib.qsync_conv3x3_prepare_weights_workspace_bytes(64, 64) >= 9 * 64 * 64
+
+
 def test_probe_validation():
     f = lib.qsync_probe_mfma
     assert f(8, 0, 10, None, None, None) == qsync.ERR_NULL

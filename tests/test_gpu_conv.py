@@ -81,6 +81,32 @@ def test_weight_flip_bit_exact():
         assert_bits_equal(host(outh), np.ascontiguousarray(wh[:, ::-1, ::-1, :].transpose(3, 1, 2, 0)).reshape(c, 9 * n), "flipped halves")
 
 
+@pytest.mark.parametrize("dt", [np.float32, np.float16])
+def test_conv_prepare_weights_equals_the_separate_calls(dt):
+    rng = np.random.default_rng(66)
+    for (n, c) in [(64, 64), (8, 16), (24, 48), (136, 32), (256, 128), (5, 3), (48, 80), (32, 16)]:   # N % 16 != 0: separate passes
+        say("conv weights", dt.__name__, n, c)
+        w = (rng.standard_normal((n, 9 * c)) * 0.05).astype(dt)
+        w[:, c - 1::c] = 0                              # an all-zero input channel: scale 1
+        e = lambda *s_, t=torch.float32: empty(tuple(s_), t)
+        sw, iw, swb, iwb = e(n), e(n), e(c), e(c)
+        wq, wflip = e(n, 9 * c, t=torch.int8), e(c, 9 * n, t=torch.int8)
+        from tests.gpu_util import ws
+        Q.qsync_conv3x3_prepare_weights(dev(w), n, c, 8, sw, iw, wq, swb, iwb, wflip,
+                                        ws(Q.qsync_conv3x3_prepare_weights_workspace_bytes(n, c)))
+        sr, ir = orc.scales_from_amax(orc.absmax(w, "row"))
+        w9 = w.reshape(9 * n, c)
+        sc, ic = orc.scales_from_amax(orc.absmax(w9, "col"))
+        assert_bits_equal(host(sw), sr, "per-n scales")
+        assert_bits_equal(host(iw), ir, "per-n inverse scales")
+        assert_bits_equal(host(swb), sc, "per-c scales")
+        assert_bits_equal(host(iwb), ic, "per-c inverse scales")
+        assert_bits_equal(host(wq), orc.quantize_int(w, ir, "row", "nearest"), "forward codes")
+        wqb = orc.quantize_int(w9, ic, "col", "nearest").reshape(n, 3, 3, c)
+        assert_bits_equal(host(wflip), np.ascontiguousarray(wqb[:, ::-1, ::-1, :].transpose(3, 1, 2, 0)).reshape(c, 9 * n),
+                          "mirrored backward codes")
+
+
 def conv_case(batch, hh, ww, c, n, seed):
     rng = np.random.default_rng(seed)
     act = np.abs(rng.standard_normal((batch, hh, ww, c))).astype(np.float16)
@@ -109,8 +135,8 @@ def run_conv_operator(act, w, bias, dy, w_gran, dy_round="stochastic", seed=5):
     assert_bits_equal(host(op.sdy), ref["sdy"], "sdy")
     assert_bits_equal(host(op.dyq), ref["dyq"], "dyq")
     assert_bits_equal(host(op.swb), ref["swb"], "swb")
-    if w_gran == "row":
-        assert_bits_equal(host(op.wqb), ref["wqb"], "wqb")
+    flipped = np.ascontiguousarray(ref["wqb"].reshape(n, 3, 3, c)[:, ::-1, ::-1, :].transpose(3, 1, 2, 0)).reshape(c, 9 * n)
+    assert_bits_equal(host(op.wflip), flipped, "mirrored backward codes")
     assert_bits_equal(host(op.acc_dx), ref["acc_dx"], "dgrad accumulators")
     assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "wgrad accumulators")
     assert_close(host(op.dx), ref["dx"], "dX", rtol=2e-3)
