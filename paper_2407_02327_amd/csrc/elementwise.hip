@@ -448,11 +448,14 @@ __global__ __launch_bounds__(kBlock) void colreduce_finalize_kernel(const float*
     const int64_t c  = static_cast<int64_t>(blockIdx.x) * 16 + tc;
     float         acc = 0.0f;
     if(c < cols)
+    {
+#pragma unroll 8                              // independent loads in flight; the fold keeps its order
         for(int s = q; s < S; s += 16)
         {
             const float o = partial[static_cast<int64_t>(s) * cols + c];
             acc = OP == OP_MAX ? fmaxf(acc, o) : acc + o;
         }
+    }
     lds[threadIdx.x] = acc;
     __syncthreads();
     if(q == 0 && c < cols)
@@ -710,8 +713,10 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
             int8_t* dst = qT + trow * rows + r0;
             if constexpr(PR == 16)
                 *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
-            else
+            else if constexpr(PR == 8)
                 *reinterpret_cast<uint2*>(dst) = make_uint2(t[0], t[1]);
+            else
+                *reinterpret_cast<uint32_t*>(dst) = t[0];
         }
     }
 }
@@ -1312,7 +1317,12 @@ static hipError_t prepare_weights_typed(const T* w, int64_t N, int64_t K, float 
         return quantize_typed(w, N, K, K, static_cast<int>(qmax), kPerCol, kNearest, 0, 0, iwb, nullptr, wqbT, st);
     }
     int gy;          // row groups = partial rows per column (at most kColParts); 16 loads in flight per thread
-    if(N <= 4 * kColParts)
+    if(N <= 2 * kColParts)
+    {
+        gy = static_cast<int>((N + 1) / 2);
+        absmax_rowcol_kernel<T, 2, 8><<<dim3(gy), dim3(kBlock), 0, st>>>(w, N, K, K, qmax, sw, iw, aw_opt, partial);
+    }
+    else if(N <= 4 * kColParts)
     {
         gy = static_cast<int>((N + 3) / 4);
         absmax_rowcol_kernel<T, 4, 4><<<dim3(gy), dim3(kBlock), 0, st>>>(w, N, K, K, qmax, sw, iw, aw_opt, partial);
@@ -1331,8 +1341,10 @@ static hipError_t prepare_weights_typed(const T* w, int64_t N, int64_t K, float 
         colreduce_finalize_kernel<OP_MAX><<<dim3((conv_C + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy * 9, conv_C, qmax, swb, iwb, nullptr);
     else
         colreduce_finalize_kernel<OP_MAX><<<dim3((K + 15) / 16), dim3(kBlock), 0, st>>>(partial, gy, K, qmax, swb, iwb, nullptr);
-    PatchShape ps = patch_shape<T>(N, K, false);          // 8-row patches
-    quantize_patch_kernel<T, kNearest, false, 8, true><<<dim3(static_cast<unsigned>(ps.gx * ps.gy)), dim3(kBlock), 0, st>>>(
+    // 4-row patches: weights are small, more wavefronts in flight matter more than wide transposed stores
+    PatchShape ps = patch_shape<T>(N, K, false);
+    ps.gy = (N + 4 * (kWaveSize >> ps.lpr_log2) * 4 - 1) / (4 * (kWaveSize >> ps.lpr_log2) * 4);
+    quantize_patch_kernel<T, kNearest, false, 4, true><<<dim3(static_cast<unsigned>(ps.gx * ps.gy)), dim3(kBlock), 0, st>>>(
         w, N, K, K, static_cast<int>(qmax), kPerRow, 0, 0, iw, wq, wqbT, ps.gx, ps.lpr_log2, iwb, static_cast<int>(conv_C));
     return hipGetLastError();
 }
