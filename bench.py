@@ -194,6 +194,22 @@ def main():
         for st in op_streams[1:nstreams]:
             main.wait_stream(st)
 
+    def step_model_order():
+        """The operators as consecutive layers of one model: all forwards, then the backwards in reverse order;
+        a layer's weight-gradient GEMM runs on a side stream (default priority) beside the next layer's gradient
+        conversion and data-gradient GEMM on the main stream."""
+        side = side_streams[0]
+        for op, (x, w, dy) in zip(ops_objs, dev_in):
+            op.convert_w(w, main)
+            op.convert_act(x, main)
+            op.gemm_fwd(main)
+        for op, (x, w, dy) in reversed(list(zip(ops_objs, dev_in))):
+            op.convert_dy(dy, main)
+            side.wait_stream(main)
+            op.gemm_bwd_part("dw", dy, side)
+            op.gemm_bwd_part("dx", dy, main)
+        main.wait_stream(side)
+
     if args.pmc_calibration:
         src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -231,6 +247,19 @@ def main():
         ms2 = (time.perf_counter() - t1) * 1e3 / args.steps
         overlapped = {"operator_streams": len(ops_objs), "ms_per_step": round(ms2, 4),
                       "value": round(gemm_ops / (ms2 * 1e-3) / 1e12, 3), "unit": "TOPS"}
+    model_order = None
+    if len(ops_objs) > 1 and not args.no_extra_passes and all(hasattr(o, "gemm_bwd_part") for o in ops_objs):
+        for _ in range(max(2, args.warmup)):
+            step_model_order()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step_model_order()
+        torch.cuda.synchronize()
+        ms3 = (time.perf_counter() - t1) * 1e3 / args.steps
+        model_order = {"schedule": "forward of every operator, then backward in reverse order; each weight-gradient GEMM on "
+                                   "a side stream beside the next operator's gradient conversion", "ms_per_step": round(ms3, 4),
+                       "value": round(gemm_ops / (ms3 * 1e-3) / 1e12, 3), "unit": "TOPS"}
     # Extra (outside the timed region): the matrix-instruction rate the GPU sustains with no memory traffic
     # (register operands), with constant and with pseudo-random operand values: context for roofline.frac.
     mfma_probe = None
@@ -370,6 +399,7 @@ def main():
         "dequantize_alone": dequant_iso,
         "mfma_probe": mfma_probe,
         "operators_on_separate_streams": overlapped,
+        "model_order_dw_on_side_stream": model_order,
     }
     if "gemm_bwd" in per_step:
         out["gemm_only_TOPS"] = round(gemm_ops / ((per_step["gemm_fwd"] + per_step["gemm_bwd"]) * 1e-3) / 1e12, 2)

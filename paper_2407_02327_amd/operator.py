@@ -174,6 +174,23 @@ class QLinear:
                             self.dx, self.dw, self.db if want_db else None, dy if want_db else None, self.acc_dx,
                             self.acc_dw, self.ws_bwd, stream)
 
+    def gemm_bwd_part(self, which: str, dy: Optional[torch.Tensor], stream=None) -> None:
+        """One of the two independent backward GEMMs ("dx" or "dw", the latter with the bias gradient when the tag
+        needs it from here), so that a caller can run them on different streams."""
+        dx = self.dx if which == "dx" else None
+        dw = self.dw if which == "dw" else None
+        if self.bwd_tag != self.tag:
+            Q.qsync_qlinear_bwd(Q.FP16, self.M, self.N, self.K, self.dyh, self.dyhT, None, self.xhT, None, self.whT, None,
+                                Q.PER_TENSOR, dx, dw, self.db if (dy is not None and dw is not None) else None,
+                                dy if dw is not None else None, None, None, self.ws_bwd, stream)
+            return
+        want_db = dy is not None and self.tag != Q.INT8 and dw is not None
+        Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
+                            self.wqbT, self.swb, self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW,
+                            dx, dw, self.db if want_db else None, dy if want_db else None,
+                            self.acc_dx if dx is not None else None, self.acc_dw if dw is not None else None,
+                            self.ws_bwd, stream)
+
     # ---- whole passes ----------------------------------------------------------------------
     def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None, side_stream=None) -> torch.Tensor:
         """With `side_stream` (a torch stream of default priority) the small, latency-bound weight
