@@ -74,6 +74,20 @@ def test_ragged_shapes_span_tiles_and_tails(tag, shape):
     run_case(case, tag, y_dtype=np.float16 if tag == Q.FP16 else np.float32)
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tag", [Q.INT8, Q.FP16])
+def test_every_gemm_tile_shape_on_ragged_operators(tile, tag):
+    """The planner picks small tiles for small outputs; pin each tile shape in turn (with the K splits the planner
+    then chooses for it) so that the 256x256 and 128x128 kernels also see ragged M, N and K tails."""
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        for (m, n, k) in [(208, 144, 272), (528, 272, 400), (16, 16, 2064), (1040, 784, 528), (48, 2064, 64)]:
+            case = wl.ragged_case(m, n, k, seed=m + n + k + tile, dtype=np.float16)
+            run_case(case, tag, y_dtype=np.float16 if tag == Q.FP16 else np.float32)
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
+
+
 def test_per_tensor_weights_share_codes_between_forward_and_backward():
     case = wl.ragged_case(144, 96, 160, seed=21)
     case.w_gran = "tensor"
