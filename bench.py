@@ -279,6 +279,29 @@ def main():
             torch.cuda.synchronize()
             mfma_probe[key] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
         del scratch
+        # the workload's forward GEMMs alone, back to back, on the codes of the last step and on constant
+        # operands (every code / half = 1): the same instruction stream at the same addresses, only the
+        # operand values differ
+        lin_ops = [o for o in ops_objs if hasattr(o, "gemm_bwd_part")]
+        if lin_ops:
+            def gemm_rate():
+                for o in lin_ops:
+                    o.gemm_fwd(main)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(main)
+                for _ in range(10):
+                    for o in lin_ops:
+                        o.gemm_fwd(main)
+                e1.record(main)
+                torch.cuda.synchronize()
+                return sum(2 * o.M * o.N * o.K for o in lin_ops) * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            mfma_probe["forward_gemms_back_to_back"] = round(gemm_rate(), 1)
+            saved = [(o.xq, o.wq) for o in lin_ops]
+            for o in lin_ops:        # xq may alias the caller's input (binary16 tag): swap in fresh buffers
+                o.xq, o.wq = torch.ones_like(o.xq), torch.ones_like(o.wq)
+            mfma_probe["forward_gemms_back_to_back_constant_operands"] = round(gemm_rate(), 1)
+            for o, (xq_, wq_) in zip(lin_ops, saved):
+                o.xq, o.wq = xq_, wq_
     # Extra (outside the timed region): the quantize kernel alone on the largest gradient tensor of the
     # workload, 20 back-to-back launches each; "cold" rotates through enough input/output sets to exceed
     # 512 MB (nothing is left in the memory-side cache), "warm" reuses one set.
