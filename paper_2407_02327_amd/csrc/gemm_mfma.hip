@@ -127,7 +127,11 @@ template <> __device__ __forceinline__ __half from_f32_out<__half>(float v) { re
 // operand panel's address at this K tile minus kDmaBias, and `voff` already contains
 // + kDmaBias - IMM.
 constexpr int kDmaBias = 4096;
-template <int D, int DPW> constexpr int dma_imm() { return (D - DPW / 2) * 1024; }   // -4096 .. 3072
+// A wavefront's DPW loads are issued in groups of at most 8 that share one LDS base (the immediate reaches
+// +-4 KB); a wavefront with 16 loads per K tile changes the base once in between.
+template <int DPW> constexpr int dma_group() { return DPW > 8 ? 8 : DPW; }
+template <int D, int DPW> constexpr int dma_imm() { return (D % dma_group<DPW>() - dma_group<DPW>() / 2) * 1024; }   // -4096 .. 3072
+template <int D, int DPW> constexpr int dma_lds_shift() { return (D / dma_group<DPW>()) * dma_group<DPW>() * 1024; }
 template <int D, int DPW>
 __device__ __forceinline__ void dma_issue(const uint8_t* sbase, uint32_t voff, uint8_t* lds_mid)
 {
@@ -135,7 +139,7 @@ __device__ __forceinline__ void dma_issue(const uint8_t* sbase, uint32_t voff, u
     static_assert(IMM >= -4096 && IMM <= 4095, "immediate offset out of range");
     asm volatile("" : "+v"(voff));      // keep the widening of the lane offset next to the load (scalar-base form)
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(sbase + voff),
-                                     (__attribute__((address_space(3))) void*)(lds_mid), 16, IMM, 0);
+                                     (__attribute__((address_space(3))) void*)(lds_mid + dma_lds_shift<D, DPW>()), 16, IMM, 0);
 }
 
 template <int DPW, int... Ds>
@@ -175,7 +179,7 @@ __device__ __forceinline__ void conv_issue(const uint8_t* a, const uint8_t* zero
                      && static_cast<unsigned>(ww) < static_cast<unsigned>(W);
     const uint8_t* src = inb ? a + static_cast<int64_t>(static_cast<int32_t>(pix_off) + t.delta[par]) : zero;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src - IMM),
-                                     (__attribute__((address_space(3))) void*)(lds_mid), 16, IMM, 0);
+                                     (__attribute__((address_space(3))) void*)(lds_mid + dma_lds_shift<D, DPW>()), 16, IMM, 0);
 }
 
 template <int DPW, int... Ds>
@@ -278,7 +282,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // (measured: +20 % GEMM throughput without it).
     auto dma = [&](int stage, int kt) {
         const int64_t  kb    = static_cast<int64_t>(kt) * kRowBytes;
-        uint8_t*       lbase = lds + stage * STAGE_BYTES + wave * (DPW * 1024) + (DPW / 2) * 1024;
+        uint8_t*       lbase = lds + stage * STAGE_BYTES + wave * (DPW * 1024) + (dma_group<DPW>() / 2) * 1024;
         if constexpr(CONV)
             if(is_a)
             {
@@ -433,22 +437,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         static_assert(32 * PITCH <= STG_BYTES && FM % FPP == 0, "staging slice too small");
         constexpr int LPR   = WTN * OS / 16;                     // lanes per output row in the store phase
         constexpr int RPI   = 64 / LPR;                          // rows per store instruction
-        float f[RAW ? 1 : FN][16], b[RAW ? 1 : FN][16];
         __syncthreads();                                  // all wavefronts are done reading the stages
-        if constexpr(!RAW)
-        {
-#pragma unroll
-            for(int j = 0; j < FN; ++j)
-#pragma unroll
-                for(int vq = 0; vq < 4; ++vq)
-                {
-                    const int     c  = wn * WTN + j * 32 + 8 * vq + 4 * khalf;          // column inside the tile
-                    const float4  fs = *reinterpret_cast<const float4*>(colp + c);
-                    const float4  bs = *reinterpret_cast<const float4*>(colp + BN + c);
-                    f[j][vq * 4 + 0] = fs.x; f[j][vq * 4 + 1] = fs.y; f[j][vq * 4 + 2] = fs.z; f[j][vq * 4 + 3] = fs.w;
-                    b[j][vq * 4 + 0] = bs.x; b[j][vq * 4 + 1] = bs.y; b[j][vq * 4 + 2] = bs.z; b[j][vq * 4 + 3] = bs.w;
-                }
-        }
 #pragma unroll
         for(int pass = 0; pass < FM / FPP; ++pass)
         {
@@ -462,6 +451,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                     for(int vq = 0; vq < 4; ++vq)
                     {
                         out_t o[4];
+                        float f4[4] = {1.0f, 1.0f, 1.0f, 1.0f}, b4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if constexpr(!RAW)
+                        {   // column scale and bias of these four columns, parked in LDS by the prologue
+                            const int    c  = wn * WTN + j * 32 + 8 * vq + 4 * khalf;          // column inside the tile
+                            const float4 fs = *reinterpret_cast<const float4*>(colp + c);
+                            const float4 bs = *reinterpret_cast<const float4*>(colp + BN + c);
+                            f4[0] = fs.x; f4[1] = fs.y; f4[2] = fs.z; f4[3] = fs.w;
+                            b4[0] = bs.x; b4[1] = bs.y; b4[2] = bs.z; b4[3] = bs.w;
+                        }
 #pragma unroll
                         for(int e = 0; e < 4; ++e)
                         {
@@ -469,7 +467,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                                 o[e] = acc[i][j][vq * 4 + e];
                             else
                             {
-                                const float y = fmaf(static_cast<float>(acc[i][j][vq * 4 + e]), f[j][vq * 4 + e], b[j][vq * 4 + e]);
+                                const float y = fmaf(static_cast<float>(acc[i][j][vq * 4 + e]), f4[e], b4[e]);
                                 o[e] = from_f32_out<out_t>(y);
                             }
                         }
@@ -630,6 +628,8 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
 struct TileShape { int bm, bn; };
 // 0: 256x256, 8 wavefronts (2x4, 128x64 each)   1: 128x128, 4 wavefronts (2x2, 64x64 each)
 // 2: 64x64, 4 wavefronts (2x2, 32x32 each)
+// (256x256 with 4 wavefronts of 128x128 -- a third fewer LDS fragment reads per matrix instruction -- was
+//  measured 8-40 % slower: one wavefront per SIMD exposes barrier and LDS latency.)
 constexpr TileShape kTiles[] = {{256, 256}, {128, 128}, {64, 64}};
 constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
