@@ -28,6 +28,18 @@ def test_philox_matches_bigint_rederivation():
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not found")
+def test_philox_published_known_answers():
+    """The generator's standard check vectors (tests/golden/philox4x32_10_known_answers.txt)."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_known_answers.txt")
+    rows = [ln for ln in open(path).read().splitlines() if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 3
+    for ln in rows:
+        ctr, key, want = [[int(w, 16) for w in part.split()] for part in ln.split("|")]
+        got = orc.philox4x32_10(np.array([ctr], dtype=np.uint32), (key[0], key[1]))
+        assert [int(v) for v in got.reshape(-1)] == want, ln
+
+
 def test_philox_matches_rocrand_host_engine(tmp_path):
     """Library pin: rocRAND's host-callable Philox4x32-10 engine produces the same blocks."""
     exe = tmp_path / "rocrand_philox_host"
