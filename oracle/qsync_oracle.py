@@ -14,7 +14,7 @@ Pins (see tests/test_oracle_*.py): brute-force big-integer re-derivation on tiny
 inputs, the <= scale/2 error bound of nearest rounding, unbiasedness and the
 D/6 variance law of stochastic rounding (Prop. 2), code range, the forward
 identity of the Prop. 2 proof (integer GEMM times scales == GEMM of dequantized
-tensors), rocRAND's host Philox4x32-10 engine for the generator, and math.fsum
+tensors), the published Philox4x32-10 known answers and rocRAND's host engine for the generator, and math.fsum
 triple loops for the floating-point contractions; for the 3x3 convolution scipy's
 2-D correlation, six-deep loops, single-tap shifts, a hand-worked example and the
 adjoint identities.
