@@ -811,6 +811,71 @@ __global__ __launch_bounds__(kBlock) void im2col3x3_i8_kernel(const int8_t* __re
     }
 }
 
+// ------------------------------------------------------------------ padded, transposed pixel layout
+// Operands of the convolution's weight gradient, which contracts over the pixels.  The codes [M, Ch] of an
+// NHWC tensor are transposed to [Ch, Mp] over a padded pixel axis: every image is preceded by a zero row,
+// rows are Wp >= W + 1 pixels long (a multiple of 16, the excess zero), one more zero row closes the axis:
+//   p = (img * (H + 1) + 1 + h) * Wp + w.
+// On this axis a window offset (dh, dw) is the plain displacement dh * Wp + dw and every out-of-image
+// neighbour is a stored zero.  NS = 3 writes the three copies displaced by dw = -1, 0, +1
+// (out[s][ch][q] = padded[ch][q + s - 1]), so that the GEMM reads 16-byte aligned rows for every tap;
+// NS = 1 writes the undisplaced copy (the gradient operand).  A lane gathers 18 (16) pixels x 16 channels
+// and leaves with one 16-byte store per channel and copy; pads are written, nothing is assumed zero.
+template <int NS>
+__global__ __launch_bounds__(kBlock) void conv_padded_transpose_kernel(const int8_t* __restrict__ in, int64_t nimg, int H,
+                                                                       int W, int Ch, int Wp, int64_t Mp,
+                                                                       int8_t* __restrict__ out, int cw_log2)
+{
+    constexpr int NP = NS == 3 ? 18 : 16;
+    const int64_t lin  = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const int     ncc  = Ch / 16, cw = 1 << cw_log2;
+    const int64_t nq   = Mp / 16, rest = lin >> cw_log2;
+    const int64_t qb   = rest % nq, ccg = rest / nq;
+    const int     cc   = static_cast<int>(ccg) * cw + static_cast<int>(lin & (cw - 1));
+    if(cc >= ncc) return;
+    const int64_t q0 = qb * 16;
+    const int     c0 = cc * 16;
+    // first gathered pixel: q0 - 1 (NS = 3) or q0; position -1 is written as the last column of a row "-1"
+    int64_t p0 = q0 - (NS == 3 ? 1 : 0);
+    int     col, hrow;
+    int64_t img;
+    if(p0 < 0) { col = Wp - 1; hrow = H; img = -1; }
+    else
+    {
+        const int64_t r = p0 / Wp;
+        col  = static_cast<int>(p0 - r * Wp);
+        img  = r / (H + 1);
+        hrow = static_cast<int>(r - img * (H + 1));
+    }
+    uint32_t code[NP][4];
+#pragma unroll
+    for(int i = 0; i < NP; ++i)
+    {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if(col < W && hrow >= 1 && img >= 0 && img < nimg)
+            v = *reinterpret_cast<const uint4*>(in + ((img * H + (hrow - 1)) * W + col) * Ch + c0);
+        code[i][0] = v.x; code[i][1] = v.y; code[i][2] = v.z; code[i][3] = v.w;
+        if(++col == Wp)
+        {
+            col = 0;
+            if(++hrow == H + 1) { hrow = 0; ++img; }
+        }
+    }
+#pragma unroll
+    for(int s = 0; s < NS; ++s)
+#pragma unroll
+        for(int ch = 0; ch < 16; ++ch)
+        {
+            uint32_t t[4];
+#pragma unroll
+            for(int g = 0; g < 4; ++g)
+                t[g] = byte_of(code[4 * g + 0 + s][ch / 4], ch % 4) | (byte_of(code[4 * g + 1 + s][ch / 4], ch % 4) << 8)
+                     | (byte_of(code[4 * g + 2 + s][ch / 4], ch % 4) << 16)
+                     | (byte_of(code[4 * g + 3 + s][ch / 4], ch % 4) << 24);
+            *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(s) * Ch + c0 + ch) * Mp + q0) = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+}
+
 // ------------------------------------------------------------------ cast / copy (+ transpose)
 template <typename To, typename Ti> __device__ __forceinline__ To convert_elem(Ti v);
 template <> __device__ __forceinline__ float  convert_elem<float, float>(float v) { return v; }
@@ -1511,6 +1576,32 @@ hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int
     const int64_t M  = nimg * H * W;
     const int64_t gx = (9 * C / 16 + 7) / 8, gy = (M + 511) / 512;
     im2col3x3_i8_kernel<<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, stream>>>(xq, nimg, H, W, C, a, aT, gx);
+    return hipGetLastError();
+}
+
+ConvPaddedAxis conv_padded_axis(int64_t nimg, int H, int W)
+{
+    ConvPaddedAxis a;
+    a.Wp = (W + 1 + 15) / 16 * 16;
+    a.Mp = (nimg * (H + 1) + 1) * a.Wp;          // a multiple of 16
+    return a;
+}
+
+hipError_t launch_conv_padded_transpose(const int8_t* in, int64_t nimg, int H, int W, int Ch, int copies, int8_t* out,
+                                        hipStream_t stream)
+{
+    const ConvPaddedAxis ax = conv_padded_axis(nimg, H, W);
+    const int     ncc = Ch / 16;
+    int           cw_log2 = 2;                                   // four channel chunks side by side when there are that many
+    while(cw_log2 > 0 && (1 << (cw_log2 - 1)) >= ncc) --cw_log2;
+    const int64_t groups = (ncc + (1 << cw_log2) - 1) >> cw_log2;
+    const int64_t lanes  = (ax.Mp / 16) * groups << cw_log2;
+    const int64_t nb     = (lanes + kBlock - 1) / kBlock;
+    if(nb >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    if(copies == 3)
+        conv_padded_transpose_kernel<3><<<dim3(static_cast<unsigned>(nb)), dim3(kBlock), 0, stream>>>(in, nimg, H, W, Ch, ax.Wp, ax.Mp, out, cw_log2);
+    else
+        conv_padded_transpose_kernel<1><<<dim3(static_cast<unsigned>(nb)), dim3(kBlock), 0, stream>>>(in, nimg, H, W, Ch, ax.Wp, ax.Mp, out, cw_log2);
     return hipGetLastError();
 }
 

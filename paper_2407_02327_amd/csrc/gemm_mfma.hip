@@ -90,6 +90,9 @@ struct GemmKernelArgs
     int            ktiles_per_split;
     int            tiles_m, tiles_n;
     int            conv_H, conv_W, conv_Cb;   // implicit 3x3 patch matrix: image height, width, bytes per pixel
+    // B rows remapped (weight gradient of a 3x3 convolution): logical row (tap, c) = tap*remap_C + c is physical
+    // row (tap%3)*remap_C + c of B, read with its K axis displaced by (tap/3 - 1)*remap_shift bytes
+    int            remap_C, remap_shift;
 };
 
 // Work item (K split, tile) of a workgroup.  Workgroups are dealt round-robin to the eight XCDs
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     constexpr bool kUniformSide = (BM / 8) % DPW == 0;
     static_assert(kUniformSide, "a wavefront must not straddle the A/B boundary of a stage");
     const bool     is_a      = wave * DPW < BM / 8;
-    const uint8_t* gbase     = is_a ? p.A + m0 * p.Kb : p.B + n0 * p.Kb;
+    const uint8_t* gbase     = is_a ? p.A + m0 * p.Kb : ((!CONV && p.remap_C > 0) ? p.B : p.B + n0 * p.Kb);
     const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
     uint32_t       voff[DPW];                                         // lane offset + kDmaBias - immediate
     uint32_t       hw[CONV ? DPW : 1];                                // CONV, A side: (h << 16) | w of the lane's pixels
@@ -260,6 +263,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
             int64_t   lrow  = srow - (is_a ? 0 : BM);
             if(lrow >= rows_left) lrow = rows_left - 1;
             voff[d] = static_cast<uint32_t>(lrow * p.Kb + chunk * 16 + kDmaBias - imm[d]);
+            if(!CONV && p.remap_C > 0 && !is_a)
+            {   // offset from p.B itself (the base below is not advanced to this tile's rows)
+                const int64_t row = n0 + lrow;
+                const int     tap = static_cast<int>(row / p.remap_C), c = static_cast<int>(row - static_cast<int64_t>(tap) * p.remap_C);
+                const int     kh = (tap * 11) >> 5, kw = tap - 3 * kh;          // tap / 3 for tap < 12
+                voff[d] = static_cast<uint32_t>(static_cast<int64_t>(kw * p.remap_C + c) * p.Kb + (kh - 1) * p.remap_shift
+                                                + chunk * 16 + kDmaBias - imm[d]);
+            }
             if constexpr(CONV)
                 if(is_a)
                 {   // A side: voff holds the byte offset of output pixel m in the NHWC tensor instead
@@ -751,6 +762,14 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.acc_dump = p.prec == 8 ? p.acc_dump : nullptr;
     a.partial  = workspace;
     a.conv_H = a.conv_W = a.conv_Cb = 0;
+    a.remap_C = a.remap_shift = 0;
+    if(p.b_remap_C > 0)
+    {   // B is [3*remap_C, K] with a margin of |remap_shift| readable bytes in front of it and behind it
+        if(p.conv_H > 0 || p.prec != 8 || p.N != 9 * p.b_remap_C || p.b_remap_shift % 16 != 0 || p.b_remap_shift < 0
+           || p.b_remap_shift > 1024 || 3 * p.b_remap_C * a.Kb >= (int64_t(1) << 32) - (1 << 20))
+            return hipErrorInvalidValue;
+        a.remap_C = static_cast<int>(p.b_remap_C); a.remap_shift = static_cast<int>(p.b_remap_shift);
+    }
     if(p.conv_H > 0)
     {   // A is the NHWC tensor [M = images*H*W, C]; its 3x3 patch matrix [M, 9*C] is formed by the loads
         if(p.K != 9 * p.conv_C || plan.splits > 1 || p.M * p.conv_C * esz >= (int64_t(1) << 31)

@@ -220,14 +220,18 @@ class QConv3x3:
     matrix, expanded from the int8 codes.  Buffers are allocated once; nothing here computes.
 
     INT8: all three passes.  FP16: forward and data gradient (no binary16 patch expansion is provided).
+    The weight gradient reads both operands transposed over a zero-padded pixel axis (qsync_conv3x3_wgrad);
+    wgrad_via_patches=True materialises the transposed patch matrix instead (qsync_im2col3x3_i8 + the linear
+    operator's dW GEMM).
     """
 
     def __init__(self, tag: int, nimg: int, H: int, W: int, C: int, N: int, x_dtype=torch.float16, w_dtype=torch.float32,
                  dy_dtype=None, y_dtype=torch.float32, dx_dtype=torch.float16, dw_dtype=torch.float32,
                  w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
-                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda"):
+                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda", wgrad_via_patches: bool = False):
         if tag not in (Q.INT8, Q.FP16):
             raise ValueError("QConv3x3: tag INT8 or FP16")
+        self.wgrad_via_patches = wgrad_via_patches
         self.tag, self.nimg, self.H, self.W, self.C, self.N = tag, nimg, H, W, C, N
         M, K = nimg * H * W, 9 * C
         self.M, self.K = M, K
@@ -235,9 +239,10 @@ class QConv3x3:
         e = lambda *s, dt: torch.empty(*s, dtype=dt, device=device)
         qd, f32 = _TORCH_OF_TAG[tag], torch.float32
         self.xq = e(M, C, dt=qd)
-        self.xqTp = e(K, M, dt=qd) if tag == Q.INT8 else None        # transposed patch matrix (weight gradient)
+        self.xqTp = e(K, M, dt=qd) if (tag == Q.INT8 and wgrad_via_patches) else None   # transposed patch matrix
         self.wq, self.wflip = e(N, K, dt=qd), e(C, 9 * N, dt=qd)
-        self.dyq, self.dyqT = e(M, N, dt=qd), e(N, M, dt=qd)
+        self.dyq = e(M, N, dt=qd)
+        self.dyqT = e(N, M, dt=qd) if wgrad_via_patches else None
         self.sx, self.ix, self.ax = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
         nsw, nswb = (N, C) if w_gran == Q.PER_ROW else (1, 1)
         self.sw, self.iw, self.aw = e(nsw, dt=f32), e(nsw, dt=f32), e(nsw, dt=f32)
@@ -254,7 +259,9 @@ class QConv3x3:
                                  Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR)), device)
         self.ws_absmax_w = _ws(max(Q.qsync_conv3x3_prepare_weights_workspace_bytes(N, C),
                                    Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), device)
-        self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K), device)
+        if tag == Q.INT8:
+            self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K) if wgrad_via_patches
+                              else Q.qsync_conv3x3_wgrad_workspace_bytes(nimg, H, W, C, N), device)
 
     def convert_x(self, act: torch.Tensor, stream=None) -> None:
         M, C = self.M, self.C
@@ -303,6 +310,10 @@ class QConv3x3:
     def conv_wgrad(self, stream=None) -> None:
         if self.tag != Q.INT8:
             raise NotImplementedError("weight gradient: INT8 tag only")
+        if not self.wgrad_via_patches:
+            Q.qsync_conv3x3_wgrad(self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.dyq, self.sdy, self.dw,
+                                  self.acc_dw, self.ws_bwd, stream)
+            return
         Q.qsync_im2col3x3_i8(self.xq, self.nimg, self.H, self.W, self.C, None, self.xqTp, stream)
         Q.qsync_qlinear_bwd(Q.INT8, self.M, self.N, self.K, None, self.dyqT, self.sdy, self.xqTp, self.sx, None, None,
                             Q.PER_TENSOR, None, self.dw, None, None, None, self.acc_dw, self.ws_bwd, stream)

@@ -157,6 +157,31 @@ def test_prepare_weights_validation():
     assert f(*a) == qsync.OK
 
 
+def test_conv_wgrad_validation():
+    f = lib.qsync_conv3x3_wgrad
+    B = P(8192)                                              # 256-byte aligned
+    ok = [1, 4, 4, 16, 16, A, A, A, A, A, 0, None, B, 1 << 24, None]
+    assert f(*ok) in (qsync.OK, qsync.ERR_HIP)
+    for i in (5, 6, 7, 8, 9):
+        a = list(ok); a[i] = None
+        assert f(*a) == qsync.ERR_NULL
+    a = list(ok); a[10] = qsync.I8
+    assert f(*a) == qsync.ERR_BAD_ENUM
+    a = list(ok); a[2] = 2000
+    assert f(*a) == qsync.ERR_BAD_SHAPE                      # W beyond the displaced-row limit
+    a = list(ok); a[3] = 24
+    assert f(*a) == qsync.ERR_ALIGN
+    a = list(ok); a[4] = 8
+    assert f(*a) == qsync.ERR_ALIGN
+    a = list(ok); a[13] = 64
+    assert f(*a) == qsync.ERR_WORKSPACE
+    a = list(ok); a[12] = P(4112)                            # 16-byte but not 256-byte aligned
+    assert f(*a) == qsync.ERR_ALIGN
+    a = list(ok); a[0] = 0
+    assert f(*a) == qsync.OK
+    assert lib.qsync_conv3x3_wgrad_workspace_bytes(64, 56, 56, 64, 64) > 3 * 64 * 64 * 57 * 64
+
+
 def test_conv_prepare_weights_validation():
     f = lib.qsync_conv3x3_prepare_weights
     ok = [A, qsync.F32, 8, 16, 8, A, A, A, A, A, A, A, 1 << 24, None]

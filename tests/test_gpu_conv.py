@@ -107,6 +107,29 @@ def test_conv_prepare_weights_equals_the_separate_calls(dt):
                           "mirrored backward codes")
 
 
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2])
+def test_weight_gradient_on_codes_bit_exact(tile):
+    from tests.gpu_util import ws
+    rng = np.random.default_rng(67)
+    Q.qsync_debug_set_gemm_tile(tile)
+    for (b, h, w, c, n) in [(1, 4, 4, 16, 16), (2, 7, 5, 16, 32), (3, 8, 8, 64, 64), (1, 13, 16, 48, 48), (2, 3, 70, 80, 16),
+                            (5, 9, 15, 32, 144), (1, 1, 1, 16, 16), (2, 31, 33, 16, 16)]:
+        say("conv wgrad codes", "tile", tile, b, h, w, c, n)
+        xq = rng.integers(-127, 128, (b, h, w, c)).astype(np.int8)
+        dyq = rng.integers(-127, 128, (b, h, w, n)).astype(np.int8)
+        sx, sdy = np.array([0.02], np.float32), np.array([3e-4], np.float32)
+        want_acc = orc.conv3x3_wgrad_f64(dyq, xq).reshape(n, 9 * c)
+        acc, dw = empty((n, 9 * c), torch.int32), empty((n, 9 * c), torch.float32)
+        wsp = ws(Q.qsync_conv3x3_wgrad_workspace_bytes(b, h, w, c, n))
+        wsp.fill_(0x5A)                                           # nothing in the workspace needs initialising
+        Q.qsync_conv3x3_wgrad(b, h, w, c, n, dev(xq), dev(sx), dev(dyq.reshape(-1, n)), dev(sdy), dw, acc, wsp)
+        assert_bits_equal(host(acc), want_acc.astype(np.int32), "weight-gradient accumulators")
+        assert_close(host(dw), want_acc * float(sx[0]) * float(sdy[0]), "dW with accumulator dump")
+        dwh = empty((n, 9 * c), torch.float16)
+        Q.qsync_conv3x3_wgrad(b, h, w, c, n, dev(xq), dev(sx), dev(dyq.reshape(-1, n)), dev(sdy), dwh, None, wsp)
+        assert_close(host(dwh), want_acc * float(sx[0]) * float(sdy[0]), "dW fp16")
+
+
 def conv_case(batch, hh, ww, c, n, seed):
     rng = np.random.default_rng(seed)
     act = np.abs(rng.standard_normal((batch, hh, ww, c))).astype(np.float16)
@@ -116,11 +139,12 @@ def conv_case(batch, hh, ww, c, n, seed):
     return act, w, bias, dy
 
 
-def run_conv_operator(act, w, bias, dy, w_gran, dy_round="stochastic", seed=5):
+def run_conv_operator(act, w, bias, dy, w_gran, dy_round="stochastic", seed=5, via_patches=False):
     b, h, wd, c = act.shape
     n = w.shape[0]
     op = QConv3x3(Q.INT8, b, h, wd, c, n, x_dtype=torch.float16, y_dtype=torch.float32, dx_dtype=torch.float16,
-                  w_gran=GRAN[w_gran], dy_round=RND[dy_round], philox_seed=seed, dump_acc=True)
+                  w_gran=GRAN[w_gran], dy_round=RND[dy_round], philox_seed=seed, dump_acc=True,
+                  wgrad_via_patches=via_patches)
     op.bias.copy_(dev(bias))
     op.forward(dev(act), dev(w))
     op.backward(dev(dy))
@@ -150,6 +174,7 @@ def run_conv_operator(act, w, bias, dy, w_gran, dy_round="stochastic", seed=5):
 def test_conv_operator_small(w_gran):
     run_conv_operator(*conv_case(2, 12, 8, 16, 32, 63), w_gran)
     run_conv_operator(*conv_case(1, 16, 16, 64, 32, 64), w_gran, dy_round="nearest")
+    run_conv_operator(*conv_case(2, 12, 8, 16, 32, 68), w_gran, via_patches=True)
 
 
 def test_conv_operator_fp16_forward_and_dgrad():
