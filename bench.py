@@ -313,7 +313,7 @@ def main():
         Mq, Nq = op.M, op.N
         bytes_per = dy.numel() * (dy.element_size() + 2)           # read once, write codes + transposed codes
         nset = max(2, int(math.ceil((512 << 20) / bytes_per)) + 1)
-        sets = [(dy.clone(), torch.empty_like(op.dyq), torch.empty_like(op.dyqT)) for _ in range(nset)]
+        sets = [(dy.clone(), torch.empty_like(op.dyq), torch.empty(Nq, Mq, dtype=op.dyq.dtype, device="cuda")) for _ in range(nset)]
         quant_iso = {"tensor": f"dY [{Mq},{Nq}] {str(dy.dtype).replace('torch.', '')}", "bytes": "read + codes + transposed codes",
                      "sets_rotated_cold": nset}
         for rname, rnd in (("rtn", Q.ROUND_NEAREST), ("sr", Q.ROUND_STOCHASTIC)):
