@@ -106,7 +106,7 @@ def main():
     ap.add_argument("--bwd-tag", default=None, choices=[None, "fp16"],
                     help="fp16 with --tag int8: the paper's pairing, FP16 backward on the dequantized saved codes")
     ap.add_argument("--ydtype", default="f16", choices=["f16", "f32"], help="forward output type")
-    ap.add_argument("--cpu-tokens", type=int, default=2048, help="rows per operator given to the CPU oracle")
+    ap.add_argument("--cpu-tokens", type=int, default=16384, help="rows per operator given to the CPU oracle")
     ap.add_argument("--streams", type=int, default=1,
                     help="streams over which the workload's independent operators are spread in the timed region "
                          "(1 = one after the other, as a dependent training step would run them)")
