@@ -317,7 +317,8 @@ def test_quantize_strided_input_and_special_values():
 @pytest.mark.parametrize("tag", [Q.FP16, Q.FP32])
 def test_cast_and_transpose(src, tag):
     rng = np.random.default_rng(5)
-    for rows, cols in [(1, 1), (64, 64), (70, 130), (300, 96), (33, 1000)]:
+    for rows, cols in [(1, 1), (64, 64), (70, 130), (300, 96), (33, 1000), (256, 200), (72, 1032), (8, 8), (4096, 64),
+                       (520, 8)]:
         say("cast", src.__name__, tag, rows, cols)
         x = _data(rng, (rows, cols), src, 100.0)
         x[0, 0] = 1.0 + 2.0**-11 if src == np.float32 else x[0, 0]     # an exact tie for binary16
@@ -325,6 +326,10 @@ def test_cast_and_transpose(src, tag):
         want = orc.cast_fp16(x) if tag == Q.FP16 else x.astype(np.float32)
         assert_bits_equal(host(q), want, "cast")
         assert_bits_equal(host(qt), want.T, "cast transposed")
+        q1, _ = _gpu_quantize(dev(x), rows, cols, cols, tag, "tensor", "nearest", 0, 0, None, True, False)
+        _, qt1 = _gpu_quantize(dev(x), rows, cols, cols, tag, "tensor", "nearest", 0, 0, None, False, True)
+        assert_bits_equal(host(q1), want, "cast, plain copy alone")
+        assert_bits_equal(host(qt1), want.T, "cast, transposed copy alone")
 
 
 @pytest.mark.parametrize("adt", [np.int32, np.int8])
