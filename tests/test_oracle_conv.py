@@ -159,3 +159,19 @@ def test_operator_composition_matches_the_linear_operator_on_patches():
             assert cv["swb"].shape == (16,)
             w9 = w.reshape(72, 16)
             assert np.array_equal(cv["swb"], (np.abs(w9).max(axis=0) / np.float32(127)).astype(np.float32))
+
+
+def test_against_torch_conv2d_and_its_autograd():
+    """An independent library: torch's CPU convolution in double and the gradients its autograd derives."""
+    import torch
+    rng = np.random.default_rng(58)
+    x = rng.integers(-127, 128, (2, 6, 7, 5)).astype(np.float64)          # NHWC
+    w = rng.integers(-127, 128, (4, 3, 3, 5)).astype(np.float64)          # [N, kh, kw, C]
+    dy = rng.integers(-127, 128, (2, 6, 7, 4)).astype(np.float64)
+    xt = torch.tensor(x.transpose(0, 3, 1, 2).copy(), requires_grad=True)          # NCHW
+    wt = torch.tensor(w.transpose(0, 3, 1, 2).copy(), requires_grad=True)          # [N, C, kh, kw]
+    yt = torch.nn.functional.conv2d(xt, wt, padding=1)
+    yt.backward(torch.tensor(dy.transpose(0, 3, 1, 2).copy()))
+    assert np.array_equal(orc.conv3x3_fwd_f64(x, w), yt.detach().numpy().transpose(0, 2, 3, 1))
+    assert np.array_equal(orc.conv3x3_dgrad_f64(dy, w), xt.grad.numpy().transpose(0, 2, 3, 1))
+    assert np.array_equal(orc.conv3x3_wgrad_f64(dy, x), wt.grad.numpy().transpose(0, 2, 3, 1))

@@ -204,3 +204,23 @@ def test_gelu_and_its_derivative():
     h = 1e-5
     num = (orc.gelu(x + h) - orc.gelu(x - h)) / (2 * h)
     np.testing.assert_allclose(orc.gelu_grad(x), num, rtol=1e-6, atol=1e-8)
+
+
+def test_fp32_operator_against_torch_linear_and_its_autograd():
+    """An independent library: torch's CPU linear layer in double and the gradients its autograd derives."""
+    import torch
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((9, 7)).astype(np.float32)
+    w = rng.standard_normal((5, 7)).astype(np.float32)
+    b = rng.standard_normal(5).astype(np.float32)
+    dy = rng.standard_normal((9, 5)).astype(np.float32)
+    r = orc.operator_fwd_bwd(orc.FP32, x, w, b, dy, y_dtype=np.float64, dx_dtype=np.float64, dw_dtype=np.float64)
+    xt = torch.tensor(x.astype(np.float64), requires_grad=True)
+    wt = torch.tensor(w.astype(np.float64), requires_grad=True)
+    bt = torch.tensor(b.astype(np.float64), requires_grad=True)
+    yt = torch.nn.functional.linear(xt, wt, bt)
+    yt.backward(torch.tensor(dy.astype(np.float64)))
+    assert np.allclose(r["y"], yt.detach().numpy(), rtol=1e-13, atol=1e-13)
+    assert np.allclose(r["dx"], xt.grad.numpy(), rtol=1e-13, atol=1e-13)
+    assert np.allclose(r["dw"], wt.grad.numpy(), rtol=1e-13, atol=1e-13)
+    assert np.allclose(r["db"], bt.grad.numpy(), rtol=1e-6, atol=1e-6)
