@@ -126,6 +126,8 @@ def main():
         raise SystemExit(2)
 
     import torch
+    from paper_2407_02327_amd.build import ensure_built
+    ensure_built()                                   # loads what is built; compiles only when there is no library at all
     from paper_2407_02327_amd import qsync as Q
     from paper_2407_02327_amd.operator import QLinear
 

@@ -63,6 +63,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """Returns the library path, compiling it first only when no library is there at all (tests, the smoke
+    check and the benchmark load what is built; after a source change run the build explicitly)."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build(force=True)
+
+
 if __name__ == "__main__":
     path = build(force="--force" in sys.argv, verbose=True)
     print(path)

@@ -8,6 +8,9 @@ sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; compile it only when there is none at all
+    from paper_2407_02327_amd.build import ensure_built
+    ensure_built()
 
 
 def pytest_collection_modifyitems(config, items):

@@ -6,7 +6,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-qsync = pytest.importorskip("paper_2407_02327_amd.qsync", reason="libqsync.so not built")
+from paper_2407_02327_amd import qsync          # fails loudly when the library is missing or does not load
 lib = qsync.lib
 P = ctypes.c_void_p
 A = P(4096)            # a non-NULL, 16-byte aligned fake device address: validation never dereferences
