@@ -155,14 +155,16 @@ def test_int32_wraparound_matches_oracle():
     assert_bits_equal(host(acc), want, "wrapped accumulators")
 
 
-def test_config4_mixed_precision_mlp_chain():
-    """12 linears (width -> hidden -> width, GELU in between), per-layer precision tags; fwd then bwd.
+@pytest.mark.parametrize("tokens", [2048, 8192])
+def test_config4_mixed_precision_mlp_chain(tokens):
+    """12 linears (width -> hidden -> width, GELU in between), per-layer precision tags; fwd then bwd
+    (8192 tokens is the configuration's full size).
 
     Parity is asserted per operator on identical input bits: each layer's actual GPU input and
     incoming gradient are downloaded and given to the oracle.  GELU and its derivative are not part
     of the operator path; the harness evaluates them with torch between the operators.
     """
-    chain = wl.config4(tokens=2048)
+    chain = wl.config4(tokens=tokens)
     M = chain.x.shape[0]
     say("config4 chain, tags", chain.tags)
     assert set(chain.tags) == {Q.INT8, Q.FP16, Q.FP32}
