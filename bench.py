@@ -172,17 +172,20 @@ def main():
     op_streams = [main] + [torch.cuda.Stream() for _ in range(len(ops_objs) - 1)]
     side_streams = [torch.cuda.Stream() for _ in ops_objs]
 
-    def step(record: str, nstreams=nstreams):
-        """record: "none", "gemm_fwd" (events around the forward GEMM only: the timed region) or "all"."""
+    def step(record: str, nstreams=nstreams, base=None):
+        """record: "none", "gemm_fwd" (events around the forward GEMM only: the timed region) or "all".
+        base: the stream of the first operator (default: the current stream at start-up)."""
         def run(name, fn, st):
             if record == "all" or record == name:
                 ev.run(name, fn, st)
             else:
                 fn()
-        for st in op_streams[1:nstreams]:
-            st.wait_stream(main)
+        first = main if base is None else base
+        streams = [first] + op_streams[1:]
+        for st in streams[1:nstreams]:
+            st.wait_stream(first)
         for i, (op, (x, w, dy)) in enumerate(zip(ops_objs, dev_in)):
-            st, side = op_streams[i % nstreams], side_streams[i]
+            st, side = streams[i % nstreams], side_streams[i]
             if args.w_side_stream:
                 side.wait_stream(st)
                 op.convert_w(w, side)
@@ -193,8 +196,8 @@ def main():
             run("gemm_fwd", lambda: op.gemm_fwd(st), st)
             run("convert_dy", lambda: op.convert_dy(dy, st), st)
             run("gemm_bwd", lambda: op.gemm_bwd(dy, st), st)
-        for st in op_streams[1:nstreams]:
-            main.wait_stream(st)
+        for st in streams[1:nstreams]:
+            first.wait_stream(st)
 
     def step_model_order():
         """The operators as consecutive layers of one model: all forwards, then the backwards in reverse order;
@@ -249,6 +252,33 @@ def main():
         ms2 = (time.perf_counter() - t1) * 1e3 / args.steps
         overlapped = {"operator_streams": len(ops_objs), "ms_per_step": round(ms2, 4),
                       "value": round(gemm_ops / (ms2 * 1e-3) / 1e12, 3), "unit": "TOPS"}
+    # Extra (outside the timed region): the same serial step captured once in a HIP graph and replayed
+    # (the library only enqueues kernels: no allocation, no memset, no host copy inside a step).
+    graph_replay = None
+    if not args.no_extra_passes and not args.w_side_stream:
+        saved_offsets = [getattr(o, "offset", 0) for o in ops_objs]
+        cap = torch.cuda.Stream()
+        cap.wait_stream(main)
+        with torch.cuda.stream(cap):
+            step("none", 1, base=cap)
+        main.wait_stream(cap)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            step("none", 1, base=torch.cuda.current_stream())
+        for _ in range(max(2, args.warmup)):
+            g.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        ms4 = (time.perf_counter() - t1) * 1e3 / args.steps
+        graph_replay = {"ms_per_step": round(ms4, 4), "value": round(gemm_ops / (ms4 * 1e-3) / 1e12, 3), "unit": "TOPS",
+                        "note": "one serial step captured in a HIP graph, replayed (every replay reuses the captured Philox offsets)"}
+        for o, off in zip(ops_objs, saved_offsets):
+            if hasattr(o, "offset"):
+                o.offset = off
     model_order = None
     if len(ops_objs) > 1 and not args.no_extra_passes and all(hasattr(o, "gemm_bwd_part") for o in ops_objs):
         for _ in range(max(2, args.warmup)):
@@ -424,6 +454,7 @@ def main():
         "dequantize_alone": dequant_iso,
         "mfma_probe": mfma_probe,
         "operators_on_separate_streams": overlapped,
+        "hip_graph_replay": graph_replay,
         "model_order_dw_on_side_stream": model_order,
     }
     if "gemm_bwd" in per_step:
