@@ -146,7 +146,7 @@ def main():
                      w_gran=Q.PER_ROW if c.w_gran == "row" else Q.PER_TENSOR,
                      dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
                      philox_seed=c.philox_seed, bwd_tag=(Q.FP16 if args.bwd_tag == "fp16" and tag == Q.INT8 else None))
-        if c.nhwc is not None and tag == Q.INT8 and args.conv_input == "implicit":
+        if c.nhwc is not None and args.conv_input == "implicit":
             from paper_2407_02327_amd.operator import QConv3x3
             b_, h_, w_, c_ = c.nhwc.shape
             op = QConv3x3(tag, b_, h_, w_, c_, N, x_dtype=tdt[str(c.nhwc.dtype)], y_dtype=ydt, dx_dtype=torch.float16,
@@ -156,7 +156,7 @@ def main():
             op.convert_x_nhwc, op.gemm_fwd = op.convert_x, op.conv_fwd
             op.gemm_bwd = (lambda o: lambda dy, st=None: (o.conv_dgrad(st), o.conv_wgrad(st)))(op)
         ops_objs.append(op)
-        nhwc = c.nhwc is not None and tag == Q.INT8 and args.conv_input in ("nhwc", "implicit")
+        nhwc = c.nhwc is not None and ((tag == Q.INT8 and args.conv_input == "nhwc") or args.conv_input == "implicit")
         x_in = torch.from_numpy(c.nhwc if nhwc else c.x).cuda()
         op.convert_act = op.convert_x_nhwc if nhwc else op.convert_x
         dev_in.append((x_in, torch.from_numpy(c.w).cuda(), torch.from_numpy(c.dy).cuda()))
@@ -436,7 +436,8 @@ def main():
                    "dy_rounding": "stochastic (Philox4x32-10)" if args.bwd_tag is None else "none (FP16 backward)",
                    "bwd_tag": args.bwd_tag or args.tag,
                    "operator_streams": nstreams,
-                   **({"conv_input": args.conv_input} if any(c.nhwc is not None for c in cases) and tag == Q.INT8 else {})},
+                   **({"conv_input": args.conv_input if (tag == Q.INT8 or args.conv_input == "implicit") else "patches"}
+                      if any(c.nhwc is not None for c in cases) else {})},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches)",
                      "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4),

@@ -222,27 +222,31 @@ int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * qsync_conv3x3_wgrad - weight gradient of the 3x3 / stride 1 / pad 1 convolution on int8 codes
+ * qsync_conv3x3_wgrad - weight gradient of the 3x3 / stride 1 / pad 1 convolution on int8 codes or binary16
  * (paper: Appendix, proof of Prop. 1, backward of an operator from the saved, compressed context):
  *   dw[n, (kh*3+kw)*C + c] = sdy * sx * sum_{b,h,w} dyq[b,h,w,n] * xq[b, h+kh-1, w+kw-1, c]   (0 outside the image)
+ * (tag FP16: the same sum over binary16 operands with fp32 accumulation, no scales).
  * The contraction runs over the pixels, so both operands are needed pixel-contiguous.  They are written to
  * the workspace transposed over a zero-padded pixel axis (a zero row in front of every image, rows padded
  * with zeros to a multiple of 16 pixels) on which every window offset is a plain displacement: the gradient
  * once, the activation three times (displaced by -1, 0, +1 pixel, so that every tap reads 16-byte aligned
- * rows), about 3.5 bytes per activation element instead of the 9 of a materialised patch matrix.  The MFMA
+ * rows), about 3.5 elements per activation element instead of the 9 of a materialised patch matrix.  The MFMA
  * GEMM then reads the nine taps as displaced rows of those copies.
  *
- * xq   [nimg, H, W, C] int8 and dyq [nimg*H*W, N] int8, device, 16-byte aligned; C % 16 == 0, N % 16 == 0
- *      (QSYNC_ERR_ALIGN); W <= 1007 (QSYNC_ERR_BAD_SHAPE).  sx, sdy: one float each (device).
- * dw   out, [N, 9*C] of dwdt (QSYNC_F32 or QSYNC_F16); acc_dump_opt: raw int32 accumulators [N, 9*C] or NULL.
+ * tag  QSYNC_INT8 or QSYNC_FP16 (QSYNC_FP32: QSYNC_ERR_UNSUPPORTED).
+ * xq   [nimg, H, W, C] and dyq [nimg*H*W, N], int8 or binary16, device, 16-byte aligned; C and N times the
+ *      element size must be multiples of 16 bytes (QSYNC_ERR_ALIGN); (W + 16) * element size <= 1024
+ *      (QSYNC_ERR_BAD_SHAPE).  sx, sdy: one float each (device; INT8 only).
+ * dw   out, [N, 9*C] of dwdt (QSYNC_F32 or QSYNC_F16); acc_dump_opt: raw int32 accumulators [N, 9*C] or NULL
+ *      (INT8 only).
  * workspace  at least qsync_conv3x3_wgrad_workspace_bytes(...) bytes, 256-byte aligned; no part of it needs
  *            to be initialised.
  */
-int qsync_conv3x3_wgrad(int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N,
+int qsync_conv3x3_wgrad(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N,
                         const void* xq, const float* sx, const void* dyq, const float* sdy,
                         void* dw, int dwdt, int32_t* acc_dump_opt,
                         void* workspace, size_t workspace_bytes, void* stream);
-size_t qsync_conv3x3_wgrad_workspace_bytes(int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N);
+size_t qsync_conv3x3_wgrad_workspace_bytes(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N);
 
 /*
  * qsync_conv3x3_prepare_weights - every weight operand of one INT8 3x3 convolution with per-output-channel

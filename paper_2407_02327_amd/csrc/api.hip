@@ -269,60 +269,67 @@ int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits
 // [gradient operand, N x Mp][split-K partials]; every part starts on a 256-byte boundary.
 namespace {
 struct WgradLayout { ConvPaddedAxis ax; size_t margin, off_x, off_dy, off_part, total; GemmPlan plan; };
-WgradLayout wgrad_layout(int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
+WgradLayout wgrad_layout(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
 {
-    WgradLayout l;
+    const size_t esz = tag == QSYNC_INT8 ? 1 : 2;
+    WgradLayout  l;
     l.ax       = conv_padded_axis(nimg, static_cast<int>(H), static_cast<int>(W));
-    l.margin   = round256(static_cast<size_t>(l.ax.Wp));
+    l.margin   = round256(static_cast<size_t>(l.ax.Wp) * esz);
     l.off_x    = l.margin;
-    l.off_dy   = l.off_x + round256(static_cast<size_t>(3 * C * l.ax.Mp)) + l.margin;
-    l.off_part = l.off_dy + round256(static_cast<size_t>(N * l.ax.Mp));
-    l.plan     = plan_gemm(QSYNC_INT8, N, 9 * C, l.ax.Mp);
+    l.off_dy   = l.off_x + round256(static_cast<size_t>(3 * C * l.ax.Mp) * esz) + l.margin;
+    l.off_part = l.off_dy + round256(static_cast<size_t>(N * l.ax.Mp) * esz);
+    l.plan     = plan_gemm(tag, N, 9 * C, l.ax.Mp);
     l.total    = l.off_part + l.plan.workspace;
     return l;
 }
-bool wgrad_shape_ok(int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
+bool wgrad_shape_ok(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
 {
-    if(nimg < 0 || H < 0 || W < 0 || C < 0 || N < 0 || H > 65535 || W > 1007 || C > (1 << 20) || N > (int64_t(1) << 31))
+    const int64_t esz = tag == QSYNC_INT8 ? 1 : 2;
+    if(nimg < 0 || H < 0 || W < 0 || C < 0 || N < 0 || H > 65535 || (W + 16) * esz > 1024 || C > (1 << 20)
+       || N > (int64_t(1) << 31))
         return false;
     if(H > 0 && W > 0 && nimg > ((int64_t(1) << 31) - 1) / ((H + 1) * (W + 16))) return false;
     const ConvPaddedAxis ax = conv_padded_axis(nimg, static_cast<int>(H), static_cast<int>(W));
-    return 3 * C * ax.Mp < (int64_t(1) << 32) - (1 << 20) && count_ok(N, ax.Mp) && count_ok(N, 9 * C);
+    return 3 * C * ax.Mp * esz < (int64_t(1) << 32) - (1 << 20) && count_ok(N, ax.Mp) && count_ok(N, 9 * C);
 }
 }  // namespace
 
-size_t qsync_conv3x3_wgrad_workspace_bytes(int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
+size_t qsync_conv3x3_wgrad_workspace_bytes(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
 {
-    if(nimg <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0 || !wgrad_shape_ok(nimg, H, W, C, N)) return 0;
-    return wgrad_layout(nimg, H, W, C, N).total;
+    if((tag != QSYNC_INT8 && tag != QSYNC_FP16) || nimg <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0
+       || !wgrad_shape_ok(tag, nimg, H, W, C, N))
+        return 0;
+    return wgrad_layout(tag, nimg, H, W, C, N).total;
 }
 
-int qsync_conv3x3_wgrad(int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq, const float* sx,
+int qsync_conv3x3_wgrad(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq, const float* sx,
                         const void* dyq, const float* sdy, void* dw, int dwdt, int32_t* acc_dump_opt, void* workspace,
                         size_t workspace_bytes, void* stream)
 {
-    if(!xq || !sx || !dyq || !sdy || !dw) return QSYNC_ERR_NULL;
-    if(!is_float_dtype(dwdt)) return QSYNC_ERR_BAD_ENUM;
-    if(!wgrad_shape_ok(nimg, H, W, C, N)) return QSYNC_ERR_BAD_SHAPE;
+    if(!xq || !dyq || !dw) return QSYNC_ERR_NULL;
+    if(!is_tag(tag) || !is_float_dtype(dwdt)) return QSYNC_ERR_BAD_ENUM;
+    if(tag == QSYNC_FP32) return QSYNC_ERR_UNSUPPORTED;
+    if(tag == QSYNC_INT8 && (!sx || !sdy)) return QSYNC_ERR_NULL;
+    if(tag != QSYNC_INT8 && acc_dump_opt) return QSYNC_ERR_UNSUPPORTED;
+    if(!wgrad_shape_ok(tag, nimg, H, W, C, N)) return QSYNC_ERR_BAD_SHAPE;
     if(nimg == 0 || H == 0 || W == 0 || C == 0 || N == 0) return QSYNC_OK;
-    if(C % 16 != 0 || N % 16 != 0 || !aligned16(xq) || !aligned16(dyq)) return QSYNC_ERR_ALIGN;
-    const WgradLayout l = wgrad_layout(nimg, H, W, C, N);
+    const int esz = tag == QSYNC_INT8 ? 1 : 2;
+    if((C * esz) % 16 != 0 || (N * esz) % 16 != 0 || !aligned16(xq) || !aligned16(dyq)) return QSYNC_ERR_ALIGN;
+    const WgradLayout l = wgrad_layout(tag, nimg, H, W, C, N);
     if(!workspace || workspace_bytes < l.total) return QSYNC_ERR_WORKSPACE;
     if((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return QSYNC_ERR_ALIGN;
     hipStream_t st  = static_cast<hipStream_t>(stream);
-    int8_t*     xT  = static_cast<int8_t*>(workspace) + l.off_x;
-    int8_t*     dyT = static_cast<int8_t*>(workspace) + l.off_dy;
-    hipError_t  e   = launch_conv_padded_transpose(static_cast<const int8_t*>(xq), nimg, static_cast<int>(H), static_cast<int>(W),
-                                                   static_cast<int>(C), 3, xT, st);
+    uint8_t*    xT  = static_cast<uint8_t*>(workspace) + l.off_x;
+    uint8_t*    dyT = static_cast<uint8_t*>(workspace) + l.off_dy;
+    hipError_t  e   = launch_conv_padded_transpose(xq, esz, nimg, static_cast<int>(H), static_cast<int>(W), static_cast<int>(C), 3, xT, static_cast<int>(l.margin), st);
     if(e != hipSuccess) return hip_status(e);
-    e = launch_conv_padded_transpose(static_cast<const int8_t*>(dyq), nimg, static_cast<int>(H), static_cast<int>(W),
-                                     static_cast<int>(N), 1, dyT, st);
+    e = launch_conv_padded_transpose(dyq, esz, nimg, static_cast<int>(H), static_cast<int>(W), static_cast<int>(N), 1, dyT, 0, st);
     if(e != hipSuccess) return hip_status(e);
     GemmProblem p{};
-    p.prec = QSYNC_INT8; p.M = N; p.N = 9 * C; p.K = l.ax.Mp;
+    p.prec = tag; p.M = N; p.N = 9 * C; p.K = l.ax.Mp;
     p.A = dyT; p.B = xT; p.C = dw; p.c_dtype = dwdt;
-    p.s0 = sdy; p.s1 = sx; p.acc_dump = acc_dump_opt;
-    p.b_remap_C = C; p.b_remap_shift = l.ax.Wp;
+    if(tag == QSYNC_INT8) { p.s0 = sdy; p.s1 = sx; p.acc_dump = acc_dump_opt; }
+    p.b_remap_C = C; p.b_remap_shift = static_cast<int64_t>(l.ax.Wp) * esz;
     return hip_status(launch_gemm(p, l.plan, static_cast<uint8_t*>(workspace) + l.off_part, st));
 }
 

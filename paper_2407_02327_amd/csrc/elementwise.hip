@@ -821,20 +821,32 @@ __global__ __launch_bounds__(kBlock) void im2col3x3_i8_kernel(const int8_t* __re
 // (out[s][ch][q] = padded[ch][q + s - 1]), so that the GEMM reads 16-byte aligned rows for every tap;
 // NS = 1 writes the undisplaced copy (the gradient operand).  A lane gathers 18 (16) pixels x 16 channels
 // and leaves with one 16-byte store per channel and copy; pads are written, nothing is assumed zero.
-template <int NS>
+// ES = element size in bytes (1: int8 codes, 2: binary16); `in`/`out` are byte pointers, Ch counts elements.
+template <int NS, int ES>
 __global__ __launch_bounds__(kBlock) void conv_padded_transpose_kernel(const int8_t* __restrict__ in, int64_t nimg, int H,
                                                                        int W, int Ch, int Wp, int64_t Mp,
-                                                                       int8_t* __restrict__ out, int cw_log2)
+                                                                       int8_t* __restrict__ out, int cw_log2,
+                                                                       int margin_bytes)
 {
-    constexpr int NP = NS == 3 ? 18 : 16;
+    constexpr int NP  = NS == 3 ? 18 : 16;
+    constexpr int CPC = 16 / ES;                  // channels per 16-byte chunk
+    // margin_bytes > 0: `out` sits between two margins of that many bytes which the GEMM's displaced rows reach
+    // into (multiplied by zeros of the other operand); they are cleared here so that no stale NaN pattern can
+    // meet a binary16 zero
+    if(margin_bytes > 0 && blockIdx.x == 0)
+        for(int t = threadIdx.x * 16; t < margin_bytes; t += kBlock * 16)
+        {
+            *reinterpret_cast<uint4*>(out - margin_bytes + t) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4*>(out + static_cast<int64_t>(NS) * Ch * Mp * ES + t) = make_uint4(0, 0, 0, 0);
+        }
     const int64_t lin  = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    const int     ncc  = Ch / 16, cw = 1 << cw_log2;
+    const int     ncc  = Ch / CPC, cw = 1 << cw_log2;
     const int64_t nq   = Mp / 16, rest = lin >> cw_log2;
     const int64_t qb   = rest % nq, ccg = rest / nq;
     const int     cc   = static_cast<int>(ccg) * cw + static_cast<int>(lin & (cw - 1));
     if(cc >= ncc) return;
     const int64_t q0 = qb * 16;
-    const int     c0 = cc * 16;
+    const int     c0 = cc * CPC;
     // first gathered pixel: q0 - 1 (NS = 3) or q0; position -1 is written as the last column of a row "-1"
     int64_t p0 = q0 - (NS == 3 ? 1 : 0);
     int     col, hrow;
@@ -853,7 +865,7 @@ __global__ __launch_bounds__(kBlock) void conv_padded_transpose_kernel(const int
     {
         uint4 v = make_uint4(0, 0, 0, 0);
         if(col < W && hrow >= 1 && img >= 0 && img < nimg)
-            v = *reinterpret_cast<const uint4*>(in + ((img * H + (hrow - 1)) * W + col) * Ch + c0);
+            v = *reinterpret_cast<const uint4*>(in + (((img * H + (hrow - 1)) * W + col) * Ch + c0) * ES);
         code[i][0] = v.x; code[i][1] = v.y; code[i][2] = v.z; code[i][3] = v.w;
         if(++col == Wp)
         {
@@ -864,15 +876,31 @@ __global__ __launch_bounds__(kBlock) void conv_padded_transpose_kernel(const int
 #pragma unroll
     for(int s = 0; s < NS; ++s)
 #pragma unroll
-        for(int ch = 0; ch < 16; ++ch)
+        for(int ch = 0; ch < CPC; ++ch)
         {
-            uint32_t t[4];
+            int8_t* dst = out + ((static_cast<int64_t>(s) * Ch + c0 + ch) * Mp + q0) * ES;
+            if constexpr(ES == 1)
+            {
+                uint32_t t[4];
 #pragma unroll
-            for(int g = 0; g < 4; ++g)
-                t[g] = byte_of(code[4 * g + 0 + s][ch / 4], ch % 4) | (byte_of(code[4 * g + 1 + s][ch / 4], ch % 4) << 8)
-                     | (byte_of(code[4 * g + 2 + s][ch / 4], ch % 4) << 16)
-                     | (byte_of(code[4 * g + 3 + s][ch / 4], ch % 4) << 24);
-            *reinterpret_cast<uint4*>(out + (static_cast<int64_t>(s) * Ch + c0 + ch) * Mp + q0) = make_uint4(t[0], t[1], t[2], t[3]);
+                for(int g = 0; g < 4; ++g)
+                    t[g] = byte_of(code[4 * g + 0 + s][ch / 4], ch % 4) | (byte_of(code[4 * g + 1 + s][ch / 4], ch % 4) << 8)
+                         | (byte_of(code[4 * g + 2 + s][ch / 4], ch % 4) << 16)
+                         | (byte_of(code[4 * g + 3 + s][ch / 4], ch % 4) << 24);
+                *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
+            }
+            else
+            {
+                uint32_t t[8];
+#pragma unroll
+                for(int g = 0; g < 8; ++g)
+                {
+                    const uint32_t lo = code[2 * g + 0 + s][ch / 2], hi = code[2 * g + 1 + s][ch / 2];
+                    t[g] = (ch % 2 == 0) ? ((lo & 0xFFFFu) | (hi << 16)) : ((lo >> 16) | (hi & 0xFFFF0000u));
+                }
+                reinterpret_cast<uint4*>(dst)[0] = make_uint4(t[0], t[1], t[2], t[3]);
+                reinterpret_cast<uint4*>(dst)[1] = make_uint4(t[4], t[5], t[6], t[7]);
+            }
         }
 }
 
@@ -1587,21 +1615,30 @@ ConvPaddedAxis conv_padded_axis(int64_t nimg, int H, int W)
     return a;
 }
 
-hipError_t launch_conv_padded_transpose(const int8_t* in, int64_t nimg, int H, int W, int Ch, int copies, int8_t* out,
-                                        hipStream_t stream)
+hipError_t launch_conv_padded_transpose(const void* in, int elem_bytes, int64_t nimg, int H, int W, int Ch, int copies,
+                                        void* out, int margin_bytes, hipStream_t stream)
 {
     const ConvPaddedAxis ax = conv_padded_axis(nimg, H, W);
-    const int     ncc = Ch / 16;
+    const int     ncc = Ch / (16 / elem_bytes);
     int           cw_log2 = 2;                                   // four channel chunks side by side when there are that many
     while(cw_log2 > 0 && (1 << (cw_log2 - 1)) >= ncc) --cw_log2;
     const int64_t groups = (ncc + (1 << cw_log2) - 1) >> cw_log2;
     const int64_t lanes  = (ax.Mp / 16) * groups << cw_log2;
     const int64_t nb     = (lanes + kBlock - 1) / kBlock;
     if(nb >= (int64_t(1) << 31)) return hipErrorInvalidValue;
-    if(copies == 3)
-        conv_padded_transpose_kernel<3><<<dim3(static_cast<unsigned>(nb)), dim3(kBlock), 0, stream>>>(in, nimg, H, W, Ch, ax.Wp, ax.Mp, out, cw_log2);
+    const dim3    grid(static_cast<unsigned>(nb)), block(kBlock);
+    const int8_t* src = static_cast<const int8_t*>(in);
+    int8_t*       dst = static_cast<int8_t*>(out);
+    if(elem_bytes == 1)
+    {
+        if(copies == 3) conv_padded_transpose_kernel<3, 1><<<grid, block, 0, stream>>>(src, nimg, H, W, Ch, ax.Wp, ax.Mp, dst, cw_log2, margin_bytes);
+        else            conv_padded_transpose_kernel<1, 1><<<grid, block, 0, stream>>>(src, nimg, H, W, Ch, ax.Wp, ax.Mp, dst, cw_log2, margin_bytes);
+    }
     else
-        conv_padded_transpose_kernel<1><<<dim3(static_cast<unsigned>(nb)), dim3(kBlock), 0, stream>>>(in, nimg, H, W, Ch, ax.Wp, ax.Mp, out, cw_log2);
+    {
+        if(copies == 3) conv_padded_transpose_kernel<3, 2><<<grid, block, 0, stream>>>(src, nimg, H, W, Ch, ax.Wp, ax.Mp, dst, cw_log2, margin_bytes);
+        else            conv_padded_transpose_kernel<1, 2><<<grid, block, 0, stream>>>(src, nimg, H, W, Ch, ax.Wp, ax.Mp, dst, cw_log2, margin_bytes);
+    }
     return hipGetLastError();
 }
 

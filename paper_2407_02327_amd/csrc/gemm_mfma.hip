@@ -751,7 +751,7 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
 hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream)
 {
     if(p.M <= 0 || p.N <= 0) return hipSuccess;
-    if(p.prec == 32) return p.conv_H > 0 ? hipErrorInvalidValue : launch_gemm_f32(p, stream);
+    if(p.prec == 32) return (p.conv_H > 0 || p.b_remap_C > 0) ? hipErrorInvalidValue : launch_gemm_f32(p, stream);
     const int      esz = p.prec == 8 ? 1 : 2;
     GemmKernelArgs a;
     a.A = static_cast<const uint8_t*>(p.A);
@@ -765,7 +765,7 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.remap_C = a.remap_shift = 0;
     if(p.b_remap_C > 0)
     {   // B is [3*remap_C, K] with a margin of |remap_shift| readable bytes in front of it and behind it
-        if(p.conv_H > 0 || p.prec != 8 || p.N != 9 * p.b_remap_C || p.b_remap_shift % 16 != 0 || p.b_remap_shift < 0
+        if(p.conv_H > 0 || p.N != 9 * p.b_remap_C || p.b_remap_shift % 16 != 0 || p.b_remap_shift < 0
            || p.b_remap_shift > 1024 || 3 * p.b_remap_C * a.Kb >= (int64_t(1) << 32) - (1 << 20))
             return hipErrorInvalidValue;
         a.remap_C = static_cast<int>(p.b_remap_C); a.remap_shift = static_cast<int>(p.b_remap_shift);

@@ -49,9 +49,11 @@ hipError_t launch_conv3x3_wflip(const void* w, int elem_bytes, int64_t N, int64_
 // padded pixel axis of the convolution's weight-gradient operands (see conv_padded_transpose_kernel)
 struct ConvPaddedAxis { int Wp; int64_t Mp; };
 ConvPaddedAxis conv_padded_axis(int64_t nimg, int H, int W);
-// in [nimg*H*W, Ch] int8 (Ch % 16 == 0) -> out [copies][Ch][Mp]; copies 3 (displaced by -1, 0, +1) or 1
-hipError_t launch_conv_padded_transpose(const int8_t* in, int64_t nimg, int H, int W, int Ch, int copies, int8_t* out,
-                                        hipStream_t stream);
+// in [nimg*H*W, Ch] of 1- or 2-byte elements (Ch * elem_bytes % 16 == 0) -> out [copies][Ch][Mp];
+// copies 3 (displaced by -1, 0, +1 pixel) or 1; margin_bytes > 0 (a multiple of 16): that many bytes in front of
+// and behind `out` are cleared as well
+hipError_t launch_conv_padded_transpose(const void* in, int elem_bytes, int64_t nimg, int H, int W, int Ch, int copies,
+                                        void* out, int margin_bytes, hipStream_t stream);
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
@@ -76,7 +78,7 @@ struct GemmProblem {
     // 3x3 / stride 1 / pad 1 patch matrix [M, K = 9*conv_C] (k = (kh, kw, c)), formed on the fly.
     int         conv_H = 0, conv_W = 0;
     int64_t     conv_C = 0;
-    // b_remap_C > 0 (int8 only): N = 9*b_remap_C logical rows (tap, c) of B are the rows (tap%3)*b_remap_C + c of a
+    // b_remap_C > 0 (int8 and binary16): N = 9*b_remap_C logical rows (tap, c) of B are the rows (tap%3)*b_remap_C + c of a
     // [3*b_remap_C, K] matrix, read with the K axis displaced by (tap/3 - 1)*b_remap_shift bytes (a multiple of
     // 16, at most 1024); that many bytes in front of and behind the matrix must be readable.
     int64_t     b_remap_C = 0, b_remap_shift = 0;

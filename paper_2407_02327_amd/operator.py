@@ -219,7 +219,7 @@ class QConv3x3:
     matrix is never stored); the weight gradient contracts over the pixels and reads the transposed patch
     matrix, expanded from the int8 codes.  Buffers are allocated once; nothing here computes.
 
-    INT8: all three passes.  FP16: forward and data gradient (no binary16 patch expansion is provided).
+    INT8 and FP16: all three passes (the patch-matrix form of the weight gradient is INT8 only).
     The weight gradient reads both operands transposed over a zero-padded pixel axis (qsync_conv3x3_wgrad);
     wgrad_via_patches=True materialises the transposed patch matrix instead (qsync_im2col3x3_i8 + the linear
     operator's dW GEMM).
@@ -259,15 +259,18 @@ class QConv3x3:
                                  Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR)), device)
         self.ws_absmax_w = _ws(max(Q.qsync_conv3x3_prepare_weights_workspace_bytes(N, C),
                                    Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), device)
-        if tag == Q.INT8:
-            self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K) if wgrad_via_patches
-                              else Q.qsync_conv3x3_wgrad_workspace_bytes(nimg, H, W, C, N), device)
+        if wgrad_via_patches and tag != Q.INT8:
+            raise ValueError("QConv3x3: the patch-matrix weight gradient exists for INT8 only")
+        self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K) if wgrad_via_patches
+                          else Q.qsync_conv3x3_wgrad_workspace_bytes(tag, nimg, H, W, C, N), device)
 
     def convert_x(self, act: torch.Tensor, stream=None) -> None:
         M, C = self.M, self.C
         if self.tag == Q.INT8:
             Q.qsync_absmax_scale(act, M, C, C, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None, self.ws_absmax, stream)
             Q.qsync_quantize(act, M, C, C, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq, None, stream)
+        elif act.dtype == _TORCH_OF_TAG[self.tag] and act.is_contiguous():
+            self.xq = act.view(M, C)           # already in the operand type: used in place
         else:
             Q.qsync_quantize(act, M, C, C, self.tag, 0, 0, 0, 0, 0, None, self.xq, None, stream)
 
@@ -299,6 +302,8 @@ class QConv3x3:
             Q.qsync_quantize(dy, M, N, N, Q.INT8, self.bits, Q.PER_TENSOR, self.dy_round, self.seed, self.offset,
                              self.idy, self.dyq, self.dyqT, stream)
             self.offset += (M * N + 7) // 8
+        elif dy.dtype == _TORCH_OF_TAG[self.tag] and dy.is_contiguous():
+            self.dyq = dy
         else:
             Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, self.dyq, None, stream)
 
@@ -308,10 +313,8 @@ class QConv3x3:
                             self.w_gran, None, self.dx, self.acc_dx, stream)
 
     def conv_wgrad(self, stream=None) -> None:
-        if self.tag != Q.INT8:
-            raise NotImplementedError("weight gradient: INT8 tag only")
         if not self.wgrad_via_patches:
-            Q.qsync_conv3x3_wgrad(self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.dyq, self.sdy, self.dw,
+            Q.qsync_conv3x3_wgrad(self.tag, self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.dyq, self.sdy, self.dw,
                                   self.acc_dw, self.ws_bwd, stream)
             return
         Q.qsync_im2col3x3_i8(self.xq, self.nimg, self.H, self.W, self.C, None, self.xqTp, stream)
@@ -327,6 +330,5 @@ class QConv3x3:
     def backward(self, dy: torch.Tensor, stream=None):
         self.convert_dy(dy, stream)
         self.conv_dgrad(stream)
-        if self.tag == Q.INT8:
-            self.conv_wgrad(stream)
-        return self.dx, self.dw, self.db
+        self.conv_wgrad(stream)
+        return self.dx, self.dw, (self.db if self.tag == Q.INT8 else None)     # db comes out of the INT8 absmax pass

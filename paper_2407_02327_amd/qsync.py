@@ -39,8 +39,8 @@ SIGNATURES = {
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
     "qsync_debug_set_gemm_tile": (None, [_i]),
-    "qsync_conv3x3_wgrad": (_i, [_i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
-    "qsync_conv3x3_wgrad_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64]),
+    "qsync_conv3x3_wgrad": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
+    "qsync_conv3x3_wgrad_workspace_bytes": (_sz, [_i, _i64, _i64, _i64, _i64, _i64]),
     "qsync_conv3x3_prepare_weights": (_i, [_vp, _i, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qsync_conv3x3_prepare_weights_workspace_bytes": (_sz, [_i64, _i64]),
     "qsync_probe_mfma": (_i, [_i, _i, _i, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
@@ -159,12 +159,12 @@ def qsync_conv3x3_prepare_weights(w, N, C, bits, sw, iw, wq, swb, iwb, wflip, wo
                                              _ptr(iwb), _ptr(wflip), _ptr(workspace), _bytes(workspace), _stream(stream)))
 
 
-def qsync_conv3x3_wgrad_workspace_bytes(nimg: int, H: int, W: int, C: int, N: int) -> int:
-    return lib.qsync_conv3x3_wgrad_workspace_bytes(nimg, H, W, C, N)
+def qsync_conv3x3_wgrad_workspace_bytes(tag: int, nimg: int, H: int, W: int, C: int, N: int) -> int:
+    return lib.qsync_conv3x3_wgrad_workspace_bytes(tag, nimg, H, W, C, N)
 
 
-def qsync_conv3x3_wgrad(nimg, H, W, C, N, xq, sx, dyq, sdy, dw, acc_dump_opt, workspace, stream=None) -> None:
-    _check(lib.qsync_conv3x3_wgrad(nimg, H, W, C, N, _ptr(xq), _ptr(sx), _ptr(dyq), _ptr(sdy), _ptr(dw), dtype_code(dw),
+def qsync_conv3x3_wgrad(tag, nimg, H, W, C, N, xq, sx, dyq, sdy, dw, acc_dump_opt, workspace, stream=None) -> None:
+    _check(lib.qsync_conv3x3_wgrad(tag, nimg, H, W, C, N, _ptr(xq), _ptr(sx), _ptr(dyq), _ptr(sdy), _ptr(dw), dtype_code(dw),
                                    _ptr(acc_dump_opt), _ptr(workspace), _bytes(workspace), _stream(stream)))
 
 

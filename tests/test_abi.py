@@ -160,26 +160,37 @@ def test_prepare_weights_validation():
 def test_conv_wgrad_validation():
     f = lib.qsync_conv3x3_wgrad
     B = P(8192)                                              # 256-byte aligned
-    ok = [1, 4, 4, 16, 16, A, A, A, A, A, 0, None, B, 1 << 24, None]
+    ok = [8, 1, 4, 4, 16, 16, A, A, A, A, A, 0, None, B, 1 << 24, None]
     assert f(*ok) in (qsync.OK, qsync.ERR_HIP)
-    for i in (5, 6, 7, 8, 9):
+    for i in (6, 7, 8, 9, 10):
         a = list(ok); a[i] = None
         assert f(*a) == qsync.ERR_NULL
-    a = list(ok); a[10] = qsync.I8
+    a = list(ok); a[0] = 16; a[7] = None; a[9] = None        # binary16: no scales needed
+    assert f(*a) in (qsync.OK, qsync.ERR_HIP)
+    a = list(ok); a[0] = 32
+    assert f(*a) == qsync.ERR_UNSUPPORTED
+    a = list(ok); a[0] = 3
     assert f(*a) == qsync.ERR_BAD_ENUM
-    a = list(ok); a[2] = 2000
+    a = list(ok); a[11] = qsync.I8
+    assert f(*a) == qsync.ERR_BAD_ENUM
+    a = list(ok); a[3] = 2000
     assert f(*a) == qsync.ERR_BAD_SHAPE                      # W beyond the displaced-row limit
-    a = list(ok); a[3] = 24
+    a = list(ok); a[0] = 16; a[3] = 600
+    assert f(*a) == qsync.ERR_BAD_SHAPE                      # half that limit for two-byte elements
+    a = list(ok); a[4] = 24
     assert f(*a) == qsync.ERR_ALIGN
-    a = list(ok); a[4] = 8
+    a = list(ok); a[5] = 8
     assert f(*a) == qsync.ERR_ALIGN
-    a = list(ok); a[13] = 64
+    a = list(ok); a[0] = 16; a[12] = A
+    assert f(*a) == qsync.ERR_UNSUPPORTED                    # accumulator dump: INT8 only
+    a = list(ok); a[14] = 64
     assert f(*a) == qsync.ERR_WORKSPACE
-    a = list(ok); a[12] = P(4112)                            # 16-byte but not 256-byte aligned
+    a = list(ok); a[13] = P(4112)                            # 16-byte but not 256-byte aligned
     assert f(*a) == qsync.ERR_ALIGN
-    a = list(ok); a[0] = 0
+    a = list(ok); a[1] = 0
     assert f(*a) == qsync.OK
-    assert lib.qsync_conv3x3_wgrad_workspace_bytes(64, 56, 56, 64, 64) > 3 * 64 * 64 * 57 * 64
+    assert lib.qsync_conv3x3_wgrad_workspace_bytes(8, 64, 56, 56, 64, 64) > 3 * 64 * 64 * 57 * 64
+    assert lib.qsync_conv3x3_wgrad_workspace_bytes(16, 64, 56, 56, 64, 64) > 2 * 3 * 64 * 64 * 57 * 64
 
 
 def test_conv_prepare_weights_validation():

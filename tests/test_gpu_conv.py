@@ -120,14 +120,32 @@ def test_weight_gradient_on_codes_bit_exact(tile):
         sx, sdy = np.array([0.02], np.float32), np.array([3e-4], np.float32)
         want_acc = orc.conv3x3_wgrad_f64(dyq, xq).reshape(n, 9 * c)
         acc, dw = empty((n, 9 * c), torch.int32), empty((n, 9 * c), torch.float32)
-        wsp = ws(Q.qsync_conv3x3_wgrad_workspace_bytes(b, h, w, c, n))
+        wsp = ws(Q.qsync_conv3x3_wgrad_workspace_bytes(Q.INT8, b, h, w, c, n))
         wsp.fill_(0x5A)                                           # nothing in the workspace needs initialising
-        Q.qsync_conv3x3_wgrad(b, h, w, c, n, dev(xq), dev(sx), dev(dyq.reshape(-1, n)), dev(sdy), dw, acc, wsp)
+        Q.qsync_conv3x3_wgrad(Q.INT8, b, h, w, c, n, dev(xq), dev(sx), dev(dyq.reshape(-1, n)), dev(sdy), dw, acc, wsp)
         assert_bits_equal(host(acc), want_acc.astype(np.int32), "weight-gradient accumulators")
         assert_close(host(dw), want_acc * float(sx[0]) * float(sdy[0]), "dW with accumulator dump")
         dwh = empty((n, 9 * c), torch.float16)
-        Q.qsync_conv3x3_wgrad(b, h, w, c, n, dev(xq), dev(sx), dev(dyq.reshape(-1, n)), dev(sdy), dwh, None, wsp)
+        Q.qsync_conv3x3_wgrad(Q.INT8, b, h, w, c, n, dev(xq), dev(sx), dev(dyq.reshape(-1, n)), dev(sdy), dwh, None, wsp)
         assert_close(host(dwh), want_acc * float(sx[0]) * float(sdy[0]), "dW fp16")
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 2])
+def test_weight_gradient_fp16(tile):
+    from tests.gpu_util import ws
+    rng = np.random.default_rng(69)
+    Q.qsync_debug_set_gemm_tile(tile)
+    for (b, h, w, c, n) in [(1, 4, 4, 8, 8), (2, 7, 5, 16, 24), (3, 8, 8, 64, 64), (1, 13, 16, 40, 48), (2, 3, 70, 8, 16),
+                            (1, 1, 1, 8, 8), (2, 31, 33, 16, 8)]:
+        say("conv wgrad fp16", "tile", tile, b, h, w, c, n)
+        x = rng.standard_normal((b, h, w, c)).astype(np.float16)
+        dy = (rng.standard_normal((b, h, w, n)) * 0.05).astype(np.float16)
+        want = orc.conv3x3_wgrad_f64(dy, x).reshape(n, 9 * c)
+        dw = empty((n, 9 * c), torch.float32)
+        wsp = ws(Q.qsync_conv3x3_wgrad_workspace_bytes(Q.FP16, b, h, w, c, n))
+        wsp.fill_(0xFF)                                           # uninitialised workspace full of NaN patterns
+        Q.qsync_conv3x3_wgrad(Q.FP16, b, h, w, c, n, dev(x), None, dev(dy.reshape(-1, n)), None, dw, None, wsp)
+        assert_close(host(dw), want, "dW fp16 tag")
 
 
 def conv_case(batch, hh, ww, c, n, seed):
@@ -183,10 +201,12 @@ def test_conv_operator_fp16_forward_and_dgrad():
     op.bias.copy_(dev(bias))
     op.forward(dev(act), dev(w))
     op.backward(dev(dy))
-    ref = orc.conv3x3_operator_fwd_bwd(orc.FP16, act, w, bias, dy, y_dtype=np.float64, dx_dtype=np.float64)
+    ref = orc.conv3x3_operator_fwd_bwd(orc.FP16, act, w, bias, dy, y_dtype=np.float64, dx_dtype=np.float64,
+                                       dw_dtype=np.float64)
     assert_bits_equal(host(op.wq), ref["wq"], "cast weights")
     assert_close(host(op.y), ref["y"], "Y")
     assert_close(host(op.dx), ref["dx"], "dX")
+    assert_close(host(op.dw), ref["dw"], "dW")
 
 
 def test_config3_resnet_conv_implicit_full_size():
