@@ -73,6 +73,25 @@ struct F16Traits
     }
 };
 
+// fp32 operands: a lane's 16 K-bytes are four floats of one row; the 32x32x2 instruction takes one float per
+// lane (rows lane%32, K index lane/32), so the four components feed four instructions.  Every instruction pairs
+// the same components of A and B, i.e. the same K indices: the K axis is merely visited in a different order.
+struct F32Traits
+{
+    typedef float  acc_t;
+    typedef v16f32 accv_t;
+    static constexpr int kElemBytes = 4;
+    __device__ static __forceinline__ accv_t mfma(const v4i32& a, const v4i32& b, const accv_t& c)
+    {
+        typedef float v4f32 __attribute__((ext_vector_type(4)));
+        const v4f32 fa = __builtin_bit_cast(v4f32, a), fb = __builtin_bit_cast(v4f32, b);
+        accv_t      r  = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.x, fb.x, c, 0, 0, 0);
+        r              = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.y, fb.y, r, 0, 0, 0);
+        r              = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.z, fb.z, r, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(fa.w, fb.w, r, 0, 0, 0);
+    }
+};
+
 struct GemmKernelArgs
 {
     const uint8_t* A;
@@ -699,8 +718,11 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
         return forced;
     }
     GemmPlan plan{1, 1, 0};
-    if(prec == 32 || M <= 0 || N <= 0) return plan;
-    const int64_t kb     = K * (prec == 8 ? 1 : 2);
+    if(M <= 0 || N <= 0) return plan;
+    const int64_t kb     = K * (prec == 8 ? 1 : (prec == 16 ? 2 : 4));
+    if(prec == 32 && kb % 16 != 0) return plan;                   // the any-shape fp32 kernel: no tiles to plan
+    // a K tile of fp32 operands takes the matrix cores eight times as long as one of int8 or binary16 operands
+    const double  kwork  = prec == 32 ? 8.0 : 1.0;
     const int64_t ktiles = (kb + kRowBytes - 1) / kRowBytes;
     auto ntiles = [&](int t) { return ((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn); };
     // Plan = (tile, K splits) with the smallest estimated time.  The estimate is a small model
@@ -718,7 +740,7 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
         const double     share = per < m.occ ? per : m.occ;                              // co-resident ones
         const double     rate  = m.rate1 * share < m.rate_max ? m.rate1 * share : m.rate_max;
         const double     kt    = std::ceil(static_cast<double>(ktiles) / static_cast<double>(s));
-        const double     mop   = 2.0 * kTiles[t].bm * kTiles[t].bn * kRowBytes * 1e-6;   // per K tile (int8 ops)
+        const double     mop   = 2.0 * kTiles[t].bm * kTiles[t].bn * kRowBytes * 1e-6 * kwork;   // per K tile (int8 ops)
         double           us    = per * kt * mop / rate + m.ovh * std::ceil(per / m.occ);
         if(s > 1) us += 3.0 + static_cast<double>(s + 1) * static_cast<double>(M) * static_cast<double>(N) * 4.0 / 5e6;
         return us;
@@ -751,8 +773,12 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
 hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream)
 {
     if(p.M <= 0 || p.N <= 0) return hipSuccess;
-    if(p.prec == 32) return (p.conv_H > 0 || p.b_remap_C > 0) ? hipErrorInvalidValue : launch_gemm_f32(p, stream);
-    const int      esz = p.prec == 8 ? 1 : 2;
+    if(p.prec == 32 && (p.conv_H > 0 || p.b_remap_C > 0)) return hipErrorInvalidValue;
+    // fp32 on the matrix cores needs 16-byte aligned, 16-byte multiple operand rows; anything else takes the
+    // any-shape kernel
+    if(p.prec == 32 && ((p.K * 4) % 16 != 0 || ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) != 0))
+        return launch_gemm_f32(p, stream);
+    const int      esz = p.prec == 8 ? 1 : (p.prec == 16 ? 2 : 4);
     GemmKernelArgs a;
     a.A = static_cast<const uint8_t*>(p.A);
     a.B = static_cast<const uint8_t*>(p.B);
@@ -785,8 +811,9 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     const TileShape ts = kTiles[plan.tile];
     a.tiles_m = static_cast<int>((p.M + ts.bm - 1) / ts.bm);
     a.tiles_n = static_cast<int>((p.N + ts.bn - 1) / ts.bn);
-    hipError_t e = p.prec == 8 ? launch_traits<I8Traits>(plan.tile, a, splits, stream)
-                               : launch_traits<F16Traits>(plan.tile, a, splits, stream);
+    hipError_t e = p.prec == 8    ? launch_traits<I8Traits>(plan.tile, a, splits, stream)
+                   : p.prec == 16 ? launch_traits<F16Traits>(plan.tile, a, splits, stream)
+                                  : launch_traits<F32Traits>(plan.tile, a, splits, stream);
     if(e != hipSuccess || splits == 1) return e;
     const bool vec4 = p.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(p.C)) & 15) == 0;
     int64_t    nb   = (p.M * p.N / (vec4 ? 4 : 1) + kThreads - 1) / kThreads;

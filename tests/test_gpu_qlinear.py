@@ -75,14 +75,14 @@ def test_ragged_shapes_span_tiles_and_tails(tag, shape):
 
 
 @pytest.mark.parametrize("tile", [0, 1, 2])
-@pytest.mark.parametrize("tag", [Q.INT8, Q.FP16])
+@pytest.mark.parametrize("tag", [Q.INT8, Q.FP16, Q.FP32])
 def test_every_gemm_tile_shape_on_ragged_operators(tile, tag):
     """The planner picks small tiles for small outputs; pin each tile shape in turn (with the K splits the planner
     then chooses for it) so that the 256x256 and 128x128 kernels also see ragged M, N and K tails."""
     Q.qsync_debug_set_gemm_tile(tile)
     try:
         for (m, n, k) in [(208, 144, 272), (528, 272, 400), (16, 16, 2064), (1040, 784, 528), (48, 2064, 64)]:
-            case = wl.ragged_case(m, n, k, seed=m + n + k + tile, dtype=np.float16)
+            case = wl.ragged_case(m, n, k, seed=m + n + k + tile, dtype=np.float16 if tag != Q.FP32 else np.float32)
             run_case(case, tag, y_dtype=np.float16 if tag == Q.FP16 else np.float32)
     finally:
         Q.qsync_debug_set_gemm_tile(-1)
@@ -116,6 +116,20 @@ def test_fp32_tag_equals_plain_matmul():
     op.forward(dev(case.x), dev(case.w))
     want = orc.naive_matmul_nt_f32(case.x, case.w) + case.bias
     np.testing.assert_allclose(host(op.y), want, rtol=2e-6, atol=2e-6)
+
+
+def test_fp32_tag_on_the_matrix_cores_stays_fp32_accurate():
+    """Rows that are 16-byte multiples run the fp32 matrix instructions (the K axis is summed in another order
+    than the textbook loop): the result must stay within fp32 rounding of the naive fp32 product."""
+    case = wl.ragged_case(96, 80, 256, seed=8)
+    say("fp32 on matrix cores")
+    op = QLinear(Q.FP32, 96, 80, 256, x_dtype=torch.float32, y_dtype=torch.float32, dx_dtype=torch.float32)
+    op.bias.copy_(dev(case.bias))
+    op.forward(dev(case.x), dev(case.w))
+    want = orc.naive_matmul_nt_f32(case.x, case.w) + case.bias
+    np.testing.assert_allclose(host(op.y), want, rtol=1e-5, atol=1e-5)
+    exact = case.x.astype(np.float64) @ case.w.astype(np.float64).T + case.bias
+    np.testing.assert_allclose(host(op.y), exact, rtol=1e-5, atol=1e-5)
 
 
 def test_fp32_tag_any_shape_forward_and_backward():
