@@ -220,6 +220,19 @@ __device__ __forceinline__ void fill_dma_imms(int (&imm)[DPW], std::integer_sequ
 
 __device__ __forceinline__ int swizzle(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) << 4; }
 
+// One 16-byte LDS read per fragment of a set, as explicit instructions (the waits are placed by hand in the
+// K loop): fragment I lies I * 32 rows further, which fits the instruction's immediate offset.
+template <int I>
+__device__ __forceinline__ void frag_read(v4i32& dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(I * 32 * kRowBytes) : "memory");
+}
+template <int F, int... Is>
+__device__ __forceinline__ void frag_reads(v4i32 (&dst)[F], uint32_t addr, std::integer_sequence<int, Is...>)
+{
+    (frag_read<Is>(dst[Is], addr), ...);
+}
+
 template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT, bool CONV = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKernelArgs p)
 {
@@ -341,9 +354,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         else
             dma_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, sb, voff, lbase);
     };
-    // Waits for this wavefront's direct loads, zero-fills its out-of-K chunks, then joins the block.
+    // Waits for this wavefront's direct loads and for its outstanding fragment reads (the barrier hands the
+    // stage they read to the next direct load, and the compiler does not see those reads), zero-fills its
+    // out-of-K chunks, then joins the block.
     auto land = [&](int stage, int kt) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);                       // vmcnt(0)
+        __builtin_amdgcn_s_waitcnt(0x0070);                       // vmcnt(0), lgkmcnt(0)
         if(kt == tail_kt)
         {
             const int64_t kb = static_cast<int64_t>(kt) * kRowBytes;
@@ -372,32 +387,46 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     for(int ks = 0; ks < 4; ++ks) roff[ks] = frag_row * kRowBytes + swizzle(frag_row, ks * 2 + khalf);
     const int a_base = (wm * WTM) * kRowBytes, b_base = BM * kRowBytes + (wn * WTN) * kRowBytes;
 
-    v4i32 af[2][FM], bf[2][FN];
-    auto  load_frags = [&](int buf, const uint8_t* st, int ks) {
-#pragma unroll
-        for(int i = 0; i < FM; ++i)
-            af[buf][i] = *reinterpret_cast<const v4i32*>(st + a_base + i * 32 * kRowBytes + roff[ks]);
-#pragma unroll
-        for(int j = 0; j < FN; ++j)
-            bf[buf][j] = *reinterpret_cast<const v4i32*>(st + b_base + j * 32 * kRowBytes + roff[ks]);
+    // The fragment reads are written as instructions with hand-placed waits.  The compiler's own wait
+    // insertion treats a direct global->LDS load as an access that may return through either counter, and
+    // while one is in flight (always, here) every wait it places on an LDS read becomes "all LDS reads
+    // done", including the reads just issued for a later chunk: the wavefront would then sit out a full LDS
+    // latency twice per K tile.  LDS reads of a wavefront return in order, so "at most FM + FN outstanding"
+    // is exactly "the older of two fragment sets has arrived".
+    v4i32          af[2][FM], bf[2][FN];
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t*)lds));
+    auto           load_frags = [&](auto buf_tag, int stage, int ks) {
+        constexpr int  buf = decltype(buf_tag)::value;
+        const uint32_t fa  = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + a_base + roff[ks]);
+        const uint32_t fb  = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + b_base + roff[ks]);
+        frag_reads<FM>(af[buf], fa, std::make_integer_sequence<int, FM>{});
+        frag_reads<FN>(bf[buf], fb, std::make_integer_sequence<int, FN>{});
     };
-    auto mma = [&](int buf) {
-        __builtin_amdgcn_sched_barrier(0);           // fences: keep the compiler from re-sinking the reads
+    constexpr int kWaitOlderSet = 0xC07F | ((FM + FN) << 8);      // lgkmcnt(FM + FN), other counters untouched
+    constexpr int kWaitAllLds   = 0xC07F;                         // lgkmcnt(0)
+    static_assert(FM + FN <= 15, "the LDS counter holds 15");
+    auto mma = [&](auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
+        __builtin_amdgcn_sched_barrier(0);           // fences: the matrix instructions stay behind the wait in front of them
 #pragma unroll
         for(int i = 0; i < FM; ++i)
 #pragma unroll
             for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(bf[buf][j], af[buf][i], acc[i][j]);
         __builtin_amdgcn_sched_barrier(0);
     };
+    const std::integral_constant<int, 0> set0{};
+    const std::integral_constant<int, 1> set1{};
 
     // K pipeline.  A tile has four 32-byte K chunks whose fragments alternate between two
     // register sets: the reads for chunk ks+2 are issued right behind the matrix instructions of
     // chunk ks (into the set those instructions have just consumed), so they complete while
-    // chunk ks+1 keeps the matrix cores busy.  At the tile boundary the wavefront (1) issues
-    // chunk 2, (2) joins the barrier that publishes the next stage, (3) issues chunk 3, whose
-    // operands are already in registers, and only then (4) requests the direct load of the tile
-    // after next into the stage just drained and reads the first two chunks of the next tile:
-    // barrier release and LDS latency hide behind chunk 3.
+    // chunk ks+1 keeps the matrix cores busy, and every wait in front of a chunk leaves the
+    // younger set's reads in flight.  At the tile boundary the wavefront (1) joins the barrier
+    // that publishes the next stage (every wavefront's reads of the current stage have returned
+    // by then: the barrier's fence waits for them), (2) requests the direct load of the tile
+    // after next into the stage just drained, (3) reads chunk 0 of the next tile, (4) issues
+    // chunk 3, whose operands are already in registers, and (5) reads chunk 1 of the next tile:
+    // barrier release, LDS latency and a whole K tile of memory latency hide behind matrix work.
     // Per-column epilogue parameters of this tile (alpha * column scale, column bias) are parked
     // in LDS behind the stages while the first direct loads are in flight; the epilogue reads them
     // back with a few 16-byte LDS reads instead of waiting on global memory.
@@ -423,28 +452,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     {
         land(0, kt_begin);
         if(kt_begin + 1 < kt_end) dma(1, kt_begin + 1);
-        load_frags(0, lds, 0);
-        load_frags(1, lds, 1);
+        load_frags(set0, 0, 0);
+        load_frags(set1, 0, 1);
         for(int kt = kt_begin; kt < kt_end; ++kt)
         {
-            const int      stage = (kt - kt_begin) & 1;
-            const bool     more  = kt + 1 < kt_end;
-            const uint8_t* st    = lds + stage * STAGE_BYTES;
-            mma(0);
-            load_frags(0, st, 2);
-            mma(1);
-            load_frags(1, st, 3);
-            mma(0);
-            if(more) land(stage ^ 1, kt + 1);
-            mma(1);
+            const int  stage = (kt - kt_begin) & 1;
+            const bool more  = kt + 1 < kt_end;
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set0);
+            load_frags(set0, stage, 2);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set1);
+            load_frags(set1, stage, 3);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set0);
             if(more)
             {
+                land(stage ^ 1, kt + 1);
                 if(kt + 2 < kt_end) dma(stage, kt + 2);
-                const uint8_t* nst = lds + (stage ^ 1) * STAGE_BYTES;
-                load_frags(0, nst, 0);
-                load_frags(1, nst, 1);
             }
+            // without a next tile the reads below fetch chunks 0 and 1 of the current stage again: in bounds, unused
+            const int nstage = more ? (stage ^ 1) : stage;
+            load_frags(set0, nstage, 0);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set1);
+            load_frags(set1, nstage, 1);
         }
+        __builtin_amdgcn_s_waitcnt(kWaitAllLds);     // the unused reads of the last trip land before the registers are reused
     }
 
     // ---- epilogue.  The B fragment is the matrix instruction's first operand, so a lane holds
