@@ -404,6 +404,39 @@ def main():
             dequant_iso[mode] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
         del dsets
 
+    # Extra: the forward GEMM collecting max |Y| in its epilogue, against the pass over Y that a directly chained
+    # consumer would otherwise need (forward GEMM + absmax of Y  vs  forward GEMM with the maximum + two divisions).
+    epilogue_max = None
+    if not args.no_extra_passes and tag == Q.INT8:
+        lin_ops = [o for o in ops_objs if hasattr(o, "gemm_bwd_part")]
+        if lin_ops:
+            o = lin_ops[0]
+            am = torch.zeros(1, dtype=torch.float32, device="cuda")
+            s_, i_, a_ = (torch.empty(1, dtype=torch.float32, device="cuda") for _ in range(3))
+            wsa = torch.zeros(max(256, Q.qsync_absmax_workspace_bytes(o.M, o.N, Q.PER_TENSOR)), dtype=torch.uint8, device="cuda")
+
+            def separate():
+                Q.qsync_qlinear_fwd(o.tag, o.M, o.N, o.K, o.xq, o.sx, o.wq, o.sw, o.w_gran, o.bias, o.y, None, o.ws_fwd, main)
+                Q.qsync_absmax_scale(o.y, o.M, o.N, o.N, Q.PER_TENSOR, 8, s_, i_, a_, None, wsa, main)
+
+            def fused():
+                Q.qsync_qlinear_fwd_amax(o.tag, o.M, o.N, o.K, o.xq, o.sx, o.wq, o.sw, o.w_gran, o.bias, o.y, None, am,
+                                         o.ws_fwd, main)
+                Q.qsync_scale_from_amax(am, 8, s_, i_, True, main)
+
+            res = {}
+            for name, fn in (("gemm_then_absmax_us", separate), ("gemm_with_maximum_then_scale_us", fused)):
+                for _ in range(3):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(main)
+                for _ in range(20):
+                    fn()
+                e1.record(main)
+                torch.cuda.synchronize()
+                res[name] = round(e0.elapsed_time(e1) / 20 * 1e3, 1)
+            epilogue_max = {"operator": "%dx%d->%d, Y %s" % (o.M, o.K, o.N, str(o.y.dtype).replace("torch.", "")), **res}
+
     # Extra (outside the timed region): a fully instrumented pass for the per-phase breakdown.
     per_step = {"gemm_fwd": fwd_ms}
     if not args.no_extra_passes:
@@ -457,6 +490,7 @@ def main():
         "operators_on_separate_streams": overlapped,
         "hip_graph_replay": graph_replay,
         "model_order_dw_on_side_stream": model_order,
+        "epilogue_maximum": epilogue_max,
     }
     if "gemm_bwd" in per_step:
         out["gemm_only_TOPS"] = round(gemm_ops / ((per_step["gemm_fwd"] + per_step["gemm_bwd"]) * 1e-3) / 1e12, 2)

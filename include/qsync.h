@@ -166,6 +166,34 @@ int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qsync_qlinear_fwd_amax - qsync_qlinear_fwd that also collects max |Y| in its epilogue, so that an
+ * operator fed directly by Y can skip its own minimum/maximum pass.  Paper: the Backend section counts the
+ * collection of the minimum/maximum as part of the casting cost ("Minimum and Maximum Optimization");
+ * the Cost Mapper's cvt_cost of the consumer shrinks by that pass.
+ *
+ * y_amax  device float, read and written: on return of the kernel it holds max(previous value, max |Y|),
+ *         where Y is taken as stored (after rounding to ydt).  Set it to 0 before the first collection
+ *         (qsync_scale_from_amax with consume != 0 leaves it at 0).  4-byte aligned.  NaN outputs are not
+ *         ordered; finite outputs are assumed.
+ * The maximum is taken where the output is written: in the GEMM's epilogue, or in the reduction pass when K is split.
+ * All other arguments and errors as qsync_qlinear_fwd (same workspace).
+ */
+int qsync_qlinear_fwd_amax(int tag, int64_t M, int64_t N, int64_t K,
+                           const void* xq, const float* sx,
+                           const void* wq, const float* sw, int wgran,
+                           const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
+                           float* y_amax, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * qsync_scale_from_amax - scale = amax / qmax, inv_scale = qmax / amax (1 and 1 for amax == 0) from a
+ * maximum already on the device, with the arithmetic of qsync_absmax_scale (PER_TENSOR); qmax = 2^(bits-1) - 1.
+ * amax       device float (read; set to 0 afterwards if consume != 0).
+ * scale, inv_scale  device floats, out.
+ * bits       2..8, otherwise QSYNC_ERR_UNSUPPORTED.
+ */
+int qsync_scale_from_amax(float* amax, int bits, float* scale, float* inv_scale, int consume, void* stream);
+
+/*
  * qsync_qlinear_bwd - both backward GEMMs of a linear operator, plus the bias gradient.
  * Paper: Appendix proof of Prop. 1 ((dW, dX) = G[dY, C(v, x)]); Backend section (dW is
  * produced in FP32, dX in FP16, dequantization fused in the epilogue).

@@ -131,9 +131,9 @@ size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t 
          + round256(colsum_workspace_bytes(M, N));
 }
 
-int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
-                      const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
-                      void* workspace, size_t workspace_bytes, void* stream)
+static int qlinear_fwd_impl(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
+                            const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
+                            float* y_amax_opt, void* workspace, size_t workspace_bytes, void* stream)
 {
     if(!xq || !wq || !y) return QSYNC_ERR_NULL;
     if(!is_tag(tag) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
@@ -167,7 +167,34 @@ int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K, const void* xq, 
         p.acc_dump = acc_dump_opt;
     }
     p.col_bias = bias_opt;
+    p.out_amax_bits = reinterpret_cast<unsigned int*>(y_amax_opt);
     return hip_status(launch_gemm(p, plan, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
+                      const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    return qlinear_fwd_impl(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, ydt, acc_dump_opt, nullptr, workspace,
+                            workspace_bytes, stream);
+}
+
+int qsync_qlinear_fwd_amax(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
+                           const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
+                           float* y_amax, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if(!y_amax) return QSYNC_ERR_NULL;
+    if((reinterpret_cast<uintptr_t>(y_amax) & 3u) != 0) return QSYNC_ERR_ALIGN;
+    return qlinear_fwd_impl(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, ydt, acc_dump_opt, y_amax, workspace,
+                            workspace_bytes, stream);
+}
+
+int qsync_scale_from_amax(float* amax, int bits, float* scale, float* inv_scale, int consume, void* stream)
+{
+    if(!amax || !scale || !inv_scale) return QSYNC_ERR_NULL;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    return hip_status(launch_scale_from_amax(amax, qmax, scale, inv_scale, consume != 0, static_cast<hipStream_t>(stream)));
 }
 
 int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq, const void* dyqT, const float* sdy,

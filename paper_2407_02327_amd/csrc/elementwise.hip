@@ -232,6 +232,16 @@ __global__ __launch_bounds__(kBlock) void absmax_tensor_finalize_kernel(const fl
     if(threadIdx.x == 0) write_scale(m, qmax, scale, inv_scale, amax_opt, 0);
 }
 
+// Scale and inverse scale from a maximum some other kernel has collected (a GEMM epilogue); `consume` clears the
+// word for the next collection.
+__global__ void scale_from_amax_kernel(float* amax, float qmax, float* scale, float* inv_scale, int consume)
+{
+    if(threadIdx.x != 0 || blockIdx.x != 0) return;
+    const float m = __hip_atomic_load(amax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    write_scale(m, qmax, scale, inv_scale, nullptr, 0);
+    if(consume) *amax = 0.0f;
+}
+
 // ------------------------------------------------------------------ absmax, per row
 // WPR wavefronts per row (1 when there are many rows, 4 = the whole block when there are few),
 // four 16-byte loads in flight per lane; no second stage.
@@ -1296,6 +1306,12 @@ static hipError_t absmax_typed(const T* x, int64_t rows, int64_t cols, int64_t l
                                            reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes), nullptr,
                                            none, st);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_from_amax(float* amax, float qmax, float* scale, float* inv_scale, int consume, hipStream_t st)
+{
+    scale_from_amax_kernel<<<dim3(1), dim3(64), 0, st>>>(amax, qmax, scale, inv_scale, consume);
     return hipGetLastError();
 }
 

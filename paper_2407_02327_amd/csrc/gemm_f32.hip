@@ -16,7 +16,8 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const float* __restric
                                                           int64_t M, int64_t N, int64_t K, void* C, int c_is_f16,
                                                           const float* s0, const float* s1,
                                                           const float* __restrict__ col_scale,
-                                                          const float* __restrict__ col_bias, int64_t tiles_n)
+                                                          const float* __restrict__ col_bias, int64_t tiles_n,
+                                                          unsigned int* amax_bits)
 {
     __shared__ float As[kBK][kT + 1];
     __shared__ float Bs[kBK][kT + 1];
@@ -50,6 +51,8 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const float* __restric
         }
         __syncthreads();
     }
+    unsigned int run = 0u;     // maximum of |C| as stored, as fp32 bits
+    const unsigned int seen = amax_bits ? __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     float alpha = 1.0f;
     if(s0) alpha *= *s0;
     if(s1) alpha *= *s1;
@@ -65,11 +68,30 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const float* __restric
             if(col >= N) continue;
             const float f = alpha * (col_scale ? col_scale[col] : 1.0f);
             const float y = acc[i][j] * f + (col_bias ? col_bias[col] : 0.0f);
+            float stored = y;
             if(c_is_f16)
-                static_cast<__half*>(C)[row * N + col] = __float2half_rn(y);
+            {
+                const __half h = __float2half_rn(y);
+                static_cast<__half*>(C)[row * N + col] = h;
+                stored = __half2float(h);
+            }
             else
                 static_cast<float*>(C)[row * N + col] = y;
+            const unsigned int u = __float_as_uint(stored) & 0x7FFFFFFFu;
+            run = run > u ? run : u;
         }
+    }
+    if(amax_bits)
+    {   // one atomic maximum per workgroup (As is free: the K loop ended with a barrier)
+        unsigned int* slots = reinterpret_cast<unsigned int*>(&As[0][0]);
+        slots[tid] = run;
+        __syncthreads();
+        for(int w = 128; w >= 1; w >>= 1)
+        {
+            if(tid < w) slots[tid] = slots[tid] > slots[tid + w] ? slots[tid] : slots[tid + w];
+            __syncthreads();
+        }
+        if(tid == 0 && slots[0] > seen) atomicMax(amax_bits, slots[0]);      // `seen` may be stale, never too large
     }
 }
 
@@ -80,7 +102,7 @@ hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t stream)
     const int64_t tiles_m = (p.M + kT - 1) / kT, tiles_n = (p.N + kT - 1) / kT;
     gemm_f32_nt_kernel<<<dim3(static_cast<unsigned>(tiles_m * tiles_n)), dim3(256), 0, stream>>>(
         static_cast<const float*>(p.A), static_cast<const float*>(p.B), p.M, p.N, p.K, p.C, p.c_dtype == kF16, p.s0,
-        p.s1, p.col_scale, p.col_bias, tiles_n);
+        p.s1, p.col_scale, p.col_bias, tiles_n, p.out_amax_bits);
     return hipGetLastError();
 }
 

@@ -112,6 +112,9 @@ struct GemmKernelArgs
     // B rows remapped (weight gradient of a 3x3 convolution): logical row (tap, c) = tap*remap_C + c is physical
     // row (tap%3)*remap_C + c of B, read with its K axis displaced by (tap/3 - 1)*remap_shift bytes
     int            remap_C, remap_shift;
+    // optional: running maximum of |C| as stored (bit pattern of a non-negative fp32), raised with one atomic
+    // maximum per workgroup
+    unsigned int*  amax_bits;
 };
 
 // Work item (K split, tile) of a workgroup.  Workgroups are dealt round-robin to the eight XCDs
@@ -219,6 +222,33 @@ __device__ __forceinline__ void fill_dma_imms(int (&imm)[DPW], std::integer_sequ
 }
 
 __device__ __forceinline__ int swizzle(int row, int chunk) { return (chunk ^ ((row >> 1) & 7)) << 4; }
+
+// Maximum magnitude of the 16 output bytes in `v`, folded into `run`: binary16 magnitudes order like their bit
+// patterns without the sign (two per dword), fp32 magnitudes likewise (one per dword).
+typedef unsigned short gus2_t __attribute__((ext_vector_type(2)));
+template <int OS> __device__ __forceinline__ uint32_t fold_abs_bits(uint32_t run, const v4u32& v)
+{
+#pragma unroll
+    for(int k = 0; k < 4; ++k)
+    {
+        if(OS == 2)
+            run = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(gus2_t, run),
+                                                                         __builtin_bit_cast(gus2_t, v[k] & 0x7FFF7FFFu)));
+        else
+        {
+            const uint32_t u = v[k] & 0x7FFFFFFFu;
+            run = run > u ? run : u;
+        }
+    }
+    return run;
+}
+// the folded maximum as the bit pattern of an fp32
+template <int OS> __device__ __forceinline__ uint32_t abs_bits_as_f32(uint32_t run)
+{
+    if(OS == 4) return run;
+    const uint32_t h = (run & 0xFFFFu) > (run >> 16) ? (run & 0xFFFFu) : (run >> 16);
+    return __float_as_uint(__half2float(__ushort_as_half(static_cast<unsigned short>(h))));
+}
 
 // One 16-byte LDS read per fragment of a set, as explicit instructions (the waits are placed by hand in the
 // K loop): fragment I lies I * 32 rows further, which fits the instruction's immediate offset.
@@ -441,6 +471,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         cp_scale = alpha * ((p.col_scale && cok) ? p.col_scale[col] : 1.0f);
         cp_bias  = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
     }
+    const uint32_t amax_seen = (!SPLIT && p.amax_bits) ? __hip_atomic_load(p.amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     const bool any_k = kt_begin < kt_end;
     if(any_k) dma(0, kt_begin);
     if(!SPLIT && tid < BN)
@@ -492,6 +523,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // they are dequantized in registers first.
     constexpr int STG_BYTES = 2 * STAGE_BYTES / (WGM * WGN);
     uint8_t*      stg       = lds + wave * STG_BYTES;
+    uint32_t out_run = 0u;     // running maximum of |C| of this lane (packed like the output type)
+    // one atomic maximum per workgroup at most: lanes -> wavefront (shuffles) -> workgroup (LDS slots behind the
+    // column parameters).  Atomics on one word retire about 10 ns apart, so a workgroup skips its own when the
+    // word, as read at the start of the kernel (`amax_seen`: possibly stale, never too large), already covers it.
+    auto publish_amax = [&](uint32_t bits_f32) {
+#pragma unroll
+        for(int off = 32; off >= 1; off >>= 1)
+        {
+            const uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(bits_f32), off));
+            bits_f32 = bits_f32 > o ? bits_f32 : o;
+        }
+        uint32_t* slots = reinterpret_cast<uint32_t*>(colp + 2 * BN);
+        if(lane == 0) slots[wave] = bits_f32;
+        __syncthreads();
+        if(tid == 0)
+        {
+            uint32_t m = slots[0];
+#pragma unroll
+            for(int w = 1; w < WGM * WGN; ++w) m = m > slots[w] ? m : slots[w];
+            if(m > amax_seen) atomicMax(p.amax_bits, m);
+        }
+    };
     auto staged_store = [&](auto out_tag, auto raw_tag, uint8_t* dst_base) {
         typedef decltype(out_tag) out_t;
         constexpr bool RAW   = decltype(raw_tag)::value;
@@ -555,6 +608,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                 const int64_t col = wcol0 + seg * (16 / OS);
                 if(row < p.M && col < p.N)
                 {
+                    if constexpr(!RAW)
+                        if(p.amax_bits) out_run = fold_abs_bits<OS>(out_run, val);
                     v4u32* dst = reinterpret_cast<v4u32*>(dst_base + (row * p.N + col) * OS);
                     if constexpr(RAW)
                         *dst = val;      // read back soon by the reduction: ordinary store
@@ -609,22 +664,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                     if(row < p.M && cok)
                     {
                         const float y = static_cast<float>(acc[i][j][v]) * f + b;
+                        float       stored = y;
                         if(p.c_is_f16)
-                            static_cast<__half*>(p.C)[row * p.N + col] = __float2half_rn(y);
+                        {
+                            const __half h = __float2half_rn(y);
+                            static_cast<__half*>(p.C)[row * p.N + col] = h;
+                            stored = __half2float(h);
+                        }
                         else
                             static_cast<float*>(p.C)[row * p.N + col] = y;
+                        const uint32_t u = __float_as_uint(stored) & 0x7FFFFFFFu;
+                        out_run = out_run > u ? out_run : u;
                         if(sizeof(acc_t) == 4 && p.acc_dump)
                             p.acc_dump[row * p.N + col] = static_cast<int32_t>(acc[i][j][v]);
                     }
                 }
             }
+        if(p.amax_bits) publish_amax(out_run);
         return;
     }
 
     if(p.c_is_f16)
+    {
         staged_store(__half{}, std::false_type{}, static_cast<uint8_t*>(p.C));
+        if(p.amax_bits) publish_amax(abs_bits_as_f32<2>(out_run));
+    }
     else
+    {
         staged_store(float{}, std::false_type{}, static_cast<uint8_t*>(p.C));
+        if(p.amax_bits) publish_amax(abs_bits_as_f32<4>(out_run));
+    }
 }
 
 // Adds the split-K partials in split order and applies the epilogue.
@@ -635,9 +704,12 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
                                                                  int64_t M, int64_t N, void* C, int c_is_f16,
                                                                  const float* s0, const float* s1,
                                                                  const float* __restrict__ col_scale,
-                                                                 const float* __restrict__ col_bias, int32_t* acc_dump)
+                                                                 const float* __restrict__ col_bias, int32_t* acc_dump,
+                                                                 unsigned int* amax_bits)
 {
     constexpr int V      = VEC4 ? 4 : 1;       // VEC4: N % 4 == 0 and 16-byte aligned buffers
+    uint32_t      run    = 0u;                 // maximum of |C| as stored (fp32 bits), when amax_bits is given
+    const uint32_t seen  = amax_bits ? __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
     const int64_t n      = M * N;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * V;
     float         alpha  = 1.0f;
@@ -667,13 +739,27 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
             const float f = alpha * (col_scale ? col_scale[col + e] : 1.0f);
             y[e] = static_cast<float>(acc[e]) * f + (col_bias ? col_bias[col + e] : 0.0f);
         }
+        if(c_is_f16)
+        {   // what is stored is the rounded value: take the maximum of that
+#pragma unroll
+            for(int e = 0; e < V; ++e) y[e] = __half2float(__float2half_rn(y[e]));
+        }
+        if(amax_bits)
+        {
+#pragma unroll
+            for(int e = 0; e < V; ++e)
+            {
+                const uint32_t u = __float_as_uint(y[e]) & 0x7FFFFFFFu;
+                run = run > u ? run : u;
+            }
+        }
         if(VEC4)
         {
             if(c_is_f16)
             {
                 __half h[4];
 #pragma unroll
-                for(int e = 0; e < 4; ++e) h[e] = __float2half_rn(y[e]);
+                for(int e = 0; e < 4; ++e) h[e] = __float2half_rn(y[e]);      // exact: y is a binary16 value
                 *reinterpret_cast<uint2*>(static_cast<__half*>(C) + i) = *reinterpret_cast<const uint2*>(h);
             }
             else
@@ -686,6 +772,25 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
         if(acc_dump)
 #pragma unroll
             for(int e = 0; e < V; ++e) acc_dump[i + e] = static_cast<int32_t>(acc[e]);
+    }
+    if(amax_bits)
+    {   // one atomic maximum per workgroup
+        __shared__ uint32_t slots[kThreads / 64];
+#pragma unroll
+        for(int off = 32; off >= 1; off >>= 1)
+        {
+            const uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(run), off));
+            run = run > o ? run : o;
+        }
+        if(threadIdx.x % 64 == 0) slots[threadIdx.x / 64] = run;
+        __syncthreads();
+        if(threadIdx.x == 0)
+        {
+            uint32_t m = slots[0];
+#pragma unroll
+            for(int w = 1; w < kThreads / 64; ++w) m = m > slots[w] ? m : slots[w];
+            if(m > seen) atomicMax(amax_bits, m);      // `seen` may be stale but never too large: skipping is safe
+        }
     }
 }
 
@@ -700,7 +805,7 @@ constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 template <typename TR, int BM, int BN, int WGM, int WGN>
 hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
 {
-    constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float);
+    constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float) + 64;   // + amax slots
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
     const dim3       block(64 * WGM * WGN);
     static bool      attr_set[3] = {false, false, false};   // per instantiation; benign if set twice
@@ -823,6 +928,7 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.partial  = workspace;
     a.conv_H = a.conv_W = a.conv_Cb = 0;
     a.remap_C = a.remap_shift = 0;
+    a.amax_bits = plan.splits > 1 ? nullptr : p.out_amax_bits;      // with K splits the reduction pass takes the maximum
     if(p.b_remap_C > 0)
     {   // B is [3*remap_C, K] with a margin of |remap_shift| readable bytes in front of it and behind it
         if(p.conv_H > 0 || p.N != 9 * p.b_remap_C || p.b_remap_shift % 16 != 0 || p.b_remap_shift < 0
@@ -852,10 +958,12 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     const bool vec4 = p.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(p.C)) & 15) == 0;
     int64_t    nb   = (p.M * p.N / (vec4 ? 4 : 1) + kThreads - 1) / kThreads;
     nb              = nb > 65536 ? 65536 : nb;
+    if(p.out_amax_bits && nb > 1024) nb = 1024;    // at most one atomic per workgroup on one word: keep them few
     auto reduce = [&](auto acc_tag, auto vec_tag, const void* ws, int32_t* dump) {
         typedef decltype(acc_tag) acc_t;
         splitk_reduce_kernel<acc_t, decltype(vec_tag)::value><<<dim3(nb), dim3(kThreads), 0, stream>>>(
-            static_cast<const acc_t*>(ws), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale, p.col_bias, dump);
+            static_cast<const acc_t*>(ws), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale, p.col_bias, dump,
+            p.out_amax_bits);
     };
     if(p.prec == 8)
     {

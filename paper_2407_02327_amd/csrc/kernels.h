@@ -16,6 +16,7 @@ enum Round { kNearest = 0, kStochastic = 1, kFloor = 2 };
 constexpr int kAbsmaxMaxBlocks = 2048;  // per-tensor stage-1 partials
 constexpr int kColParts = 512;          // most stage-1 partials per column of a per-column reduction
 size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
+hipError_t launch_scale_from_amax(float* amax, float qmax, float* scale, float* inv_scale, int consume, hipStream_t st);
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran,
                                float qmax, float* scale, float* inv_scale, float* amax_opt,
                                float* colsum_opt /* per-tensor only: fused column sums */,
@@ -82,6 +83,9 @@ struct GemmProblem {
     // [3*b_remap_C, K] matrix, read with the K axis displaced by (tap/3 - 1)*b_remap_shift bytes (a multiple of
     // 16, at most 1024); that many bytes in front of and behind the matrix must be readable.
     int64_t     b_remap_C = 0, b_remap_shift = 0;
+    // optional device word holding a running maximum of |C| as stored (bit pattern of a non-negative fp32);
+    // raised by the epilogue (by the reduction pass when K is split)
+    unsigned int* out_amax_bits = nullptr;
 };
 
 struct GemmPlan {

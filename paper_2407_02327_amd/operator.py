@@ -37,8 +37,10 @@ class QLinear:
                  dy_dtype=None, y_dtype=torch.float32, dx_dtype=torch.float16, dw_dtype=torch.float32,
                  w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
                  bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda",
-                 bwd_tag: Optional[int] = None):
+                 bwd_tag: Optional[int] = None, collect_y_amax: bool = False):
         self.tag, self.M, self.N, self.K = tag, M, N, K
+        # max |Y| collected by the forward GEMM's epilogue, for a consumer that quantizes Y as it is
+        self.y_amax = torch.zeros(1, dtype=torch.float32, device=device) if collect_y_amax else None
         self.bwd_tag = tag if bwd_tag is None else bwd_tag
         if self.bwd_tag != tag and not (tag == Q.INT8 and self.bwd_tag == Q.FP16):
             raise ValueError("bwd_tag: only the FP16 backward of an INT8 forward differs from the forward tag")
@@ -81,11 +83,16 @@ class QLinear:
             self.dyh, self.dyhT = e(M, N, dt=h), e(N, M, dt=h)
 
     # ---- precision conversion -----------------------------------------------------------
-    def convert_x(self, x: torch.Tensor, stream=None) -> None:
+    def convert_x(self, x: torch.Tensor, stream=None, x_amax: Optional[torch.Tensor] = None) -> None:
+        """x_amax: device float holding max |x| already (the producer's `y_amax`); it replaces the pass over x
+        that finds the maximum and is left at zero for the producer's next step."""
         M, K = self.M, self.K
         if self.tag == Q.INT8:
-            Q.qsync_absmax_scale(x, M, K, K, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None, self.ws_absmax,
-                                 stream)
+            if x_amax is not None:
+                Q.qsync_scale_from_amax(x_amax, self.bits, self.sx, self.ix, True, stream)
+            else:
+                Q.qsync_absmax_scale(x, M, K, K, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None,
+                                     self.ws_absmax, stream)
             Q.qsync_quantize(x, M, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq,
                              self.xqT, stream)
         elif x.dtype == _TORCH_OF_TAG[self.tag] and x.is_contiguous():
@@ -159,6 +166,10 @@ class QLinear:
 
     # ---- GEMMs ---------------------------------------------------------------------------
     def gemm_fwd(self, stream=None) -> None:
+        if self.y_amax is not None:
+            Q.qsync_qlinear_fwd_amax(self.tag, self.M, self.N, self.K, self.xq, self.sx, self.wq, self.sw, self.w_gran,
+                                     self.bias, self.y, self.acc, self.y_amax, self.ws_fwd, stream)
+            return
         Q.qsync_qlinear_fwd(self.tag, self.M, self.N, self.K, self.xq, self.sx, self.wq, self.sw, self.w_gran,
                             self.bias, self.y, self.acc, self.ws_fwd, stream)
 
@@ -192,17 +203,18 @@ class QLinear:
                             self.ws_bwd, stream)
 
     # ---- whole passes ----------------------------------------------------------------------
-    def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None, side_stream=None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, w: torch.Tensor, stream=None, side_stream=None,
+                x_amax: Optional[torch.Tensor] = None) -> torch.Tensor:
         """With `side_stream` (a torch stream of default priority) the small, latency-bound weight
         conversion kernels run beside the HBM-bound activation conversion and join before the GEMM."""
         if side_stream is None:
-            self.convert_x(x, stream)
+            self.convert_x(x, stream, x_amax)
             self.convert_w(w, stream)
         else:
             main = stream if stream is not None else torch.cuda.current_stream()
             side_stream.wait_stream(main)
             self.convert_w(w, side_stream)
-            self.convert_x(x, main)
+            self.convert_x(x, main, x_amax)
             main.wait_stream(side_stream)
         self.gemm_fwd(stream)
         return self.y

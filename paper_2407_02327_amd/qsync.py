@@ -32,6 +32,8 @@ SIGNATURES = {
     "qsync_absmax_workspace_bytes": (_sz, [_i64, _i64, _i]),
     "qsync_quantize": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _i, _i, _u64, _u64, _vp, _vp, _vp, _vp]),
     "qsync_qlinear_fwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
+    "qsync_qlinear_fwd_amax": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
+    "qsync_scale_from_amax": (_i, [_vp, _i, _vp, _vp, _i, _vp]),
     "qsync_qlinear_bwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i,
                                _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
@@ -119,6 +121,18 @@ def qsync_qlinear_fwd(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump
     _check(lib.qsync_qlinear_fwd(tag, M, N, K, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
                                  _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _ptr(workspace), _bytes(workspace),
                                  _stream(stream)))
+
+
+def qsync_qlinear_fwd_amax(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt, y_amax, workspace,
+                           stream=None) -> None:
+    _check(lib.qsync_qlinear_fwd_amax(tag, M, N, K, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
+                                      _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _ptr(y_amax), _ptr(workspace),
+                                      _bytes(workspace), _stream(stream)))
+
+
+def qsync_scale_from_amax(amax, bits, scale, inv_scale, consume=True, stream=None) -> None:
+    _check(lib.qsync_scale_from_amax(_ptr(amax), bits, _ptr(scale), _ptr(inv_scale), 1 if consume else 0,
+                                     _stream(stream)))
 
 
 def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, dx_opt, dw_opt, db_opt, dy_float_opt,

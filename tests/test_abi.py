@@ -99,6 +99,24 @@ def test_qlinear_validation():
     assert call(M=64, N=576, K=200704) == qsync.ERR_WORKSPACE
     assert call(M=64, N=576, K=200704, ws=A, wsb=1024) == qsync.ERR_WORKSPACE
 
+
+def test_qlinear_fwd_amax_and_scale_from_amax_validation():
+    f = lib.qsync_qlinear_fwd_amax
+    #        tag M   N   K  xq sx wq sw wgran bias y ydt dump amax ws wsb st
+    assert f(8, 64, 64, 64, A, A, A, A, 0, None, A, 0, None, None, None, 0, None) == qsync.ERR_NULL     # no maximum word
+    assert f(8, 64, 64, 64, A, A, A, A, 0, None, A, 0, None, P(4098), None, 0, None) == qsync.ERR_ALIGN   # not 4-byte aligned
+    assert f(8, 64, 64, 64, None, A, A, A, 0, None, A, 0, None, A, None, 0, None) == qsync.ERR_NULL
+    assert f(4, 64, 64, 64, A, A, A, A, 0, None, A, 0, None, A, None, 0, None) == qsync.ERR_BAD_ENUM
+    assert f(8, 64, 64, 40, A, A, A, A, 0, None, A, 0, None, A, None, 0, None) == qsync.ERR_ALIGN
+    assert f(8, 0, 64, 64, A, A, A, A, 0, None, A, 0, None, A, None, 0, None) == qsync.OK
+    assert f(8, 64, 576, 200704, A, A, A, A, 0, None, A, 0, None, A, None, 0, None) == qsync.ERR_WORKSPACE   # split K
+    g = lib.qsync_scale_from_amax
+    assert g(None, 8, A, A, 1, None) == qsync.ERR_NULL
+    assert g(A, 8, None, A, 1, None) == qsync.ERR_NULL
+    assert g(A, 8, A, None, 0, None) == qsync.ERR_NULL
+    assert g(A, 1, A, A, 1, None) == qsync.ERR_UNSUPPORTED
+    assert g(A, 9, A, A, 1, None) == qsync.ERR_UNSUPPORTED
+
     g = lib.qsync_qlinear_bwd
     base = [8, 64, 64, 64, A, A, A, A, A, A, A, 0, A, 1, A, 0, None, None, 0, None, None, A, 1 << 24, None]
     assert g(*base) in (qsync.OK, qsync.ERR_HIP)

@@ -313,3 +313,86 @@ def test_conv_activation_quantized_once_then_expanded():
     assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "dW accumulators")
     assert_close(host(op.y), ref["y"], "Y")
     assert_close(host(op.dw), ref["dw"], "dW")
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tag,ydt", [(Q.INT8, torch.float16), (Q.INT8, torch.float32), (Q.FP16, torch.float16),
+                                     (Q.FP32, torch.float32)])
+def test_forward_epilogue_collects_the_output_maximum(tile, tag, ydt):
+    """qsync_qlinear_fwd_amax: same Y as qsync_qlinear_fwd bit for bit, and the collected word is max |Y| of the
+    stored values exactly (a maximum has no rounding); against the oracle's Y it holds to the output tolerance.
+    Shapes cover the 16-byte store path, the element-wise path (odd N), ragged tiles and split K (where the
+    reduction pass takes the maximum); the word accumulates."""
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        shapes = [(300, 264, 272), (257, 131, 144), (64, 128, 128), (192, 264, 4096), (96, 101, 4096)]   # the last two split K
+        if tag == Q.FP32:
+            shapes.append((130, 70, 50))          # rows that are not 16-byte multiples: the any-shape kernel
+        for (M, N, K) in shapes:
+            rng = np.random.default_rng(M * 7 + N)
+            x = rng.standard_normal((M, K)).astype(np.float32)
+            w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+            b = rng.standard_normal(N).astype(np.float32)
+            say("fwd_amax tile", tile, "tag", tag, "ydt", ydt, "MNK", M, N, K)
+            mk = lambda: QLinear(tag, M, N, K, x_dtype=torch.float32, y_dtype=ydt, w_gran=Q.PER_ROW)
+            plain, fused = mk(), QLinear(tag, M, N, K, x_dtype=torch.float32, y_dtype=ydt, w_gran=Q.PER_ROW,
+                                         collect_y_amax=True)
+            for op in (plain, fused):
+                op.bias.copy_(dev(b))
+                op.forward(dev(x), dev(w))
+            torch.cuda.synchronize()
+            assert torch.equal(plain.y, fused.y), "Y changes when the maximum is collected"
+            want = fused.y.float().abs().max().item()
+            assert fused.y_amax.item() == want, (fused.y_amax.item(), want)
+            ref = orc.operator_fwd_bwd(tag, x, w, b, np.zeros((M, N), np.float32), "row", "nearest", y_dtype=np.float64)
+            ref_amax = np.abs(ref["y"]).max()
+            assert abs(fused.y_amax.item() - ref_amax) <= 2e-3 * ref_amax
+            # the word is a running maximum: a larger value survives the next collection, then it is consumed
+            fused.y_amax.fill_(want * 4.0)
+            fused.gemm_fwd()
+            torch.cuda.synchronize()
+            assert fused.y_amax.item() == want * 4.0
+            s_, i_ = torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
+            fused.y_amax.fill_(want)
+            Q.qsync_scale_from_amax(fused.y_amax, 8, s_, i_, True)
+            s2, i2, a2 = torch.empty(1, device="cuda"), torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
+            yf = fused.y.float().contiguous()
+            ws = torch.zeros(max(256, Q.qsync_absmax_workspace_bytes(M, N, Q.PER_TENSOR)), dtype=torch.uint8, device="cuda")
+            Q.qsync_absmax_scale(yf, M, N, N, Q.PER_TENSOR, 8, s2, i2, a2, None, ws)
+            torch.cuda.synchronize()
+            assert fused.y_amax.item() == 0.0
+            assert_bits_equal(host(s_), host(s2), "scale from the collected maximum")
+            assert_bits_equal(host(i_), host(i2), "inverse scale from the collected maximum")
+            sref, iref = orc.scales_from_amax(np.asarray([want], np.float32), 8)
+            assert_bits_equal(host(s_), sref, "scale vs oracle arithmetic")
+            assert_bits_equal(host(i_), iref, "inverse scale vs oracle arithmetic")
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
+
+
+def test_chained_operator_takes_its_scale_from_the_producers_epilogue():
+    """Two linears back to back (no nonlinearity in between, as after every odd layer of config 4): the consumer
+    quantizes the producer's Y with the maximum the producer's epilogue collected.  Its codes, scales and
+    accumulators equal those of a consumer that finds the maximum itself, and the oracle's on the same Y."""
+    rng = np.random.default_rng(5)
+    M, K0, N0, N1 = 1000, 256, 528, 264
+    x = rng.standard_normal((M, K0)).astype(np.float32)
+    w0 = (rng.standard_normal((N0, K0)) * 0.05).astype(np.float32)
+    w1 = (rng.standard_normal((N1, N0)) * 0.05).astype(np.float32)
+    prod = QLinear(Q.INT8, M, N0, K0, x_dtype=torch.float32, y_dtype=torch.float16, collect_y_amax=True, bias=False)
+    cons = QLinear(Q.INT8, M, N1, N0, x_dtype=torch.float16, y_dtype=torch.float32, dump_acc=True, bias=False)
+    base = QLinear(Q.INT8, M, N1, N0, x_dtype=torch.float16, y_dtype=torch.float32, dump_acc=True, bias=False)
+    for step in range(2):            # twice: the consumed maximum starts the next step at zero
+        y0 = prod.forward(dev(x), dev(w0))
+        cons.forward(y0, dev(w1), x_amax=prod.y_amax)
+        base.forward(y0, dev(w1))
+        torch.cuda.synchronize()
+        assert prod.y_amax.item() == 0.0
+        for name in ("sx", "ix", "xq", "xqT", "acc", "y"):
+            assert torch.equal(getattr(cons, name), getattr(base, name)), (step, name)
+    ref = orc.operator_fwd_bwd(Q.INT8, host(y0), w1, None, np.zeros((M, N1), np.float32), "row", "nearest",
+                               y_dtype=np.float64)
+    assert_bits_equal(host(cons.sx), ref["sx"], "sx")
+    assert_bits_equal(host(cons.xq), ref["xq"], "xq")
+    assert_bits_equal(host(cons.acc), ref["acc"], "accumulators")
+    assert_close(host(cons.y), ref["y"], "Y")
