@@ -137,6 +137,28 @@ int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t l
                    void* q_opt, void* qT_opt, void* stream);
 
 /*
+ * qsync_absmax_quantize - qsync_absmax_scale (PER_TENSOR) followed by qsync_quantize (tag INT8, PER_TENSOR) on a
+ * packed tensor (ld == cols), with identical results, in one launch where that pays: for a small tensor (up to
+ * 4M elements, 1M with stochastic rounding) that meets the vector path's rules (cols % 8 == 0, 16-byte aligned x
+ * and outputs, rows % 16 == 0 with a transposed copy) every workgroup finds the maximum of its share, they meet
+ * once, and each quantizes the part it has just read; other tensors take the two launches.  Paper: Backend section, "Minimum and Maximum
+ * Optimization" (the collection of the maximum is the casting cost the paper trims); Cost Mapper, cvt_cost.
+ *
+ * scale, inv_scale, amax_opt, q_opt, qT_opt, bits, rnd, philox_seed, philox_offset: as in the two calls.
+ * workspace   at least qsync_absmax_quantize_workspace_bytes(rows, cols) bytes, 16-byte aligned; its first 4 bytes
+ *             must be zero before the first use and are zero again after every call (the same rule, and the same
+ *             buffer if wanted, as qsync_absmax_scale).  Calls that overlap in time need separate workspaces.
+ * poll_limit  how many times a workgroup polls for the others before it finds the maximum by reading the whole
+ *             tensor itself (same result; this bounds every wait, so the call cannot hang when its workgroups
+ *             are not all resident at once, e.g. beside another stream's kernel).  < 0: library default.
+ */
+int qsync_absmax_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int bits, int rnd,
+                          uint64_t philox_seed, uint64_t philox_offset,
+                          float* scale, float* inv_scale, float* amax_opt, void* q_opt, void* qT_opt,
+                          void* workspace, size_t workspace_bytes, int poll_limit, void* stream);
+size_t qsync_absmax_quantize_workspace_bytes(int64_t rows, int64_t cols);
+
+/*
  * qsync_qlinear_fwd - forward GEMM with the dequantizer and bias fused into the epilogue.
  * Paper: proof of Prop. 2 (y = q_v q_w sum(v_q w_q) + b), Backend section "Dequantization
  * Fusion" (int32 accumulation, INT32 -> FP32 conversion with the scale in the epilogue),

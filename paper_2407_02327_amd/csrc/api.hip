@@ -118,6 +118,30 @@ int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t l
     return hip_status(launch_convert(x, xdt, rows, cols, ld, tag == QSYNC_FP16 ? kF16 : kF32, q_opt, qT_opt, st));
 }
 
+size_t qsync_absmax_quantize_workspace_bytes(int64_t rows, int64_t cols)
+{
+    return qsync_absmax_workspace_bytes(rows, cols, QSYNC_PER_TENSOR);
+}
+
+int qsync_absmax_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int bits, int rnd, uint64_t philox_seed,
+                          uint64_t philox_offset, float* scale, float* inv_scale, float* amax_opt, void* q_opt,
+                          void* qT_opt, void* workspace, size_t workspace_bytes, int poll_limit, void* stream)
+{
+    if(!x || !scale || !inv_scale || (!q_opt && !qT_opt)) return QSYNC_ERR_NULL;
+    if(!is_float_dtype(xdt) || !is_round(rnd)) return QSYNC_ERR_BAD_ENUM;
+    if(!count_ok(rows, cols)) return QSYNC_ERR_BAD_SHAPE;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    if(rows == 0 || cols == 0) return QSYNC_OK;
+    const size_t need = qsync_absmax_quantize_workspace_bytes(rows, cols);
+    if(!workspace || workspace_bytes < need) return QSYNC_ERR_WORKSPACE;
+    if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
+    const int          qmax  = (1 << (bits - 1)) - 1;
+    const unsigned int polls = poll_limit < 0 ? (1u << 14) : static_cast<unsigned int>(poll_limit);
+    return hip_status(launch_absmax_quantize(x, xdt, rows, cols, qmax, rnd, philox_seed, philox_offset, scale, inv_scale,
+                                             amax_opt, static_cast<int8_t*>(q_opt), static_cast<int8_t*>(qT_opt),
+                                             workspace, polls, static_cast<hipStream_t>(stream)));
+}
+
 size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K)
 {
     if(!is_tag(tag) || M < 0 || N < 0 || K < 0) return 0;

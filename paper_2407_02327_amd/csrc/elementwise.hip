@@ -568,14 +568,14 @@ __global__ __launch_bounds__(kBlock) void absmax_rowcol_kernel(const T* __restri
 
 __device__ __forceinline__ uint32_t byte_of(uint32_t w, int b) { return (w >> (8 * b)) & 0xFFu; }
 
-template <typename T, int RND, bool PERCOL, int PR, bool DUAL = false>
-__global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
-                                                                int64_t ld, int qmax, int gran, uint64_t seed,
-                                                                uint64_t offset, const float* __restrict__ inv_scale,
-                                                                int8_t* __restrict__ q, int8_t* __restrict__ qT,
-                                                                int64_t grid_x, int lpr_log2,
-                                                                const float* __restrict__ inv_scale_T = nullptr,
-                                                                int flip_C = 0)
+// `block` is the workgroup's index in the patch grid; GIVEN: the per-tensor inverse scale arrives as a value
+// (a kernel that has just computed it) instead of through inv_scale.
+template <typename T, int RND, bool PERCOL, int PR, bool DUAL, bool GIVEN>
+__device__ __forceinline__ void quantize_patch_body(int64_t block, float inv_given, const T* __restrict__ x, int64_t rows,
+                                                    int64_t cols, int64_t ld, int qmax, int gran, uint64_t seed,
+                                                    uint64_t offset, const float* __restrict__ inv_scale,
+                                                    int8_t* __restrict__ q, int8_t* __restrict__ qT, int64_t grid_x,
+                                                    int lpr_log2, const float* __restrict__ inv_scale_T, int flip_C)
 {
     // DUAL (weights): q takes the scales of `gran` (per row), the transposed copy takes one scale per column
     // from inv_scale_T -- two quantizations of the same values from one read.  flip_C > 0 (3x3 convolution
@@ -591,7 +591,7 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
     constexpr int CW    = PCOLS / 4;              // code dwords per patch row
     const int     wtile_r = (kWaveSize >> lpr_log2) * PR, wtile_c = PCOLS << lpr_log2;
     const int     lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
-    const int64_t by   = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
+    const int64_t by   = block / grid_x, bx = block - by * grid_x;
     const int64_t r0   = (by * (kBlock / kWaveSize) + wave) * wtile_r + (lane >> lpr_log2) * PR;
     const int64_t c0   = bx * wtile_c + (lane & ((1 << lpr_log2) - 1)) * PCOLS;
     if(r0 >= rows || c0 >= cols) return;
@@ -605,7 +605,7 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
         for(int j = 0; j < PCOLS; ++j)
             fcol[j] = (j < 8 || second_ok) ? cs[(DUAL && flip_C > 0) ? (c0 + j) % flip_C : (c0 + j)] : 1.0f;
     }
-    const float ftensor = (!PERCOL && gran == kPerTensor) ? inv_scale[0] : 1.0f;
+    const float ftensor = GIVEN ? inv_given : ((!PERCOL && gran == kPerTensor) ? inv_scale[0] : 1.0f);
 
     uint32_t code[PR][CW];   // row i, columns 4w..4w+3 in dword w
     uint32_t codeT[DUAL ? PR : 1][CW];   // DUAL: the codes of the transposed copy
@@ -729,6 +729,112 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
                 *reinterpret_cast<uint32_t*>(dst) = t[0];
         }
     }
+}
+
+template <typename T, int RND, bool PERCOL, int PR, bool DUAL = false>
+__global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                                int64_t ld, int qmax, int gran, uint64_t seed,
+                                                                uint64_t offset, const float* __restrict__ inv_scale,
+                                                                int8_t* __restrict__ q, int8_t* __restrict__ qT,
+                                                                int64_t grid_x, int lpr_log2,
+                                                                const float* __restrict__ inv_scale_T = nullptr,
+                                                                int flip_C = 0)
+{
+    quantize_patch_body<T, RND, PERCOL, PR, DUAL, false>(blockIdx.x, 1.0f, x, rows, cols, ld, qmax, gran, seed, offset,
+                                                         inv_scale, q, qT, grid_x, lpr_log2, inv_scale_T, flip_C);
+}
+
+// ------------------------------------------------------------------ maximum and quantize in one launch
+// Per-tensor scale, contiguous tensor.  Every workgroup (1) folds its share of the tensor into a partial
+// maximum and publishes it, (2) takes a ticket; the last one to arrive clears the ticket counter and advances a
+// generation word, the others poll that word, (3) folds all partials (the same maximum in every workgroup),
+// forms the scale with the arithmetic of the separate pass, and (4) quantizes its patches, which it has just
+// read and which therefore mostly still sit in cache.  The wait in (2) is bounded: a workgroup whose polls run
+// out (the grid does not fit the device at once, or shares it with another kernel) finds the maximum by reading
+// the whole tensor itself -- slower, same result, and no workgroup ever depends on one that has not started.
+// `sync`: two 32-bit words, [0] tickets (zero before first use, zero again afterwards), [1] generation (any
+// value); `partial`: one float per workgroup.
+template <typename T, int RND, int PR>
+__global__ __launch_bounds__(kBlock, 3) void absmax_quantize_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                                     int qmax, uint64_t seed, uint64_t offset,
+                                                                     unsigned int* sync, float* partial, float* scale,
+                                                                     float* inv_scale,
+                                                                     float* amax_opt, int8_t* __restrict__ q,
+                                                                     int8_t* __restrict__ qT, int64_t grid_x, int lpr_log2,
+                                                                     int64_t patch_blocks, unsigned int poll_limit)
+{
+    __shared__ float lds[16];
+    __shared__ int   timed_out;
+    __shared__ float amax_all;
+    constexpr int E = Vec16<T>::N;
+    constexpr int U = 8;
+    const int64_t nvec = rows * cols / E;                  // cols % 8 == 0: no scalar tail
+    const uint4*  xv   = reinterpret_cast<const uint4*>(x);
+    unsigned int  gen = 0u;
+    if(threadIdx.x == 0) gen = __hip_atomic_load(sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // before the ticket
+    auto fold_range = [&](int64_t first, int64_t step) {
+        RunMax<T> rm;
+        for(int64_t c = first + threadIdx.x; c < nvec; c += step)
+        {
+            uint4 v[U];
+#pragma unroll
+            for(int u = 0; u < U; ++u)
+            {
+                const int64_t idx = c + static_cast<int64_t>(u) * kBlock;
+                v[u] = idx < nvec ? xv[idx] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for(int u = 0; u < U; ++u) rm.add(v[u]);
+        }
+        return block_reduce_max(rm.get(), lds);
+    };
+    // (1) this workgroup's share: pieces of kBlock * U vectors, dealt round-robin
+    const float mine = fold_range(static_cast<int64_t>(blockIdx.x) * kBlock * U, static_cast<int64_t>(gridDim.x) * kBlock * U);
+    // (2)
+    if(threadIdx.x == 0)
+    {
+        st_partial(partial + blockIdx.x, mine);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the partial has been written
+        const unsigned int t = atomicAdd(sync, 1u);
+        int late = 0;
+        if(t == gridDim.x - 1u)
+        {
+            __hip_atomic_store(sync, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __hip_atomic_store(sync + 1, gen + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        else
+        {
+            unsigned int polls = 0u;
+            while(__hip_atomic_load(sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen)
+            {
+                if(++polls > poll_limit) { late = 1; break; }
+                __builtin_amdgcn_s_sleep(4);
+            }
+        }
+        timed_out = late;
+    }
+    __syncthreads();
+    // (3)
+    float folded;                                           // valid in thread 0
+    if(!timed_out)
+    {
+        float m = 0.0f;
+        for(int i = threadIdx.x; i < static_cast<int>(gridDim.x); i += kBlock) m = fmaxf(m, ld_partial(partial + i));
+        folded = block_reduce_max(m, lds);
+    }
+    else
+        folded = fold_range(0, static_cast<int64_t>(kBlock) * U);
+    if(threadIdx.x == 0) amax_all = folded;
+    __syncthreads();
+    const float amax = amax_all;
+    float inv = 1.0f;
+    if(amax != 0.0f) inv = __fdiv_rn(static_cast<float>(qmax), amax);
+    if(blockIdx.x == 0 && threadIdx.x == 0) write_scale(amax, static_cast<float>(qmax), scale, inv_scale, amax_opt, 0);
+    // (4)
+    for(int64_t b = blockIdx.x; b < patch_blocks; b += gridDim.x)
+        quantize_patch_body<T, RND, false, PR, false, true>(b, inv, x, rows, cols, cols, qmax, kPerTensor, seed, offset,
+                                                            nullptr, q, qT, grid_x, lpr_log2, nullptr, 0);
 }
 
 // Any shape, any alignment: one element per thread.
@@ -1398,6 +1504,68 @@ hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t co
                               q, qT, stream);
     return quantize_typed(static_cast<const __half*>(x), rows, cols, ld, qmax, gran, rnd, seed, offset, inv_scale, q,
                           qT, stream);
+}
+
+// Per-tensor maximum, scales and codes with one launch where that pays (a small contiguous tensor: the second
+// read comes from cache and one dependent launch is saved), otherwise the two separate launches.  The single
+// launch runs one workgroup per compute unit at most (few tickets), a third of what the separate quantize kernel
+// keeps in flight, so it stops paying at about 4M elements (measured: 2048x1024 14 vs 17 us, 8192x1024 22 vs 18
+// us) and, with the arithmetic-heavy stochastic rounding, at about 1M (1024x1024 13 vs 17 us, 2048x1024 17 vs 17 us).
+constexpr int64_t kOneLaunchMaxElems = int64_t(1) << 22, kOneLaunchMaxElemsStochastic = int64_t(1) << 20;
+
+template <typename T>
+static hipError_t absmax_quantize_typed(const T* x, int64_t rows, int64_t cols, int qmax, int rnd, uint64_t seed,
+                                        uint64_t offset, float* scale, float* inv_scale, float* amax_opt, int8_t* q,
+                                        int8_t* qT, void* workspace, unsigned int poll_limit, hipStream_t st)
+{
+    const PatchShape ps = patch_shape<T>(rows, cols, qT != nullptr);
+    const int64_t    patch_blocks = ps.gx * ps.gy;
+    const bool one_launch = cols % 8 == 0 && aligned16(x) && (!q || aligned16(q)) && (!qT || (aligned16(qT) && rows % 16 == 0))
+                         && patch_blocks < (int64_t(1) << 31)
+                         && rows * cols <= (rnd == kStochastic ? kOneLaunchMaxElemsStochastic : kOneLaunchMaxElems);
+    if(!one_launch)
+    {
+        hipError_t e = absmax_typed(x, rows, cols, cols, kPerTensor, static_cast<float>(qmax), scale, inv_scale, amax_opt,
+                                    nullptr, nullptr, workspace, st);
+        if(e != hipSuccess) return e;
+        return quantize_typed(x, rows, cols, cols, qmax, kPerTensor, rnd, seed, offset, inv_scale, q, qT, st);
+    }
+    // one workgroup per compute unit at most: all of them resident at once on an otherwise idle device, and few
+    // tickets on the counter
+    static int cus = 0;
+    if(cus == 0)
+    {
+        int dev = 0, n = 0;
+        if(hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 64;
+        cus = n;
+    }
+    const int64_t g = patch_blocks < cus ? patch_blocks : cus;
+    unsigned int* sync    = static_cast<unsigned int*>(workspace);
+    float*        partial = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kCtrBytes);
+    auto go = [&](auto rnd_tag, auto pr) {
+        absmax_quantize_kernel<T, decltype(rnd_tag)::value, decltype(pr)::value><<<dim3(static_cast<unsigned>(g)), dim3(kBlock), 0, st>>>(
+            x, rows, cols, qmax, seed, offset, sync, partial, scale, inv_scale, amax_opt, q, qT, ps.gx, ps.lpr_log2,
+            patch_blocks, poll_limit);
+    };
+    typedef std::integral_constant<int, 16> P16;
+    typedef std::integral_constant<int, 8>  P8;
+    auto by_pr = [&](auto rnd_tag) { if(ps.pr == 16) go(rnd_tag, P16{}); else go(rnd_tag, P8{}); };
+    if(rnd == kStochastic) by_pr(std::integral_constant<int, kStochastic>{});
+    else if(rnd == kFloor) by_pr(std::integral_constant<int, kFloor>{});
+    else                   by_pr(std::integral_constant<int, kNearest>{});
+    return hipGetLastError();
+}
+
+hipError_t launch_absmax_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int qmax, int rnd, uint64_t seed,
+                                  uint64_t offset, float* scale, float* inv_scale, float* amax_opt, int8_t* q, int8_t* qT,
+                                  void* workspace, unsigned int poll_limit, hipStream_t stream)
+{
+    if(xdt == kF32)
+        return absmax_quantize_typed(static_cast<const float*>(x), rows, cols, qmax, rnd, seed, offset, scale, inv_scale,
+                                     amax_opt, q, qT, workspace, poll_limit, stream);
+    return absmax_quantize_typed(static_cast<const __half*>(x), rows, cols, qmax, rnd, seed, offset, scale, inv_scale,
+                                 amax_opt, q, qT, workspace, poll_limit, stream);
 }
 
 // Weights of one linear operator in one go: per-row scales and codes for the forward, per-column scales

@@ -25,6 +25,9 @@ hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t col
                                hipStream_t stream);
 
 // ---- quantize / cast / copy (+ transpose) ---------------------------------------------
+hipError_t launch_absmax_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int qmax, int rnd, uint64_t seed,
+                                  uint64_t offset, float* scale, float* inv_scale, float* amax_opt, int8_t* q, int8_t* qT,
+                                  void* workspace, unsigned int poll_limit, hipStream_t stream);
 hipError_t launch_quantize_int8(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int qmax,
                                 int gran, int rnd, uint64_t seed, uint64_t offset, const float* inv_scale,
                                 int8_t* q, int8_t* qT, hipStream_t stream);

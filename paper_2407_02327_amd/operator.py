@@ -91,8 +91,10 @@ class QLinear:
             if x_amax is not None:
                 Q.qsync_scale_from_amax(x_amax, self.bits, self.sx, self.ix, True, stream)
             else:
-                Q.qsync_absmax_scale(x, M, K, K, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None,
-                                     self.ws_absmax, stream)
+                # maximum, scale and codes: one launch for small activations, the two separate passes otherwise
+                Q.qsync_absmax_quantize(x, M, K, self.bits, Q.ROUND_NEAREST, 0, 0, self.sx, self.ix, self.ax, self.xq,
+                                        self.xqT, self.ws_absmax, -1, stream)
+                return
             Q.qsync_quantize(x, M, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq,
                              self.xqT, stream)
         elif x.dtype == _TORCH_OF_TAG[self.tag] and x.is_contiguous():
@@ -279,8 +281,8 @@ class QConv3x3:
     def convert_x(self, act: torch.Tensor, stream=None) -> None:
         M, C = self.M, self.C
         if self.tag == Q.INT8:
-            Q.qsync_absmax_scale(act, M, C, C, Q.PER_TENSOR, self.bits, self.sx, self.ix, self.ax, None, self.ws_absmax, stream)
-            Q.qsync_quantize(act, M, C, C, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq, None, stream)
+            Q.qsync_absmax_quantize(act, M, C, self.bits, Q.ROUND_NEAREST, 0, 0, self.sx, self.ix, self.ax, self.xq, None,
+                                    self.ws_absmax, -1, stream)
         elif act.dtype == _TORCH_OF_TAG[self.tag] and act.is_contiguous():
             self.xq = act.view(M, C)           # already in the operand type: used in place
         else:

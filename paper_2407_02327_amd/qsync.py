@@ -32,6 +32,9 @@ SIGNATURES = {
     "qsync_absmax_workspace_bytes": (_sz, [_i64, _i64, _i]),
     "qsync_quantize": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _i, _i, _u64, _u64, _vp, _vp, _vp, _vp]),
     "qsync_qlinear_fwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
+    "qsync_absmax_quantize": (_i, [_vp, _i, _i64, _i64, _i, _i, ctypes.c_uint64, ctypes.c_uint64, _vp, _vp, _vp, _vp, _vp,
+                                   _vp, _sz, _i, _vp]),
+    "qsync_absmax_quantize_workspace_bytes": (_sz, [_i64, _i64]),
     "qsync_qlinear_fwd_amax": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_scale_from_amax": (_i, [_vp, _i, _vp, _vp, _i, _vp]),
     "qsync_qlinear_bwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i,
@@ -121,6 +124,17 @@ def qsync_qlinear_fwd(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump
     _check(lib.qsync_qlinear_fwd(tag, M, N, K, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
                                  _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _ptr(workspace), _bytes(workspace),
                                  _stream(stream)))
+
+
+def qsync_absmax_quantize_workspace_bytes(rows, cols) -> int:
+    return int(lib.qsync_absmax_quantize_workspace_bytes(rows, cols))
+
+
+def qsync_absmax_quantize(x, rows, cols, bits, rnd, seed, offset, scale, inv_scale, amax_opt, q_opt, qT_opt, workspace,
+                          poll_limit=-1, stream=None) -> None:
+    _check(lib.qsync_absmax_quantize(_ptr(x), dtype_code(x), rows, cols, bits, rnd, seed, offset, _ptr(scale),
+                                     _ptr(inv_scale), _ptr(amax_opt), _ptr(q_opt), _ptr(qT_opt), _ptr(workspace),
+                                     _bytes(workspace), poll_limit, _stream(stream)))
 
 
 def qsync_qlinear_fwd_amax(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt, y_amax, workspace,

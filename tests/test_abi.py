@@ -285,3 +285,21 @@ def test_no_gpu_gives_hip_error_not_a_crash():
         pytest.skip("GPU present")
     rc = lib.qsync_dequantize(A, 3, 4, 4, 4, None, None, 1.0, None, None, A, 0, None)
     assert rc == qsync.ERR_HIP and lib.qsync_last_hip_error() != 0
+
+
+def test_absmax_quantize_validation():
+    f = lib.qsync_absmax_quantize
+    #        x xdt rows cols bits rnd seed off scale inv amax q qT ws wsb polls stream
+    need = lib.qsync_absmax_quantize_workspace_bytes(64, 128)
+    assert need == lib.qsync_absmax_workspace_bytes(64, 128, qsync.PER_TENSOR) and need > 0
+    assert f(None, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, A, need, -1, None) == qsync.ERR_NULL
+    assert f(A, 0, 64, 128, 8, 0, 0, 0, None, A, None, A, None, A, need, -1, None) == qsync.ERR_NULL
+    assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, None, None, A, need, -1, None) == qsync.ERR_NULL      # no output
+    assert f(A, 7, 64, 128, 8, 0, 0, 0, A, A, None, A, None, A, need, -1, None) == qsync.ERR_BAD_ENUM
+    assert f(A, 0, 64, 128, 8, 5, 0, 0, A, A, None, A, None, A, need, -1, None) == qsync.ERR_BAD_ENUM
+    assert f(A, 0, -1, 128, 8, 0, 0, 0, A, A, None, A, None, A, need, -1, None) == qsync.ERR_BAD_SHAPE
+    assert f(A, 0, 64, 128, 9, 0, 0, 0, A, A, None, A, None, A, need, -1, None) == qsync.ERR_UNSUPPORTED
+    assert f(A, 0, 0, 128, 8, 0, 0, 0, A, A, None, A, None, None, 0, -1, None) == qsync.OK
+    assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, None, 0, -1, None) == qsync.ERR_WORKSPACE
+    assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, A, need - 1, -1, None) == qsync.ERR_WORKSPACE
+    assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, U, need, -1, None) == qsync.ERR_ALIGN

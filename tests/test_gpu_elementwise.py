@@ -363,3 +363,67 @@ def test_empty_tensors_are_noops():
     Q.qsync_absmax_scale(s, 0, 16, 16, Q.PER_TENSOR, 8, s, s, None, None, None)
     Q.qsync_quantize(s, 0, 16, 16, Q.INT8, 8, 0, 0, 0, 0, s, s, None)
     Q.qsync_dequantize(a, 16, 0, 0, None, None, 1.0, None, s)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("rnd", ["nearest", "stochastic", "floor"])
+def test_absmax_quantize_in_one_launch(dtype, rnd):
+    """qsync_absmax_quantize: maximum, scales, codes and transposed codes equal the oracle's absmax ->
+    scales_from_amax -> quantize_int bit for bit -- on shapes the single launch serves (one to 128 workgroups, ragged
+    patch tails), on shapes it hands to the two launches (odd columns, large tensors), with the
+    wait for the other workgroups cut to zero polls (every workgroup but the last then finds the maximum by itself),
+    and on repeated calls that share one workspace without clearing it."""
+    rng = np.random.default_rng(31)
+    shapes = [(64, 128), (272, 1000), (1008, 72), (4096, 768), (2048, 2048), (48, 8200), (130, 72), (3, 5), (257, 1001)]
+    w = ws(max(Q.qsync_absmax_quantize_workspace_bytes(r, c) for r, c in shapes))       # zero-filled once
+    for rows, cols in shapes:
+        x = _data(rng, (rows, cols), dtype, sigma=0.3)
+        x[rows // 2, cols // 3] = dtype(-7.5)                                          # the maximum, negative
+        xd = dev(x)
+        amax = orc.absmax(x, "tensor")
+        so, io = orc.scales_from_amax(amax)
+        want = orc.quantize_int(x, io, "tensor", rnd, 77, 1234)
+        for polls in (-1, 0, 3):
+            for with_t in (True, False):
+                if with_t and rows % 16 != 0:
+                    continue
+                say("absmax_quantize", dtype.__name__, rnd, rows, cols, "polls", polls, "transposed", with_t)
+                s, iv, am = empty(1, torch.float32), empty(1, torch.float32), empty(1, torch.float32)
+                q = torch.full((rows, cols), 99, dtype=torch.int8, device="cuda")
+                qT = torch.full((cols, rows), 99, dtype=torch.int8, device="cuda") if with_t else None
+                Q.qsync_absmax_quantize(xd, rows, cols, 8, RND[rnd], 77, 1234, s, iv, am, q, qT, w, polls)
+                torch.cuda.synchronize()
+                assert_bits_equal(host(am), amax, "amax")
+                assert_bits_equal(host(s), so, "scale")
+                assert_bits_equal(host(iv), io, "inverse scale")
+                assert_bits_equal(host(q), want, "codes")
+                if with_t:
+                    assert_bits_equal(host(qT), want.T, "transposed codes")
+    # the workspace's ticket word is back at zero: the separate maximum pass can use the same buffer next
+    assert int(w[:4].view(torch.int32).item()) == 0
+    x = _data(rng, (512, 4096), dtype)
+    s, iv, am = empty(1, torch.float32), empty(1, torch.float32), empty(1, torch.float32)
+    Q.qsync_absmax_scale(dev(x), 512, 4096, 4096, Q.PER_TENSOR, 8, s, iv, am, None, w)
+    torch.cuda.synchronize()
+    assert_bits_equal(host(am), orc.absmax(x, "tensor"), "amax by the separate pass on the shared workspace")
+
+
+def test_absmax_quantize_all_zero_and_lower_bits():
+    w = ws(Q.qsync_absmax_quantize_workspace_bytes(128, 256))
+    z = torch.zeros(64, 128, dtype=torch.float16, device="cuda")
+    s, iv, am = empty(1, torch.float32), empty(1, torch.float32), empty(1, torch.float32)
+    q = torch.full((64, 128), 99, dtype=torch.int8, device="cuda")
+    Q.qsync_absmax_quantize(z, 64, 128, 8, Q.ROUND_NEAREST, 0, 0, s, iv, am, q, None, w)
+    torch.cuda.synchronize()
+    assert s.item() == 1.0 and iv.item() == 1.0 and am.item() == 0.0 and int(q.abs().max().item()) == 0
+    rng = np.random.default_rng(8)
+    x = _data(rng, (128, 256), np.float32)
+    so, io = orc.scales_from_amax(orc.absmax(x, "tensor"), 5)
+    want = orc.quantize_int(x, io, "tensor", "stochastic", 9, 9, bits=5)
+    q = torch.empty(128, 256, dtype=torch.int8, device="cuda")
+    qT = torch.empty(256, 128, dtype=torch.int8, device="cuda")
+    Q.qsync_absmax_quantize(dev(x), 128, 256, 5, Q.ROUND_STOCHASTIC, 9, 9, s, iv, am, q, qT, w)
+    torch.cuda.synchronize()
+    assert_bits_equal(host(s), so, "scale, 5 bits")
+    assert_bits_equal(host(q), want, "codes, 5 bits")
+    assert_bits_equal(host(qT), want.T, "transposed codes, 5 bits")
