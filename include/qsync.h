@@ -179,7 +179,9 @@ size_t qsync_absmax_quantize_workspace_bytes(int64_t rows, int64_t cols);
  * workspace     at least qsync_qlinear_workspace_bytes(tag, M, N, K) bytes, 16-byte aligned
  *     (may be NULL if that is 0).
  * INT8 needs K % 16 == 0 and FP16 needs K % 8 == 0 (rows of 16-byte vectors feed the matrix
- * cores); otherwise QSYNC_ERR_ALIGN.  M and N are arbitrary.
+ * cores); otherwise QSYNC_ERR_ALIGN.  M and N are arbitrary.  A row of K elements may take at most
+ * 16 MiB (QSYNC_ERR_UNSUPPORTED beyond; the same bound holds for N in the dX GEMM and M in the dW GEMM
+ * of qsync_qlinear_bwd).
  */
 int qsync_qlinear_fwd(int tag, int64_t M, int64_t N, int64_t K,
                       const void* xq, const float* sx,

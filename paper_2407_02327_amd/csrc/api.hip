@@ -34,6 +34,13 @@ bool count_ok(int64_t a, int64_t b)
     return a <= (std::numeric_limits<int64_t>::max() / 64) / b;
 }
 
+// the contraction axis of an MFMA GEMM: rows of at most 16 MiB (32-bit lane offsets inside an operand panel)
+bool gemm_row_ok(int tag, int64_t k)
+{
+    const int64_t esz = tag == QSYNC_INT8 ? 1 : (tag == QSYNC_FP16 ? 2 : 4);
+    return k <= kGemmMaxRowBytes / esz;
+}
+
 size_t round256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 }  // namespace
@@ -167,6 +174,7 @@ static int qlinear_fwd_impl(int tag, int64_t M, int64_t N, int64_t K, const void
         if(!is_gran(wgran)) return QSYNC_ERR_BAD_ENUM;
     }
     if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if(!gemm_row_ok(tag, K)) return QSYNC_ERR_UNSUPPORTED;
     if(tag == QSYNC_INT8 && wgran == QSYNC_PER_COL) return QSYNC_ERR_UNSUPPORTED;
     if(tag != QSYNC_INT8 && acc_dump_opt) return QSYNC_ERR_UNSUPPORTED;
     if(tag != QSYNC_FP32)
@@ -242,6 +250,7 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
         if(dx_opt && !is_gran(wbgran)) return QSYNC_ERR_BAD_ENUM;
     }
     if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if((dx_opt && !gemm_row_ok(tag, N)) || (dw_opt && !gemm_row_ok(tag, M))) return QSYNC_ERR_UNSUPPORTED;
     if(tag == QSYNC_INT8 && dx_opt && wbgran == QSYNC_PER_COL) return QSYNC_ERR_UNSUPPORTED;
     if(tag != QSYNC_INT8 && (acc_dx_dump_opt || acc_dw_dump_opt)) return QSYNC_ERR_UNSUPPORTED;
     if(tag != QSYNC_FP32)

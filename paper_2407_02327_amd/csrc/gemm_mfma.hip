@@ -918,6 +918,8 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     if(p.prec == 32 && ((p.K * 4) % 16 != 0 || ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) != 0))
         return launch_gemm_f32(p, stream);
     const int      esz = p.prec == 8 ? 1 : (p.prec == 16 ? 2 : 4);
+    // lane offsets inside an operand panel are 32-bit: 255 rows of K bytes (plus the load immediates) must fit
+    if(p.K > kGemmMaxRowBytes / esz) return hipErrorInvalidValue;
     GemmKernelArgs a;
     a.A = static_cast<const uint8_t*>(p.A);
     a.B = static_cast<const uint8_t*>(p.B);

@@ -91,6 +91,9 @@ struct GemmProblem {
     unsigned int* out_amax_bits = nullptr;
 };
 
+// longest operand row (contraction axis) in bytes the MFMA GEMM addresses: 32-bit lane offsets span 255 rows
+constexpr int64_t kGemmMaxRowBytes = int64_t(16) << 20;
+
 struct GemmPlan {
     int     tile;          // index into the tile table (see gemm_mfma.hip)
     int     splits;        // split-K factor (1 = epilogue fused in the GEMM kernel)

@@ -94,6 +94,8 @@ def test_qlinear_validation():
     assert call(xq=U) == qsync.ERR_ALIGN
     assert call(tag=32, K=13, xq=U) in (qsync.OK, qsync.ERR_HIP)   # fp32 path has no alignment rule
     assert call(M=0) == qsync.OK
+    assert call(K=(16 << 20) + 16) == qsync.ERR_UNSUPPORTED      # operand rows longer than 16 MiB
+    assert call(tag=16, K=(8 << 20) + 8) == qsync.ERR_UNSUPPORTED
     # a split-K shape needs a workspace
     assert lib.qsync_qlinear_workspace_bytes(8, 64, 576, 200704) > 0
     assert call(M=64, N=576, K=200704) == qsync.ERR_WORKSPACE
