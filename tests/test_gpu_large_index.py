@@ -75,3 +75,37 @@ def test_forward_gemm_with_more_than_2_to_31_outputs():
         want = orc.qlinear_fwd(Q.INT8, xq[r:r + 1], sx, wq, sw, bias, out_dtype=np.float64)[0]
         assert_close(host(y[r])[None, :], want, f"Y row {r}")
     del y
+
+
+def test_cast_and_dequantize_over_more_than_2_to_31_elements():
+    rows, cols = 71680, 32768
+    say("large index: fp16 cast with transposed copy, dequantize", rows, cols)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    picks = _sample_rows(rows, cols)
+    # binary16 cast of fp32 input, with the transposed copy
+    x = torch.empty(rows, cols, dtype=torch.float32, device="cuda")
+    for r0 in range(0, rows, 8192):
+        n = min(8192, rows - r0)
+        x[r0:r0 + n] = torch.randn(n, cols, device="cuda", generator=g)
+    h = torch.empty(rows, cols, dtype=torch.float16, device="cuda")
+    hT = torch.empty(cols, rows, dtype=torch.float16, device="cuda")
+    Q.qsync_quantize(x, rows, cols, cols, Q.FP16, 0, 0, 0, 0, 0, None, h, hT)
+    torch.cuda.synchronize()
+    for r in picks:
+        want = orc.cast_fp16(host(x[r])[None, :])
+        assert_bits_equal(host(h[r])[None, :], want, f"cast row {r}")
+        assert_bits_equal(host(hT[:, r])[None, :], want, f"transposed cast row {r}")
+    del h, hT
+    # int32 accumulators -> binary16 with column scales and bias (reusing x's memory as the int32 input)
+    acc = x.view(torch.int32)
+    acc.random_(-(1 << 20), 1 << 20, generator=g)
+    cs = (torch.rand(cols, device="cuda", generator=g) + 0.5) * 1e-4
+    cb = torch.randn(cols, device="cuda", generator=g)
+    y = torch.empty(rows, cols, dtype=torch.float16, device="cuda")
+    Q.qsync_dequantize(acc, rows, cols, cols, None, cs, 0.5, cb, y)
+    torch.cuda.synchronize()
+    for r in picks:
+        want = orc.dequantize(host(acc[r])[None, :], 0.5, None, host(cs), host(cb), out_dtype=np.float64)
+        assert_close(host(y[r])[None, :], want, f"dequantized row {r}")
+    del x, y
