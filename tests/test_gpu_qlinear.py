@@ -169,10 +169,12 @@ def test_int32_wraparound_matches_oracle():
     assert_bits_equal(host(acc), want, "wrapped accumulators")
 
 
-@pytest.mark.parametrize("tokens", [2048, 8192])
-def test_config4_mixed_precision_mlp_chain(tokens):
+@pytest.mark.parametrize("tokens,epilogue_maxima", [(2048, False), (8192, False), (8192, True)])
+def test_config4_mixed_precision_mlp_chain(tokens, epilogue_maxima):
     """12 linears (width -> hidden -> width, GELU in between), per-layer precision tags; fwd then bwd
-    (8192 tokens is the configuration's full size).
+    (8192 tokens is the configuration's full size).  With `epilogue_maxima` every layer whose output feeds the
+    next layer as it is (no GELU in between: the odd layers) collects max |Y| in its GEMM epilogue and the
+    consumer takes its activation scale from that word; every comparison below stays the same.
 
     Parity is asserted per operator on identical input bits: each layer's actual GPU input and
     incoming gradient are downloaded and given to the oracle.  GELU and its derivative are not part
@@ -186,9 +188,13 @@ def test_config4_mixed_precision_mlp_chain(tokens):
     wd = [dev(w) for w in chain.weights]
     for l, (w, tag) in enumerate(zip(chain.weights, chain.tags)):
         N, K = w.shape
+        feeds_next_directly = epilogue_maxima and l % 2 == 1 and l + 1 < len(chain.weights)
         op = QLinear(tag, M, N, K, x_dtype=torch.float32, y_dtype=torch.float32, dx_dtype=torch.float32,
-                     w_gran=Q.PER_ROW, dy_round=Q.ROUND_STOCHASTIC, philox_seed=chain.philox_seed, dump_acc=True)
-        y = op.forward(acts[-1], wd[l])
+                     w_gran=Q.PER_ROW, dy_round=Q.ROUND_STOCHASTIC, philox_seed=chain.philox_seed, dump_acc=True,
+                     collect_y_amax=feeds_next_directly)
+        producer = ops[-1] if ops else None
+        x_amax = producer.y_amax if (producer is not None and producer.y_amax is not None and tag == Q.INT8) else None
+        y = op.forward(acts[-1], wd[l], x_amax=x_amax)
         ops.append(op)
         pre.append(y)
         acts.append(torch.nn.functional.gelu(y) if l % 2 == 0 else y)
