@@ -169,7 +169,7 @@ def cast_fp16(x: np.ndarray) -> np.ndarray:
     return x.astype(np.float16)
 
 
-def cast_fp16_stochastic(x: np.ndarray, seed: int = 0, offset: int = 0, k: int = 10) -> np.ndarray:
+def cast_fp16_stochastic(x: np.ndarray, seed: int = 0, offset: int = 0, k: int = 9) -> np.ndarray:
     """Floating-point stochastic quantization to binary16 (Appendix, Proposition 2, the two-case rule
     for the rounded value): with x = s 2^e (1 + m), the mantissa is truncated to k bits and the value moves
     up by eps = 2^-k (in units of 2^e) with probability (m - floor_k(m)) / eps.
@@ -180,7 +180,8 @@ def cast_fp16_stochastic(x: np.ndarray, seed: int = 0, offset: int = 0, k: int =
     floor(rem * 2^16 / 2^D) and the element's 16-bit draw u (same Philox mapping as the fixed-point
     quantizer) rounds up iff u < threshold.  The result is exactly representable in binary16 unless it
     reaches 2^16, which becomes infinity as in IEEE narrowing.  binary16 input is returned unchanged.
-    k = 10 is the full binary16 mantissa; the paper quotes k = 9.
+    The default k = 9 is the value the paper states for float16 (remark after Prop. 2 of the Indicator
+    section); k = 10 keeps the full binary16 mantissa.
     """
     if x.dtype == np.float16:
         return x.copy()
@@ -394,20 +395,23 @@ def fp16_backward_of_int8_forward(xq: np.ndarray, sx, wq: np.ndarray, sw, w_gran
     """Backward of a fixed-point operator the way the paper runs it (footnote in the Cost Mapper
     paragraph: the backward of fixed-point kernels is executed in FP16).
 
-    The saved forward codes are dequantized (x_hat = code * q, Indicator section; one binary32
-    multiply, the precision the dequantizer kernel works in) and narrowed to binary16 with round to
-    nearest even, the incoming gradient is narrowed to binary16, and the two contractions of the
-    Prop. 1 proof run on those operands:  dX = dY16 W16,  dW = dY16^T X16,  db = sum_m dY.
+    The saved forward codes are dequantized and narrowed to binary16, the incoming gradient is narrowed
+    to binary16, and the two contractions of the Prop. 1 proof run on those operands:
+    dX = dY16 W16,  dW = dY16^T X16,  db = sum_m dY.
+
+    The dequantized scalar of the Indicator section is x_hat = round(x_bar) * q_x, a product of an 8-bit
+    code and a binary32 scale: at most 32 significant bits, so it is exact in double.  The binary16
+    operand is that exact value rounded once to nearest even; no intermediate binary32 rounding is part
+    of the definition.
     Returns dict(xh, wh, dyh, dx, dw, db).
     """
-    # x_hat = code * q is one binary32 product (codes and scales are binary32-exact), then narrowed
-    sxv = _F32(np.asarray(sx).reshape(-1)[0])
-    xh = cast_fp16(xq.astype(_F32) * sxv)
+    sxv = float(_F32(np.asarray(sx).reshape(-1)[0]))
+    xh = dequantize(xq, tensor_scale=sxv, out_dtype=np.float16)
     swv = np.asarray(sw, _F32).reshape(-1)
     if w_gran == "row":
-        wh = cast_fp16(wq.astype(_F32) * swv.reshape(-1, 1))
+        wh = dequantize(wq, row_scale=swv, out_dtype=np.float16)
     else:
-        wh = cast_fp16(wq.astype(_F32) * swv[0])
+        wh = dequantize(wq, tensor_scale=float(swv[0]), out_dtype=np.float16)
     dyh = cast_fp16(dy)
     b = qlinear_bwd(FP16, dyh, None, xh, None, wh, None, dy, dx_dtype, dw_dtype)
     return dict(xh=xh, wh=wh, dyh=dyh, dx=b["dx"], dw=b["dw"], db=b["db"])

@@ -34,6 +34,29 @@ def round_f32(q: Fraction) -> Fraction:
     return sign * r
 
 
+def round_f16(q: Fraction) -> Fraction:
+    """Nearest binary16 value (ties to even) of an exact rational, subnormals included; overflow not modelled."""
+    if q == 0:
+        return Fraction(0)
+    sign = -1 if q < 0 else 1
+    a = abs(q)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    if Fraction(2) ** (e + 1) <= a:
+        e += 1
+    e = max(e, -14)                                                # subnormal range shares 2^-24 spacing
+    ulp = Fraction(2) ** (e - 10)
+    n = a / ulp
+    lo = n.numerator // n.denominator
+    rem = n - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    r = lo * ulp
+    assert r < Fraction(2) ** 16, "overflow not modelled"
+    return sign * r
+
+
 def f32_mul(a: Fraction, b: Fraction) -> Fraction:
     return round_f32(a * b)
 

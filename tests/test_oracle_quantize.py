@@ -103,6 +103,54 @@ def test_nearest_error_at_most_half_a_step(gran):
     np.testing.assert_allclose(xh, q * sb, rtol=1e-7)
 
 
+def test_dequantize_with_row_and_column_scale_and_bias_exact_rational():
+    """x_hat = code * q_tensor * q_row * q_col + bias on exact rationals, rounded once to the output type
+    (Indicator section: the dequantized scalar; Cost Mapper paragraph: layer-wise and channel-wise dequantizers)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(77)
+    for dtype, lo, hi in ((np.int8, -127, 128), (np.int32, -(1 << 16), 1 << 16)):
+        a = rng.integers(lo, hi, size=(5, 7)).astype(dtype)
+        rs = rng.uniform(1e-3, 1.0, size=5).astype(np.float32)
+        cs = rng.uniform(1e-3, 1.0, size=7).astype(np.float32)
+        cb = rng.standard_normal(7).astype(np.float32)
+        ts = np.float32(0.37)
+        for use_r, use_c, use_b in [(True, True, True), (True, False, True), (False, True, False), (True, True, False),
+                                    (False, False, True)]:
+            for out, rnd in ((np.float32, ref.round_f32), (np.float16, ref.round_f16)):
+                got = orc.dequantize(a, float(ts), rs if use_r else None, cs if use_c else None, cb if use_b else None, out)
+                assert got.dtype == out
+                for r in range(5):
+                    for c in range(7):
+                        v = Fraction(int(a[r, c])) * Fraction(float(ts))
+                        if use_r: v *= Fraction(float(rs[r]))
+                        if use_c: v *= Fraction(float(cs[c]))
+                        if use_b: v += Fraction(float(cb[c]))
+                        assert Fraction(float(got[r, c])) == rnd(v), (dtype, use_r, use_c, use_b, out, r, c)
+
+
+def test_dequantized_binary16_operand_is_rounded_once():
+    """The binary16 operand of the FP16 backward is the exact product code * scale rounded once.  Rounding the
+    product to binary32 first and narrowing afterwards differs on some inputs; the search below finds such
+    inputs (so the test bites) and the oracle must return the once-rounded value on them."""
+    from fractions import Fraction
+    rng = np.random.default_rng(3)
+    scales = rng.uniform(0.5, 1.0, size=200000).astype(np.float32) * np.float32(2.0 ** -7)
+    codes = rng.integers(3, 128, size=scales.size).astype(np.int8)
+    once = (codes.astype(np.float64) * scales.astype(np.float64)).astype(np.float16)          # exact in double
+    twice = (codes.astype(np.float32) * scales).astype(np.float16)
+    hard = np.flatnonzero(once.view(np.uint16) != twice.view(np.uint16))
+    assert hard.size >= 3, "no input separates one rounding from two"
+    for i in hard[:20]:
+        exact = Fraction(int(codes[i])) * Fraction(float(scales[i]))
+        want = ref.round_f16(exact)
+        assert Fraction(float(once[i])) == want and Fraction(float(twice[i])) != want
+        got = orc.dequantize(codes[i:i + 1].reshape(1, 1), float(scales[i]), out_dtype=np.float16)
+        assert Fraction(float(got[0, 0])) == want
+        out = orc.fp16_backward_of_int8_forward(codes[i:i + 1].reshape(1, 1), scales[i:i + 1], codes[i:i + 1].reshape(1, 1),
+                                                scales[i:i + 1], "row", np.zeros((1, 1), np.float32))
+        assert Fraction(float(out["xh"][0, 0])) == want and Fraction(float(out["wh"][0, 0])) == want
+
+
 def test_codes_never_reach_minus_128():
     rng = np.random.default_rng(6)
     x = rng.standard_normal((257, 33)).astype(np.float32)
