@@ -114,7 +114,8 @@ size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
  *   tag FP16: IEEE round-to-nearest-even narrowing to binary16 (copy if x is binary16).
  *             With rnd = QSYNC_ROUND_STOCHASTIC and fp32 input: the floating-point stochastic
  *             quantizer of the paper (Appendix, Proposition 2): the mantissa is truncated to k bits
- *             (k = bits, 7..10; bits = 0 means 10, the full binary16 mantissa; the paper quotes 9) and
+ *             (k = bits, 7..10; bits = 0 means 9, the value the paper states for float16; 10 keeps the full
+ *             binary16 mantissa) and
  *             the value moves up by one spacing 2^(max(e,-14)-k) with probability dropped/spacing,
  *             decided as u < floor(p * 2^16) with the same per-element Philox draw u as tag INT8.
  *             Values that reach 2^16 become infinity, as in IEEE narrowing.
@@ -320,29 +321,6 @@ int qsync_conv3x3_prepare_weights(const void* w, int wdt, int64_t N, int64_t C, 
 size_t qsync_conv3x3_prepare_weights_workspace_bytes(int64_t N, int64_t C);
 
 /*
- * qsync_probe_mfma - measurement probe, not part of the operator path: launches a kernel that issues
- * `iters` x 4 back-to-back 32x32 matrix instructions per wavefront on register operands (512 workgroups
- * of 4 wavefronts, no memory traffic), so that a caller can time the matrix-instruction rate this GPU
- * sustains: with constant operands (random_operands = 0) and with pseudo-random operand values
- * (random_operands = 1; power management lowers the clock when operand bits toggle); random_operands = 2
- * is mode 1 with the second binary16 operand drawn from the subnormal range (same as 1 for QSYNC_INT8).
- * tag QSYNC_INT8 (v_mfma_i32_32x32x32_i8) or QSYNC_FP16 (v_mfma_f32_32x32x16_f16); 1 <= iters <= 2^24,
- * rounded up to a multiple of 4.
- * out      device scratch, at least 512 KiB (one 4-byte word per thread).
- * ops_out  host pointer or NULL: receives the number of arithmetic operations the launch performs.
- * The caller times the launch on `stream`.
- */
-int qsync_probe_mfma(int tag, int random_operands, int iters, void* out, double* ops_out, void* stream);
-
-/*
- * qsync_debug_set_gemm_tile - for tests and tuning runs: pin the tile shape of the MFMA GEMM
- * (0: 256x256, 1: 128x128, 2: 64x64) for every later call of this process, -1 (or any other value)
- * returns the choice to the planner.  Workspace sizes reported afterwards follow the pinned tile.
- * Process-wide and not synchronized: do not call it while another thread is inside the library.
- */
-void qsync_debug_set_gemm_tile(int tile);
-
-/*
  * qsync_conv3x3_fwd - 3x3 / stride 1 / pad 1 convolution over an NHWC tensor as an implicit GEMM.
  * Paper: Backend section (low-precision convolution kernels run on NHWC tensors; dequantization is
  * fused into the kernel's epilogue); Appendix, proof of Prop. 2 (forward flow of a fixed-point
@@ -411,6 +389,29 @@ int qsync_dequantize(const void* a, int adt, int64_t rows, int64_t cols, int64_t
                      const float* row_scale_opt, const float* col_scale_opt, float tensor_scale,
                      const float* tensor_scale_dev_opt, const float* col_bias_opt, void* y, int ydt,
                      void* stream);
+
+/*
+ * qsync_variance_increment - HOST function (no GPU work, every pointer is a host pointer): the indicator
+ * of one unary computation-intensive operator (linear, convolution) from tensor statistics.
+ * Paper: Indicator section, Prop. 2 (a stochastic-rounding grid of spacing d adds a variance of
+ * d^2 D / 6 to a tensor of D elements; d = q on a fixed-point grid, d = 2^e eps with eps = 2^-k and
+ * 2^e <= max|t| < 2^(e+1) on a floating-point one) and Prop. 3 with its two case equations:
+ *
+ *   sigma_fp = |x|^2 Var[v] + |v|^2 Var[x]            x: parameter, v: activation, in the operator's format
+ *   sigma_bp = |grad_v|^2 Var[v] + |v|^2 Var[grad_v]   the activation gradient always on the floating-point grid
+ *   Omega    = gamma^2 d_o sigma_fp + (d_L - d_o) sigma_bp
+ *
+ * The statistics are what qsync_absmax_scale delivers in one pass (sumsq_opt, amax_opt) plus the element
+ * count.  kind QSYNC_QUANT_FIXED uses the fixed-point scales q_x, q_v for x and v; QSYNC_QUANT_FLOAT ignores
+ * them.  k: mantissa bits kept by the floating-point format (the paper states 9 for float16).
+ * sigma_fp / sigma_bp may be NULL.  Errors: QSYNC_ERR_NULL, _BAD_ENUM, _BAD_SHAPE (negative or non-finite
+ * statistics, d_L < d_o), _UNSUPPORTED (k outside 1..52, negative or non-finite scales or gamma).
+ */
+typedef enum { QSYNC_QUANT_FIXED = 0, QSYNC_QUANT_FLOAT = 1 } qsync_quant_kind_t;
+typedef struct { double sumsq; double amax; int64_t D; } qsync_tensor_stats_t;
+int qsync_variance_increment(int kind, const qsync_tensor_stats_t* x, const qsync_tensor_stats_t* v,
+                             const qsync_tensor_stats_t* grad_v, double q_x, double q_v, int k, double gamma,
+                             int64_t d_o, int64_t d_L, double* sigma_fp, double* sigma_bp, double* omega);
 
 /* hipError_t (as int) of the last failing HIP call made by this thread, 0 if none. */
 int qsync_last_hip_error(void);

@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libqsync.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm_mfma.hip", "gemm_f32.hip", "probe.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm_mfma.hip", "gemm_f32.hip", "probe.hip", "indicator.hip"]
 
 # -ffp-contract=off: the quantizer's multiply and subtract must stay separately rounded.
 # packed fp32 VALU ops are disabled for the device pass (hipcc's host pass warns that it
@@ -37,7 +37,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     obj_dir = os.path.join(PKG_DIR, "_build")
     os.makedirs(obj_dir, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers.append(os.path.join(os.path.dirname(PKG_DIR), "include", "qsync.h"))
+    inc = os.path.join(os.path.dirname(PKG_DIR), "include")
+    headers += [os.path.join(inc, f) for f in os.listdir(inc) if f.endswith(".h")]
     newest_header = max(os.path.getmtime(h) for h in headers)
 
     def compile_one(src: str) -> str:
@@ -63,10 +64,25 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB_PATH
 
 
-def ensure_built() -> str:
-    """Returns the library path, compiling it first only when no library is there at all (tests, the smoke
-    check and the benchmark load what is built; after a source change run the build explicitly)."""
-    return LIB_PATH if os.path.exists(LIB_PATH) else build(force=True)
+def library_is_stale() -> bool:
+    """True when any kernel source or header is newer than the built library."""
+    if not os.path.exists(LIB_PATH):
+        return True
+    built = os.path.getmtime(LIB_PATH)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))]
+    inc = os.path.join(os.path.dirname(PKG_DIR), "include")
+    deps += [os.path.join(inc, f) for f in os.listdir(inc) if f.endswith(".h")]
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
+def ensure_built(rebuild_if_stale: bool = False) -> str:
+    """Returns the library path, compiling it first when no library is there at all.  Tests and the smoke
+    check load what is built; with `rebuild_if_stale` (the benchmark) a library older than any of its
+    sources is rebuilt as well, and if that is impossible (no compiler) the call fails instead of timing
+    stale code."""
+    if not os.path.exists(LIB_PATH) or (rebuild_if_stale and library_is_stale()):
+        return build(force=True)
+    return LIB_PATH
 
 
 if __name__ == "__main__":

@@ -2,6 +2,7 @@
 // puts around its tensorized kernels) and dispatch to the gfx950 kernels.  Validation never
 // touches the HIP runtime, so every argument error is reported even on a machine with no GPU.
 #include "../../include/qsync.h"
+#include "../../include/qsync_debug.h"
 #include "kernels.h"
 
 #include <limits>
@@ -113,7 +114,7 @@ int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t l
     if(rows == 0 || cols == 0) return QSYNC_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if(fp_sr)
-        return hip_status(launch_convert_sr(static_cast<const float*>(x), rows, cols, ld, bits == 0 ? 10 : bits,
+        return hip_status(launch_convert_sr(static_cast<const float*>(x), rows, cols, ld, bits == 0 ? 9 : bits,
                                             philox_seed, philox_offset, q_opt, qT_opt, st));
     if(tag == QSYNC_INT8)
     {
@@ -299,7 +300,13 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
         const int rc = hip_status(launch_gemm(p, plan_dw, wsb ? wsb + off_dw : nullptr, st));
         if(rc != QSYNC_OK) return rc;
     }
-    if(db_opt && N > 0)
+    if(db_opt && N > 0 && M == 0)
+    {   // no rows to sum: the bias gradient is zero (the column-sum kernels need their workspace, which an
+        // empty batch does not have to bring)
+        const int rc = hip_status(launch_zero_f32(db_opt, N, st));
+        if(rc != QSYNC_OK) return rc;
+    }
+    else if(db_opt && N > 0)
     {
         const int rc = hip_status(launch_colsum(dy_float_opt, dydt, M, N, db_opt,
                                                 reinterpret_cast<float*>(wsb + off_db), st));

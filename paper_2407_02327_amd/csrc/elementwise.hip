@@ -1154,9 +1154,27 @@ __global__ __launch_bounds__(kBlock) void cast_f16_patch_kernel(const Ti* __rest
 }
 
 // ------------------------------------------------------------------ standalone dequantize
-template <typename To> __device__ __forceinline__ To from_f32(float v);
-template <> __device__ __forceinline__ float  from_f32<float>(float v) { return v; }
-template <> __device__ __forceinline__ __half from_f32<__half>(float v) { return __float2half_rn(v); }
+// code * scale (+ bias) in the output type.  The dequantized scalar is the exact product of a code and a scale
+// (Indicator section: x_hat = round(x_bar) * q_x); for an 8-bit code and one binary32 scale that product has at
+// most 32 significant bits.  The binary16 result is that exact value rounded once: the binary32 product is
+// brought to round-to-odd with the exact residual of the multiplication (fused multiply-add), and a value
+// rounded to odd at 24 bits narrows to 11 bits like the exact one.  With a bias the sum is formed in binary32.
+template <typename To> __device__ __forceinline__ To scaled_code(float a, float g, float bias, bool has_bias);
+template <> __device__ __forceinline__ float scaled_code<float>(float a, float g, float bias, bool has_bias)
+{
+    const float v = a * g;
+    return has_bias ? v + bias : v;
+}
+template <> __device__ __forceinline__ __half scaled_code<__half>(float a, float g, float bias, bool has_bias)
+{
+    const float p = a * g;
+    if(has_bias) return __float2half_rn(p + bias);
+    const float e = fmaf(a, g, -p);                         // exact residual of a normal product
+    uint32_t    b = __float_as_uint(p);
+    if(e != 0.0f && (b & 1u) == 0u && (b & 0x7F800000u) != 0u)
+        b += ((e > 0.0f) == (p > 0.0f)) ? 1u : 0xFFFFFFFFu;       // the neighbour on the residual's side is the odd one
+    return __float2half_rn(__uint_as_float(b));
+}
 
 template <typename Ti, typename To, int V>
 __global__ __launch_bounds__(kBlock) void dequantize_kernel(const Ti* __restrict__ a, int64_t rows, int64_t cols,
@@ -1179,17 +1197,13 @@ __global__ __launch_bounds__(kBlock) void dequantize_kernel(const Ti* __restrict
             *reinterpret_cast<uint32_t*>(in) = *reinterpret_cast<const uint32_t*>(a + r * ld + c);
         else
             in[0] = a[r * ld + c];
-        const float frow = rs ? rs[r] : 1.0f;
+        // the scales are multiplied together first: with a single scale in use that product is the scale itself
+        const float grow = ts * (rs ? rs[r] : 1.0f);
         alignas(16) To out[V];
 #pragma unroll
         for(int e = 0; e < V; ++e)
-        {
-            float v = static_cast<float>(in[e]) * ts;
-            v       = v * frow;
-            if(cs) v = v * cs[c + e];
-            if(cb) v = v + cb[c + e];
-            out[e] = from_f32<To>(v);
-        }
+            out[e] = scaled_code<To>(static_cast<float>(in[e]), cs ? grow * cs[c + e] : grow, cb ? cb[c + e] : 0.0f,
+                                     cb != nullptr);
         To* dst = y + r * cols + c;
         if(V == 4 && sizeof(To) == 4)
             *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(out);
@@ -1242,19 +1256,13 @@ __global__ __launch_bounds__(kBlock) void dequantize_cols_kernel(const Ti* __res
         {
             const int64_t r = base + u * TY + ty;
             if(r >= rows) continue;
-            const float frow = rs ? rs[r] : 1.0f;
+            const float grow = ts * (rs ? rs[r] : 1.0f);
             alignas(16) Ti in[V];
             *reinterpret_cast<uint4*>(in) = raw[u];
             alignas(16) To out[V];
 #pragma unroll
             for(int e = 0; e < V; ++e)
-            {
-                float v = static_cast<float>(in[e]) * ts;
-                v       = v * frow;
-                if(cs) v = v * fcs[e];
-                if(cb) v = v + fcb[e];
-                out[e] = from_f32<To>(v);
-            }
+                out[e] = scaled_code<To>(static_cast<float>(in[e]), cs ? grow * fcs[e] : grow, fcb[e], cb != nullptr);
             To* dst = y + r * cols + c;
 #pragma unroll
             for(int e = 0; e < V * static_cast<int>(sizeof(To)) / 16; ++e)
@@ -1830,6 +1838,22 @@ size_t colsum_workspace_bytes(int64_t rows, int64_t cols)
 {
     (void)rows;
     return sizeof(float) * static_cast<size_t>(kColParts) * static_cast<size_t>(cols > 0 ? cols : 0);
+}
+
+// Clears n floats with a kernel (a memset node recorded into a captured graph is avoided on purpose).
+__global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, int64_t n)
+{
+    for(int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += static_cast<int64_t>(gridDim.x) * 256)
+        p[i] = 0.0f;
+}
+
+hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t stream)
+{
+    if(n <= 0) return hipSuccess;
+    int64_t nb = (n + 255) / 256;
+    nb         = nb > 1024 ? 1024 : nb;
+    zero_f32_kernel<<<dim3(static_cast<unsigned>(nb)), dim3(256), 0, stream>>>(p, n);
+    return hipGetLastError();
 }
 
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,

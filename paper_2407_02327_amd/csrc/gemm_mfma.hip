@@ -846,7 +846,7 @@ hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStrea
 
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t stream);   // gemm_f32.hip
 
-static int g_tile_override = -1;     // set by tests and tuning runs only (not synchronized)
+static thread_local int g_tile_override = -1;     // set by tests and tuning runs only; per calling thread
 void set_gemm_tile_override(int tile) { g_tile_override = (tile >= 0 && tile < kNumTiles) ? tile : -1; }
 
 GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits, bool allow_split)

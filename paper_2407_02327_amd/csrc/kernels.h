@@ -60,6 +60,7 @@ hipError_t launch_conv_padded_transpose(const void* in, int elem_bytes, int64_t 
                                         void* out, int margin_bytes, hipStream_t stream);
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream);
+hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream);

@@ -1,14 +1,12 @@
-"""Variance-increment indicator of one operator from device-side tensor statistics.
+"""Gathers the tensor statistics the variance-increment indicator needs from the device.
 
-Paper: Indicator section, Prop. 3 (Omega = gamma^2 d_o sigma_fp + (d_L - d_o) sigma_bp) and the two case
-equations for sigma_fp / sigma_bp of unary computation-intensive operators.  The statistics (squared
-norm, absmax) come out of the same pass that computes the quantization scale (`qsync_absmax_scale`
-with `sumsq_opt`); this module only gathers the handful of scalars and evaluates the closed form on the
-host, as the paper does after profiling.
+Paper: Indicator section, Prop. 3.  The statistics (squared norm, absmax) come out of the same pass that
+computes the quantization scale (`qsync_absmax_scale` with `sumsq_opt`); this module copies the two scalars
+to the host.  The indicator itself is evaluated by libqsync (`qsync_variance_increment`, a host function of
+the C ABI); nothing here computes.
 """
 from __future__ import annotations
 
-import math
 from dataclasses import dataclass
 
 import torch
@@ -21,11 +19,6 @@ class TensorStats:
     sumsq: float
     amax: float
     D: int
-
-    @property
-    def e(self) -> int:
-        """Effective exponent: 2^e <= amax < 2^(e+1); -126 for an all-zero tensor."""
-        return int(math.floor(math.log2(self.amax))) if self.amax > 0 else -126
 
 
 def tensor_stats(x: torch.Tensor, stream=None) -> TensorStats:
@@ -41,15 +34,10 @@ def tensor_stats(x: torch.Tensor, stream=None) -> TensorStats:
 
 
 def variance_increment(kind: str, x: TensorStats, v: TensorStats, gv: TensorStats, q_x: float = 0.0, q_v: float = 0.0,
-                       eps: float = 2.0 ** -9, gamma: float = 1.0, d_o: int = 1, d_L: int = 1) -> dict:
-    """Omega of one operator; `kind` is "fixed" (q_x, q_v: the fixed-point scales of parameter and
-    activation) or "float" (eps = 2^-k of the floating-point format)."""
-    if kind == "fixed":
-        s_fp = (x.sumsq * q_v ** 2 * v.D + v.sumsq * q_x ** 2 * x.D) / 6.0
-        s_bp = (gv.sumsq * q_v ** 2 * v.D + v.sumsq * 4.0 ** gv.e * eps ** 2 * gv.D) / 6.0
-    elif kind == "float":
-        s_fp = eps ** 2 * (x.sumsq * 4.0 ** v.e * v.D + v.sumsq * 4.0 ** x.e * x.D) / 6.0
-        s_bp = eps ** 2 * (gv.sumsq * 4.0 ** v.e * v.D + v.sumsq * 4.0 ** gv.e * gv.D) / 6.0
-    else:
+                       k: int = 9, gamma: float = 1.0, d_o: int = 1, d_L: int = 1) -> dict:
+    """Omega of one operator through `qsync_variance_increment`; `kind` is "fixed" (q_x, q_v: the fixed-point
+    scales of parameter and activation) or "float"; k: mantissa bits of the floating-point format."""
+    kinds = {"fixed": Q.QUANT_FIXED, "float": Q.QUANT_FLOAT}
+    if kind not in kinds:
         raise ValueError(kind)
-    return dict(sigma_fp=s_fp, sigma_bp=s_bp, omega=gamma ** 2 * d_o * s_fp + (d_L - d_o) * s_bp)
+    return Q.qsync_variance_increment(kinds[kind], x, v, gv, q_x, q_v, k, gamma, d_o, d_L)

@@ -15,6 +15,7 @@ from typing import Optional
 import torch
 
 INT8, FP16, FP32 = 8, 16, 32                       # qsync_prec_t
+QUANT_FIXED, QUANT_FLOAT = 0, 1                    # qsync_quant_kind_t
 F32, F16, I8, I32 = 0, 1, 2, 3                     # qsync_dtype_t
 PER_TENSOR, PER_ROW, PER_COL = 0, 1, 2             # qsync_gran_t
 ROUND_NEAREST, ROUND_STOCHASTIC, ROUND_FLOOR = 0, 1, 2
@@ -52,6 +53,9 @@ SIGNATURES = {
     "qsync_prepare_weights": (_i, [_vp, _i, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qsync_conv3x3_wflip": (_i, [_vp, _i, _i64, _i64, _vp, _vp]),
     "qsync_dequantize": (_i, [_vp, _i, _i64, _i64, _i64, _vp, _vp, _f, _vp, _vp, _vp, _i, _vp]),
+    "qsync_variance_increment": (_i, [_i, _vp, _vp, _vp, ctypes.c_double, ctypes.c_double, _i, ctypes.c_double, _i64, _i64,
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]),
     "qsync_last_hip_error": (_i, []),
     "qsync_strerror": (ctypes.c_char_p, [_i]),
     "qsync_version": (_i, []),
@@ -213,3 +217,19 @@ def qsync_dequantize(a, rows, cols, ld, row_scale_opt, col_scale_opt, tensor_sca
     _check(lib.qsync_dequantize(_ptr(a), dtype_code(a), rows, cols, ld, _ptr(row_scale_opt), _ptr(col_scale_opt),
                                 float(tensor_scale), _ptr(tensor_scale_dev_opt), _ptr(col_bias_opt), _ptr(y),
                                 dtype_code(y), _stream(stream)))
+
+
+class TensorStatsC(ctypes.Structure):
+    """qsync_tensor_stats_t"""
+    _fields_ = [("sumsq", ctypes.c_double), ("amax", ctypes.c_double), ("D", ctypes.c_int64)]
+
+
+def qsync_variance_increment(kind: int, x, v, grad_v, q_x: float, q_v: float, k: int, gamma: float, d_o: int,
+                             d_L: int) -> dict:
+    """x, v, grad_v: objects with fields sumsq, amax, D.  Returns dict(sigma_fp, sigma_bp, omega) (host doubles)."""
+    c = [TensorStatsC(float(t.sumsq), float(t.amax), int(t.D)) for t in (x, v, grad_v)]
+    out = [ctypes.c_double() for _ in range(3)]
+    _check(lib.qsync_variance_increment(kind, ctypes.byref(c[0]), ctypes.byref(c[1]), ctypes.byref(c[2]), float(q_x),
+                                        float(q_v), int(k), float(gamma), int(d_o), int(d_L), ctypes.byref(out[0]),
+                                        ctypes.byref(out[1]), ctypes.byref(out[2])))
+    return dict(sigma_fp=out[0].value, sigma_bp=out[1].value, omega=out[2].value)

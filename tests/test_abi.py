@@ -14,7 +14,10 @@ U = P(4100)            # misaligned
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "qsync.h")).read()
+    inc = os.path.join(ROOT, "include")
+    headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
+    assert "qsync.h" in headers
+    header = "\n".join(open(os.path.join(inc, f)).read() for f in headers)
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(qsync_[a-z0-9_]+)\s*\(", header))
     assert {"qsync_absmax_scale", "qsync_quantize", "qsync_qlinear_fwd", "qsync_qlinear_bwd",
@@ -305,3 +308,87 @@ def test_absmax_quantize_validation():
     assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, None, 0, -1, None) == qsync.ERR_WORKSPACE
     assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, A, need - 1, -1, None) == qsync.ERR_WORKSPACE
     assert f(A, 0, 64, 128, 8, 0, 0, 0, A, A, None, A, None, U, need, -1, None) == qsync.ERR_ALIGN
+
+
+# ---- qsync_variance_increment: a host function, so it is exercised in full here (no GPU needed) ----
+class _Stats:
+    def __init__(self, sumsq, amax, D):
+        self.sumsq, self.amax, self.D = sumsq, amax, D
+
+
+def test_variance_increment_hand_computed_cases():
+    """The library's indicator on the cases worked out by hand from Prop. 3's two case equations (Indicator
+    section): small integers, distinct values for every tensor, so that a swapped tensor, a dropped factor or a
+    mixed-up branch changes the result.  Independent of the oracle: the expected numbers are typed in here."""
+    x, v, g = _Stats(2.0, 1.0, 3), _Stats(5.0, 2.5, 7), _Stats(11.0, 0.3, 7)       # exponents 0, 1, -2
+    r = qsync.qsync_variance_increment(qsync.QUANT_FIXED, x, v, g, 0.5, 0.25, 3, 2.0, 3, 10)
+    s_fp = (2.0 * 0.0625 * 7 + 5.0 * 0.25 * 3) / 6
+    s_bp = (11.0 * 0.0625 * 7 + 5.0 * (2.0 ** -4) * (2.0 ** -6) * 7) / 6
+    assert r["sigma_fp"] == pytest.approx(s_fp, rel=1e-14) and r["sigma_bp"] == pytest.approx(s_bp, rel=1e-14)
+    assert r["omega"] == pytest.approx(4.0 * 3 * s_fp + 7 * s_bp, rel=1e-14)
+    r = qsync.qsync_variance_increment(qsync.QUANT_FLOAT, x, v, g, 0.0, 0.0, 3, 1.0, 2, 5)
+    s_fp = (2.0 ** -6) * (2.0 * 4.0 * 7 + 5.0 * 1.0 * 3) / 6
+    s_bp = (2.0 ** -6) * (11.0 * 4.0 * 7 + 5.0 * (2.0 ** -4) * 7) / 6
+    assert r["sigma_fp"] == pytest.approx(s_fp, rel=1e-14) and r["sigma_bp"] == pytest.approx(s_bp, rel=1e-14)
+    assert r["omega"] == pytest.approx(2 * s_fp + 3 * s_bp, rel=1e-14)
+
+
+def test_variance_increment_matches_the_oracle_on_random_statistics():
+    import numpy as np
+    from oracle import qsync_oracle as orc
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        st = []
+        for _t in range(3):
+            amax = float(np.exp(rng.uniform(-12, 6)))
+            st.append(dict(sumsq=float(rng.uniform(0.1, 1e4)), amax=amax, e=orc.effective_exponent(amax),
+                           D=int(rng.integers(1, 1 << 24))))
+        st[int(rng.integers(0, 3))]["amax"] = float(2.0 ** int(rng.integers(-8, 8)))     # exact powers of two too
+        for t in st:
+            t["e"] = orc.effective_exponent(t["amax"])
+        q_x, q_v = float(rng.uniform(1e-4, 1e-1)), float(rng.uniform(1e-4, 1e-1))
+        k, gamma = int(rng.integers(2, 12)), float(rng.uniform(0.5, 2.0))
+        d_o = int(rng.integers(0, 20)); d_L = d_o + int(rng.integers(0, 30))
+        for kind, name in ((qsync.QUANT_FIXED, "fixed"), (qsync.QUANT_FLOAT, "float")):
+            got = qsync.qsync_variance_increment(kind, *[_Stats(t["sumsq"], t["amax"], t["D"]) for t in st], q_x, q_v, k,
+                                                 gamma, d_o, d_L)
+            want = orc.variance_increment(name, *st, q_x=q_x, q_v=q_v, eps=2.0 ** -k, gamma=gamma, d_o=d_o, d_L=d_L)
+            for key in ("sigma_fp", "sigma_bp", "omega"):
+                assert got[key] == pytest.approx(want[key], rel=1e-12), (name, key)
+    # an all-zero tensor sits in the smallest normal binade of binary32 on both sides
+    z = dict(sumsq=0.0, amax=0.0, e=-126, D=16)
+    one = dict(sumsq=3.0, amax=1.5, e=0, D=16)
+    got = qsync.qsync_variance_increment(qsync.QUANT_FLOAT, _Stats(3.0, 1.5, 16), _Stats(0.0, 0.0, 16), _Stats(3.0, 1.5, 16),
+                                         0, 0, 9, 1.0, 1, 2)
+    want = orc.variance_increment("float", one, z, one, eps=2.0 ** -9, d_o=1, d_L=2)
+    assert got["omega"] == pytest.approx(want["omega"], rel=1e-12)
+
+
+def test_variance_increment_validation():
+    f = lib.qsync_variance_increment
+    S = qsync.TensorStatsC
+    ok = S(1.0, 1.0, 4)
+    out = ctypes.c_double()
+    call = lambda kind, a, b, c, qx, qv, k, gamma, do, dl, o=out: f(kind, ctypes.byref(a) if a is not None else None,
+                                                                    ctypes.byref(b) if b is not None else None,
+                                                                    ctypes.byref(c) if c is not None else None, qx, qv, k, gamma, do,
+                                                                    dl, None, None, ctypes.byref(o) if o is not None else None)
+    assert call(0, ok, ok, ok, 0.1, 0.1, 9, 1.0, 1, 2) == qsync.OK
+    assert call(0, None, ok, ok, 0.1, 0.1, 9, 1.0, 1, 2) == qsync.ERR_NULL
+    assert call(0, ok, ok, ok, 0.1, 0.1, 9, 1.0, 1, 2, None) == qsync.ERR_NULL
+    assert call(2, ok, ok, ok, 0.1, 0.1, 9, 1.0, 1, 2) == qsync.ERR_BAD_ENUM
+    assert call(0, S(-1.0, 1.0, 4), ok, ok, 0.1, 0.1, 9, 1.0, 1, 2) == qsync.ERR_BAD_SHAPE
+    assert call(0, ok, S(1.0, float("inf"), 4), ok, 0.1, 0.1, 9, 1.0, 1, 2) == qsync.ERR_BAD_SHAPE
+    assert call(0, ok, ok, S(1.0, 1.0, -4), 0.1, 0.1, 9, 1.0, 1, 2) == qsync.ERR_BAD_SHAPE
+    assert call(0, ok, ok, ok, 0.1, 0.1, 9, 1.0, 3, 2) == qsync.ERR_BAD_SHAPE
+    assert call(0, ok, ok, ok, 0.1, 0.1, 0, 1.0, 1, 2) == qsync.ERR_UNSUPPORTED
+    assert call(0, ok, ok, ok, -0.1, 0.1, 9, 1.0, 1, 2) == qsync.ERR_UNSUPPORTED
+    assert call(1, ok, ok, ok, -0.1, 0.1, 9, 1.0, 1, 2) == qsync.OK            # the scales are ignored for the float kind
+
+
+def test_backward_with_an_empty_batch_needs_no_workspace():
+    """M = 0 with a bias gradient requested: no column-sum workspace is touched (the call clears db with a small
+    kernel); without a GPU the launch itself fails, the argument check must not."""
+    rc = lib.qsync_qlinear_bwd(qsync.INT8, 0, 64, 32, None, None, None, None, None, None, None, 0, None, 0, None, 0, A, A, 0,
+                               None, None, None, 0, None)
+    assert rc in (qsync.OK, qsync.ERR_HIP)

@@ -181,7 +181,7 @@ def run_conv_operator(act, w, bias, dy, w_gran, dy_round="stochastic", seed=5, v
     assert_bits_equal(host(op.wflip), flipped, "mirrored backward codes")
     assert_bits_equal(host(op.acc_dx), ref["acc_dx"], "dgrad accumulators")
     assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "wgrad accumulators")
-    assert_close(host(op.dx), ref["dx"], "dX", rtol=2e-3)
+    assert_close(host(op.dx), ref["dx"], "dX")
     assert_close(host(op.dw), ref["dw"], "dW")
     assert_close(host(op.db), ref["db"], "db")
     assert not ref["overflow"]
@@ -203,6 +203,25 @@ def test_conv_operator_fp16_forward_and_dgrad():
     op.backward(dev(dy))
     ref = orc.conv3x3_operator_fwd_bwd(orc.FP16, act, w, bias, dy, y_dtype=np.float64, dx_dtype=np.float64,
                                        dw_dtype=np.float64)
+    assert_bits_equal(host(op.wq), ref["wq"], "cast weights")
+    assert_close(host(op.y), ref["y"], "Y")
+    assert_close(host(op.dx), ref["dx"], "dX")
+    assert_close(host(op.dw), ref["dw"], "dW")
+
+
+def test_config3_resnet_conv_implicit_full_size_fp16_tag():
+    """Config 3 as a convolution with the FP16 precision tag at full size: implicit forward and data gradient,
+    weight gradient over the padded pixel axis."""
+    case = wl.config3()
+    b, h, wd, c = case.nhwc.shape
+    n = case.w.shape[0]
+    say("config3 conv fp16 tag full size")
+    op = QConv3x3(Q.FP16, b, h, wd, c, n, x_dtype=torch.float16, y_dtype=torch.float16, dx_dtype=torch.float16)
+    op.bias.copy_(dev(case.bias))
+    op.forward(dev(case.nhwc), dev(case.w))
+    op.backward(dev(case.dy))
+    ref = orc.conv3x3_operator_fwd_bwd(orc.FP16, case.nhwc, case.w, case.bias, case.dy, y_dtype=np.float64,
+                                       dx_dtype=np.float64, dw_dtype=np.float64)
     assert_bits_equal(host(op.wq), ref["wq"], "cast weights")
     assert_close(host(op.y), ref["y"], "Y")
     assert_close(host(op.dx), ref["dx"], "dX")

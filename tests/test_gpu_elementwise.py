@@ -237,11 +237,11 @@ def test_indicator_from_device_statistics_matches_oracle():
     sw, sv, sg = ind.tensor_stats(dev(w)), ind.tensor_stats(dev(v)), ind.tensor_stats(dev(g))
     ow, ov, og = orc.tensor_stats(w), orc.tensor_stats(v), orc.tensor_stats(g)
     for got, want in ((sw, ow), (sv, ov), (sg, og)):
-        assert got.amax == want["amax"] and got.e == want["e"] and got.D == want["D"]
+        assert got.amax == want["amax"] and got.D == want["D"]
         assert abs(got.sumsq - want["sumsq"]) <= 1e-4 * want["sumsq"]
     q_x, q_v = ow["amax"] / 127, ov["amax"] / 127
     for kind in ("fixed", "float"):
-        a = ind.variance_increment(kind, sw, sv, sg, q_x=q_x, q_v=q_v, eps=2.0 ** -9, gamma=1.5, d_o=3, d_L=24)
+        a = ind.variance_increment(kind, sw, sv, sg, q_x=q_x, q_v=q_v, k=9, gamma=1.5, d_o=3, d_L=24)
         b = orc.variance_increment(kind, ow, ov, og, q_x=q_x, q_v=q_v, eps=2.0 ** -9, gamma=1.5, d_o=3, d_L=24)
         for k in ("sigma_fp", "sigma_bp", "omega"):
             assert a[k] == pytest.approx(b[k], rel=2e-4), (kind, k)
@@ -355,6 +355,35 @@ def test_dequantize(adt, ydt):
     y = empty((20, 40), TORCH[ydt])
     Q.qsync_dequantize(dev(a)[:, 4:44], 20, 40, 64, None, None, 0.5, None, y)
     assert_close(host(y), a[:, 4:44] * 0.5, "dequantize strided")
+
+
+def test_dequantize_to_binary16_rounds_the_exact_product_once():
+    """int8 codes times one binary32 scale, binary16 output: the result is the exact product rounded once, bit
+    for bit, also on inputs where rounding to binary32 first would give the other neighbour."""
+    rng = np.random.default_rng(3)
+    n = 1 << 18
+    scales = (rng.uniform(0.5, 1.0, size=n).astype(np.float32) * np.float32(2.0 ** -7))
+    codes = rng.integers(-127, 128, size=n).astype(np.int8)
+    twice = (codes.astype(np.float32) * scales).astype(np.float16)
+    want = orc.dequantize(codes.reshape(-1, 1), 1.0, row_scale=scales, out_dtype=np.float16)
+    assert (want.reshape(-1).view(np.uint16) != twice.view(np.uint16)).sum() >= 3
+    say("dequantize once-rounded, per-row scales")
+    y = empty((n, 1), torch.float16)
+    Q.qsync_dequantize(dev(codes.reshape(-1, 1)), n, 1, 1, dev(scales), None, 1.0, None, y)
+    assert_bits_equal(host(y), want, "per-row scale")
+    # the same pairs with the scale along the columns (the vector kernel), and a tensor scale held on the device
+    rows = 64
+    a = np.tile(codes[:4096].reshape(1, -1), (rows, 1))
+    want = orc.dequantize(a, 1.0, col_scale=scales[:4096], out_dtype=np.float16)
+    y = empty((rows, 4096), torch.float16)
+    Q.qsync_dequantize(dev(a), rows, 4096, 4096, None, dev(scales[:4096]), 1.0, None, y)
+    assert_bits_equal(host(y), want, "per-column scale")
+    for i in np.flatnonzero(want[0].view(np.uint16) != twice[:4096].view(np.uint16))[:3]:
+        a1 = rng.integers(-127, 128, size=(48, 272)).astype(np.int8)
+        a1[0, 0] = codes[i]
+        y = empty(a1.shape, torch.float16)
+        Q.qsync_dequantize(dev(a1), 48, 272, 272, None, None, 1.0, None, y, tensor_scale_dev_opt=dev(scales[i:i + 1]))
+        assert_bits_equal(host(y), orc.dequantize(a1, float(scales[i]), out_dtype=np.float16), "tensor scale on the device")
 
 
 def test_empty_tensors_are_noops():

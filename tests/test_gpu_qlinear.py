@@ -18,14 +18,19 @@ TORCH = {np.dtype(np.float32): torch.float32, np.dtype(np.float16): torch.float1
 
 
 def run_case(case: wl.LinearCase, tag: int, y_dtype=np.float32, dx_dtype=np.float16, dw_dtype=np.float32,
-             check_codes=True):
-    """Runs one operator fwd+bwd on the GPU and compares every stage with the oracle."""
+             check_codes=True, dump_acc=True):
+    """Runs one operator fwd+bwd on the GPU and compares every stage with the oracle.
+
+    dump_acc=True asks the INT8 GEMMs for their raw int32 accumulators (compared bit for bit); a GEMM that
+    dumps takes the element-wise store path.  dump_acc=False is the production launch (what the benchmark
+    times): dequantize in registers, staged 16-byte stores, no accumulators in memory; Y, dX, dW, db are then
+    compared element by element with the oracle to the output tolerance."""
     M, N, K = case.mnk
     say(case.name, "tag", tag, "MNK", M, N, K, "w_gran", case.w_gran, "dy_round", case.dy_round)
     op = QLinear(tag, M, N, K, x_dtype=TORCH[case.x.dtype], w_dtype=TORCH[case.w.dtype],
                  dy_dtype=TORCH[case.dy.dtype], y_dtype=TORCH[np.dtype(y_dtype)], dx_dtype=TORCH[np.dtype(dx_dtype)],
                  dw_dtype=TORCH[np.dtype(dw_dtype)], w_gran=GRAN[case.w_gran], dy_round=RND[case.dy_round],
-                 philox_seed=case.philox_seed, dump_acc=True)
+                 philox_seed=case.philox_seed, dump_acc=dump_acc)
     op.offset = 12345
     op.bias.copy_(dev(case.bias))
     xd, wd, dyd = dev(case.x), dev(case.w), dev(case.dy)
@@ -47,9 +52,12 @@ def run_case(case: wl.LinearCase, tag: int, y_dtype=np.float32, dx_dtype=np.floa
             assert_bits_equal(host(op.wqbT), ref["wqb"].T, "wqbT")
             assert_bits_equal(host(op.dyq), ref["dyq"], "dyq")
             assert_bits_equal(host(op.dyqT), ref["dyq"].T, "dyqT")
-        assert_bits_equal(host(op.acc), ref["acc"], "fwd accumulators")
-        assert_bits_equal(host(op.acc_dx), ref["acc_dx"], "dX accumulators")
-        assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "dW accumulators")
+        if dump_acc:
+            assert_bits_equal(host(op.acc), ref["acc"], "fwd accumulators")
+            assert_bits_equal(host(op.acc_dx), ref["acc_dx"], "dX accumulators")
+            assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "dW accumulators")
+        else:
+            assert op.acc is None and op.acc_dx is None and op.acc_dw is None
     elif check_codes:
         assert_bits_equal(host(op.xq), ref["xq"], "x cast")
         assert_bits_equal(host(op.wqbT), ref["wq"].T, "w cast transposed")
@@ -84,6 +92,27 @@ def test_every_gemm_tile_shape_on_ragged_operators(tile, tag):
         for (m, n, k) in [(208, 144, 272), (528, 272, 400), (16, 16, 2064), (1040, 784, 528), (48, 2064, 64)]:
             case = wl.ragged_case(m, n, k, seed=m + n + k + tile, dtype=np.float16 if tag != Q.FP32 else np.float32)
             run_case(case, tag, y_dtype=np.float16 if tag == Q.FP16 else np.float32)
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
+
+
+@pytest.mark.parametrize("ydt,dxdt,dwdt", [(np.float16, np.float16, np.float32), (np.float32, np.float32, np.float16)])
+def test_production_epilogue_on_ragged_shapes_int8(ydt, dxdt, dwdt):
+    """INT8 without accumulator dumps: the staged-store epilogue (and the split-K reduction) on ragged shapes
+    whose row lengths are 16-byte multiples in both output types, planner's choice of tile."""
+    for (m, n, k) in [(64, 64, 64), (208, 144, 272), (272, 528, 144), (528, 272, 400), (16, 16, 2064), (1040, 784, 528),
+                      (48, 2064, 64)]:
+        case = wl.ragged_case(m, n, k, seed=m + n + k + 9, dtype=np.float16)
+        run_case(case, Q.INT8, y_dtype=ydt, dx_dtype=dxdt, dw_dtype=dwdt, dump_acc=False)
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2])
+def test_production_epilogue_every_tile_shape_int8(tile):
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        for (m, n, k) in [(208, 144, 272), (528, 272, 400), (1040, 784, 528), (48, 2064, 64), (784, 1040, 272)]:
+            case = wl.ragged_case(m, n, k, seed=m + n + k + tile + 17, dtype=np.float16)
+            run_case(case, Q.INT8, y_dtype=np.float16, dump_acc=False)
     finally:
         Q.qsync_debug_set_gemm_tile(-1)
 
@@ -139,6 +168,10 @@ def test_fp32_tag_any_shape_forward_and_backward():
 
 def test_config2_bert_base_ffn_full_size():
     run_case(wl.config2(), Q.INT8, y_dtype=np.float16)
+
+
+def test_config2_bert_base_ffn_full_size_production_epilogue():
+    run_case(wl.config2(), Q.INT8, y_dtype=np.float16, dump_acc=False)
 
 
 def test_config2_fp32_outputs_and_split_k_paths():
@@ -243,18 +276,38 @@ def test_config4_mixed_precision_mlp_chain(tokens, epilogue_maxima):
 
 @pytest.mark.parametrize("which", ["up", "down"])
 def test_config5_bert_large_full_size_int8(which):
-    """Full-size BERT-large-scale linears in the launch configuration the benchmark times."""
+    """Full-size BERT-large-scale linears with the raw accumulators of all three GEMMs compared bit for bit
+    (a GEMM that dumps its accumulators stores element-wise)."""
     case = wl.config5()[which]
     run_case(case, Q.INT8, y_dtype=np.float16)
 
 
-def test_config5_fp16_tag_full_size():
-    run_case(wl.config5()["up"], Q.FP16, y_dtype=np.float16, check_codes=False)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config5_bert_large_full_size_int8_as_benchmarked(which):
+    """The launch configuration the benchmark times: no accumulator dumps, so every GEMM leaves through the
+    production epilogue (dequantize in registers, staged stores; split-K reduction for dW).  Y, dX, dW and db
+    element by element against the oracle; codes and scales bit for bit."""
+    case = wl.config5()[which]
+    run_case(case, Q.INT8, y_dtype=np.float16, dump_acc=False)
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config5_fp16_tag_full_size(which):
+    run_case(wl.config5()[which], Q.FP16, y_dtype=np.float16)
 
 
 def test_config3_resnet_conv_full_size_int8():
     """M = 200704: split-K dW over a contraction of 200704, HBM-bound forward and dX."""
     run_case(wl.config3(), Q.INT8, y_dtype=np.float16)
+
+
+def test_config3_resnet_conv_full_size_int8_production_epilogue():
+    run_case(wl.config3(), Q.INT8, y_dtype=np.float16, dump_acc=False)
+
+
+def test_config3_resnet_conv_full_size_fp16_tag():
+    """Config 3 with the FP16 precision tag at full size (M = 200704), cast operands compared bit for bit."""
+    run_case(wl.config3(), Q.FP16, y_dtype=np.float16)
 
 
 def run_case_fp16_backward(case: wl.LinearCase, y_dtype=np.float32):
@@ -271,7 +324,7 @@ def run_case_fp16_backward(case: wl.LinearCase, y_dtype=np.float32):
                                dx_dtype=np.float64, dw_dtype=np.float64, bwd_tag=Q.FP16)
     assert_bits_equal(host(op.xq), ref["xq"], "xq")
     assert_bits_equal(host(op.wq), ref["wq"], "wq")
-    # dequantized binary16 operands: one fp32 product rounded to binary16 on both sides
+    # dequantized binary16 operands: the exact product code * scale rounded once to binary16
     assert_bits_equal(host(op.xhT), ref["xh"].T, "x_hat transposed")
     assert_bits_equal(host(op.wh), ref["wh"], "w_hat")
     assert_bits_equal(host(op.whT), ref["wh"].T, "w_hat transposed")
