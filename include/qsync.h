@@ -100,6 +100,22 @@ int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64
 size_t qsync_absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
 
 /*
+ * qsync_absmax_scale_static - qsync_absmax_scale for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+ * Per-tensor granularity only; same results as qsync_absmax_scale(..., QSYNC_PER_TENSOR, ...), bit for bit.
+ * The scratch (arrival counter, block partials, column-sum partials) is a device array inside the library,
+ * about 8.4 MB per GPU, held until the process ends; its device address is looked up on the first call on each
+ * device.  The call allocates and frees nothing and clears its counter with a kernel (no memset node).
+ * Limit: with colsum_opt, cols <= 4096 (QSYNC_ERR_WORKSPACE beyond: the partials would not fit); without it any
+ * size.  All calls on one GPU share that GPU's scratch: calls that may overlap (different streams, or
+ * different threads) race and give undefined results; serialise them or use qsync_absmax_scale with separate
+ * workspaces.  Other arguments and errors as for qsync_absmax_scale.
+ */
+int qsync_absmax_scale_static(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int bits,
+                              float* scale, float* inv_scale, float* amax_opt, float* colsum_opt,
+                              float* sumsq_opt, void* stream);
+
+/*
  * qsync_quantize - precision conversion of one tensor under a precision tag.
  * Paper: Indicator section (x_bar = (x - z)/q, x_hat = round(x_bar) q + z, stochastic
  * rounding as the unbiased quantizer), Cost Mapper (casting kernels), Backend section.

@@ -96,6 +96,30 @@ int qsync_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64
                                           sumsq_opt, workspace, static_cast<hipStream_t>(stream)));
 }
 
+int qsync_absmax_scale_static(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int bits, float* scale,
+                              float* inv_scale, float* amax_opt, float* colsum_opt, float* sumsq_opt, void* stream)
+{
+    if(!x || !scale || !inv_scale) return QSYNC_ERR_NULL;
+    if(!is_float_dtype(xdt)) return QSYNC_ERR_BAD_ENUM;
+    if(!count_ok(rows, cols) || ld < cols || !count_ok(rows, ld)) return QSYNC_ERR_BAD_SHAPE;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    // the library's own scratch holds the column-sum partials of at most kStaticMaxCols columns
+    if(colsum_opt && cols > kStaticMaxCols) return QSYNC_ERR_WORKSPACE;
+    if(rows == 0 || cols == 0) return QSYNC_OK;
+    if(absmax_workspace_bytes(rows, colsum_opt ? cols : 0, kPerTensor) > kStaticScratchBytes) return QSYNC_ERR_WORKSPACE;
+    void*      ws = nullptr;
+    hipError_t e  = static_scratch(&ws);
+    if(e != hipSuccess) return hip_status(e);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the arrival counter must start at zero whatever an earlier call left behind (cleared by a kernel, not by a
+    // memset node, so that the call can be captured into a graph)
+    e = launch_zero_f32(static_cast<float*>(ws), 64, st);
+    if(e != hipSuccess) return hip_status(e);
+    const float qmax = static_cast<float>((1 << (bits - 1)) - 1);
+    return hip_status(launch_absmax_scale(x, xdt, rows, cols, ld, kPerTensor, qmax, scale, inv_scale, amax_opt, colsum_opt,
+                                          sumsq_opt, ws, st));
+}
+
 int qsync_quantize(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int tag, int bits, int gran,
                    int rnd, uint64_t philox_seed, uint64_t philox_offset, const float* inv_scale, void* q_opt,
                    void* qT_opt, void* stream)

@@ -9,6 +9,8 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <mutex>
+
 #include <type_traits>
 
 namespace qsync {
@@ -1427,6 +1429,34 @@ hipError_t launch_scale_from_amax(float* amax, float qmax, float* scale, float* 
 {
     scale_from_amax_kernel<<<dim3(1), dim3(64), 0, st>>>(amax, qmax, scale, inv_scale, consume);
     return hipGetLastError();
+}
+
+// ---- scratch that the library owns: for the entry point that may not allocate ---------------------------------
+// One array per GPU (every device that loads this code object holds its own copy at its own address), kept
+// until the process ends.  Host code must never pass the array's name to a kernel: that name is a host-side
+// stand-in.  The device address is looked up once per device and handed to the kernels like any workspace.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void** ptr_out)
+{
+    constexpr int      kMaxDevices = 64;
+    static std::mutex  lock;
+    static void*       per_device[kMaxDevices] = {};
+    int                dev = -1;
+    hipError_t         e   = hipGetDevice(&dev);
+    if(e != hipSuccess) return e;
+    if(dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(lock);
+    if(!per_device[dev])
+    {
+        void* p = nullptr;
+        e       = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if(e != hipSuccess) return e;
+        if(!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr_out = per_device[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran, float qmax,

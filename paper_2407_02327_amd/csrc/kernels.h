@@ -16,6 +16,12 @@ enum Round { kNearest = 0, kStochastic = 1, kFloor = 2 };
 constexpr int kAbsmaxMaxBlocks = 2048;  // per-tensor stage-1 partials
 constexpr int kColParts = 512;          // most stage-1 partials per column of a per-column reduction
 size_t absmax_workspace_bytes(int64_t rows, int64_t cols, int gran);
+// Library-owned scratch (a file-scope device array, one copy per GPU) for qsync_absmax_scale_static: large enough
+// for a per-tensor pass with fused column sums over kStaticMaxCols columns.
+constexpr int64_t kStaticMaxCols      = 4096;
+constexpr size_t  kStaticScratchBytes = 256 + sizeof(float) * (2 * kAbsmaxMaxBlocks + static_cast<size_t>(kColParts) * kStaticMaxCols);
+// device address of the calling thread's current GPU's copy (looked up on first use per device)
+hipError_t static_scratch(void** ptr_out);
 hipError_t launch_scale_from_amax(float* amax, float qmax, float* scale, float* inv_scale, int consume, hipStream_t st);
 hipError_t launch_absmax_scale(const void* x, int xdt, int64_t rows, int64_t cols, int64_t ld, int gran,
                                float qmax, float* scale, float* inv_scale, float* amax_opt,

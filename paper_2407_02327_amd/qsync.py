@@ -31,6 +31,7 @@ _vp, _i, _i64, _u64, _sz, _f = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, c
 SIGNATURES = {
     "qsync_absmax_scale": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qsync_absmax_workspace_bytes": (_sz, [_i64, _i64, _i]),
+    "qsync_absmax_scale_static": (_i, [_vp, _i, _i64, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "qsync_quantize": (_i, [_vp, _i, _i64, _i64, _i64, _i, _i, _i, _i, _u64, _u64, _vp, _vp, _vp, _vp]),
     "qsync_qlinear_fwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "qsync_absmax_quantize": (_i, [_vp, _i, _i64, _i64, _i, _i, ctypes.c_uint64, ctypes.c_uint64, _vp, _vp, _vp, _vp, _vp,
@@ -116,6 +117,12 @@ def qsync_absmax_scale(x, rows, cols, ld, gran, bits, scale, inv_scale, amax_opt
     _check(lib.qsync_absmax_scale(_ptr(x), dtype_code(x), rows, cols, ld, gran, bits, _ptr(scale), _ptr(inv_scale),
                                   _ptr(amax_opt), _ptr(colsum_opt), _ptr(sumsq_opt), _ptr(workspace),
                                   _bytes(workspace), _stream(stream)))
+
+
+def qsync_absmax_scale_static(x, rows, cols, ld, bits, scale, inv_scale, amax_opt, colsum_opt, sumsq_opt,
+                              stream=None) -> None:
+    _check(lib.qsync_absmax_scale_static(_ptr(x), dtype_code(x), rows, cols, ld, bits, _ptr(scale), _ptr(inv_scale),
+                                         _ptr(amax_opt), _ptr(colsum_opt), _ptr(sumsq_opt), _stream(stream)))
 
 
 def qsync_quantize(x, rows, cols, ld, tag, bits, gran, rnd, philox_seed, philox_offset, inv_scale, q_opt, qT_opt,

@@ -392,3 +392,14 @@ def test_backward_with_an_empty_batch_needs_no_workspace():
     rc = lib.qsync_qlinear_bwd(qsync.INT8, 0, 64, 32, None, None, None, None, None, None, None, 0, None, 0, None, 0, A, A, 0,
                                None, None, None, 0, None)
     assert rc in (qsync.OK, qsync.ERR_HIP)
+
+
+def test_static_scratch_absmax_validation():
+    f = lib.qsync_absmax_scale_static
+    assert f(None, 0, 4, 4, 4, 8, A, A, None, None, None, None) == qsync.ERR_NULL
+    assert f(A, 0, 4, 4, 4, 8, None, A, None, None, None, None) == qsync.ERR_NULL
+    assert f(A, qsync.I8, 4, 4, 4, 8, A, A, None, None, None, None) == qsync.ERR_BAD_ENUM
+    assert f(A, 0, 4, 4, 3, 8, A, A, None, None, None, None) == qsync.ERR_BAD_SHAPE
+    assert f(A, 0, 4, 4, 4, 1, A, A, None, None, None, None) == qsync.ERR_UNSUPPORTED
+    assert f(A, 0, 4, 4097, 4097, 8, A, A, None, A, None, None) == qsync.ERR_WORKSPACE      # column sums beyond the scratch
+    assert f(A, 0, 0, 4097, 4097, 8, A, A, None, None, None, None) == qsync.OK              # empty: no-op
