@@ -120,6 +120,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (known traffic) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled")
+    ap.add_argument("--gemm-persistent", default="auto", choices=["auto", "0", "1"],
+                    help="tuning: 1 launches the persistent 256x256 GEMM kernel whenever a GEMM is eligible (default: never)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -127,8 +129,10 @@ def main():
 
     import torch
     from paper_2407_02327_amd.build import ensure_built
-    ensure_built()                                   # loads what is built; compiles only when there is no library at all
+    ensure_built(rebuild_if_stale=True)              # a library older than its sources is rebuilt (or the run fails)
     from paper_2407_02327_amd import qsync as Q
+    if args.gemm_persistent != "auto":
+        Q.qsync_debug_set_gemm_persistent(int(args.gemm_persistent))
     from paper_2407_02327_amd.operator import QLinear
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

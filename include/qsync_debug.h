@@ -37,6 +37,15 @@ int qsync_probe_mfma(int tag, int random_operands, int iters, void* out, double*
  */
 void qsync_debug_set_gemm_tile(int tile);
 
+/*
+ * qsync_debug_set_gemm_persistent - for tests and tuning runs, per calling thread: 0 = never launch the
+ * persistent 256x256 GEMM kernel, 1 = launch it whenever a problem is eligible (binary16 output, M and N
+ * multiples of 256, operand rows multiples of 256 bytes, no accumulator dump, no output maximum), any other
+ * value = the default, which is 0 as well: the kernel is opt-in.  Results are the same bits either way for
+ * int8 operands; binary16 operands sum in the same order, too.
+ */
+void qsync_debug_set_gemm_persistent(int mode);
+
 #ifdef __cplusplus
 }
 #endif

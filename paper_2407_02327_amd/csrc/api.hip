@@ -460,6 +460,7 @@ int qsync_probe_mfma(int tag, int random_operands, int iters, void* out, double*
 }
 
 void qsync_debug_set_gemm_tile(int tile) { set_gemm_tile_override(tile); }
+void qsync_debug_set_gemm_persistent(int mode) { set_gemm_persistent_mode(mode); }
 
 int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,
                       const float* sx, const void* wq, const float* sw, int wgran, const float* bias_opt, void* y,

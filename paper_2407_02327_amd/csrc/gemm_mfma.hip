@@ -49,6 +49,8 @@ typedef unsigned v4u32 __attribute__((ext_vector_type(4)));
 constexpr int kRowBytes   = 128;  // K bytes per tile row and per LDS row
 constexpr int kChunks     = 8;    // 16-byte chunks per LDS row
 constexpr int kNumXcd     = 8;
+constexpr int kNumCu      = 256;  // compute units of the target: one persistent workgroup each
+constexpr int kPersistentLdsBytes = 159744;   // two 64 KB stages, hand-over area, column parameters
 constexpr int kGroupM     = 8;    // tile rows walked together
 
 struct I8Traits
@@ -696,6 +698,323 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Persistent variant of the 256x256 kernel for binary16 outputs whose M, N are multiples of 256 and whose operand
+// rows are multiples of two K tiles.  One workgroup per compute unit walks its tiles; three things differ from
+// gemm_nt_kernel:
+//   * the wavefronts split the vector-memory roles.  Loads and stores of a wavefront share one in-flight counter
+//     that retires in issue order, so a wavefront that has just stored its part of C cannot see a later load
+//     land before those stores have reached the cache, microseconds later.  Wavefronts 0-3 (one per SIMD, the
+//     upper half of the tile) therefore issue every direct global->LDS load and never store; wavefronts 4-7 (the
+//     lower half) issue every store of C and never load.  The loaders pass their dequantized half through LDS;
+//   * the next tile's first K tile is requested while the last K tile of the current one is still being
+//     multiplied (its stage is free by then), the second one as soon as the storers have drained the hand-over
+//     area (which is the other stage plus the spare LDS behind the stages); nobody waits for a store, so the
+//     write-back of a tile overlaps the next tile's K loop;
+//   * barriers are bare s_barrier instructions behind an LDS wait (the compiler's __syncthreads would wait for
+//     every vector-memory operation of the wavefront, stores included), and every LDS access behind the first
+//     store is written as an instruction for the same reason.
+typedef unsigned v2u32 __attribute__((ext_vector_type(2)));
+typedef float    v2f32 __attribute__((ext_vector_type(2)));
+typedef _Float16 v2f16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_lds_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); __builtin_amdgcn_sched_barrier(0); }
+// LDS accesses as instructions; OFF is the instruction's immediate byte offset (16 bits)
+template <int OFF> __device__ __forceinline__ void lds_write_b64(uint32_t addr, const v2u32& v)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "immediate offset");
+    asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ void lds_write_b32(uint32_t addr, uint32_t v) { asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory"); }
+template <int OFF> __device__ __forceinline__ void lds_read_b128(v4u32& d, uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "immediate offset");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
+}
+// bit patterns by value (a vector element is not an object a bit cast could be applied to directly)
+template <typename T> __device__ __forceinline__ T word_as(uint32_t u);
+template <> __device__ __forceinline__ int32_t word_as<int32_t>(uint32_t u) { return static_cast<int32_t>(u); }
+template <> __device__ __forceinline__ float   word_as<float>(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t as_word(int32_t v) { return static_cast<uint32_t>(v); }
+__device__ __forceinline__ uint32_t as_word(float v) { return __float_as_uint(v); }
+template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <typename TR>
+__global__ __launch_bounds__(512) void gemm_nt_persistent_kernel(const GemmKernelArgs p, const int total_tiles)
+{
+    typedef typename TR::accv_t accv_t;
+    constexpr int BM = 256, BN = 256, WGN = 4, WTM = 128, WTN = 64, FM = 4, FN = 2;
+    constexpr int STAGE_BYTES = (BM + BN) * kRowBytes;        // 64 KB
+    constexpr int DPW         = 16;                           // direct loads per loader wavefront and K tile
+    constexpr int PITCH       = WTN * 2 + 16;                 // padded row of 64 binary16 outputs in the hand-over area
+    constexpr int L_STG       = WTM * PITCH;                  // a loader's whole sub-tile
+    constexpr int S_STG       = 32 * PITCH;                   // a storer's private slice: one row of fragments
+    constexpr int STG_BASE    = STAGE_BYTES;                  // the hand-over area starts where stage 1 starts
+    constexpr int S_BASE      = STG_BASE + 4 * L_STG;
+    constexpr int COLP_BASE   = S_BASE + 4 * S_STG;           // [2][BN] floats: alpha * column scale, column bias
+    static_assert(COLP_BASE + 2 * BN * 4 <= kPersistentLdsBytes, "LDS layout");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t*)lds));
+    const int  tid = threadIdx.x, lane = tid % kWaveSize;
+    const int  wave = __builtin_amdgcn_readfirstlane(tid / kWaveSize);
+    const int  wm = wave / WGN, wn = wave % WGN;
+    const bool loader = wave < 4;                              // uniform per wavefront
+    const int  KT = static_cast<int>(p.Kb / kRowBytes);        // even, >= 2 (checked by the launcher)
+    const int  G  = static_cast<int>(gridDim.x);
+
+    // ---- loader set-up: wavefront l covers stage rows [128 l, 128 l + 128): l = 0, 1 rows of A, l = 2, 3 rows of B
+    const int  lw   = wave & 3;
+    const bool is_a = lw < 2;
+    uint32_t   voff[DPW];
+    {
+        int imm[DPW];
+        fill_dma_imms<DPW>(imm, std::make_integer_sequence<int, DPW>{});
+#pragma unroll
+        for(int d = 0; d < DPW; ++d)
+        {
+            const int srow  = (lw * DPW + d) * 8 + lane / 8;
+            const int chunk = (lane % 8) ^ ((srow >> 1) & 7);
+            const int lrow  = srow - (is_a ? 0 : BM);
+            voff[d] = static_cast<uint32_t>(static_cast<int64_t>(lrow) * p.Kb + chunk * 16 + kDmaBias - imm[d]);
+        }
+    }
+    auto panel_base = [&](int tm, int tn) -> const uint8_t* {
+        const uint8_t* g = is_a ? p.A + static_cast<int64_t>(tm) * BM * p.Kb : p.B + static_cast<int64_t>(tn) * BN * p.Kb;
+        const uint64_t bits = reinterpret_cast<uint64_t>(g) - kDmaBias;
+        const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(bits))));
+        const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(bits >> 32))));
+        return reinterpret_cast<const uint8_t*>((static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo));
+    };
+    auto dma = [&](int stage, const uint8_t* sbase, int kt) {
+        const uint8_t* sb    = sbase + static_cast<int64_t>(kt) * kRowBytes;
+        uint8_t*       lbase = lds + stage * STAGE_BYTES + lw * (DPW * 1024) + (dma_group<DPW>() / 2) * 1024;
+        asm volatile("" : "+s"(sb));
+        dma_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, sb, voff, lbase);
+    };
+    auto park_column_parameters = [&](int tn) {               // threads 0..255 are exactly the loaders
+        float alpha = 1.0f;
+        if(p.s0) alpha *= *p.s0;
+        if(p.s1) alpha *= *p.s1;
+        const int64_t col = static_cast<int64_t>(tn) * BN + tid;
+        const float   sc  = alpha * (p.col_scale ? p.col_scale[col] : 1.0f);
+        const float   bi  = p.col_bias ? p.col_bias[col] : 0.0f;
+        lds_write_b32(lds0 + COLP_BASE + tid * 4, __float_as_uint(sc));
+        lds_write_b32(lds0 + COLP_BASE + (BN + tid) * 4, __float_as_uint(bi));
+    };
+
+    // ---- fragment reads (as in gemm_nt_kernel)
+    const int frag_row = lane & 31, khalf = lane >> 5;
+    int       roff[4];
+#pragma unroll
+    for(int ks = 0; ks < 4; ++ks) roff[ks] = frag_row * kRowBytes + swizzle(frag_row, ks * 2 + khalf);
+    const int a_base = (wm * WTM) * kRowBytes, b_base = BM * kRowBytes + (wn * WTN) * kRowBytes;
+    v4i32     af[2][FM], bf[2][FN];
+    auto      load_frags = [&](auto buf_tag, int stage, int ks) {
+        constexpr int  buf = decltype(buf_tag)::value;
+        const uint32_t fa  = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + a_base + roff[ks]);
+        const uint32_t fb  = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + b_base + roff[ks]);
+        frag_reads<FM>(af[buf], fa, std::make_integer_sequence<int, FM>{});
+        frag_reads<FN>(bf[buf], fb, std::make_integer_sequence<int, FN>{});
+    };
+    constexpr int kWaitOlderSet = 0xC07F | ((FM + FN) << 8);
+    accv_t        acc[FM][FN];
+    auto          mma = [&](auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for(int i = 0; i < FM; ++i)
+#pragma unroll
+            for(int j = 0; j < FN; ++j) acc[i][j] = TR::mfma(bf[buf][j], af[buf][i], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto clear_acc = [&]() {
+#pragma unroll
+        for(int i = 0; i < FM; ++i)
+#pragma unroll
+            for(int j = 0; j < FN; ++j)
+#pragma unroll
+                for(int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+    };
+    const std::integral_constant<int, 0> set0{};
+    const std::integral_constant<int, 1> set1{};
+
+    // ---- first tile: both stages requested, column parameters parked, first K tile awaited
+    int lin = static_cast<int>(blockIdx.x);
+    int split_unused, tm, tn;
+    item_of_block(lin, p.tiles_m, p.tiles_n, 1, split_unused, tm, tn);
+    const uint8_t* cur = panel_base(tm, tn);
+    if(loader)
+    {
+        dma(0, cur, 0);
+        dma(1, cur, 1);
+        park_column_parameters(tn);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    wg_barrier();
+
+    while(true)
+    {
+        __builtin_amdgcn_sched_barrier(0);     // the accumulators' live range starts here, not before the last tile's stores
+        clear_acc();
+        const int  nlin     = lin + G;
+        const bool has_next = nlin < total_tiles;
+        int        ntm = 0, ntn = 0;
+        if(has_next) item_of_block(nlin, p.tiles_m, p.tiles_n, 1, split_unused, ntm, ntn);
+        const uint8_t* nxt = has_next ? panel_base(ntm, ntn) : cur;
+
+        // ---- K loop.  On entry K tile 0 is in stage 0 and published, K tile 1 is in flight towards stage 1.
+        load_frags(set0, 0, 0);
+        load_frags(set1, 0, 1);
+        for(int kt = 0; kt < KT; ++kt)
+        {
+            const int stage = kt & 1;
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set0);
+            load_frags(set0, stage, 2);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set1);
+            load_frags(set1, stage, 3);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set0);
+            const bool more = kt + 1 < KT;
+            if(more)
+            {
+                // the loaders' K tile kt+1 has landed, everybody's reads of this stage have returned
+                if(loader) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                wg_barrier();
+                if(loader)
+                {
+                    if(kt + 2 < KT) dma(stage, cur, kt + 2);
+                    else if(has_next) dma(stage, nxt, 0);        // kt + 2 == KT: stage 0, first K tile of the next tile
+                }
+            }
+            // on the last K tile the reads below fetch chunks 0 and 1 of the current stage again: in bounds, unused
+            const int nstage = more ? (stage ^ 1) : stage;
+            load_frags(set0, nstage, 0);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            mma(set1);
+            load_frags(set1, nstage, 1);
+        }
+
+        // ---- epilogue.  Stage 1 (last K tile) is drained once everybody passes this barrier.
+        wg_barrier();
+        const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
+        // where this wavefront's dequantized rows go: a loader fills its whole 128-row region, a storer its
+        // private 32-row slice, pass by pass (the storer's base steps back by one pass per pass, so that both
+        // use the same immediates)
+        const uint32_t my_stg  = lds0 + (loader ? STG_BASE + wave * L_STG : S_BASE + (wave - 4) * S_STG);
+        const uint32_t wr_lane = my_stg + static_cast<uint32_t>(frag_row * PITCH + 8 * khalf);
+        const uint32_t cp_lane = lds0 + COLP_BASE + static_cast<uint32_t>((wn * WTN + 4 * khalf) * 4);
+        const int      lr8 = lane / 8, seg = lane % 8;
+        const uint32_t rd_lane = static_cast<uint32_t>(lr8 * PITCH + seg * 16);
+        const int64_t  wcol0 = n0 + wn * WTN;
+        __half* const  cbase = static_cast<__half*>(p.C) + wcol0 + seg * 8;
+        // alpha * column scale and bias of this lane's 2 x 16 columns, read once per tile
+        v4u32 rs[FN][4], rb[FN][4];
+        static_for<FN>([&](auto jt) {                         // (a batch of 8 reads per fragment column: the LDS counter holds 15)
+            constexpr int j = decltype(jt)::value;
+            static_for<4>([&](auto vt) {
+                constexpr int vq = decltype(vt)::value;
+                lds_read_b128<(j * 32 + 8 * vq) * 4>(rs[j][vq], cp_lane);
+                lds_read_b128<(BN + j * 32 + 8 * vq) * 4>(rb[j][vq], cp_lane);
+            });
+            wait_lds_all();
+        });
+        static_for<FM>([&](auto it) {
+            constexpr int  i       = decltype(it)::value;
+            const uint32_t wr_base = loader ? wr_lane : wr_lane - static_cast<uint32_t>(i * 32 * PITCH);
+            static_for<FN>([&](auto jt) {
+                constexpr int j = decltype(jt)::value;
+                static_for<4>([&](auto vt) {
+                    constexpr int vq = decltype(vt)::value;
+                    float y[4];
+#pragma unroll
+                    for(int e = 0; e < 4; ++e)
+                        y[e] = fmaf(static_cast<float>(acc[i][j][vq * 4 + e]), __uint_as_float(rs[j][vq][e]),
+                                    __uint_as_float(rb[j][vq][e]));
+                    // two values per conversion instruction (round to nearest even, as the scalar conversion)
+                    const v2f16 lo = __builtin_convertvector(v2f32{y[0], y[1]}, v2f16);
+                    const v2f16 hi = __builtin_convertvector(v2f32{y[2], y[3]}, v2f16);
+                    const v2u32 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    lds_write_b64<i * 32 * PITCH + (j * 32 + 8 * vq) * 2>(wr_base, packed);
+                });
+            });
+            if(!loader)
+            {   // the storer's own rows leave right away: written by this wavefront, read back transposed
+                wait_lds_all();
+                v4u32 val[4];
+                static_for<4>([&](auto qt) { lds_read_b128<decltype(qt)::value * 8 * PITCH>(val[decltype(qt)::value], my_stg + rd_lane); });
+                wait_lds_all();
+#pragma unroll
+                for(int q = 0; q < 4; ++q)
+                {
+                    const int64_t row = m0 + WTM + i * 32 + q * 8 + lr8;
+                    __builtin_nontemporal_store(val[q], reinterpret_cast<v4u32*>(cbase + row * p.N));
+                }
+            }
+        });
+        wg_barrier();                                        // the loaders' rows are in the hand-over area
+        // The storers take the partner's sub-tile (same columns, the upper half of the tile) out of the hand-over
+        // area into registers, so that the area is free again after one more barrier and the loaders' request for
+        // the next tile's second K tile enters the memory pipeline ahead of the stores that follow.
+        // (The 64 registers are those of the accumulators, dead by now: a separate array would raise the kernel's
+        // register demand and the compiler would spill the results of the LDS instructions before they arrive.)
+        if(!loader)
+        {
+            const uint32_t src = lds0 + STG_BASE + static_cast<uint32_t>((wave - 4) * L_STG) + rd_lane;
+            static_for<2>([&](auto bt) {                       // two batches: the LDS counter of a wavefront holds 15
+                constexpr int b = decltype(bt)::value;
+                v4u32 t[8];
+                static_for<8>([&](auto rt) { lds_read_b128<(b * 8 + decltype(rt)::value) * 8 * PITCH>(t[decltype(rt)::value], src); });
+                wait_lds_all();
+                static_for<8>([&](auto rt) {
+                    constexpr int r = b * 8 + decltype(rt)::value;
+#pragma unroll
+                    for(int e = 0; e < 4; ++e)
+                        {
+                        const uint32_t word = t[decltype(rt)::value][e];
+                        acc[r / 4][0][4 * (r % 4) + e] = word_as<typename TR::acc_t>(word);
+                    }
+                });
+            });
+        }
+        if(loader && has_next)
+        {
+            park_column_parameters(ntn);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the next tile's first K tile has landed
+        }
+        wg_barrier();                                        // hand-over area drained, stage 0 and parameters published
+        if(loader && has_next) dma(1, nxt, 1);
+        if(!loader)
+        {
+#pragma unroll
+            for(int r = 0; r < 16; ++r)
+            {
+                const int64_t row = m0 + r * 8 + lr8;
+                v4u32         val;
+#pragma unroll
+                for(int e = 0; e < 4; ++e)
+                {
+                    const typename TR::acc_t a = acc[r / 4][0][4 * (r % 4) + e];
+                    val[e] = as_word(a);
+                }
+                __builtin_nontemporal_store(val, reinterpret_cast<v4u32*>(cbase + row * p.N));
+            }
+        }
+        if(!has_next) break;
+        lin = nlin; tm = ntm; tn = ntn; cur = nxt;
+    }
+}
+
+
 // Adds the split-K partials in split order and applies the epilogue.
 constexpr int kThreads = 256;   // split-K reduction
 
@@ -842,12 +1161,38 @@ hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStrea
     }
 }
 
+// The persistent kernel serves full 256x256 tiles with binary16 output and nothing optional in the epilogue.
+bool persistent_eligible(const GemmKernelArgs& a, int prec, int tile, int splits)
+{
+    return (prec == 8 || prec == 16) && tile == 0 && splits == 1 && a.c_is_f16 && !a.acc_dump && !a.amax_bits && a.conv_H == 0
+        && a.remap_C == 0 && a.M % 256 == 0 && a.N % 256 == 0 && a.Kb % (2 * kRowBytes) == 0 && a.Kb >= 2 * kRowBytes
+        && (reinterpret_cast<uintptr_t>(a.C) & 15) == 0;
+}
+
+template <typename TR> hipError_t launch_persistent(const GemmKernelArgs& a, hipStream_t st)
+{
+    static bool      attr_set = false;      // per instantiation; benign if set twice
+    const void*      fn = reinterpret_cast<const void*>(&gemm_nt_persistent_kernel<TR>);
+    if(!attr_set)
+    {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kPersistentLdsBytes);
+        if(e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int total = a.tiles_m * a.tiles_n;
+    const int grid  = total < kNumCu ? total : kNumCu;
+    gemm_nt_persistent_kernel<TR><<<dim3(static_cast<unsigned>(grid)), dim3(512), kPersistentLdsBytes, st>>>(a, total);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t stream);   // gemm_f32.hip
 
 static thread_local int g_tile_override = -1;     // set by tests and tuning runs only; per calling thread
 void set_gemm_tile_override(int tile) { g_tile_override = (tile >= 0 && tile < kNumTiles) ? tile : -1; }
+static thread_local int g_persistent_mode = -1;   // 1: whenever eligible; anything else: never (the default, see launch_gemm)
+void set_gemm_persistent_mode(int mode) { g_persistent_mode = (mode == 0 || mode == 1) ? mode : -1; }
 
 GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits, bool allow_split)
 {
@@ -953,6 +1298,13 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     const TileShape ts = kTiles[plan.tile];
     a.tiles_m = static_cast<int>((p.M + ts.bm - 1) / ts.bm);
     a.tiles_n = static_cast<int>((p.N + ts.bn - 1) / ts.bn);
+    // The persistent kernel is opt-in.  Launched alone and back to back it beats the per-tile kernel by 7-20 % (the
+    // write-back of a tile overlaps the next tile's K loop), but inside an operator sequence its fixed tile
+    // assignment loses what it gains: workgroups that start late, behind the tail of the previous kernel, still
+    // walk their full share of tiles, while the per-tile grid is balanced by the hardware dispatcher.
+    if(persistent_eligible(a, p.prec, plan.tile, splits)
+       && g_persistent_mode == 1)
+        return p.prec == 8 ? launch_persistent<I8Traits>(a, stream) : launch_persistent<F16Traits>(a, stream);
     hipError_t e = p.prec == 8    ? launch_traits<I8Traits>(plan.tile, a, splits, stream)
                    : p.prec == 16 ? launch_traits<F16Traits>(plan.tile, a, splits, stream)
                                   : launch_traits<F32Traits>(plan.tile, a, splits, stream);

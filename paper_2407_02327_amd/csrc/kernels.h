@@ -111,6 +111,8 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile = -
                    bool allow_split = true);
 // tile >= 0 pins the tile shape of every later plan (tests, tuning); -1 returns the choice to the planner.
 void set_gemm_tile_override(int tile);
+// 1: launch the persistent 256x256 kernel whenever a problem is eligible; anything else: never (the default)
+void set_gemm_persistent_mode(int mode);
 hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspace, hipStream_t stream);
 
 // ---- measurement probe (probe.hip): matrix instructions on register operands, no memory traffic

@@ -46,6 +46,7 @@ SIGNATURES = {
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
     "qsync_debug_set_gemm_tile": (None, [_i]),
+    "qsync_debug_set_gemm_persistent": (None, [_i]),
     "qsync_conv3x3_wgrad": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "qsync_conv3x3_wgrad_workspace_bytes": (_sz, [_i, _i64, _i64, _i64, _i64, _i64]),
     "qsync_conv3x3_prepare_weights": (_i, [_vp, _i, _i64, _i64, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -209,6 +210,10 @@ def qsync_conv3x3_wgrad(tag, nimg, H, W, C, N, xq, sx, dyq, sdy, dw, acc_dump_op
 
 def qsync_debug_set_gemm_tile(tile: int) -> None:
     lib.qsync_debug_set_gemm_tile(tile)
+
+
+def qsync_debug_set_gemm_persistent(mode: int) -> None:
+    lib.qsync_debug_set_gemm_persistent(mode)
 
 
 def qsync_conv3x3_wflip(w, N, C, wflip, stream=None) -> None:

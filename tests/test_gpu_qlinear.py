@@ -455,3 +455,45 @@ def test_chained_operator_takes_its_scale_from_the_producers_epilogue():
     assert_bits_equal(host(cons.xq), ref["xq"], "xq")
     assert_bits_equal(host(cons.acc), ref["acc"], "accumulators")
     assert_close(host(cons.y), ref["y"], "Y")
+
+
+@pytest.mark.parametrize("tag", [Q.INT8, Q.FP16])
+def test_persistent_gemm_kernel_against_oracle_and_per_tile_kernel(tag):
+    """The persistent 256x256 kernel (loader / storer wavefronts, next tile prefetched behind the epilogue) on
+    outputs with fewer tiles than compute units, exactly as many, and more (some workgroups then walk two or
+    three tiles): Y against the oracle's contraction element by element, and bit for bit against the per-tile
+    kernel, which dequantizes with the same fused multiply-add."""
+    rng = np.random.default_rng(90)
+    try:
+        for (M, N, K) in [(256, 256, 256), (512, 768, 512), (4096, 4096, 256), (8192, 2304, 256), (4352, 4352, 768),
+                          (2816, 6656, 1280)]:
+            say("persistent gemm", tag, M, N, K)
+            bias = rng.standard_normal(N).astype(np.float32)
+            if tag == Q.INT8:
+                a = rng.integers(-127, 128, (M, K)).astype(np.int8)
+                b = rng.integers(-127, 128, (N, K)).astype(np.int8)
+                sx = np.array([0.004], np.float32)
+                sw = (rng.random(N) * 0.002 + 0.0005).astype(np.float32)
+                acc, ovf = orc.int_gemm_nt(a, b)
+                assert not ovf
+                want = acc.astype(np.float64) * float(sx[0]) * sw.astype(np.float64).reshape(1, -1) + bias.astype(np.float64)
+                args = (dev(a), dev(sx), dev(b), dev(sw), Q.PER_ROW)
+            else:
+                a = rng.standard_normal((M, K)).astype(np.float16)
+                b = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+                want = orc.float_gemm_nt(a, b) + bias.astype(np.float64)
+                args = (dev(a), None, dev(b), None, Q.PER_TENSOR)
+            w = torch.zeros(max(Q.qsync_qlinear_workspace_bytes(tag, M, N, K), 256), dtype=torch.uint8, device="cuda")
+            ys = []
+            for mode in (0, 1):
+                Q.qsync_debug_set_gemm_persistent(mode)
+                Q.qsync_debug_set_gemm_tile(0)
+                y = torch.full((M, N), 7.0, dtype=torch.float16, device="cuda")
+                Q.qsync_qlinear_fwd(tag, M, N, K, args[0], args[1], args[2], args[3], args[4], dev(bias), y, None, w)
+                ys.append(host(y))
+            assert_close(ys[1], want, "Y from the persistent kernel")
+            assert_close(ys[0], want, "Y from the per-tile kernel")
+            assert_bits_equal(ys[1], ys[0], "persistent against per-tile kernel")
+    finally:
+        Q.qsync_debug_set_gemm_persistent(-1)
+        Q.qsync_debug_set_gemm_tile(-1)
