@@ -23,10 +23,22 @@ sys.path.insert(0, ROOT)
 
 PEAK = {"int8": 5000.0, "fp16": 2500.0}          # dense MFMA peak of MI355X, TOP/s and TFLOP/s
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes per forward-GEMM launch (mean of the two forward launches of config 5, INT8, fp16 output),
-# from rocprofv3 --pmc FETCH_SIZE (x2.0) and WRITE_SIZE (x1.0), scaled by a plain 512 MiB copy:
-# see profiles/config5_int8_hbm_traffic.md.  (54.4 + 128.4 + 96.2 + 32.0) MiB / 2.
-MEASURED_FWD_GEMM_TRAFFIC_BYTES = {("c5", "int8", "f16"): int((54.4 + 128.4 + 96.2 + 32.0) / 2 * 2**20)}
+# HBM-side bytes per forward-GEMM launch come from the committed rocprofv3 --pmc summaries (FETCH_SIZE and
+# WRITE_SIZE, scaled by a plain 512 MiB copy): a line "forward_gemm_traffic_bytes_per_launch: N" in each file.
+TRAFFIC_PROFILE = {("c5", "int8", "f16"): "config5_int8_hbm_traffic.md", ("c5", "fp16", "f16"): "config5_fp16_hbm_traffic.md"}
+
+
+def measured_traffic(workload: str, tag: str, ydtype: str):
+    name = TRAFFIC_PROFILE.get((workload, tag, ydtype))
+    if name is None:
+        return None
+    try:
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if line.startswith("forward_gemm_traffic_bytes_per_launch:"):
+                return int(line.split(":")[1].strip())
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -91,7 +103,7 @@ def cpu_baseline(cases, tag, tokens: int):
                       f"incl. absmax/quantize, {dt:.1f} s"}
 
 
-def main():
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -122,11 +134,18 @@ def main():
                          "WRITE_SIZE readings can be scaled")
     ap.add_argument("--gemm-persistent", default="auto", choices=["auto", "0", "1"],
                     help="tuning: 1 launches the persistent 256x256 GEMM kernel whenever a GEMM is eligible (default: never)")
+    ap.add_argument("--no-fp16-pass", action="store_true",
+                    help="default run (config 5, tag int8): skip the second timed pass with tag fp16")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
         raise SystemExit(2)
+    return args
 
+
+def run(args):
+    """One timed pass (warm-up, K steps) of the workload under args.tag plus, unless args.no_extra_passes, the
+    untimed extra passes; returns the dictionary of the JSON line."""
     import torch
     from paper_2407_02327_amd.build import ensure_built
     ensure_built(rebuild_if_stale=True)              # a library older than its sources is rebuilt (or the run fails)
@@ -231,13 +250,15 @@ def main():
     for _ in range(args.warmup):
         step("none")
     torch.cuda.synchronize()
+    # (An event pair costs the stream about 3 us; with events around both forward GEMMs of every step that was
+    # 3 % of the step, so every fourth step carries them.)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step("gemm_fwd")
+    for i in range(args.steps):
+        step("gemm_fwd" if i % 4 == 0 else "none")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
-    fwd_ms = ev.totals()["gemm_fwd"][0] / args.steps
+    fwd_ms = ev.totals()["gemm_fwd"][0] / len(range(0, args.steps, 4))
 
     gemm_ops = sum(6 * c.mnk[0] * c.mnk[1] * c.mnk[2] for c in cases)          # three GEMMs, 2MNK each
     value = gemm_ops / (ms_per_step * 1e-3) / 1e12
@@ -351,7 +372,7 @@ def main():
         nset = max(2, int(math.ceil((512 << 20) / bytes_per)) + 1)
         sets = [(dy.clone(), torch.empty_like(op.dyq), torch.empty(Nq, Mq, dtype=op.dyq.dtype, device="cuda")) for _ in range(nset)]
         quant_iso = {"tensor": f"dY [{Mq},{Nq}] {str(dy.dtype).replace('torch.', '')}", "bytes": "read + codes + transposed codes",
-                     "sets_rotated_cold": nset}
+                     "bytes_per_launch": int(bytes_per), "sets_rotated_cold": nset}
         for rname, rnd in (("rtn", Q.ROUND_NEAREST), ("sr", Q.ROUND_STOCHASTIC)):
             for mode in ("cold", "warm"):
                 def one(i):
@@ -391,7 +412,8 @@ def main():
         dsets = [(torch.randint(-2**20, 2**20, (Mq, Nq), dtype=torch.int32, device="cuda"),
                   torch.empty(Mq, Nq, dtype=torch.float16, device="cuda")) for _ in range(nset)]
         csv_, cbv_ = torch.rand(Nq, device="cuda"), torch.rand(Nq, device="cuda")
-        dequant_iso = {"tensor": f"int32 accumulators [{Mq},{Nq}] -> float16, per-column scale + bias", "sets_rotated_cold": nset}
+        dequant_iso = {"tensor": f"int32 accumulators [{Mq},{Nq}] -> float16, per-column scale + bias",
+                       "bytes_per_launch": int(dq_bytes), "sets_rotated_cold": nset}
         for mode in ("cold", "warm"):
             def oned(i):
                 a_, y_ = dsets[i % nset] if mode == "cold" else dsets[0]
@@ -465,7 +487,7 @@ def main():
 
     out = {
         "metric": "qlinear fwd+bwd TOPS (whole step incl. absmax/quantize/dequantize)",
-        "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": round(value, 3), "unit": "TOPS" if args.tag == "int8" else "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.tag if args.tag == "int8" else "f16", "data": "synthetic",
         "config": {"workload": desc, "tag": args.tag, "y_dtype": args.ydtype, "dx_dtype": "f16", "dw_dtype": "f32",
@@ -475,10 +497,10 @@ def main():
                    "operator_streams": nstreams,
                    **({"conv_input": args.conv_input if (tag == Q.INT8 or args.conv_input == "implicit") else "patches"}
                       if any(c.nhwc is not None for c in cases) else {})},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches)",
-                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches; HIP events on every 4th timed step)",
+                     "achieved": round(achieved, 2), "peak": peak, "unit": "TOP/s" if args.tag == "int8" else "TFLOP/s",
                      "frac": round(achieved / peak, 4),
-                     "traffic": MEASURED_FWD_GEMM_TRAFFIC_BYTES.get((args.workload, args.tag, args.ydtype)),
+                     "traffic": measured_traffic(args.workload, args.tag, args.ydtype),
                      "algorithmic_bytes": int(sum((c.mnk[0] + c.mnk[1]) * c.mnk[2] * (1 if args.tag == "int8" else 2)
                                                   + c.mnk[0] * c.mnk[1] * (2 if args.ydtype == "f16" else 4)
                                                   for c in cases) / len(cases))},
@@ -496,11 +518,41 @@ def main():
         "model_order_dw_on_side_stream": model_order,
         "epilogue_maximum": epilogue_max,
     }
+    if quant_iso is not None:
+        # the HBM-bound kernels against the published 8 TB/s, cold (inputs and outputs rotated through > 512 MB)
+        out["roofline_quantize"] = {"bound": "hbm", "kernel": "quantize_patch_kernel, stochastic rounding, " + quant_iso["tensor"]
+                                    + ", codes + transposed codes, cold",
+                                    "achieved": quant_iso["sr_cold"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": quant_iso["sr_cold"]["frac_hbm"], "algorithmic_bytes": quant_iso["bytes_per_launch"]}
+        out["roofline_quantize_nearest"] = {"bound": "hbm", "kernel": "quantize_patch_kernel, round to nearest, " + quant_iso["tensor"]
+                                            + ", codes + transposed codes, cold",
+                                            "achieved": quant_iso["rtn_cold"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                            "frac": quant_iso["rtn_cold"]["frac_hbm"],
+                                            "algorithmic_bytes": quant_iso["bytes_per_launch"]}
+    if dequant_iso is not None:
+        out["roofline_dequantize"] = {"bound": "hbm", "kernel": "dequantize_cols_kernel, " + dequant_iso["tensor"] + ", cold",
+                                      "achieved": dequant_iso["cold"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                      "frac": dequant_iso["cold"]["frac_hbm"], "algorithmic_bytes": dequant_iso["bytes_per_launch"]}
     if "gemm_bwd" in per_step:
         out["gemm_only_TOPS"] = round(gemm_ops / ((per_step["gemm_fwd"] + per_step["gemm_bwd"]) * 1e-3) / 1e12, 2)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(cases, tag, args.cpu_tokens)
+    return out
+
+
+def main():
+    args = parse_args()
+    out = run(args)
+    # The metric names INT8 and FP16: the default run times the same workload a second time under the FP16 tag
+    # (its own warm-up and K steps, its own HIP events around the forward GEMMs) and reports it beside the INT8 line.
+    if args.tag == "int8" and args.workload == "c5" and args.bwd_tag is None and not args.no_fp16_pass:
+        import copy
+        a16 = copy.copy(args)
+        a16.tag, a16.no_cpu, a16.no_extra_passes = "fp16", True, True
+        o16 = run(a16)
+        out["fp16_tag"] = {k: o16[k] for k in ("metric", "value", "unit", "ms_per_step", "steps", "warmup", "dtype",
+                                               "config", "roofline")}
     print(json.dumps(out), flush=True)
 
 
