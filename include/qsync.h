@@ -271,6 +271,34 @@ size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 
 /*
+ * qsync_qlinear_bwd_fp16_of_int8 - backward of an INT8 operator the way the paper runs it: in FP16, on the
+ * dequantized codes the forward saved.  Paper: footnote of the Cost Mapper paragraph (integer backward is
+ * inefficient, the backward of fixed-point kernels is executed in FP16 and incurs additional casting);
+ * Indicator section (x_hat = code * q); Backend section (dW in FP32, dX in FP16).
+ *
+ *   x_hat^T = binary16(xqT * sx)            w_hat = binary16(wq * sw[n or 0])      dY16 = binary16(dY)
+ *   dX = dY16 w_hat      dW = dY16^T x_hat      db = sum_m dY         (fp32 accumulation)
+ *   Each binary16 operand is the exact product (or value) rounded once to nearest even.
+ *
+ * One call runs the dequantizers, the casts / transposes and both FP16 GEMMs (the per-operator tag of the
+ * backward is thereby a parameter of the C boundary, not of the caller's sequencing).
+ * dy    [M,N] of dydt (QSYNC_F32 or QSYNC_F16), 16-byte aligned; a binary16 gradient is used in place.
+ * xqT   [K,M] int8: the transposed activation codes the forward kept; sx 1 float.
+ * wq    [N,K] int8: the forward's weight codes; sw 1 float (wgran PER_TENSOR) or N floats (PER_ROW).
+ * dx_opt [M,K] of dxdt, dw_opt [N,K] of dwdt, db_opt N floats; each may be NULL (its inputs may then be NULL).
+ * workspace  at least qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M, N, K, dydt) bytes, 256-byte aligned
+ *        (QSYNC_ERR_WORKSPACE / QSYNC_ERR_ALIGN otherwise); it receives the binary16 operands.
+ * operand_offsets_opt  HOST array of 5 or NULL: byte offsets in the workspace of x_hat^T [K,M], w_hat [N,K],
+ *        w_hat^T [K,N], dY16 [M,N] (unused when dy is binary16) and dY16^T [N,M] (verification aid).
+ * FP16 alignment rules as for qsync_qlinear_bwd: N % 8 == 0 for dX, M % 8 == 0 for dW.
+ */
+int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* dy, int dydt,
+                                   const void* xqT, const float* sx, const void* wq, const float* sw, int wgran,
+                                   void* dx_opt, int dxdt, void* dw_opt, int dwdt, float* db_opt,
+                                   void* workspace, size_t workspace_bytes, size_t* operand_offsets_opt, void* stream);
+size_t qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(int64_t M, int64_t N, int64_t K, int dydt);
+
+/*
  * qsync_prepare_weights - every weight operand of one INT8 linear operator with per-output-channel
  * scales, from one call (paper: Cost Mapper paragraph, casting cost of the weights in the forward pass;
  * channel-wise weight quantization).  Equivalent to, and bit-identical with, the sequence

@@ -339,6 +339,80 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
     return QSYNC_OK;
 }
 
+// Workspace of qsync_qlinear_bwd_fp16_of_int8: binary16 operands of the FP16 backward, then the GEMMs' own scratch;
+// every part starts on a 256-byte boundary.
+namespace {
+struct Fp16BwdLayout { size_t off_xhT, off_wh, off_whT, off_dyh, off_dyhT, off_gemm, total; };
+Fp16BwdLayout fp16_bwd_layout(int64_t M, int64_t N, int64_t K, int dydt)
+{
+    Fp16BwdLayout l;
+    size_t at = 0;
+    auto take = [&](int64_t elems) { const size_t o = at; at += round256(static_cast<size_t>(elems) * 2); return o; };
+    l.off_xhT  = take(K * M);
+    l.off_wh   = take(N * K);
+    l.off_whT  = take(K * N);
+    l.off_dyh  = take(dydt == QSYNC_F16 ? 0 : M * N);          // a binary16 gradient is used in place
+    l.off_dyhT = take(N * M);
+    l.off_gemm = at;
+    l.total    = at + qsync_qlinear_bwd_workspace_bytes(QSYNC_FP16, M, N, K);
+    return l;
+}
+}  // namespace
+
+size_t qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(int64_t M, int64_t N, int64_t K, int dydt)
+{
+    if(M < 0 || N < 0 || K < 0 || !is_float_dtype(dydt) || !count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return 0;
+    return fp16_bwd_layout(M, N, K, dydt).total;
+}
+
+int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* dy, int dydt, const void* xqT,
+                                   const float* sx, const void* wq, const float* sw, int wgran, void* dx_opt, int dxdt,
+                                   void* dw_opt, int dwdt, float* db_opt, void* workspace, size_t workspace_bytes,
+                                   size_t* operand_offsets_opt, void* stream)
+{
+    if(!dy || !workspace) return !dy ? QSYNC_ERR_NULL : QSYNC_ERR_WORKSPACE;
+    if(dx_opt && (!wq || !sw)) return QSYNC_ERR_NULL;
+    if(dw_opt && (!xqT || !sx)) return QSYNC_ERR_NULL;
+    if(!is_float_dtype(dydt)) return QSYNC_ERR_BAD_ENUM;
+    if(dx_opt && (!is_float_dtype(dxdt) || (wgran != QSYNC_PER_TENSOR && wgran != QSYNC_PER_ROW))) return QSYNC_ERR_BAD_ENUM;
+    if(dw_opt && !is_float_dtype(dwdt)) return QSYNC_ERR_BAD_ENUM;
+    if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if((dx_opt && N % 8 != 0) || (dw_opt && M % 8 != 0) || !aligned16(dy)) return QSYNC_ERR_ALIGN;
+    const Fp16BwdLayout l = fp16_bwd_layout(M, N, K, dydt);
+    if(workspace_bytes < l.total) return QSYNC_ERR_WORKSPACE;
+    if((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return QSYNC_ERR_ALIGN;
+    if(operand_offsets_opt)
+    {   // where the binary16 operands lie in the workspace (host array of 5: xhT, wh, whT, dyh, dyhT)
+        const size_t offs[5] = {l.off_xhT, l.off_wh, l.off_whT, l.off_dyh, l.off_dyhT};
+        for(int i = 0; i < 5; ++i) operand_offsets_opt[i] = offs[i];
+    }
+    if(M == 0 || N == 0 || K == 0)
+        return qsync_qlinear_bwd(QSYNC_FP16, M, N, K, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                 QSYNC_PER_TENSOR, nullptr, dxdt, nullptr, dwdt, db_opt, dy, dydt, nullptr, nullptr,
+                                 static_cast<char*>(workspace) + l.off_gemm, workspace_bytes - l.off_gemm, stream);
+    hipStream_t st   = static_cast<hipStream_t>(stream);
+    char*       base = static_cast<char*>(workspace);
+    void *xhT = base + l.off_xhT, *wh = base + l.off_wh, *whT = base + l.off_whT, *dyhT = base + l.off_dyhT;
+    const void* dyh = dydt == QSYNC_F16 ? dy : base + l.off_dyh;
+    hipError_t e = hipSuccess;
+    if(dw_opt)      // x_hat^T = code * q_x narrowed to binary16, straight from the saved transposed codes
+        e = launch_dequantize(xqT, kI8, K, M, M, nullptr, nullptr, 1.0f, sx, nullptr, xhT, kF16, st);
+    if(e == hipSuccess && dx_opt)
+    {   // w_hat with the forward's scales (one per output channel, or one), then its transpose for dX
+        e = launch_dequantize(wq, kI8, N, K, K, wgran == QSYNC_PER_ROW ? sw : nullptr, nullptr, 1.0f,
+                              wgran == QSYNC_PER_ROW ? nullptr : sw, nullptr, wh, kF16, st);
+        if(e == hipSuccess) e = launch_convert(wh, kF16, N, K, K, kF16, nullptr, whT, st);
+    }
+    void* const dyh_out  = dydt == QSYNC_F16 ? nullptr : const_cast<void*>(dyh);
+    void* const dyhT_out = dw_opt ? dyhT : nullptr;
+    if(e == hipSuccess && (dyh_out || dyhT_out))      // dY narrowed to binary16 (or used in place) and transposed
+        e = launch_convert(dy, dydt == QSYNC_F16 ? kF16 : kF32, M, N, N, kF16, dyh_out, dyhT_out, st);
+    if(e != hipSuccess) return hip_status(e);
+    return qsync_qlinear_bwd(QSYNC_FP16, M, N, K, dyh, dyhT, nullptr, xhT, nullptr, whT, nullptr, QSYNC_PER_TENSOR, dx_opt, dxdt,
+                             dw_opt, dwdt, db_opt, dy, dydt, nullptr, nullptr, base + l.off_gemm, workspace_bytes - l.off_gemm,
+                             stream);
+}
+
 int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits, float* sw, float* iw, float* aw_opt,
                           void* wq, float* swb, float* iwb, void* wqbT, void* workspace, size_t workspace_bytes,
                           void* stream)

@@ -77,10 +77,11 @@ class QLinear:
         self.ws_fwd = _ws(Q.qsync_qlinear_workspace_bytes(tag, M, N, K), dev)
         self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(self.bwd_tag, M, N, K), dev)
         if self.bwd_tag != tag:
-            h = torch.float16
-            # binary16 operands of the FP16 backward: dequantized X^T, dequantized W and its transpose, cast dY
-            self.xhT, self.wh, self.whT = e(K, M, dt=h), e(N, K, dt=h), e(K, N, dt=h)
-            self.dyh, self.dyhT = e(M, N, dt=h), e(N, M, dt=h)
+            # FP16 backward of the INT8 forward: one C-ABI call; its workspace receives the binary16 operands
+            # (dequantized X^T, dequantized W and its transpose, cast dY and its transpose)
+            self.dy_dtype = dy_dtype
+            nb = Q.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M, N, K, Q._DTYPE_OF[dy_dtype])
+            self.ws_bwd16 = torch.zeros(max(nb, 256), dtype=torch.uint8, device=dev)
 
     # ---- precision conversion -----------------------------------------------------------
     def convert_x(self, x: torch.Tensor, stream=None, x_amax: Optional[torch.Tensor] = None) -> None:
@@ -138,20 +139,7 @@ class QLinear:
     def convert_dy(self, dy: torch.Tensor, stream=None) -> None:
         M, N, K = self.M, self.N, self.K
         if self.bwd_tag != self.tag:
-            # FP16 backward of the INT8 forward: x_hat = code * q narrowed to binary16 (straight from the saved
-            # transposed codes), w_hat likewise and then transposed, dY narrowed and transposed
-            Q.qsync_dequantize(self.xqT, K, M, M, None, None, 1.0, None, self.xhT, stream, tensor_scale_dev_opt=self.sx)
-            if self.w_gran == Q.PER_ROW:
-                Q.qsync_dequantize(self.wq, N, K, K, self.sw, None, 1.0, None, self.wh, stream)
-            else:
-                Q.qsync_dequantize(self.wq, N, K, K, None, None, 1.0, None, self.wh, stream, tensor_scale_dev_opt=self.sw)
-            Q.qsync_quantize(self.wh, N, K, K, Q.FP16, 0, 0, 0, 0, 0, None, None, self.whT, stream)
-            if dy.dtype == torch.float16 and dy.is_contiguous():
-                self.dyh = dy
-                Q.qsync_quantize(dy, M, N, N, Q.FP16, 0, 0, 0, 0, 0, None, None, self.dyhT, stream)
-            else:
-                Q.qsync_quantize(dy, M, N, N, Q.FP16, 0, 0, 0, 0, 0, None, self.dyh, self.dyhT, stream)
-            return
+            return          # the FP16 backward converts its operands inside its own call (gemm_bwd)
         if self.tag == Q.INT8:
             # the same pass over dY yields its absmax and the bias gradient db (column sums)
             Q.qsync_absmax_scale(dy, M, N, N, Q.PER_TENSOR, self.bits, self.sdy, self.idy, self.ady, self.db,
@@ -177,9 +165,7 @@ class QLinear:
 
     def gemm_bwd(self, dy: Optional[torch.Tensor], stream=None) -> None:
         if self.bwd_tag != self.tag:
-            Q.qsync_qlinear_bwd(Q.FP16, self.M, self.N, self.K, self.dyh, self.dyhT, None, self.xhT, None, self.whT, None,
-                                Q.PER_TENSOR, self.dx, self.dw, self.db if dy is not None else None, dy, None, None,
-                                self.ws_bwd, stream)
+            self._fp16_backward(dy, self.dx, self.dw, self.db, stream)
             return
         want_db = dy is not None and self.tag != Q.INT8      # INT8: db already came out of the absmax pass over dY
         Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
@@ -187,15 +173,26 @@ class QLinear:
                             self.dx, self.dw, self.db if want_db else None, dy if want_db else None, self.acc_dx,
                             self.acc_dw, self.ws_bwd, stream)
 
+    def _fp16_backward(self, dy, dx, dw, db, stream) -> None:
+        M, N, K = self.M, self.N, self.K
+        if not dy.is_contiguous():
+            dy = dy.contiguous()
+        offs = Q.qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, self.xqT, self.sx, self.wq, self.sw, self.w_gran, dx, dw, db,
+                                                self.ws_bwd16, stream)
+        h = torch.float16
+        view = lambda off, r, c: self.ws_bwd16[off:off + 2 * r * c].view(h).view(r, c)
+        # the binary16 operands as the call left them in its workspace (for inspection and tests)
+        self.xhT, self.wh, self.whT = view(offs[0], K, M), view(offs[1], N, K), view(offs[2], K, N)
+        self.dyh = dy if dy.dtype == h else view(offs[3], M, N)
+        self.dyhT = view(offs[4], N, M)
+
     def gemm_bwd_part(self, which: str, dy: Optional[torch.Tensor], stream=None) -> None:
         """One of the two independent backward GEMMs ("dx" or "dw", the latter with the bias gradient when the tag
         needs it from here), so that a caller can run them on different streams."""
         dx = self.dx if which == "dx" else None
         dw = self.dw if which == "dw" else None
         if self.bwd_tag != self.tag:
-            Q.qsync_qlinear_bwd(Q.FP16, self.M, self.N, self.K, self.dyh, self.dyhT, None, self.xhT, None, self.whT, None,
-                                Q.PER_TENSOR, dx, dw, self.db if (dy is not None and dw is not None) else None,
-                                dy if dw is not None else None, None, None, self.ws_bwd, stream)
+            self._fp16_backward(dy, dx, dw, self.db if dw is not None else None, stream)
             return
         want_db = dy is not None and self.tag != Q.INT8 and dw is not None
         Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,

@@ -42,6 +42,9 @@ SIGNATURES = {
     "qsync_qlinear_bwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i,
                                _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
+    "qsync_qlinear_bwd_fp16_of_int8": (_i, [_i64, _i64, _i64, _vp, _i, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _sz,
+                                           ctypes.POINTER(ctypes.c_size_t), _vp]),
+    "qsync_qlinear_bwd_fp16_of_int8_workspace_bytes": (_sz, [_i64, _i64, _i64, _i]),
     "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
@@ -171,6 +174,20 @@ def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, 
                                  F32 if dy_float_opt is None else dtype_code(dy_float_opt),
                                  _ptr(acc_dx_dump_opt), _ptr(acc_dw_dump_opt), _ptr(workspace), _bytes(workspace),
                                  _stream(stream)))
+
+
+def qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M: int, N: int, K: int, dy_dtype_code: int) -> int:
+    return int(lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M, N, K, dy_dtype_code))
+
+
+def qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, xqT, sx, wq, sw, wgran, dx_opt, dw_opt, db_opt, workspace, stream=None):
+    """Returns the five byte offsets of the binary16 operands inside the workspace (x_hat^T, w_hat, w_hat^T, dY16, dY16^T)."""
+    offs = (ctypes.c_size_t * 5)()
+    _check(lib.qsync_qlinear_bwd_fp16_of_int8(M, N, K, _ptr(dy), dtype_code(dy), _ptr(xqT), _ptr(sx), _ptr(wq), _ptr(sw), wgran,
+                                              _ptr(dx_opt), dtype_code(dx_opt) if dx_opt is not None else F32,
+                                              _ptr(dw_opt), dtype_code(dw_opt) if dw_opt is not None else F32, _ptr(db_opt),
+                                              _ptr(workspace), _bytes(workspace), offs, _stream(stream)))
+    return [int(o) for o in offs]
 
 
 def qsync_conv3x3_fwd(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt=None, stream=None) -> None:

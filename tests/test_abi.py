@@ -403,3 +403,29 @@ def test_static_scratch_absmax_validation():
     assert f(A, 0, 4, 4, 4, 1, A, A, None, None, None, None) == qsync.ERR_UNSUPPORTED
     assert f(A, 0, 4, 4097, 4097, 8, A, A, None, A, None, None) == qsync.ERR_WORKSPACE      # column sums beyond the scratch
     assert f(A, 0, 0, 4097, 4097, 8, A, A, None, None, None, None) == qsync.OK              # empty: no-op
+
+
+def test_fp16_backward_of_int8_forward_validation():
+    f = lib.qsync_qlinear_bwd_fp16_of_int8
+    need = lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(64, 32, 48, qsync.F32)
+    assert need >= 2 * (48 * 64 + 2 * 32 * 48 + 2 * 64 * 32)
+    assert lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(64, 32, 48, qsync.F16) < need      # binary16 dY is used in place
+    assert lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(64, 32, 48, qsync.I8) == 0
+    W = P(1 << 20)                                     # 256-byte aligned fake workspace
+    ok = (64, 32, 48, A, qsync.F32, A, A, A, A, qsync.PER_ROW, A, qsync.F16, A, qsync.F32, A, W, need, None, None)
+    chg = lambda **kw: tuple(kw.get(i, v) for i, v in zip("M N K dy dydt xqT sx wq sw wgran dx dxdt dw dwdt db ws wsb offs st".split(), ok))
+    assert f(*chg(dy=None)) == qsync.ERR_NULL
+    assert f(*chg(wq=None)) == qsync.ERR_NULL
+    assert f(*chg(sx=None)) == qsync.ERR_NULL
+    assert f(*chg(dydt=qsync.I8)) == qsync.ERR_BAD_ENUM
+    assert f(*chg(wgran=qsync.PER_COL)) == qsync.ERR_BAD_ENUM
+    assert f(*chg(M=-1)) == qsync.ERR_BAD_SHAPE
+    assert f(*chg(N=36)) == qsync.ERR_ALIGN            # dX contracts over N: multiple of 8
+    assert f(*chg(M=60)) == qsync.ERR_ALIGN            # dW contracts over M
+    assert f(*chg(dy=U)) == qsync.ERR_ALIGN
+    assert f(*chg(wsb=need - 1)) == qsync.ERR_WORKSPACE
+    assert f(*chg(ws=None)) == qsync.ERR_WORKSPACE
+    assert f(*chg(ws=P((1 << 20) + 16))) == qsync.ERR_ALIGN
+    offs = (ctypes.c_size_t * 5)()
+    assert f(*chg(offs=offs)) in (qsync.OK, qsync.ERR_HIP)          # valid call: only the launch can fail without a GPU
+    assert list(offs) == sorted(offs) and offs[0] == 0 and all(o % 256 == 0 for o in offs)
