@@ -433,6 +433,7 @@ def run(args):
     # Extra: the forward GEMM collecting max |Y| in its epilogue, against the pass over Y that a directly chained
     # consumer would otherwise need (forward GEMM + absmax of Y  vs  forward GEMM with the maximum + two divisions).
     epilogue_max = None
+    epilogue_codes = None
     if not args.no_extra_passes and tag == Q.INT8:
         lin_ops = [o for o in ops_objs if hasattr(o, "gemm_bwd_part")]
         if lin_ops:
@@ -462,6 +463,31 @@ def run(args):
                 torch.cuda.synchronize()
                 res[name] = round(e0.elapsed_time(e1) / 20 * 1e3, 1)
             epilogue_max = {"operator": "%dx%d->%d, Y %s" % (o.M, o.K, o.N, str(o.y.dtype).replace("torch.", "")), **res}
+            # the consumer's codes from the producer's epilogue against the consumer's own quantize pass over Y
+            # (row-major codes in both cases; scale given)
+            yq = torch.empty(o.M, o.N, dtype=torch.int8, device="cuda")
+            inv_ = torch.full((1,), 20.0, dtype=torch.float32, device="cuda")
+
+            def separate_q():
+                Q.qsync_qlinear_fwd(o.tag, o.M, o.N, o.K, o.xq, o.sx, o.wq, o.sw, o.w_gran, o.bias, o.y, None, o.ws_fwd, main)
+                Q.qsync_quantize(o.y, o.M, o.N, o.N, Q.INT8, 8, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, inv_, yq, None, main)
+
+            def fused_q():
+                Q.qsync_qlinear_fwd_codes(o.tag, o.M, o.N, o.K, o.xq, o.sx, o.wq, o.sw, o.w_gran, o.bias, o.y, 8, inv_, yq, None,
+                                          o.ws_fwd, main)
+
+            res = {}
+            for name, fn in (("gemm_then_quantize_us", separate_q), ("gemm_with_codes_us", fused_q)):
+                for _ in range(3):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(main)
+                for _ in range(20):
+                    fn()
+                e1.record(main)
+                torch.cuda.synchronize()
+                res[name] = round(e0.elapsed_time(e1) / 20 * 1e3, 1)
+            epilogue_codes = {"operator": epilogue_max["operator"], **res}
 
     # Extra (outside the timed region): a fully instrumented pass for the per-phase breakdown.
     per_step = {"gemm_fwd": fwd_ms}
@@ -517,6 +543,7 @@ def run(args):
         "hip_graph_replay": graph_replay,
         "model_order_dw_on_side_stream": model_order,
         "epilogue_maximum": epilogue_max,
+        "epilogue_codes": epilogue_codes,
     }
     if quant_iso is not None:
         # the HBM-bound kernels against the published 8 TB/s, cold (inputs and outputs rotated through > 512 MB)

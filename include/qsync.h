@@ -226,6 +226,38 @@ int qsync_qlinear_fwd_amax(int tag, int64_t M, int64_t N, int64_t K,
                            float* y_amax, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qsync_qlinear_fwd_codes - qsync_qlinear_fwd whose epilogue also writes the fixed-point codes of Y for the
+ * operator that consumes Y, so that the consumer's quantization pass (read Y, write codes) disappears.
+ * Paper: Cost Mapper paragraph (cvt_cost, the casting of an operator's input, is "non-negligible for all
+ * cases"; the output scaling factor is part of runtime fixed-point quantization); Backend section (work fused
+ * into the epilogue before the result leaves the kernel).
+ *
+ *   yq[m,n] = clamp(round(Y[m,n] * next_inv_scale[0]), -qmax, qmax),  qmax = 2^(bits-1) - 1
+ *   with Y as stored (after rounding to ydt), one fp32 multiply, ties to even: the same bits as
+ *   qsync_quantize(Y, ..., QSYNC_INT8, bits, QSYNC_PER_TENSOR, QSYNC_ROUND_NEAREST, ..., next_inv_scale, yq).
+ *
+ * A per-tensor scale needs the maximum of the whole of Y, which is not known while Y is being produced: the
+ * caller supplies the inverse scale (for instance from the maximum this call collected on the previous
+ * step) and may collect max |Y| of this step in y_amax_opt (semantics of qsync_qlinear_fwd_amax) to check
+ * that nothing was clamped (max |Y| * inv_scale <= qmax + 0.5) and to derive the next scale.
+ * next_inv_scale  device float.   yq  out [M,N] int8, packed.   bits 2..8.
+ * The consumer's transposed copy (needed for its weight gradient only) is qsync_transpose_i8 of yq.
+ * No accumulator dump; tag FP32 needs 16-byte aligned operands with K % 4 == 0 (QSYNC_ERR_UNSUPPORTED
+ * otherwise).  All other arguments, the workspace and errors as qsync_qlinear_fwd.
+ */
+int qsync_qlinear_fwd_codes(int tag, int64_t M, int64_t N, int64_t K,
+                            const void* xq, const float* sx,
+                            const void* wq, const float* sw, int wgran,
+                            const float* bias_opt, void* y, int ydt, int bits, const float* next_inv_scale,
+                            void* yq, float* y_amax_opt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * qsync_transpose_i8 - out[c, r] = in[r, c] for int8 codes (the K-contiguous operand layout of the backward
+ * GEMMs from row-major codes, see qsync_qlinear_bwd).  in [rows, cols], out [cols, rows], both packed, distinct.
+ */
+int qsync_transpose_i8(const void* in, int64_t rows, int64_t cols, void* out, void* stream);
+
+/*
  * qsync_scale_from_amax - scale = amax / qmax, inv_scale = qmax / amax (1 and 1 for amax == 0) from a
  * maximum already on the device, with the arithmetic of qsync_absmax_scale (PER_TENSOR); qmax = 2^(bits-1) - 1.
  * amax       device float (read; set to 0 afterwards if consume != 0).

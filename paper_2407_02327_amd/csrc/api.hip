@@ -189,7 +189,8 @@ size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t 
 
 static int qlinear_fwd_impl(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
                             const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt,
-                            float* y_amax_opt, void* workspace, size_t workspace_bytes, void* stream)
+                            float* y_amax_opt, void* workspace, size_t workspace_bytes, void* stream,
+                            void* yq_opt = nullptr, const float* yq_inv = nullptr, int yq_qmax = 127)
 {
     if(!xq || !wq || !y) return QSYNC_ERR_NULL;
     if(!is_tag(tag) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
@@ -225,6 +226,7 @@ static int qlinear_fwd_impl(int tag, int64_t M, int64_t N, int64_t K, const void
     }
     p.col_bias = bias_opt;
     p.out_amax_bits = reinterpret_cast<unsigned int*>(y_amax_opt);
+    p.out_codes = yq_opt; p.out_code_inv = yq_inv; p.out_code_qmax = yq_qmax;
     return hip_status(launch_gemm(p, plan, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -244,6 +246,29 @@ int qsync_qlinear_fwd_amax(int tag, int64_t M, int64_t N, int64_t K, const void*
     if((reinterpret_cast<uintptr_t>(y_amax) & 3u) != 0) return QSYNC_ERR_ALIGN;
     return qlinear_fwd_impl(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, ydt, acc_dump_opt, y_amax, workspace,
                             workspace_bytes, stream);
+}
+
+int qsync_qlinear_fwd_codes(int tag, int64_t M, int64_t N, int64_t K, const void* xq, const float* sx, const void* wq,
+                            const float* sw, int wgran, const float* bias_opt, void* y, int ydt, int bits,
+                            const float* next_inv_scale, void* yq, float* y_amax_opt, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if(!yq || !next_inv_scale) return QSYNC_ERR_NULL;
+    if(bits < 2 || bits > 8) return QSYNC_ERR_UNSUPPORTED;
+    if(y_amax_opt && (reinterpret_cast<uintptr_t>(y_amax_opt) & 3u) != 0) return QSYNC_ERR_ALIGN;
+    // fp32 operands whose rows are not 16-byte multiples run the any-shape kernel, which has no code output
+    if(tag == QSYNC_FP32 && ((K * 4) % 16 != 0 || !aligned16(xq) || !aligned16(wq))) return QSYNC_ERR_UNSUPPORTED;
+    return qlinear_fwd_impl(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, ydt, nullptr, y_amax_opt, workspace,
+                            workspace_bytes, stream, yq, next_inv_scale, (1 << (bits - 1)) - 1);
+}
+
+int qsync_transpose_i8(const void* in, int64_t rows, int64_t cols, void* out, void* stream)
+{
+    if(!in || !out) return QSYNC_ERR_NULL;
+    if(!count_ok(rows, cols)) return QSYNC_ERR_BAD_SHAPE;
+    if(in == out) return QSYNC_ERR_UNSUPPORTED;
+    return hip_status(launch_transpose_i8(static_cast<const int8_t*>(in), rows, cols, static_cast<int8_t*>(out),
+                                          static_cast<hipStream_t>(stream)));
 }
 
 int qsync_scale_from_amax(float* amax, int bits, float* scale, float* inv_scale, int consume, void* stream)

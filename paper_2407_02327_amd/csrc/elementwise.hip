@@ -1870,6 +1870,64 @@ size_t colsum_workspace_bytes(int64_t rows, int64_t cols)
     return sizeof(float) * static_cast<size_t>(kColParts) * static_cast<size_t>(cols > 0 ? cols : 0);
 }
 
+// ------------------------------------------------------------------ transpose of int8 codes
+// out[c, r] = in[r, c].  A lane owns a 16 x 16 byte patch: sixteen 16-byte loads, a byte transpose in registers,
+// sixteen 16-byte stores; a wavefront is 8 patches wide (128-byte row segments) and 8 patches high.
+__global__ __launch_bounds__(kBlock) void transpose_i8_patch_kernel(const int8_t* __restrict__ in, int64_t rows, int64_t cols,
+                                                                   int8_t* __restrict__ out, int64_t grid_x)
+{
+    const int     lane = threadIdx.x % kWaveSize, wave = threadIdx.x / kWaveSize;
+    const int64_t by = blockIdx.x / grid_x, bx = blockIdx.x - by * grid_x;
+    const int64_t r0 = (by * (kBlock / kWaveSize) + wave) * 128 + (lane / 8) * 16;
+    const int64_t c0 = bx * 128 + (lane % 8) * 16;
+    if(r0 >= rows || c0 >= cols) return;                   // rows and cols are multiples of 16: patches are whole
+    uint4 raw[16];
+#pragma unroll
+    for(int i = 0; i < 16; ++i) raw[i] = *reinterpret_cast<const uint4*>(in + (r0 + i) * cols + c0);
+#pragma unroll
+    for(int c = 0; c < 16; ++c)
+    {
+        uint32_t t[4];
+#pragma unroll
+        for(int g = 0; g < 4; ++g)
+        {
+            auto word = [&](int r) -> uint32_t {
+                const uint4& v = raw[r];
+                return (c / 4) == 0 ? v.x : (c / 4) == 1 ? v.y : (c / 4) == 2 ? v.z : v.w;
+            };
+            t[g] = byte_of(word(4 * g + 0), c % 4) | (byte_of(word(4 * g + 1), c % 4) << 8)
+                 | (byte_of(word(4 * g + 2), c % 4) << 16) | (byte_of(word(4 * g + 3), c % 4) << 24);
+        }
+        *reinterpret_cast<uint4*>(out + (c0 + c) * rows + r0) = make_uint4(t[0], t[1], t[2], t[3]);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void transpose_i8_generic_kernel(const int8_t* __restrict__ in, int64_t rows, int64_t cols,
+                                                                     int8_t* __restrict__ out)
+{
+    const int64_t n = rows * cols, stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for(int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride)
+    {
+        const int64_t r = i / cols, c = i - r * cols;
+        out[c * rows + r] = in[i];
+    }
+}
+
+hipError_t launch_transpose_i8(const int8_t* in, int64_t rows, int64_t cols, int8_t* out, hipStream_t stream)
+{
+    if(rows <= 0 || cols <= 0) return hipSuccess;
+    const int64_t gx = (cols + 127) / 128, gy = (rows + 128 * (kBlock / kWaveSize) - 1) / (128 * (kBlock / kWaveSize));
+    if(rows % 16 == 0 && cols % 16 == 0 && aligned16(in) && aligned16(out) && gx * gy < (int64_t(1) << 31))
+        transpose_i8_patch_kernel<<<dim3(static_cast<unsigned>(gx * gy)), dim3(kBlock), 0, stream>>>(in, rows, cols, out, gx);
+    else
+    {
+        int64_t nb = (rows * cols + kBlock - 1) / kBlock;
+        nb         = nb > 65536 ? 65536 : nb;
+        transpose_i8_generic_kernel<<<dim3(static_cast<unsigned>(nb)), dim3(kBlock), 0, stream>>>(in, rows, cols, out);
+    }
+    return hipGetLastError();
+}
+
 // Clears n floats with a kernel (a memset node recorded into a captured graph is avoided on purpose).
 __global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, int64_t n)
 {

@@ -117,6 +117,10 @@ struct GemmKernelArgs
     // optional: running maximum of |C| as stored (bit pattern of a non-negative fp32), raised with one atomic
     // maximum per workgroup
     unsigned int*  amax_bits;
+    // optional: fixed-point codes of C as stored, clamp(round(C * code_inv[0]), -code_qmax, code_qmax), [M][N] int8
+    int8_t*        codes;
+    const float*   code_inv;
+    int            code_qmax;
 };
 
 // Work item (K split, tile) of a workgroup.  Workgroups are dealt round-robin to the eight XCDs
@@ -474,6 +478,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         cp_bias  = (p.col_bias && cok) ? p.col_bias[col] : 0.0f;
     }
     const uint32_t amax_seen = (!SPLIT && p.amax_bits) ? __hip_atomic_load(p.amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+    const float    code_inv  = (!SPLIT && p.codes) ? *p.code_inv : 0.0f;
     const bool any_k = kt_begin < kt_end;
     if(any_k) dma(0, kt_begin);
     if(!SPLIT && tid < BN)
@@ -552,8 +557,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         constexpr bool RAW   = decltype(raw_tag)::value;
         constexpr int  OS    = sizeof(out_t);
         constexpr int  PITCH = WTN * OS + 16;                     // padded row pitch in the staging slice
-        constexpr int  FPP   = (STG_BYTES / (32 * PITCH)) >= FM ? FM : ((STG_BYTES / (32 * PITCH)) >= 2 ? 2 : 1);
-        static_assert(32 * PITCH <= STG_BYTES && FM % FPP == 0, "staging slice too small");
+        constexpr int  CPITCH = WTN + 16;                         // the same for the optional int8 codes of the rows
+        constexpr int  FITS  = STG_BYTES / (32 * (PITCH + CPITCH));
+        constexpr int  FPP   = FITS >= FM ? FM : (FITS >= 2 ? 2 : 1);
+        static_assert(32 * (PITCH + CPITCH) <= STG_BYTES && FM % FPP == 0, "staging slice too small");
+        uint8_t* const cstg  = stg + FPP * 32 * PITCH;            // codes behind the output rows
         constexpr int LPR   = WTN * OS / 16;                     // lanes per output row in the store phase
         constexpr int RPI   = 64 / LPR;                          // rows per store instruction
         __syncthreads();                                  // all wavefronts are done reading the stages
@@ -595,6 +603,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                             *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o);
                         else
                             *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
+                        if constexpr(!RAW)
+                            if(p.codes)
+                            {   // the quantizer's arithmetic on the value as stored (one fp32 multiply, ties to even, clamp)
+                                uint32_t cw = 0u;
+#pragma unroll
+                                for(int e = 0; e < 4; ++e)
+                                {
+                                    float stored;
+                                    if constexpr(OS == 2) stored = __half2float(o[e]); else stored = o[e];
+                                    cw |= (static_cast<uint32_t>(quantize_code<kNearest>(stored, code_inv, p.code_qmax, 0u)) & 0xFFu) << (8 * e);
+                                }
+                                *reinterpret_cast<uint32_t*>(cstg + (ii * 32 + frag_row) * CPITCH + (j * 32 + 8 * vq + 4 * khalf)) = cw;
+                            }
                     }
             }
             // Lanes read what other lanes of the wavefront have just written: the hardware keeps a
@@ -619,6 +640,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                         __builtin_nontemporal_store(val, dst);
                 }
             }
+            if constexpr(!RAW)
+                if(p.codes)
+                {   // rows of WTN code bytes leave as 16-byte vectors too
+                    constexpr int CLPR = WTN / 16, CRPI = 64 / CLPR;
+#pragma unroll
+                    for(int r0 = 0; r0 < FPP * 32; r0 += CRPI)
+                    {
+                        const int     lr  = r0 + lane / CLPR, seg = lane % CLPR;
+                        const v4u32   val = *reinterpret_cast<const v4u32*>(cstg + lr * CPITCH + seg * 16);
+                        const int64_t row = wrow0 + pass * FPP * 32 + lr;
+                        const int64_t col = wcol0 + seg * 16;
+                        if(lr < FPP * 32 && row < p.M && col < p.N)
+                            *reinterpret_cast<v4u32*>(p.codes + row * p.N + col) = val;      // read next by the consumer's GEMM
+                    }
+                }
         }
     };
 
@@ -647,7 +683,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     }
 
     const int osize = p.c_is_f16 ? 2 : 4;
-    const bool fast = !p.acc_dump && (p.N * osize) % 16 == 0 && (reinterpret_cast<uintptr_t>(p.C) & 15) == 0;
+    const bool fast = !p.acc_dump && (p.N * osize) % 16 == 0 && (reinterpret_cast<uintptr_t>(p.C) & 15) == 0
+                   && (!p.codes || (p.N % 16 == 0 && (reinterpret_cast<uintptr_t>(p.codes) & 15) == 0));
     if(!fast)
     {   // element-wise stores: any N, any alignment, optional raw accumulator dump
 #pragma unroll
@@ -665,18 +702,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                     const int64_t row = wrow0 + i * 32 + frag_row;
                     if(row < p.M && cok)
                     {
-                        const float y = static_cast<float>(acc[i][j][v]) * f + b;
-                        float       stored = y;
+                        // (the same expressions as the vector path: a binary16 output is the fused multiply-add rounded
+                        // once to binary16, which the compiler maps to one mixed-precision instruction)
+                        float stored;
                         if(p.c_is_f16)
                         {
-                            const __half h = __float2half_rn(y);
+                            const __half h = __float2half_rn(fmaf(static_cast<float>(acc[i][j][v]), f, b));
                             static_cast<__half*>(p.C)[row * p.N + col] = h;
                             stored = __half2float(h);
                         }
                         else
-                            static_cast<float*>(p.C)[row * p.N + col] = y;
+                        {
+                            stored = fmaf(static_cast<float>(acc[i][j][v]), f, b);
+                            static_cast<float*>(p.C)[row * p.N + col] = stored;
+                        }
                         const uint32_t u = __float_as_uint(stored) & 0x7FFFFFFFu;
                         out_run = out_run > u ? out_run : u;
+                        if(p.codes)
+                            p.codes[row * p.N + col] = static_cast<int8_t>(quantize_code<kNearest>(stored, code_inv, p.code_qmax, 0u));
                         if(sizeof(acc_t) == 4 && p.acc_dump)
                             p.acc_dump[row * p.N + col] = static_cast<int32_t>(acc[i][j][v]);
                     }
@@ -1024,8 +1067,10 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
                                                                  const float* s0, const float* s1,
                                                                  const float* __restrict__ col_scale,
                                                                  const float* __restrict__ col_bias, int32_t* acc_dump,
-                                                                 unsigned int* amax_bits)
+                                                                 unsigned int* amax_bits, int8_t* codes,
+                                                                 const float* code_inv_p, int code_qmax)
 {
+    const float code_inv = codes ? *code_inv_p : 0.0f;
     constexpr int V      = VEC4 ? 4 : 1;       // VEC4: N % 4 == 0 and 16-byte aligned buffers
     uint32_t      run    = 0u;                 // maximum of |C| as stored (fp32 bits), when amax_bits is given
     const uint32_t seen  = amax_bits ? __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
@@ -1071,6 +1116,18 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
                 const uint32_t u = __float_as_uint(y[e]) & 0x7FFFFFFFu;
                 run = run > u ? run : u;
             }
+        }
+        if(codes)
+        {   // codes of the values as stored (y holds the rounded value when the output is binary16)
+            uint32_t cw = 0u;
+#pragma unroll
+            for(int e = 0; e < V; ++e)
+                cw |= (static_cast<uint32_t>(quantize_code<kNearest>(y[e], code_inv, code_qmax, 0u)) & 0xFFu) << (8 * e);
+            if(VEC4 && (reinterpret_cast<uintptr_t>(codes) & 3) == 0)
+                *reinterpret_cast<uint32_t*>(codes + i) = cw;
+            else
+#pragma unroll
+                for(int e = 0; e < V; ++e) codes[i + e] = static_cast<int8_t>((cw >> (8 * e)) & 0xFFu);
         }
         if(VEC4)
         {
@@ -1164,7 +1221,7 @@ hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStrea
 // The persistent kernel serves full 256x256 tiles with binary16 output and nothing optional in the epilogue.
 bool persistent_eligible(const GemmKernelArgs& a, int prec, int tile, int splits)
 {
-    return (prec == 8 || prec == 16) && tile == 0 && splits == 1 && a.c_is_f16 && !a.acc_dump && !a.amax_bits && a.conv_H == 0
+    return (prec == 8 || prec == 16) && tile == 0 && splits == 1 && a.c_is_f16 && !a.acc_dump && !a.amax_bits && !a.codes && a.conv_H == 0
         && a.remap_C == 0 && a.M % 256 == 0 && a.N % 256 == 0 && a.Kb % (2 * kRowBytes) == 0 && a.Kb >= 2 * kRowBytes
         && (reinterpret_cast<uintptr_t>(a.C) & 15) == 0;
 }
@@ -1276,6 +1333,9 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.conv_H = a.conv_W = a.conv_Cb = 0;
     a.remap_C = a.remap_shift = 0;
     a.amax_bits = plan.splits > 1 ? nullptr : p.out_amax_bits;      // with K splits the reduction pass takes the maximum
+    a.codes     = plan.splits > 1 ? nullptr : static_cast<int8_t*>(p.out_codes);      // ... and writes the codes
+    a.code_inv  = p.out_code_inv;
+    a.code_qmax = p.out_code_qmax;
     if(p.b_remap_C > 0)
     {   // B is [3*remap_C, K] with a margin of |remap_shift| readable bytes in front of it and behind it
         if(p.conv_H > 0 || p.N != 9 * p.b_remap_C || p.b_remap_shift % 16 != 0 || p.b_remap_shift < 0
@@ -1317,7 +1377,7 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
         typedef decltype(acc_tag) acc_t;
         splitk_reduce_kernel<acc_t, decltype(vec_tag)::value><<<dim3(nb), dim3(kThreads), 0, stream>>>(
             static_cast<const acc_t*>(ws), splits, p.M, p.N, p.C, a.c_is_f16, p.s0, p.s1, p.col_scale, p.col_bias, dump,
-            p.out_amax_bits);
+            p.out_amax_bits, static_cast<int8_t*>(p.out_codes), p.out_code_inv, p.out_code_qmax);
     };
     if(p.prec == 8)
     {

@@ -67,6 +67,8 @@ hipError_t launch_conv_padded_transpose(const void* in, int elem_bytes, int64_t 
 hipError_t launch_im2col3x3_i8(const int8_t* xq, int64_t nimg, int H, int W, int C, int8_t* a, int8_t* aT,
                                hipStream_t stream);
 hipError_t launch_zero_f32(float* p, int64_t n, hipStream_t stream);
+// out[c, r] = in[r, c] for int8 codes, any shape (16-byte patches when rows and cols are multiples of 16)
+hipError_t launch_transpose_i8(const int8_t* in, int64_t rows, int64_t cols, int8_t* out, hipStream_t stream);
 size_t colsum_workspace_bytes(int64_t rows, int64_t cols);
 hipError_t launch_colsum(const void* x, int xdt, int64_t rows, int64_t cols, float* out, float* workspace,
                          hipStream_t stream);
@@ -96,6 +98,11 @@ struct GemmProblem {
     // optional device word holding a running maximum of |C| as stored (bit pattern of a non-negative fp32);
     // raised by the epilogue (by the reduction pass when K is split)
     unsigned int* out_amax_bits = nullptr;
+    // optional int8 codes of C as stored, [M][N]: clamp(round(C * out_code_inv[0]), -out_code_qmax, out_code_qmax)
+    // with the quantizer's arithmetic (round to nearest even); out_code_inv is a device scalar
+    void*        out_codes = nullptr;
+    const float* out_code_inv = nullptr;
+    int          out_code_qmax = 127;
 };
 
 // longest operand row (contraction axis) in bytes the MFMA GEMM addresses: 32-bit lane offsets span 255 rows

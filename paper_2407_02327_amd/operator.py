@@ -163,6 +163,22 @@ class QLinear:
         Q.qsync_qlinear_fwd(self.tag, self.M, self.N, self.K, self.xq, self.sx, self.wq, self.sw, self.w_gran,
                             self.bias, self.y, self.acc, self.ws_fwd, stream)
 
+    def gemm_fwd_codes(self, consumer: "QLinear", stream=None) -> None:
+        """Forward GEMM whose epilogue also writes the INT8 codes of Y straight into `consumer.xq`, quantized with
+        the inverse scale the consumer holds (`consumer.ix`, e.g. from the previous step); max |Y| of this step
+        goes to `self.y_amax` when that is collected."""
+        Q.qsync_qlinear_fwd_codes(self.tag, self.M, self.N, self.K, self.xq, self.sx, self.wq, self.sw, self.w_gran,
+                                  self.bias, self.y, consumer.bits, consumer.ix, consumer.xq, self.y_amax, self.ws_fwd,
+                                  stream)
+
+    def forward_from_codes(self, w: torch.Tensor, stream=None) -> torch.Tensor:
+        """Forward of an INT8 operator whose activation codes (`xq`, scale `sx`/`ix`) were written by its
+        producer's epilogue: only the transposed copy for the weight gradient is still to be made."""
+        self.convert_w(w, stream)
+        Q.qsync_transpose_i8(self.xq, self.M, self.K, self.xqT, stream)
+        self.gemm_fwd(stream)
+        return self.y
+
     def gemm_bwd(self, dy: Optional[torch.Tensor], stream=None) -> None:
         if self.bwd_tag != self.tag:
             self._fp16_backward(dy, self.dx, self.dw, self.db, stream)

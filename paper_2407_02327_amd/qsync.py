@@ -39,6 +39,8 @@ SIGNATURES = {
     "qsync_absmax_quantize_workspace_bytes": (_sz, [_i64, _i64]),
     "qsync_qlinear_fwd_amax": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_scale_from_amax": (_i, [_vp, _i, _vp, _vp, _i, _vp]),
+    "qsync_qlinear_fwd_codes": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "qsync_transpose_i8": (_i, [_vp, _i64, _i64, _vp, _vp]),
     "qsync_qlinear_bwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i,
                                _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
@@ -157,6 +159,17 @@ def qsync_qlinear_fwd_amax(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, acc
     _check(lib.qsync_qlinear_fwd_amax(tag, M, N, K, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
                                       _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _ptr(y_amax), _ptr(workspace),
                                       _bytes(workspace), _stream(stream)))
+
+
+def qsync_qlinear_fwd_codes(tag, M, N, K, xq, sx, wq, sw, wgran, bias_opt, y, bits, next_inv_scale, yq, y_amax_opt, workspace,
+                            stream=None) -> None:
+    _check(lib.qsync_qlinear_fwd_codes(tag, M, N, K, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt), _ptr(y),
+                                       dtype_code(y), bits, _ptr(next_inv_scale), _ptr(yq), _ptr(y_amax_opt), _ptr(workspace),
+                                       _bytes(workspace), _stream(stream)))
+
+
+def qsync_transpose_i8(a, rows, cols, out, stream=None) -> None:
+    _check(lib.qsync_transpose_i8(_ptr(a), rows, cols, _ptr(out), _stream(stream)))
 
 
 def qsync_scale_from_amax(amax, bits, scale, inv_scale, consume=True, stream=None) -> None:

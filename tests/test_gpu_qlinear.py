@@ -497,3 +497,100 @@ def test_persistent_gemm_kernel_against_oracle_and_per_tile_kernel(tag):
     finally:
         Q.qsync_debug_set_gemm_persistent(-1)
         Q.qsync_debug_set_gemm_tile(-1)
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2])
+@pytest.mark.parametrize("tag,ydt", [(Q.INT8, torch.float16), (Q.INT8, torch.float32), (Q.FP16, torch.float16),
+                                     (Q.FP32, torch.float32)])
+def test_forward_epilogue_writes_the_consumers_codes(tile, tag, ydt):
+    """qsync_qlinear_fwd_codes: Y unchanged bit for bit; the codes equal the oracle's quantizer applied to the
+    GPU's Y bits with the given inverse scale (both sides decide in fp32 on the stored value), and equal what
+    qsync_quantize makes of that Y.  Shapes: 16-byte store path, element-wise path (N not a multiple of 16),
+    ragged tiles, split K (the reduction pass writes the codes); a scale that clamps part of the values."""
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        for (M, N, K) in [(300, 272, 272), (257, 136, 144), (64, 128, 128), (192, 272, 4096), (96, 104, 4096), (528, 1040, 400)]:
+            rng = np.random.default_rng(M * 11 + N)
+            x = rng.standard_normal((M, K)).astype(np.float32)
+            w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+            b = rng.standard_normal(N).astype(np.float32)
+            say("fwd_codes tile", tile, "tag", tag, "ydt", ydt, "MNK", M, N, K)
+            op = QLinear(tag, M, N, K, x_dtype=torch.float32, y_dtype=ydt, w_gran=Q.PER_ROW, collect_y_amax=True)
+            op.bias.copy_(dev(b))
+            op.forward(dev(x), dev(w))
+            y_plain = host(op.y).copy()
+            amax = float(np.abs(y_plain.astype(np.float32)).max())
+            for bits, slack in ((8, 1.0), (8, 0.6), (5, 1.0)):            # slack < 1: the scale clamps the largest values
+                qmax = (1 << (bits - 1)) - 1
+                inv = np.array([np.float32(qmax) / np.float32(amax * slack)], np.float32)
+                yq = torch.full((M, N), 99, dtype=torch.int8, device="cuda")
+                op.y.fill_(0)
+                op.y_amax.zero_()
+                Q.qsync_qlinear_fwd_codes(tag, M, N, K, op.xq, op.sx, op.wq, op.sw, op.w_gran, op.bias, op.y, bits, dev(inv), yq,
+                                          op.y_amax, op.ws_fwd)
+                got_y = host(op.y)
+                if N % 16 == 0:                       # same store path as the plain forward: the same bits
+                    assert_bits_equal(got_y, y_plain, "Y with code output")
+                    assert float(host(op.y_amax)[0]) == amax
+                else:                                 # element-wise stores: a tie of the binary16 output may fall the other way
+                    assert_close(got_y, y_plain.astype(np.float64), "Y with code output")
+                    assert float(host(op.y_amax)[0]) == float(np.abs(got_y.astype(np.float32)).max())
+                want = orc.quantize_int(got_y.astype(np.float32), inv, "tensor", "nearest", bits=bits)
+                assert_bits_equal(host(yq), want, "codes from the epilogue")
+                if slack < 1.0:
+                    assert (np.abs(want) == qmax).sum() > 1
+                q2 = torch.empty((M, N), dtype=torch.int8, device="cuda")
+                Q.qsync_quantize(op.y, M, N, N, Q.INT8, bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, dev(inv), q2, None)
+                assert torch.equal(q2, yq), "epilogue codes against the quantizer on the same Y"
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
+
+
+def test_transpose_of_codes():
+    rng = np.random.default_rng(17)
+    for rows, cols in [(16, 16), (128, 128), (1024, 4096), (272, 144), (48, 8208), (5, 7), (17, 64), (130, 66)]:
+        say("transpose i8", rows, cols)
+        a = rng.integers(-128, 128, (rows, cols)).astype(np.int8)
+        out = torch.full((cols, rows), 3, dtype=torch.int8, device="cuda")
+        Q.qsync_transpose_i8(dev(a), rows, cols, out)
+        assert_bits_equal(host(out), np.ascontiguousarray(a.T), "transposed codes")
+
+
+def test_chained_operator_consumes_codes_from_the_producers_epilogue():
+    """Two INT8 linears back to back.  Step 0 runs the consumer's own quantizer and leaves its scale; in step 1 the
+    producer's epilogue writes the consumer's codes with that scale (the activations barely move between steps, as
+    in training), the consumer only transposes them.  Codes against the oracle's quantizer on the producer's Y bits;
+    the consumer's accumulators and Y against the oracle's GEMM on those codes; its dW against the oracle too."""
+    rng = np.random.default_rng(6)
+    M, K0, N0, N1 = 1024, 256, 528, 272
+    w0 = (rng.standard_normal((N0, K0)) * 0.05).astype(np.float32)
+    w1 = (rng.standard_normal((N1, N0)) * 0.05).astype(np.float32)
+    prod = QLinear(Q.INT8, M, N0, K0, x_dtype=torch.float32, y_dtype=torch.float16, collect_y_amax=True, bias=False)
+    cons = QLinear(Q.INT8, M, N1, N0, x_dtype=torch.float16, y_dtype=torch.float32, dump_acc=True, bias=False)
+    x0 = rng.standard_normal((M, K0)).astype(np.float32)
+    y0 = prod.forward(dev(x0), dev(w0))
+    cons.forward(y0, dev(w1))                                   # step 0: the consumer finds its own scale
+    inv0 = host(cons.ix).copy()
+    x1 = (x0 * 0.98).astype(np.float32)                         # step 1: slightly smaller activations, nothing clamps
+    prod.convert_x(dev(x1)); prod.convert_w(dev(w0))
+    prod.y_amax.zero_()
+    prod.gemm_fwd_codes(cons)
+    cons.forward_from_codes(dev(w1))
+    dy = (rng.standard_normal((M, N1)) * 1e-2).astype(np.float32)
+    cons.backward(dev(dy))
+    y1 = host(prod.y)
+    want_codes = orc.quantize_int(y1.astype(np.float32), inv0, "tensor", "nearest")
+    assert float(host(prod.y_amax)[0]) * float(inv0[0]) <= 127.5
+    assert_bits_equal(host(cons.xq), want_codes, "consumer codes written by the producer")
+    assert_bits_equal(host(cons.xqT), np.ascontiguousarray(want_codes.T), "their transpose")
+    ref_w = orc.scales_from_amax(orc.absmax(w1, "row"))
+    wq = orc.quantize_int(w1, ref_w[1], "row", "nearest")
+    acc, ovf = orc.int_gemm_nt(want_codes, wq)
+    assert not ovf
+    assert_bits_equal(host(cons.acc), acc, "consumer accumulators")
+    sx0 = host(cons.sx).astype(np.float64)
+    assert_close(host(cons.y), acc.astype(np.float64) * sx0[0] * ref_w[0].astype(np.float64).reshape(1, -1), "consumer Y")
+    ady = orc.absmax(dy, "tensor"); sdy, idy = orc.scales_from_amax(ady)
+    dyq = orc.quantize_int(dy, idy, "tensor", "stochastic", cons.seed, cons.last_dy_offset)
+    acc_dw, _ = orc.int_gemm_nt(np.ascontiguousarray(dyq.T), np.ascontiguousarray(want_codes.T))
+    assert_bits_equal(host(cons.acc_dw), acc_dw, "consumer weight-gradient accumulators")
