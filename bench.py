@@ -134,6 +134,10 @@ def parse_args():
                          "WRITE_SIZE readings can be scaled")
     ap.add_argument("--gemm-persistent", default="auto", choices=["auto", "0", "1"],
                     help="tuning: 1 launches the persistent 256x256 GEMM kernel whenever a GEMM is eligible (default: never)")
+    ap.add_argument("--transposed-copies", default="auto", choices=["auto", "0", "1"],
+                    help="tag int8: 1 makes the quantizer also write the transposed activation / gradient codes and the "
+                         "weight-gradient GEMM read those; 0 / auto: one row-major copy, transposed on the way into the "
+                         "matrix-instruction fragments")
     ap.add_argument("--no-fp16-pass", action="store_true",
                     help="default run (config 5, tag int8): skip the second timed pass with tag fp16")
     args = ap.parse_args()
@@ -168,7 +172,8 @@ def run(args):
                      dx_dtype=torch.float16, dw_dtype=torch.float32,
                      w_gran=Q.PER_ROW if c.w_gran == "row" else Q.PER_TENSOR,
                      dy_round=Q.ROUND_STOCHASTIC if c.dy_round == "stochastic" else Q.ROUND_NEAREST,
-                     philox_seed=c.philox_seed, bwd_tag=(Q.FP16 if args.bwd_tag == "fp16" and tag == Q.INT8 else None))
+                     philox_seed=c.philox_seed, bwd_tag=(Q.FP16 if args.bwd_tag == "fp16" and tag == Q.INT8 else None),
+                     transposed_copies=(True if args.transposed_copies == "1" else None))
         if c.nhwc is not None and args.conv_input == "implicit":
             from paper_2407_02327_amd.operator import QConv3x3
             b_, h_, w_, c_ = c.nhwc.shape
@@ -368,26 +373,35 @@ def run(args):
         big = max(range(len(cases)), key=lambda i: cases[i].dy.size)
         op, dy = ops_objs[big], dev_in[big][2]
         Mq, Nq = op.M, op.N
-        bytes_per = dy.numel() * (dy.element_size() + 2)           # read once, write codes + transposed codes
-        nset = max(2, int(math.ceil((512 << 20) / bytes_per)) + 1)
-        sets = [(dy.clone(), torch.empty_like(op.dyq), torch.empty(Nq, Mq, dtype=op.dyq.dtype, device="cuda")) for _ in range(nset)]
-        quant_iso = {"tensor": f"dY [{Mq},{Nq}] {str(dy.dtype).replace('torch.', '')}", "bytes": "read + codes + transposed codes",
+        one_copy = bool(getattr(op, "rowmajor_bwd", False))          # the form this run's step uses
+        bytes_one, bytes_two = dy.numel() * (dy.element_size() + 1), dy.numel() * (dy.element_size() + 2)
+        bytes_per = bytes_one if one_copy else bytes_two
+        nset = max(2, int(math.ceil((512 << 20) / bytes_one)) + 1)
+        sets = [(dy.clone(), torch.empty(Mq, Nq, dtype=torch.int8, device="cuda"), torch.empty(Nq, Mq, dtype=torch.int8, device="cuda"))
+                for _ in range(nset)]
+        quant_iso = {"tensor": f"dY [{Mq},{Nq}] {str(dy.dtype).replace('torch.', '')}",
+                     "bytes": "read + codes" if one_copy else "read + codes + transposed codes",
                      "bytes_per_launch": int(bytes_per), "sets_rotated_cold": nset}
-        for rname, rnd in (("rtn", Q.ROUND_NEAREST), ("sr", Q.ROUND_STOCHASTIC)):
-            for mode in ("cold", "warm"):
-                def one(i):
-                    x_, q_, qt_ = sets[i % nset] if mode == "cold" else sets[0]
-                    Q.qsync_quantize(x_, Mq, Nq, Nq, Q.INT8, 8, Q.PER_TENSOR, rnd, 1, 0, op.idy, q_, qt_, main)
-                for i in range(5):
-                    one(i)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(main)
-                for i in range(20):
-                    one(i)
-                e1.record(main)
-                torch.cuda.synchronize()
-                gbs = bytes_per / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
-                quant_iso[f"{rname}_{mode}"] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+        other = {"bytes": "read + codes + transposed codes" if one_copy else "read + codes",
+                 "bytes_per_launch": int(bytes_two if one_copy else bytes_one)}
+        quant_iso["other_form"] = other
+        for dest, single, nbytes in ((quant_iso, one_copy, bytes_per), (other, not one_copy, other["bytes_per_launch"])):
+            for rname, rnd in (("rtn", Q.ROUND_NEAREST), ("sr", Q.ROUND_STOCHASTIC)):
+                for mode in ("cold", "warm"):
+                    def one(i):
+                        x_, q_, qt_ = sets[i % nset] if mode == "cold" else sets[0]
+                        Q.qsync_quantize(x_, Mq, Nq, Nq, Q.INT8, 8, Q.PER_TENSOR, rnd, 1, 0, op.idy, q_, None if single else qt_, main)
+                    for i in range(5):
+                        one(i)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(main)
+                    for i in range(20):
+                        one(i)
+                    e1.record(main)
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) / 20 * 1e3
+                    gbs = nbytes / (us * 1e-6) / 1e9
+                    dest[f"{rname}_{mode}"] = {"us": round(us, 1), "GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
         # reference on the same machine: a plain device copy moving the same bytes (read 2 B, write 2 B per element)
         csets = [(s_[0], torch.empty_like(s_[0])) for s_ in sets]
         for mode in ("cold", "warm"):
@@ -402,7 +416,7 @@ def run(args):
                 onec(i)
             e1.record(main)
             torch.cuda.synchronize()
-            gbs = bytes_per / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
+            gbs = dy.numel() * 2 * dy.element_size() / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
             quant_iso[f"plain_copy_{mode}"] = {"GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
         del sets, csets
         # the standalone dequantizer on raw accumulators of the same shape: int32 -> fp16 with the per-column
@@ -506,9 +520,10 @@ def run(args):
     peak = PEAK[args.tag]
     if mfma_probe is not None:
         mfma_probe["forward_gemm_frac_of_random_operand_rate"] = round(achieved / mfma_probe["random_operands"], 4)
-    # HBM-bound side: absmax + quantize of dY (read twice, write codes + transposed codes)
+    # HBM-bound side: absmax + quantize of dY (read twice, write the codes, and their transpose when that is kept)
     esz = cases[0].dy.dtype.itemsize
-    dy_bytes = sum(c.dy.size * (2 * esz + 2) for c in cases)
+    ncopies = [1 if getattr(o, "rowmajor_bwd", False) else 2 for o in ops_objs]
+    dy_bytes = sum(c.dy.size * (2 * esz + n) for c, n in zip(cases, ncopies))
     quant_gbs = dy_bytes / (per_step["convert_dy"] * 1e-3) / 1e9 if "convert_dy" in per_step else None
 
     out = {
@@ -521,6 +536,7 @@ def run(args):
                    "dy_rounding": "stochastic (Philox4x32-10)" if args.bwd_tag is None else "none (FP16 backward)",
                    "bwd_tag": args.bwd_tag or args.tag,
                    "operator_streams": nstreams,
+                   "activation_and_gradient_codes": "row-major only" if min(ncopies) == 1 else "row-major + transposed copy",
                    **({"conv_input": args.conv_input if (tag == Q.INT8 or args.conv_input == "implicit") else "patches"}
                       if any(c.nhwc is not None for c in cases) else {})},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (forward GEMM launches; HIP events on every 4th timed step)",
@@ -535,7 +551,7 @@ def run(args):
                           "themselves lengthen that pass); convert_x includes the weight conversion",
         "quantize_dy": None if quant_gbs is None else
                        {"GBps": round(quant_gbs, 1), "frac_hbm": round(quant_gbs / HBM_PEAK_GBS, 4),
-                        "bytes": "absmax read + quantize read + codes + transposed codes"},
+                        "bytes": "absmax read + quantize read + codes" + ("" if min(ncopies) == 1 else " + transposed codes")},
         "quantize_alone": quant_iso,
         "dequantize_alone": dequant_iso,
         "mfma_probe": mfma_probe,
@@ -547,12 +563,12 @@ def run(args):
     }
     if quant_iso is not None:
         # the HBM-bound kernels against the published 8 TB/s, cold (inputs and outputs rotated through > 512 MB)
-        out["roofline_quantize"] = {"bound": "hbm", "kernel": "quantize_patch_kernel, stochastic rounding, " + quant_iso["tensor"]
-                                    + ", codes + transposed codes, cold",
+        out["roofline_quantize"] = {"bound": "hbm", "kernel": "quantize kernel, stochastic rounding, " + quant_iso["tensor"]
+                                    + ", " + quant_iso["bytes"] + ", cold",
                                     "achieved": quant_iso["sr_cold"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                     "frac": quant_iso["sr_cold"]["frac_hbm"], "algorithmic_bytes": quant_iso["bytes_per_launch"]}
-        out["roofline_quantize_nearest"] = {"bound": "hbm", "kernel": "quantize_patch_kernel, round to nearest, " + quant_iso["tensor"]
-                                            + ", codes + transposed codes, cold",
+        out["roofline_quantize_nearest"] = {"bound": "hbm", "kernel": "quantize kernel, round to nearest, " + quant_iso["tensor"]
+                                            + ", " + quant_iso["bytes"] + ", cold",
                                             "achieved": quant_iso["rtn_cold"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                             "frac": quant_iso["rtn_cold"]["frac_hbm"],
                                             "algorithmic_bytes": quant_iso["bytes_per_launch"]}

@@ -263,16 +263,41 @@ __device__ __forceinline__ void frag_read(v4i32& dst, uint32_t addr)
 {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(I * 32 * kRowBytes) : "memory");
 }
+typedef unsigned v2u32 __attribute__((ext_vector_type(2)));
+// compile-time loop: f(std::integral_constant<int, 0>), ..., f(std::integral_constant<int, N - 1>)
+template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+// Transposing 8-byte read (int8): within 16 lanes, lane j receives byte j%8 of the words read by lanes j/8, j/8 + 2, ...
+template <int OFF> __device__ __forceinline__ void frag_read_tr(v2u32& dst, uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "immediate offset");
+    asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
 template <int F, int... Is>
 __device__ __forceinline__ void frag_reads(v4i32 (&dst)[F], uint32_t addr, std::integer_sequence<int, Is...>)
 {
     (frag_read<Is>(dst[Is], addr), ...);
 }
 
-template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT, bool CONV = false>
+// TN (int8 only): both operands are handed over with the contraction axis as their ROW axis, A [P, M] and
+// B [P, N] row-major (C[m,n] = sum_p A[p,m] B[p,n]): the weight gradient dW = dY^T X straight from the row-major
+// codes, no transposed copies.  A stage then holds 128 contraction rows of each operand (rows of BM / BN bytes),
+// and the fragments come out of LDS through the transposing read of gfx950 (ds_read_b64_tr_b8): sixteen lanes read
+// eight rows x 16 bytes and receive, lane j, the eight bytes of column j -- eight consecutive contraction
+// indices of one output row, which is what the matrix instruction wants.  16-byte chunks are XOR-swizzled per
+// row so that the 32 lanes of one access pass touch all 64 banks once.  Everything behind the fragments
+// (matrix instructions, epilogue, split K) is shared with the NT form.  Kb is the contraction length P here.
+template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT, bool CONV = false, bool TN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKernelArgs p)
 {
     static_assert(!(SPLIT && CONV), "the implicit patch matrix is not combined with split K");
+    static_assert(!TN || (std::is_same<TR, I8Traits>::value && !CONV && BM == BN), "TN: int8 operands, square tiles");
     typedef typename TR::accv_t accv_t;
     typedef typename TR::acc_t  acc_t;
     constexpr int kThreads = 64 * WGM * WGN;
@@ -315,7 +340,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     constexpr bool kUniformSide = (BM / 8) % DPW == 0;
     static_assert(kUniformSide, "a wavefront must not straddle the A/B boundary of a stage");
     const bool     is_a      = wave * DPW < BM / 8;
-    const uint8_t* gbase     = is_a ? p.A + m0 * p.Kb : ((!CONV && p.remap_C > 0) ? p.B : p.B + n0 * p.Kb);
+    // TN: the panel starts at the tile's first column of the operand (its rows are contraction indices)
+    const uint8_t* gbase     = TN ? (is_a ? p.A + m0 : p.B + n0)
+                                  : (is_a ? p.A + m0 * p.Kb : ((!CONV && p.remap_C > 0) ? p.B : p.B + n0 * p.Kb));
     const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
     uint32_t       voff[DPW];                                         // lane offset + kDmaBias - immediate
     uint32_t       hw[CONV ? DPW : 1];                                // CONV, A side: (h << 16) | w of the lane's pixels
@@ -323,6 +350,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     {
         int imm[DPW];
         fill_dma_imms<DPW>(imm, std::make_integer_sequence<int, DPW>{});
+        if constexpr(TN)
+        {   // instruction q of the stage fills LDS bytes [1024 q, 1024 q + 1024) of the A region (128 rows of BM
+            // bytes), then of the B region; a lane's 16 bytes are chunk (position ^ swizzle(row)) of its row
+            constexpr int CPR = BM / 16;                                   // chunks per region row
+            const int64_t ld    = is_a ? p.M : p.N;                        // operand row length in bytes
+            const int64_t width = is_a ? p.M - m0 : p.N - n0;              // valid bytes of this tile's columns (>= 16)
+#pragma unroll
+            for(int d = 0; d < DPW; ++d)
+            {
+                const int q     = wave * DPW + d - (is_a ? 0 : BM / 8);
+                const int o     = q * 1024 + lane * 16;
+                const int row   = o / BM, pos = (o % BM) / 16;
+                int       chunk = pos ^ (2 * ((row / (16 / CPR)) % (CPR / 2)));
+                if(static_cast<int64_t>(chunk) * 16 >= width) chunk = 0;    // columns past the matrix: any valid chunk, never stored
+                voff[d] = static_cast<uint32_t>(static_cast<int64_t>(row) * ld + chunk * 16 + kDmaBias - imm[d]);
+            }
+            gchunk[0] = gchunk[1] = 0;
+        }
+        else
 #pragma unroll
         for(int d = 0; d < DPW; ++d)
         {
@@ -383,9 +429,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                                    reinterpret_cast<const uint8_t*>(&g_zero_chunk), voff, hw, t, p.conv_H, p.conv_W, lbase);
                 return;
             }
-        const uint8_t* sb    = sbase0 + kb;
+        const uint8_t* sb    = TN ? sbase0 + kb * (is_a ? p.M : p.N) : sbase0 + kb;      // TN: 128 operand rows further
         asm volatile("" : "+s"(sb));      // keep base + K offset a scalar pair: the lane offsets stay loop-invariant 32-bit values
-        if(kt == tail_kt)
+        if(!TN && kt == tail_kt)
             dma_sequence_tail<DPW>(std::make_integer_sequence<int, DPW>{}, sb, voff, gchunk, kb, p.Kb, lbase);
         else
             dma_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, sb, voff, lbase);
@@ -395,7 +441,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // out-of-K chunks, then joins the block.
     auto land = [&](int stage, int kt) {
         __builtin_amdgcn_s_waitcnt(0x0070);                       // vmcnt(0), lgkmcnt(0)
-        if(kt == tail_kt)
+        if(!TN && kt == tail_kt)
         {
             const int64_t kb = static_cast<int64_t>(kt) * kRowBytes;
 #pragma unroll
@@ -431,14 +477,54 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // is exactly "the older of two fragment sets has arrived".
     v4i32          af[2][FM], bf[2][FN];
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t*)lds));
+    // TN: lane (kb = lane/32, g = (lane%32)/16, s = lane%16) supplies, for fragment f of a side, the 8-byte half s%2
+    // of chunk (first chunk of the sub-tile + 2f + g) of contraction row 32 ks + 16 kb + 8 r + s/2 (r = 0, 1: the two
+    // reads of a fragment) and receives row 16 g + s of the fragment, contraction indices 32 ks + 16 kb + 8 r + 0..7.
+    uint32_t tn_a[TN ? FM : 1], tn_b[TN ? FN : 1];
+    if constexpr(TN)
+    {
+        constexpr int CPR = BM / 16;
+        const int s16 = lane & 15, g = (lane >> 4) & 1, kb16 = lane >> 5;
+        const int prow = 16 * kb16 + s16 / 2;                              // + 32 ks + 8 r through the immediate
+        const int swz  = 2 * ((prow / (16 / CPR)) % (CPR / 2));            // unchanged by + 8 r and + 32 ks
+#pragma unroll
+        for(int f = 0; f < FM; ++f)
+            tn_a[f] = static_cast<uint32_t>(prow * BM + ((((wm * WTM) / 16 + 2 * f + g) ^ swz) * 16) + 8 * (s16 & 1));
+#pragma unroll
+        for(int f = 0; f < FN; ++f)
+            tn_b[f] = static_cast<uint32_t>(128 * BM + prow * BN + ((((wn * WTN) / 16 + 2 * f + g) ^ swz) * 16) + 8 * (s16 & 1));
+    }
     auto           load_frags = [&](auto buf_tag, int stage, int ks) {
         constexpr int  buf = decltype(buf_tag)::value;
+        if constexpr(TN)
+        {
+            const uint32_t sb = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + ks * 32 * BM);
+            static_for<FM>([&](auto ft) {
+                constexpr int f = decltype(ft)::value;
+                v2u32 lo, hi;
+                frag_read_tr<0>(lo, sb + tn_a[f]);
+                frag_read_tr<8 * BM>(hi, sb + tn_a[f]);
+                af[buf][f] = v4i32{static_cast<int>(lo.x), static_cast<int>(lo.y), static_cast<int>(hi.x), static_cast<int>(hi.y)};
+            });
+            static_for<FN>([&](auto ft) {
+                constexpr int f = decltype(ft)::value;
+                v2u32 lo, hi;
+                frag_read_tr<0>(lo, sb + tn_b[f]);
+                frag_read_tr<8 * BN>(hi, sb + tn_b[f]);
+                bf[buf][f] = v4i32{static_cast<int>(lo.x), static_cast<int>(lo.y), static_cast<int>(hi.x), static_cast<int>(hi.y)};
+            });
+            return;
+        }
         const uint32_t fa  = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + a_base + roff[ks]);
         const uint32_t fb  = lds0 + static_cast<uint32_t>(stage * STAGE_BYTES + b_base + roff[ks]);
         frag_reads<FM>(af[buf], fa, std::make_integer_sequence<int, FM>{});
         frag_reads<FN>(bf[buf], fb, std::make_integer_sequence<int, FN>{});
     };
-    constexpr int kWaitOlderSet = 0xC07F | ((FM + FN) << 8);      // lgkmcnt(FM + FN), other counters untouched
+    // lgkmcnt(reads of one fragment set), other counters untouched.  TN issues two reads per fragment (at most 12
+    // per set; the counter holds 15 and a wavefront's further LDS instructions wait while it is full).
+    constexpr int kReadsPerSet  = TN ? 2 * (FM + FN) : FM + FN;
+    static_assert(kReadsPerSet <= 15, "the LDS counter holds 15");
+    constexpr int kWaitOlderSet = 0xC07F | (kReadsPerSet << 8);
     constexpr int kWaitAllLds   = 0xC07F;                         // lgkmcnt(0)
     static_assert(FM + FN <= 15, "the LDS counter holds 15");
     auto mma = [&](auto buf_tag) {
@@ -757,7 +843,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
 //   * barriers are bare s_barrier instructions behind an LDS wait (the compiler's __syncthreads would wait for
 //     every vector-memory operation of the wavefront, stores included), and every LDS access behind the first
 //     store is written as an instruction for the same reason.
-typedef unsigned v2u32 __attribute__((ext_vector_type(2)));
 typedef float    v2f32 __attribute__((ext_vector_type(2)));
 typedef _Float16 v2f16 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -780,14 +865,6 @@ template <> __device__ __forceinline__ int32_t word_as<int32_t>(uint32_t u) { re
 template <> __device__ __forceinline__ float   word_as<float>(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t as_word(int32_t v) { return static_cast<uint32_t>(v); }
 __device__ __forceinline__ uint32_t as_word(float v) { return __float_as_uint(v); }
-template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, typename F> __device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
 
 template <typename TR>
 __global__ __launch_bounds__(512) void gemm_nt_persistent_kernel(const GemmKernelArgs p, const int total_tiles)
@@ -1179,25 +1256,41 @@ constexpr TileShape kTiles[] = {{256, 256}, {128, 128}, {64, 64}};
 constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 template <typename TR, int BM, int BN, int WGM, int WGN>
-hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
+hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool tn = false)
 {
     constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float) + 64;   // + amax slots
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
     const dim3       block(64 * WGM * WGN);
-    static bool      attr_set[3] = {false, false, false};   // per instantiation; benign if set twice
+    static bool      attr_set[5] = {false, false, false, false, false};   // per instantiation; benign if set twice
     const bool       conv  = a.conv_H > 0;
-    const int        which = conv ? 2 : (splits > 1 ? 1 : 0);
+    const int        which = tn ? (splits > 1 ? 4 : 3) : (conv ? 2 : (splits > 1 ? 1 : 0));
     if(conv && splits > 1) return hipErrorInvalidValue;
+    if(tn && (conv || !std::is_same<TR, I8Traits>::value)) return hipErrorInvalidValue;
+    const void* fn = nullptr;
+    if constexpr(std::is_same<TR, I8Traits>::value)
+        if(tn)
+            fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, false, true>)
+                            : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, false, true>);
+    if(!fn)
+        fn = conv ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true>)
+           : splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
+                        : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false>);
     if(!attr_set[which])
     {
-        const void* fn = conv ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true>)
-                       : splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
-                                    : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false>);
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  static_cast<int>(lds_bytes));
         if(e != hipSuccess) return e;
         attr_set[which] = true;
     }
+    if constexpr(std::is_same<TR, I8Traits>::value)
+        if(tn)
+        {
+            if(splits > 1)
+                gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, false, true><<<grid, block, lds_bytes, st>>>(a);
+            else
+                gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, false, true><<<grid, block, lds_bytes, st>>>(a);
+            return hipGetLastError();
+        }
     if(conv)
         gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true><<<grid, block, lds_bytes, st>>>(a);
     else if(splits > 1)
@@ -1208,13 +1301,13 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st)
 }
 
 template <typename TR>
-hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStream_t st)
+hipError_t launch_traits(int tile, const GemmKernelArgs& a, int splits, hipStream_t st, bool tn = false)
 {
     switch(tile)
     {
-    case 0: return launch_tile<TR, 256, 256, 2, 4>(a, splits, st);
-    case 1: return launch_tile<TR, 128, 128, 2, 2>(a, splits, st);
-    default: return launch_tile<TR, 64, 64, 2, 2>(a, splits, st);
+    case 0: return launch_tile<TR, 256, 256, 2, 4>(a, splits, st, tn);
+    case 1: return launch_tile<TR, 128, 128, 2, 2>(a, splits, st, tn);
+    default: return launch_tile<TR, 64, 64, 2, 2>(a, splits, st, tn);
     }
 }
 
@@ -1251,11 +1344,11 @@ void set_gemm_tile_override(int tile) { g_tile_override = (tile >= 0 && tile < k
 static thread_local int g_persistent_mode = -1;   // 1: whenever eligible; anything else: never (the default, see launch_gemm)
 void set_gemm_persistent_mode(int mode) { g_persistent_mode = (mode == 0 || mode == 1) ? mode : -1; }
 
-GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits, bool allow_split)
+GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, int force_splits, bool allow_split, bool tn)
 {
     if(force_tile < 0 && g_tile_override >= 0)
     {   // a forced tile keeps the planner's split choice for that tile
-        GemmPlan forced = plan_gemm(prec, M, N, K, g_tile_override, force_splits >= 1 ? force_splits : 0, allow_split);
+        GemmPlan forced = plan_gemm(prec, M, N, K, g_tile_override, force_splits >= 1 ? force_splits : 0, allow_split, tn);
         return forced;
     }
     GemmPlan plan{1, 1, 0};
@@ -1273,9 +1366,13 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
     //   epilogue (overlapped among co-resident workgroups), split K adds its reduction pass.
     struct TileModel { double rate1, rate_max, ovh; int occ; int fill; };
     const TileModel model[kNumTiles] = {{8.6, 8.6, 8.0, 1, 256}, {5.4, 6.5, 5.0, 2, 512}, {2.6, 6.0, 5.0, 4, 512}};
+    // Row-major (TN) operands: a K tile takes twice the LDS fragment reads, and a 64-wide tile loads 64-byte row
+    // pieces; measured slow-down of the main loop per tile shape.
+    const double    tn_rate[kNumTiles] = {0.93, 0.88, 0.68};
     const double    cus = 256.0;
     auto estimate = [&](int t, int64_t s) {
-        const TileModel& m     = model[t];
+        TileModel m = model[t];
+        if(tn) { m.rate1 *= tn_rate[t]; m.rate_max *= tn_rate[t]; }
         const double     wgs   = static_cast<double>(ntiles(t)) * static_cast<double>(s);
         const double     per   = std::ceil(wgs / cus);                                   // workgroups per unit
         const double     share = per < m.occ ? per : m.occ;                              // co-resident ones
@@ -1332,6 +1429,13 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.partial  = workspace;
     a.conv_H = a.conv_W = a.conv_Cb = 0;
     a.remap_C = a.remap_shift = 0;
+    if(p.tn)
+    {   // A [K, M], B [K, N] row-major int8: rows are contraction indices (128 per K tile), 16-byte column chunks
+        if(p.prec != 8 || p.conv_H > 0 || p.b_remap_C > 0 || p.K % kRowBytes != 0 || p.M % 16 != 0 || p.N % 16 != 0
+           || p.M >= (int64_t(1) << 24) || p.N >= (int64_t(1) << 24)
+           || ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) != 0)
+            return hipErrorInvalidValue;
+    }
     a.amax_bits = plan.splits > 1 ? nullptr : p.out_amax_bits;      // with K splits the reduction pass takes the maximum
     a.codes     = plan.splits > 1 ? nullptr : static_cast<int8_t*>(p.out_codes);      // ... and writes the codes
     a.code_inv  = p.out_code_inv;
@@ -1362,10 +1466,10 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     // write-back of a tile overlaps the next tile's K loop), but inside an operator sequence its fixed tile
     // assignment loses what it gains: workgroups that start late, behind the tail of the previous kernel, still
     // walk their full share of tiles, while the per-tile grid is balanced by the hardware dispatcher.
-    if(persistent_eligible(a, p.prec, plan.tile, splits)
+    if(!p.tn && persistent_eligible(a, p.prec, plan.tile, splits)
        && g_persistent_mode == 1)
         return p.prec == 8 ? launch_persistent<I8Traits>(a, stream) : launch_persistent<F16Traits>(a, stream);
-    hipError_t e = p.prec == 8    ? launch_traits<I8Traits>(plan.tile, a, splits, stream)
+    hipError_t e = p.prec == 8    ? launch_traits<I8Traits>(plan.tile, a, splits, stream, p.tn)
                    : p.prec == 16 ? launch_traits<F16Traits>(plan.tile, a, splits, stream)
                                   : launch_traits<F32Traits>(plan.tile, a, splits, stream);
     if(e != hipSuccess || splits == 1) return e;

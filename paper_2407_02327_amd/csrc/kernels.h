@@ -95,6 +95,9 @@ struct GemmProblem {
     // [3*b_remap_C, K] matrix, read with the K axis displaced by (tap/3 - 1)*b_remap_shift bytes (a multiple of
     // 16, at most 1024); that many bytes in front of and behind the matrix must be readable.
     int64_t     b_remap_C = 0, b_remap_shift = 0;
+    // tn (int8 only): A is [K, M] and B is [K, N], row-major with the contraction axis as rows (K % 128 == 0,
+    // M % 16 == 0, N % 16 == 0): C[m,n] = sum_k A[k,m] B[k,n] without transposed copies of the operands
+    bool        tn = false;
     // optional device word holding a running maximum of |C| as stored (bit pattern of a non-negative fp32);
     // raised by the epilogue (by the reduction pass when K is split)
     unsigned int* out_amax_bits = nullptr;
@@ -113,9 +116,9 @@ struct GemmPlan {
     int     splits;        // split-K factor (1 = epilogue fused in the GEMM kernel)
     size_t  workspace;     // bytes needed for split-K partials
 };
-// force_tile / force_splits < 0 leave the choice to the heuristic.
+// force_tile / force_splits < 0 leave the choice to the heuristic; tn: plan for GemmProblem::tn operands.
 GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile = -1, int force_splits = -1,
-                   bool allow_split = true);
+                   bool allow_split = true, bool tn = false);
 // tile >= 0 pins the tile shape of every later plan (tests, tuning); -1 returns the choice to the planner.
 void set_gemm_tile_override(int tile);
 // 1: launch the persistent 256x256 kernel whenever a problem is eligible; anything else: never (the default)

@@ -13,6 +13,19 @@ A = P(4096)            # a non-NULL, 16-byte aligned fake device address: valida
 U = P(4100)            # misaligned
 
 
+def _gpu_visible() -> bool:
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except Exception:
+        return False
+
+
+# Several tests end with a well-formed call on the fake addresses above, expecting "OK or launch failed": with a GPU
+# present such a launch would dereference them, so the whole module runs only where there is none.
+pytestmark = pytest.mark.skipif(_gpu_visible(), reason="argument validation on fake device addresses: CPU-only boxes")
+
+
 def test_every_declared_symbol_is_exported():
     inc = os.path.join(ROOT, "include")
     headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
@@ -429,3 +442,28 @@ def test_fp16_backward_of_int8_forward_validation():
     offs = (ctypes.c_size_t * 5)()
     assert f(*chg(offs=offs)) in (qsync.OK, qsync.ERR_HIP)          # valid call: only the launch can fail without a GPU
     assert list(offs) == sorted(offs) and offs[0] == 0 and all(o % 256 == 0 for o in offs)
+
+
+def test_row_major_backward_validation():
+    f = lib.qsync_qlinear_bwd_rm
+    need = lib.qsync_qlinear_bwd_rm_workspace_bytes(256, 32, 48)
+    assert need >= lib.qsync_qlinear_bwd_workspace_bytes(qsync.INT8, 256, 32, 48)
+    assert lib.qsync_qlinear_bwd_rm_workspace_bytes(-1, 32, 48) == 0
+    W = P(1 << 20)
+    ok = (256, 32, 48, A, A, A, A, A, A, qsync.PER_ROW, A, qsync.F16, A, qsync.F32, None, None, qsync.F32, None, None, W, 1 << 20, None)
+    names = "M N K dyq sdy xq sx wqbT swb wbgran dx dxdt dw dwdt db dyf dydt accdx accdw ws wsb st".split()
+    chg = lambda **kw: tuple(kw.get(i, v) for i, v in zip(names, ok))
+    assert f(*chg(dyq=None)) == qsync.ERR_NULL
+    assert f(*chg(xq=None)) == qsync.ERR_NULL
+    assert f(*chg(xq=None, dw=None)) in (qsync.OK, qsync.ERR_HIP)       # the activation codes serve the weight gradient only
+    assert f(*chg(wqbT=None)) == qsync.ERR_NULL
+    assert f(*chg(db=A)) == qsync.ERR_NULL                             # the bias gradient sums the float gradient
+    assert f(*chg(dxdt=qsync.I8)) == qsync.ERR_BAD_ENUM
+    assert f(*chg(wbgran=qsync.PER_COL)) == qsync.ERR_UNSUPPORTED
+    assert f(*chg(M=-1)) == qsync.ERR_BAD_SHAPE
+    assert f(*chg(M=192)) == qsync.ERR_ALIGN                           # whole tiles of 128 contraction rows
+    assert f(*chg(N=24)) == qsync.ERR_ALIGN
+    assert f(*chg(K=40)) == qsync.ERR_ALIGN
+    assert f(*chg(xq=U)) == qsync.ERR_ALIGN
+    assert f(*chg(M=0)) in (qsync.OK, qsync.ERR_HIP)                   # empty batch: dW is written as zeros
+    assert f(*chg()) in (qsync.OK, qsync.ERR_HIP)

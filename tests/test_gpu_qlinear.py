@@ -18,7 +18,7 @@ TORCH = {np.dtype(np.float32): torch.float32, np.dtype(np.float16): torch.float1
 
 
 def run_case(case: wl.LinearCase, tag: int, y_dtype=np.float32, dx_dtype=np.float16, dw_dtype=np.float32,
-             check_codes=True, dump_acc=True):
+             check_codes=True, dump_acc=True, transposed_copies=None):
     """Runs one operator fwd+bwd on the GPU and compares every stage with the oracle.
 
     dump_acc=True asks the INT8 GEMMs for their raw int32 accumulators (compared bit for bit); a GEMM that
@@ -30,7 +30,7 @@ def run_case(case: wl.LinearCase, tag: int, y_dtype=np.float32, dx_dtype=np.floa
     op = QLinear(tag, M, N, K, x_dtype=TORCH[case.x.dtype], w_dtype=TORCH[case.w.dtype],
                  dy_dtype=TORCH[case.dy.dtype], y_dtype=TORCH[np.dtype(y_dtype)], dx_dtype=TORCH[np.dtype(dx_dtype)],
                  dw_dtype=TORCH[np.dtype(dw_dtype)], w_gran=GRAN[case.w_gran], dy_round=RND[case.dy_round],
-                 philox_seed=case.philox_seed, dump_acc=dump_acc)
+                 philox_seed=case.philox_seed, dump_acc=dump_acc, transposed_copies=transposed_copies)
     op.offset = 12345
     op.bias.copy_(dev(case.bias))
     xd, wd, dyd = dev(case.x), dev(case.w), dev(case.dy)
@@ -47,11 +47,13 @@ def run_case(case: wl.LinearCase, tag: int, y_dtype=np.float32, dx_dtype=np.floa
         assert_bits_equal(host(op.swb), ref["swb"], "swb")
         if check_codes:
             assert_bits_equal(host(op.xq), ref["xq"], "xq")
-            assert_bits_equal(host(op.xqT), ref["xq"].T, "xqT")
+            if op.xqT is not None:
+                assert_bits_equal(host(op.xqT), ref["xq"].T, "xqT")
             assert_bits_equal(host(op.wq), ref["wq"], "wq")
             assert_bits_equal(host(op.wqbT), ref["wqb"].T, "wqbT")
             assert_bits_equal(host(op.dyq), ref["dyq"], "dyq")
-            assert_bits_equal(host(op.dyqT), ref["dyq"].T, "dyqT")
+            if op.dyqT is not None:
+                assert_bits_equal(host(op.dyqT), ref["dyq"].T, "dyqT")
         if dump_acc:
             assert_bits_equal(host(op.acc), ref["acc"], "fwd accumulators")
             assert_bits_equal(host(op.acc_dx), ref["acc_dx"], "dX accumulators")
@@ -168,6 +170,15 @@ def test_fp32_tag_any_shape_forward_and_backward():
 
 def test_config2_bert_base_ffn_full_size():
     run_case(wl.config2(), Q.INT8, y_dtype=np.float16)
+
+
+@pytest.mark.parametrize("transposed_copies", [False, True])
+def test_config2_with_and_without_transposed_copies(transposed_copies):
+    """Both weight-gradient paths at full size: one row-major copy of the X and dY codes read as they are, and the
+    quantizer writing xqT / dyqT for the NT GEMM; codes and accumulators exact either way."""
+    op, _ = run_case(wl.config2(), Q.INT8, y_dtype=np.float16, transposed_copies=transposed_copies)
+    assert op.rowmajor_bwd == (not transposed_copies) and (op.xqT is None) == (not transposed_copies)
+    assert (op.dyqT is None) == (not transposed_copies)
 
 
 def test_config2_bert_base_ffn_full_size_production_epilogue():
@@ -367,7 +378,8 @@ def test_conv_activation_quantized_once_then_expanded():
                                dw_dtype=np.float64)
     assert_bits_equal(host(op.sx), ref["sx"], "sx")
     assert_bits_equal(host(op.xq), ref["xq"], "xq")
-    assert_bits_equal(host(op.xqT), ref["xq"].T, "xqT")
+    if op.xqT is not None:
+        assert_bits_equal(host(op.xqT), ref["xq"].T, "xqT")
     assert_bits_equal(host(op.acc), ref["acc"], "fwd accumulators")
     assert_bits_equal(host(op.acc_dw), ref["acc_dw"], "dW accumulators")
     assert_close(host(op.y), ref["y"], "Y")
@@ -447,7 +459,7 @@ def test_chained_operator_takes_its_scale_from_the_producers_epilogue():
         base.forward(y0, dev(w1))
         torch.cuda.synchronize()
         assert prod.y_amax.item() == 0.0
-        for name in ("sx", "ix", "xq", "xqT", "acc", "y"):
+        for name in ("sx", "ix", "xq", "acc", "y"):
             assert torch.equal(getattr(cons, name), getattr(base, name)), (step, name)
     ref = orc.operator_fwd_bwd(Q.INT8, host(y0), w1, None, np.zeros((M, N1), np.float32), "row", "nearest",
                                y_dtype=np.float64)
@@ -582,7 +594,8 @@ def test_chained_operator_consumes_codes_from_the_producers_epilogue():
     want_codes = orc.quantize_int(y1.astype(np.float32), inv0, "tensor", "nearest")
     assert float(host(prod.y_amax)[0]) * float(inv0[0]) <= 127.5
     assert_bits_equal(host(cons.xq), want_codes, "consumer codes written by the producer")
-    assert_bits_equal(host(cons.xqT), np.ascontiguousarray(want_codes.T), "their transpose")
+    if cons.xqT is not None:
+        assert_bits_equal(host(cons.xqT), np.ascontiguousarray(want_codes.T), "their transpose")
     ref_w = orc.scales_from_amax(orc.absmax(w1, "row"))
     wq = orc.quantize_int(w1, ref_w[1], "row", "nearest")
     acc, ovf = orc.int_gemm_nt(want_codes, wq)
@@ -594,3 +607,43 @@ def test_chained_operator_consumes_codes_from_the_producers_epilogue():
     dyq = orc.quantize_int(dy, idy, "tensor", "stochastic", cons.seed, cons.last_dy_offset)
     acc_dw, _ = orc.int_gemm_nt(np.ascontiguousarray(dyq.T), np.ascontiguousarray(want_codes.T))
     assert_bits_equal(host(cons.acc_dw), acc_dw, "consumer weight-gradient accumulators")
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2])
+def test_weight_gradient_from_row_major_codes(tile):
+    """qsync_qlinear_bwd_rm: dW = dY^T X from the row-major codes (no transposed copies; the GEMM transposes on the
+    way from LDS into the matrix instructions), dX as before.  int32 accumulators bit for bit against the oracle,
+    dW and dX values in tolerance, on every tile shape, ragged N and K (multiples of 16), one and several K tiles,
+    split K."""
+    rng = np.random.default_rng(123)
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        for (M, N, K) in [(128, 16, 16), (128, 256, 256), (256, 272, 144), (384, 48, 528), (1024, 528, 272), (4096, 144, 80),
+                          (8192, 1040, 784), (2048, 2064, 64)]:
+            say("bwd_rm tile", tile, "MNK", M, N, K)
+            dyq = rng.integers(-127, 128, (M, N)).astype(np.int8)
+            xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
+            wqb = rng.integers(-127, 128, (N, K)).astype(np.int8)
+            sdy, sx = np.array([3e-5], np.float32), np.array([0.01], np.float32)
+            swb = (rng.random(K) * 0.002 + 0.0005).astype(np.float32)
+            acc_dw, o1 = orc.int_gemm_nt(np.ascontiguousarray(dyq.T), np.ascontiguousarray(xq.T))
+            acc_dx, o2 = orc.int_gemm_nt(dyq, np.ascontiguousarray(wqb.T))
+            assert not (o1 or o2)
+            dx, dw = torch.empty((M, K), dtype=torch.float16, device="cuda"), torch.empty((N, K), dtype=torch.float32, device="cuda")
+            adx, adw = torch.empty((M, K), dtype=torch.int32, device="cuda"), torch.empty((N, K), dtype=torch.int32, device="cuda")
+            w = torch.zeros(max(Q.qsync_qlinear_bwd_rm_workspace_bytes(M, N, K), 256), dtype=torch.uint8, device="cuda")
+            wqbT = dev(np.ascontiguousarray(wqb.T))
+            Q.qsync_qlinear_bwd_rm(M, N, K, dev(dyq), dev(sdy), dev(xq), dev(sx), wqbT, dev(swb), Q.PER_ROW, dx, dw, None, None,
+                                   adx, adw, w)
+            assert_bits_equal(host(adw), acc_dw, "dW accumulators (row-major operands)")
+            assert_bits_equal(host(adx), acc_dx, "dX accumulators")
+            want_dw = acc_dw.astype(np.float64) * float(sdy[0]) * float(sx[0])
+            assert_close(host(dw), want_dw, "dW")
+            # the production epilogue (no accumulator dump), fp32 and binary16 outputs
+            for dt in (torch.float32, torch.float16):
+                dw2 = torch.empty((N, K), dtype=dt, device="cuda")
+                Q.qsync_qlinear_bwd_rm(M, N, K, dev(dyq), dev(sdy), dev(xq), dev(sx), None, None, Q.PER_ROW, None, dw2, None, None,
+                                       None, None, w)
+                assert_close(host(dw2), want_dw, f"dW {dt} without dump")
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
