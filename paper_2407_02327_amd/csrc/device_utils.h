@@ -135,9 +135,11 @@ __device__ __forceinline__ uint32_t philox_draw16(const uint4& blk, int slot)
 }
 
 // Fixed-point code of one value: clamp(round(x * inv), -qmax, qmax).  RND is a qsync::Round.
-// The product is a single fp32 multiply; for stochastic rounding the residual x*inv - floor(.)
-// is exact in fp32 and the value rounds up iff u16 < floor(residual * 2^16).  The rounded value
-// is integral and small, so the increment and the clamp run on integers.
+// The product is a single fp32 multiply.  Stochastic rounding: the value rounds up iff
+// u16 < floor(residual * 2^16) with residual = x*inv - floor(x*inv).  It is evaluated in 16.16 fixed point:
+// t = floor(x*inv * 2^16) is exact (a power-of-two scaling), floor(x*inv) = t >> 16 and floor(residual * 2^16) =
+// t & 0xFFFF, so "floor + (u16 < low half)" is the carry of t + (65535 - u16) into bit 16.  Clamping t to
+// +-qmax * 2^16 first is the clamp of the code (a clamped t has a zero low half) and keeps the sum inside 32 bits.
 template <int RND>
 __device__ __forceinline__ int quantize_code(float x, float inv, int qmax, uint32_t u16)
 {
@@ -147,10 +149,10 @@ __device__ __forceinline__ int quantize_code(float x, float inv, int qmax, uint3
     else if(RND == 2) c = static_cast<int>(floorf(v));
     else
     {
-        const float    fl  = floorf(v);
-        const float    fr  = __fsub_rn(v, fl);
-        const uint32_t thr = static_cast<uint32_t>(__fmul_rn(fr, 65536.0f));
-        c = static_cast<int>(fl) + (u16 < thr ? 1 : 0);
+        int       t   = static_cast<int>(floorf(__fmul_rn(v, 65536.0f)));     // saturates; NaN -> 0
+        const int lim = qmax << 16;
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t) : "v"(t), "v"(-lim), "v"(lim));
+        return (t + static_cast<int>(65535u - u16)) >> 16;
     }
     return min(max(c, -qmax), qmax);
 }

@@ -746,6 +746,56 @@ __global__ __launch_bounds__(kBlock, 3) void quantize_patch_kernel(const T* __re
                                                          inv_scale, q, qT, grid_x, lpr_log2, inv_scale_T, flip_C);
 }
 
+// ------------------------------------------------------------------ INT8 quantize, row-major codes only
+// Contiguous tensor, one scale, no transposed copy: nothing ties a lane to a patch, so the lanes of a wavefront take
+// adjacent groups of 8 elements (one Philox block each; a load instruction of a wavefront covers 1 KB of consecutive
+// memory for binary16 input) with U groups in flight per lane, and the 8 codes of a group leave as one 8-byte store.
+template <typename T, int RND>
+__global__ __launch_bounds__(kBlock) void quantize_stream_kernel(const T* __restrict__ x, int64_t ngroups, int qmax,
+                                                                 uint64_t seed, uint64_t offset,
+                                                                 const float* __restrict__ inv_scale, int8_t* __restrict__ q)
+{
+    constexpr int E  = Vec16<T>::N;       // elements per 16-byte load (8 or 4)
+    constexpr int VG = 8 / E;             // loads per group
+    constexpr int U  = 4;
+    const float   f  = inv_scale[0];
+    const uint4*  xv = reinterpret_cast<const uint4*>(x);
+    const int64_t g0 = static_cast<int64_t>(blockIdx.x) * (kBlock * U) + threadIdx.x;
+    uint4         raw[U][VG];
+#pragma unroll
+    for(int u = 0; u < U; ++u)
+    {
+        const int64_t g = g0 + u * kBlock;
+#pragma unroll
+        for(int l = 0; l < VG; ++l) raw[u][l] = g < ngroups ? xv[g * VG + l] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for(int u = 0; u < U; ++u)
+    {
+        const int64_t g = g0 + u * kBlock;
+        if(g >= ngroups) continue;
+        float v[8];
+#pragma unroll
+        for(int l = 0; l < VG; ++l)
+        {
+            float t[E];
+            Vec16<T>::decode(raw[u][l], t);
+#pragma unroll
+            for(int e = 0; e < E; ++e) v[l * E + e] = t[e];
+        }
+        uint4 blk = {0u, 0u, 0u, 0u};
+        if(RND == kStochastic) blk = philox_group(seed, offset, static_cast<uint64_t>(g));
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for(int j = 0; j < 8; ++j)
+        {
+            const int c = quantize_code<RND>(v[j], f, qmax, philox_draw16(blk, j));
+            w[j / 4] |= (static_cast<uint32_t>(c) & 0xFFu) << (8 * (j % 4));
+        }
+        *reinterpret_cast<uint2*>(q + g * 8) = make_uint2(w[0], w[1]);
+    }
+}
+
 // ------------------------------------------------------------------ maximum and quantize in one launch
 // Per-tensor scale, contiguous tensor.  Every workgroup (1) folds its share of the tensor into a partial
 // maximum and publishes it, (2) takes a ticket; the last one to arrive clears the ticket counter and advances a
@@ -1514,7 +1564,18 @@ static hipError_t quantize_typed(const T* x, int64_t rows, int64_t cols, int64_t
     const int64_t    gx = ps.gx, gy = ps.gy;
     const bool    fast = cols % 8 == 0 && aligned16(x) && (ld * sizeof(T)) % 16 == 0 && (!q || aligned16(q))
                       && (!qT || (aligned16(qT) && rows % 16 == 0)) && gx * gy < (int64_t(1) << 31);
-    if(fast)
+    if(fast && q && !qT && gran == kPerTensor && ld == cols && rows * cols / 8 < (int64_t(1) << 40))
+    {   // row-major codes of a contiguous tensor with one scale: the streaming form
+        const int64_t ngroups = rows * cols / 8;
+        const dim3    grid(static_cast<unsigned>((ngroups + kBlock * 4 - 1) / (kBlock * 4)));
+        if(rnd == kStochastic)
+            quantize_stream_kernel<T, kStochastic><<<grid, dim3(kBlock), 0, st>>>(x, ngroups, qmax, seed, offset, inv, q);
+        else if(rnd == kFloor)
+            quantize_stream_kernel<T, kFloor><<<grid, dim3(kBlock), 0, st>>>(x, ngroups, qmax, seed, offset, inv, q);
+        else
+            quantize_stream_kernel<T, kNearest><<<grid, dim3(kBlock), 0, st>>>(x, ngroups, qmax, seed, offset, inv, q);
+    }
+    else if(fast)
     {
         if(rnd == kStochastic)
             quantize_patch_launch<T, kStochastic>(x, rows, cols, ld, qmax, gran, seed, offset, inv, q, qT, st);
