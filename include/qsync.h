@@ -303,26 +303,29 @@ size_t qsync_qlinear_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 size_t qsync_qlinear_bwd_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 
 /*
- * qsync_qlinear_bwd_rm - qsync_qlinear_bwd for INT8 operands without transposed copies of the activation and
- * gradient codes: the weight gradient dW = dY^T X contracts over the rows of both operands, and its GEMM reads
- * the row-major codes dyq [M,N] and xq [M,K] directly (transposing LDS reads feed the matrix instructions), so
- * qsync_quantize has to write one copy of X and of dY only.  Paper: Cost Mapper paragraph (cvt_cost and bp_cost,
+ * qsync_qlinear_bwd_rm - qsync_qlinear_bwd for INT8 or FP16 operands without transposed copies of the activation
+ * and gradient operands: the weight gradient dW = dY^T X contracts over the rows of both operands, and its GEMM
+ * reads the row-major dyq [M,N] and xq [M,K] directly (transposing LDS reads feed the matrix instructions), so
+ * qsync_quantize has to write one copy of X and of dY only -- none at all for a binary16 tensor under the FP16 tag,
+ * which is its own operand.  Paper: Cost Mapper paragraph (cvt_cost and bp_cost,
  * the casting costs of the forward and backward pass); Appendix, proof of Prop. 1 (the two gradient contractions).
  *
  *   dX[m,k] = sum_n dyq[m,n] wqbT[k,n] * (sdy swb[k or 0])      dW[n,k] = sum_m dyq[m,n] xq[m,k] * (sdy sx)
  *   db[n] = sum_m dY[m,n]                                          same bits as qsync_qlinear_bwd
  *
- * dyq [M,N], xq [M,K] int8 row-major (the forward's own operand), wqbT [K,N]; scales as in qsync_qlinear_bwd.
- * The weight gradient needs M % 128 == 0, N % 16 == 0, K % 16 == 0 and N, K < 2^24 (QSYNC_ERR_ALIGN /
- * QSYNC_ERR_UNSUPPORTED otherwise: use qsync_qlinear_bwd with transposed copies then).
- * workspace  at least qsync_qlinear_bwd_rm_workspace_bytes(M, N, K) bytes.
+ * tag  QSYNC_INT8 or QSYNC_FP16 (QSYNC_ERR_UNSUPPORTED otherwise).
+ * dyq [M,N], xq [M,K] int8 / binary16 row-major (the forward's own operand), wqbT [K,N]; scales as in
+ * qsync_qlinear_bwd (INT8 only; ignored for FP16, whose sums carry no scale).
+ * The weight gradient needs M % 128 == 0, N and K multiples of 16 (INT8) or 8 (FP16) and N, K < 2^24
+ * (QSYNC_ERR_ALIGN / QSYNC_ERR_UNSUPPORTED otherwise: use qsync_qlinear_bwd with transposed copies then).
+ * workspace  at least qsync_qlinear_bwd_rm_workspace_bytes(tag, M, N, K) bytes.
  */
-int qsync_qlinear_bwd_rm(int64_t M, int64_t N, int64_t K, const void* dyq, const float* sdy,
+int qsync_qlinear_bwd_rm(int tag, int64_t M, int64_t N, int64_t K, const void* dyq, const float* sdy,
                          const void* xq, const float* sx, const void* wqbT, const float* swb, int wbgran,
                          void* dx_opt, int dxdt, void* dw_opt, int dwdt, float* db_opt,
                          const void* dy_float_opt, int dydt, int32_t* acc_dx_dump_opt, int32_t* acc_dw_dump_opt,
                          void* workspace, size_t workspace_bytes, void* stream);
-size_t qsync_qlinear_bwd_rm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t qsync_qlinear_bwd_rm_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K);
 
 /*
  * qsync_qlinear_bwd_fp16_of_int8 - backward of an INT8 operator the way the paper runs it: in FP16, on the

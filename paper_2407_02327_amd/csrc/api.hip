@@ -364,55 +364,60 @@ int qsync_qlinear_bwd(int tag, int64_t M, int64_t N, int64_t K, const void* dyq,
     return QSYNC_OK;
 }
 
-size_t qsync_qlinear_bwd_rm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+size_t qsync_qlinear_bwd_rm_workspace_bytes(int tag, int64_t M, int64_t N, int64_t K)
 {
-    if(M < 0 || N < 0 || K < 0) return 0;
+    if((tag != QSYNC_INT8 && tag != QSYNC_FP16) || M < 0 || N < 0 || K < 0) return 0;
     // the data gradient (and bias gradient) go through qsync_qlinear_bwd, which asks for its own full size
-    const size_t nt = qsync_qlinear_bwd_workspace_bytes(QSYNC_INT8, M, N, K);
-    const size_t rm = round256(plan_gemm(QSYNC_INT8, M, K, N).workspace)
-                    + round256(plan_gemm(QSYNC_INT8, N, K, M, -1, -1, true, /*tn=*/true).workspace);
+    const size_t nt = qsync_qlinear_bwd_workspace_bytes(tag, M, N, K);
+    const size_t rm = round256(plan_gemm(tag, M, K, N).workspace)
+                    + round256(plan_gemm(tag, N, K, M, -1, -1, true, /*tn=*/true).workspace);
     return nt > rm ? nt : rm;
 }
 
-int qsync_qlinear_bwd_rm(int64_t M, int64_t N, int64_t K, const void* dyq, const float* sdy, const void* xq, const float* sx,
+int qsync_qlinear_bwd_rm(int tag, int64_t M, int64_t N, int64_t K, const void* dyq, const float* sdy, const void* xq, const float* sx,
                          const void* wqbT, const float* swb, int wbgran, void* dx_opt, int dxdt, void* dw_opt, int dwdt,
                          float* db_opt, const void* dy_float_opt, int dydt, int32_t* acc_dx_dump_opt,
                          int32_t* acc_dw_dump_opt, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if((dx_opt || dw_opt) && (!dyq || !sdy)) return QSYNC_ERR_NULL;
-    if(dx_opt && (!wqbT || !swb)) return QSYNC_ERR_NULL;
-    if(dw_opt && (!xq || !sx)) return QSYNC_ERR_NULL;
+    if(!is_tag(tag)) return QSYNC_ERR_BAD_ENUM;
+    if(tag != QSYNC_INT8 && tag != QSYNC_FP16) return QSYNC_ERR_UNSUPPORTED;
+    const bool i8 = tag == QSYNC_INT8;
+    if((dx_opt || dw_opt) && (!dyq || (i8 && !sdy))) return QSYNC_ERR_NULL;
+    if(dx_opt && (!wqbT || (i8 && !swb))) return QSYNC_ERR_NULL;
+    if(dw_opt && (!xq || (i8 && !sx))) return QSYNC_ERR_NULL;
     if(db_opt && !dy_float_opt) return QSYNC_ERR_NULL;
+    if(!i8 && (acc_dx_dump_opt || acc_dw_dump_opt)) return QSYNC_ERR_UNSUPPORTED;
     if(dx_opt && (!is_float_dtype(dxdt) || !is_gran(wbgran))) return QSYNC_ERR_BAD_ENUM;
     if(dw_opt && !is_float_dtype(dwdt)) return QSYNC_ERR_BAD_ENUM;
     if(db_opt && !is_float_dtype(dydt)) return QSYNC_ERR_BAD_ENUM;
     if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
     if(dx_opt && wbgran == QSYNC_PER_COL) return QSYNC_ERR_UNSUPPORTED;
-    if((dx_opt && !gemm_row_ok(QSYNC_INT8, N)) || (dw_opt && (N >= (int64_t(1) << 24) || K >= (int64_t(1) << 24))))
+    if((dx_opt && !gemm_row_ok(tag, N)) || (dw_opt && (N >= (int64_t(1) << 24) || K >= (int64_t(1) << 24))))
         return QSYNC_ERR_UNSUPPORTED;
-    if(dx_opt && (N % 16 != 0 || !aligned16(dyq) || !aligned16(wqbT))) return QSYNC_ERR_ALIGN;
-    // the weight gradient reads both operands row-major: whole K tiles of 128 contraction rows, 16-byte column chunks
-    if(dw_opt && (M % 128 != 0 || N % 16 != 0 || K % 16 != 0 || !aligned16(dyq) || !aligned16(xq))) return QSYNC_ERR_ALIGN;
+    const int64_t mult = i8 ? 16 : 8;                           // elements per 16-byte chunk
+    if(dx_opt && (N % mult != 0 || !aligned16(dyq) || !aligned16(wqbT))) return QSYNC_ERR_ALIGN;
+    // the weight gradient reads both operands row-major: whole K tiles of contraction rows, 16-byte column chunks
+    if(dw_opt && (M % 128 != 0 || N % mult != 0 || K % mult != 0 || !aligned16(dyq) || !aligned16(xq))) return QSYNC_ERR_ALIGN;
     // the data gradient is the NT GEMM of qsync_qlinear_bwd; it also owns the bias gradient
     if(dx_opt || db_opt)
     {
-        const int rc = qsync_qlinear_bwd(QSYNC_INT8, M, N, K, dyq, nullptr, sdy, nullptr, nullptr, wqbT, swb, wbgran, dx_opt, dxdt,
+        const int rc = qsync_qlinear_bwd(tag, M, N, K, dyq, nullptr, sdy, nullptr, nullptr, wqbT, swb, wbgran, dx_opt, dxdt,
                                          nullptr, dwdt, db_opt, dy_float_opt, dydt, acc_dx_dump_opt, nullptr, workspace,
                                          workspace_bytes, stream);
         if(rc != QSYNC_OK) return rc;
     }
     if(!dw_opt || N == 0 || K == 0) return QSYNC_OK;
-    const GemmPlan plan   = plan_gemm(QSYNC_INT8, N, K, M, -1, -1, true, /*tn=*/M > 0);
-    const size_t   off_dw = round256(plan_gemm(QSYNC_INT8, M, K, N).workspace);
+    const GemmPlan plan   = plan_gemm(tag, N, K, M, -1, -1, true, /*tn=*/M > 0);
+    const size_t   off_dw = round256(plan_gemm(tag, M, K, N).workspace);
     if(plan.workspace > 0)
     {
-        if(!workspace || workspace_bytes < qsync_qlinear_bwd_rm_workspace_bytes(M, N, K)) return QSYNC_ERR_WORKSPACE;
+        if(!workspace || workspace_bytes < qsync_qlinear_bwd_rm_workspace_bytes(tag, M, N, K)) return QSYNC_ERR_WORKSPACE;
         if(!aligned16(workspace)) return QSYNC_ERR_ALIGN;
     }
     GemmProblem p{};
-    p.prec = QSYNC_INT8; p.M = N; p.N = K; p.K = M;
+    p.prec = tag; p.M = N; p.N = K; p.K = M;
     p.A = dyq; p.B = xq; p.C = dw_opt; p.c_dtype = dwdt;
-    p.s0 = sdy; p.s1 = sx; p.acc_dump = acc_dw_dump_opt;
+    p.s0 = i8 ? sdy : nullptr; p.s1 = i8 ? sx : nullptr; p.acc_dump = acc_dw_dump_opt;
     p.tn = true;
     if(M == 0)
     {   // empty contraction: the NT form writes the zeros (no operand is read)

@@ -146,9 +146,27 @@ __device__ __forceinline__ void item_of_block(int lin, int tiles_m, int tiles_n,
     tn    = __builtin_amdgcn_readfirstlane(in / gsz);
 }
 
-template <typename T> __device__ __forceinline__ T from_f32_out(float v);
-template <> __device__ __forceinline__ float  from_f32_out<float>(float v) { return v; }
-template <> __device__ __forceinline__ __half from_f32_out<__half>(float v) { return __float2half_rn(v); }
+// Output value a*s + b of the fused epilogues.  fp32: the fused multiply-add.  binary16: the same sum rounded ONCE
+// to binary16, by the mixed-precision fused multiply-add (fp32 sources, binary16 result) -- written as an
+// instruction so that every epilogue (per-tile staged and element-wise, persistent) produces the same bits; left to
+// the compiler, fmaf + conversion becomes that instruction in some places and a fp32 result converted afterwards
+// (two roundings, different at binary16 ties) in others.
+template <typename T> __device__ __forceinline__ T fma_out(float a, float s, float b);
+template <> __device__ __forceinline__ float fma_out<float>(float a, float s, float b) { return fmaf(a, s, b); }
+template <> __device__ __forceinline__ __half fma_out<__half>(float a, float s, float b)
+{
+    uint32_t r;
+    asm("v_fma_mixlo_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(s), "v"(b));
+    return __ushort_as_half(static_cast<unsigned short>(r & 0xFFFFu));
+}
+// two of them packed in one word (first value in the low half)
+__device__ __forceinline__ uint32_t fma_out_half2(float a0, float s0, float b0, float a1, float s1, float b1)
+{
+    uint32_t r;
+    asm("v_fma_mixlo_f16 %0, %1, %2, %3\n\tv_fma_mixhi_f16 %0, %4, %5, %6"
+        : "=&v"(r) : "v"(a0), "v"(s0), "v"(b0), "v"(a1), "v"(s1), "v"(b1));
+    return r;
+}
 
 // One direct global->LDS load of 16 bytes per lane.  D selects the wavefront's D-th 1 KB slot
 // relative to the shared LDS base `lds_mid` (which points DPW/2 KB into the wavefront's slice).
@@ -273,11 +291,25 @@ template <int N, typename F> __device__ __forceinline__ void static_for(F&& f)
 {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
-// Transposing 8-byte read (int8): within 16 lanes, lane j receives byte j%8 of the words read by lanes j/8, j/8 + 2, ...
-template <int OFF> __device__ __forceinline__ void frag_read_tr(v2u32& dst, uint32_t addr)
+// Transposing 8-byte reads, sixteen lanes at a time.  ESZ 1: the lanes read 8 rows x 16 bytes (lane s: half s%2 of
+// row s/2) and lane j receives the eight bytes of column j.  ESZ 2: they read 4 rows x 32 bytes (lane s: quarter
+// s%4 of row s/4) and lane j receives the four 16-bit elements of column j.
+template <int ESZ, int OFF> __device__ __forceinline__ void frag_read_tr(v2u32& dst, uint32_t addr)
 {
     static_assert(OFF >= 0 && OFF < 65536, "immediate offset");
-    asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    if constexpr(ESZ == 1)
+        asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    else
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+}
+// XOR term (in 16-byte chunks) of stage row `row` of a TN operand region whose rows are RB bytes long: the rows that
+// one pass of a transposing read touches (8 rows x 32 bytes for ESZ 1, 4 rows x 64 bytes for ESZ 2) land in
+// different bank groups.  Unchanged by the row steps between the reads of one lane (multiples of 8, resp. 4).
+template <int ESZ, int RB> __device__ __forceinline__ int tn_swizzle(int row)
+{
+    constexpr int CPR = RB / 16;                                    // chunks per row
+    if constexpr(ESZ == 1) return 2 * ((row / (16 / CPR)) % (CPR / 2));
+    else                   return RB >= 256 ? 4 * (row % 4) : 4 * ((row / 2) % 2);
 }
 template <int F, int... Is>
 __device__ __forceinline__ void frag_reads(v4i32 (&dst)[F], uint32_t addr, std::integer_sequence<int, Is...>)
@@ -285,19 +317,21 @@ __device__ __forceinline__ void frag_reads(v4i32 (&dst)[F], uint32_t addr, std::
     (frag_read<Is>(dst[Is], addr), ...);
 }
 
-// TN (int8 only): both operands are handed over with the contraction axis as their ROW axis, A [P, M] and
+// TN (int8 and binary16): both operands are handed over with the contraction axis as their ROW axis, A [P, M] and
 // B [P, N] row-major (C[m,n] = sum_p A[p,m] B[p,n]): the weight gradient dW = dY^T X straight from the row-major
-// codes, no transposed copies.  A stage then holds 128 contraction rows of each operand (rows of BM / BN bytes),
-// and the fragments come out of LDS through the transposing read of gfx950 (ds_read_b64_tr_b8): sixteen lanes read
-// eight rows x 16 bytes and receive, lane j, the eight bytes of column j -- eight consecutive contraction
-// indices of one output row, which is what the matrix instruction wants.  16-byte chunks are XOR-swizzled per
-// row so that the 32 lanes of one access pass touch all 64 banks once.  Everything behind the fragments
+// operands, no transposed copies.  A stage then holds 128 (int8) or 64 (binary16) contraction rows of each operand
+// (rows of BM / BN elements), and the fragments come out of LDS through the transposing reads of gfx950
+// (ds_read_b64_tr_b8 / _b16): sixteen lanes read 8 rows x 16 bytes (4 rows x 32 bytes) and receive, lane j, the
+// eight (four) elements of column j -- consecutive contraction indices of one output row, which is what the
+// matrix instruction wants; two reads make a lane's 16 operand bytes.  16-byte chunks are XOR-swizzled per row so
+// that the lanes of one access pass touch all banks once.  Everything behind the fragments
 // (matrix instructions, epilogue, split K) is shared with the NT form.  Kb is the contraction length P here.
 template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT, bool CONV = false, bool TN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKernelArgs p)
 {
     static_assert(!(SPLIT && CONV), "the implicit patch matrix is not combined with split K");
-    static_assert(!TN || (std::is_same<TR, I8Traits>::value && !CONV && BM == BN), "TN: int8 operands, square tiles");
+    static_assert(!TN || (TR::kElemBytes <= 2 && !CONV && BM == BN && BM >= 64), "TN: int8 or binary16 operands, square tiles");
+    constexpr int ESZ = TR::kElemBytes;
     typedef typename TR::accv_t accv_t;
     typedef typename TR::acc_t  acc_t;
     constexpr int kThreads = 64 * WGM * WGN;
@@ -341,7 +375,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     static_assert(kUniformSide, "a wavefront must not straddle the A/B boundary of a stage");
     const bool     is_a      = wave * DPW < BM / 8;
     // TN: the panel starts at the tile's first column of the operand (its rows are contraction indices)
-    const uint8_t* gbase     = TN ? (is_a ? p.A + m0 : p.B + n0)
+    const uint8_t* gbase     = TN ? (is_a ? p.A + m0 * ESZ : p.B + n0 * ESZ)
                                   : (is_a ? p.A + m0 * p.Kb : ((!CONV && p.remap_C > 0) ? p.B : p.B + n0 * p.Kb));
     const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
     uint32_t       voff[DPW];                                         // lane offset + kDmaBias - immediate
@@ -351,18 +385,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
         int imm[DPW];
         fill_dma_imms<DPW>(imm, std::make_integer_sequence<int, DPW>{});
         if constexpr(TN)
-        {   // instruction q of the stage fills LDS bytes [1024 q, 1024 q + 1024) of the A region (128 rows of BM
-            // bytes), then of the B region; a lane's 16 bytes are chunk (position ^ swizzle(row)) of its row
-            constexpr int CPR = BM / 16;                                   // chunks per region row
-            const int64_t ld    = is_a ? p.M : p.N;                        // operand row length in bytes
-            const int64_t width = is_a ? p.M - m0 : p.N - n0;              // valid bytes of this tile's columns (>= 16)
+        {   // instruction q of the stage fills LDS bytes [1024 q, 1024 q + 1024) of the A region (128 / ESZ rows of
+            // BM elements), then of the B region; a lane's 16 bytes are chunk (position ^ swizzle(row)) of its row
+            constexpr int RB = BM * ESZ;                                   // bytes per region row
+            const int64_t ld    = (is_a ? p.M : p.N) * ESZ;                // operand row length in bytes
+            const int64_t width = (is_a ? p.M - m0 : p.N - n0) * ESZ;      // valid bytes of this tile's columns (>= 16)
 #pragma unroll
             for(int d = 0; d < DPW; ++d)
             {
                 const int q     = wave * DPW + d - (is_a ? 0 : BM / 8);
                 const int o     = q * 1024 + lane * 16;
-                const int row   = o / BM, pos = (o % BM) / 16;
-                int       chunk = pos ^ (2 * ((row / (16 / CPR)) % (CPR / 2)));
+                const int row   = o / RB, pos = (o % RB) / 16;
+                int       chunk = pos ^ tn_swizzle<ESZ, RB>(row);
                 if(static_cast<int64_t>(chunk) * 16 >= width) chunk = 0;    // columns past the matrix: any valid chunk, never stored
                 voff[d] = static_cast<uint32_t>(static_cast<int64_t>(row) * ld + chunk * 16 + kDmaBias - imm[d]);
             }
@@ -477,22 +511,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // is exactly "the older of two fragment sets has arrived".
     v4i32          af[2][FM], bf[2][FN];
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t*)lds));
-    // TN: lane (kb = lane/32, g = (lane%32)/16, s = lane%16) supplies, for fragment f of a side, the 8-byte half s%2
-    // of chunk (first chunk of the sub-tile + 2f + g) of contraction row 32 ks + 16 kb + 8 r + s/2 (r = 0, 1: the two
-    // reads of a fragment) and receives row 16 g + s of the fragment, contraction indices 32 ks + 16 kb + 8 r + 0..7.
+    // TN: lane (kb = lane/32, g = (lane%32)/16, s = lane%16) receives row 16 g + s of a fragment.
+    // int8: it supplies the 8-byte half s%2 of chunk (first chunk of the sub-tile + 2f + g) of contraction row
+    // 32 ks + 16 kb + 8 r + s/2 (r = 0, 1: the two reads of a fragment) and receives contraction indices
+    // 32 ks + 16 kb + 8 r + 0..7.  binary16: the 8-byte half s%2 of chunk (first chunk + 4f + 2g + (s%4)/2) of
+    // contraction row 16 ks + 8 kb + 4 r + s/4; it receives contraction indices 16 ks + 8 kb + 4 r + 0..3.
     uint32_t tn_a[TN ? FM : 1], tn_b[TN ? FN : 1];
     if constexpr(TN)
     {
-        constexpr int CPR = BM / 16;
+        constexpr int RB = BM * ESZ;
         const int s16 = lane & 15, g = (lane >> 4) & 1, kb16 = lane >> 5;
-        const int prow = 16 * kb16 + s16 / 2;                              // + 32 ks + 8 r through the immediate
-        const int swz  = 2 * ((prow / (16 / CPR)) % (CPR / 2));            // unchanged by + 8 r and + 32 ks
+        const int prow = ESZ == 1 ? 16 * kb16 + s16 / 2 : 8 * kb16 + s16 / 4;   // + ks and r steps through the immediate
+        const int swz  = tn_swizzle<ESZ, RB>(prow);
+        const int lch  = ESZ == 1 ? g : 2 * g + (s16 & 3) / 2;                   // chunk inside the fragment's columns
+        constexpr int CPF = 2 * ESZ;                                            // chunks per 32-column fragment
 #pragma unroll
         for(int f = 0; f < FM; ++f)
-            tn_a[f] = static_cast<uint32_t>(prow * BM + ((((wm * WTM) / 16 + 2 * f + g) ^ swz) * 16) + 8 * (s16 & 1));
+            tn_a[f] = static_cast<uint32_t>(prow * RB + ((((wm * WTM * ESZ) / 16 + CPF * f + lch) ^ swz) * 16) + 8 * (s16 & 1));
 #pragma unroll
         for(int f = 0; f < FN; ++f)
-            tn_b[f] = static_cast<uint32_t>(128 * BM + prow * BN + ((((wn * WTN) / 16 + 2 * f + g) ^ swz) * 16) + 8 * (s16 & 1));
+            tn_b[f] = static_cast<uint32_t>(128 * BM + prow * RB + ((((wn * WTN * ESZ) / 16 + CPF * f + lch) ^ swz) * 16) + 8 * (s16 & 1));
     }
     auto           load_frags = [&](auto buf_tag, int stage, int ks) {
         constexpr int  buf = decltype(buf_tag)::value;
@@ -502,15 +540,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
             static_for<FM>([&](auto ft) {
                 constexpr int f = decltype(ft)::value;
                 v2u32 lo, hi;
-                frag_read_tr<0>(lo, sb + tn_a[f]);
-                frag_read_tr<8 * BM>(hi, sb + tn_a[f]);
+                frag_read_tr<ESZ, 0>(lo, sb + tn_a[f]);
+                frag_read_tr<ESZ, 8 * BM>(hi, sb + tn_a[f]);
                 af[buf][f] = v4i32{static_cast<int>(lo.x), static_cast<int>(lo.y), static_cast<int>(hi.x), static_cast<int>(hi.y)};
             });
             static_for<FN>([&](auto ft) {
                 constexpr int f = decltype(ft)::value;
                 v2u32 lo, hi;
-                frag_read_tr<0>(lo, sb + tn_b[f]);
-                frag_read_tr<8 * BN>(hi, sb + tn_b[f]);
+                frag_read_tr<ESZ, 0>(lo, sb + tn_b[f]);
+                frag_read_tr<ESZ, 8 * BN>(hi, sb + tn_b[f]);
                 bf[buf][f] = v4i32{static_cast<int>(lo.x), static_cast<int>(lo.y), static_cast<int>(hi.x), static_cast<int>(hi.y)};
             });
             return;
@@ -680,8 +718,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                                 o[e] = acc[i][j][vq * 4 + e];
                             else
                             {
-                                const float y = fmaf(static_cast<float>(acc[i][j][vq * 4 + e]), f4[e], b4[e]);
-                                o[e] = from_f32_out<out_t>(y);
+                                o[e] = fma_out<out_t>(static_cast<float>(acc[i][j][vq * 4 + e]), f4[e], b4[e]);
                             }
                         }
                         uint8_t* dst = stg + (ii * 32 + frag_row) * PITCH + (j * 32 + 8 * vq + 4 * khalf) * OS;
@@ -788,12 +825,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                     const int64_t row = wrow0 + i * 32 + frag_row;
                     if(row < p.M && cok)
                     {
-                        // (the same expressions as the vector path: a binary16 output is the fused multiply-add rounded
-                        // once to binary16, which the compiler maps to one mixed-precision instruction)
+                        // (the same arithmetic as the vector path: a binary16 output is the fused multiply-add rounded
+                        // once to binary16)
                         float stored;
                         if(p.c_is_f16)
                         {
-                            const __half h = __float2half_rn(fmaf(static_cast<float>(acc[i][j][v]), f, b));
+                            const __half h = fma_out<__half>(static_cast<float>(acc[i][j][v]), f, b);
                             static_cast<__half*>(p.C)[row * p.N + col] = h;
                             stored = __half2float(h);
                         }
@@ -843,8 +880,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
 //   * barriers are bare s_barrier instructions behind an LDS wait (the compiler's __syncthreads would wait for
 //     every vector-memory operation of the wavefront, stores included), and every LDS access behind the first
 //     store is written as an instruction for the same reason.
-typedef float    v2f32 __attribute__((ext_vector_type(2)));
-typedef _Float16 v2f16 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_lds_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); __builtin_amdgcn_sched_barrier(0); }
 // LDS accesses as instructions; OFF is the instruction's immediate byte offset (16 bits)
@@ -1055,15 +1090,14 @@ __global__ __launch_bounds__(512) void gemm_nt_persistent_kernel(const GemmKerne
                 constexpr int j = decltype(jt)::value;
                 static_for<4>([&](auto vt) {
                     constexpr int vq = decltype(vt)::value;
-                    float y[4];
-#pragma unroll
-                    for(int e = 0; e < 4; ++e)
-                        y[e] = fmaf(static_cast<float>(acc[i][j][vq * 4 + e]), __uint_as_float(rs[j][vq][e]),
-                                    __uint_as_float(rb[j][vq][e]));
-                    // two values per conversion instruction (round to nearest even, as the scalar conversion)
-                    const v2f16 lo = __builtin_convertvector(v2f32{y[0], y[1]}, v2f16);
-                    const v2f16 hi = __builtin_convertvector(v2f32{y[2], y[3]}, v2f16);
-                    const v2u32 packed = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    // the per-tile kernel's arithmetic: each value one fused multiply-add rounded once to binary16
+                    auto pair = [&](int e) {
+                        return fma_out_half2(static_cast<float>(acc[i][j][vq * 4 + e]), __uint_as_float(rs[j][vq][e]),
+                                             __uint_as_float(rb[j][vq][e]),
+                                             static_cast<float>(acc[i][j][vq * 4 + e + 1]), __uint_as_float(rs[j][vq][e + 1]),
+                                             __uint_as_float(rb[j][vq][e + 1]));
+                    };
+                    const v2u32 packed = {pair(0), pair(2)};
                     lds_write_b64<i * 32 * PITCH + (j * 32 + 8 * vq) * 2>(wr_base, packed);
                 });
             });
@@ -1265,9 +1299,9 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool
     const bool       conv  = a.conv_H > 0;
     const int        which = tn ? (splits > 1 ? 4 : 3) : (conv ? 2 : (splits > 1 ? 1 : 0));
     if(conv && splits > 1) return hipErrorInvalidValue;
-    if(tn && (conv || !std::is_same<TR, I8Traits>::value)) return hipErrorInvalidValue;
+    if(tn && (conv || TR::kElemBytes > 2)) return hipErrorInvalidValue;
     const void* fn = nullptr;
-    if constexpr(std::is_same<TR, I8Traits>::value)
+    if constexpr(TR::kElemBytes <= 2)
         if(tn)
             fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, false, true>)
                             : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, false, true>);
@@ -1282,7 +1316,7 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool
         if(e != hipSuccess) return e;
         attr_set[which] = true;
     }
-    if constexpr(std::is_same<TR, I8Traits>::value)
+    if constexpr(TR::kElemBytes <= 2)
         if(tn)
         {
             if(splits > 1)
@@ -1430,8 +1464,10 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     a.conv_H = a.conv_W = a.conv_Cb = 0;
     a.remap_C = a.remap_shift = 0;
     if(p.tn)
-    {   // A [K, M], B [K, N] row-major int8: rows are contraction indices (128 per K tile), 16-byte column chunks
-        if(p.prec != 8 || p.conv_H > 0 || p.b_remap_C > 0 || p.K % kRowBytes != 0 || p.M % 16 != 0 || p.N % 16 != 0
+    {   // A [K, M], B [K, N] row-major int8 or binary16: rows are contraction indices (128 bytes' worth per K tile),
+        // 16-byte column chunks
+        if((p.prec != 8 && p.prec != 16) || p.conv_H > 0 || p.b_remap_C > 0 || (p.K * esz) % kRowBytes != 0
+           || (p.M * esz) % 16 != 0 || (p.N * esz) % 16 != 0
            || p.M >= (int64_t(1) << 24) || p.N >= (int64_t(1) << 24)
            || ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) != 0)
             return hipErrorInvalidValue;
@@ -1470,7 +1506,7 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
        && g_persistent_mode == 1)
         return p.prec == 8 ? launch_persistent<I8Traits>(a, stream) : launch_persistent<F16Traits>(a, stream);
     hipError_t e = p.prec == 8    ? launch_traits<I8Traits>(plan.tile, a, splits, stream, p.tn)
-                   : p.prec == 16 ? launch_traits<F16Traits>(plan.tile, a, splits, stream)
+                   : p.prec == 16 ? launch_traits<F16Traits>(plan.tile, a, splits, stream, p.tn)
                                   : launch_traits<F32Traits>(plan.tile, a, splits, stream);
     if(e != hipSuccess || splits == 1) return e;
     const bool vec4 = p.N % 4 == 0 && ((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(p.C)) & 15) == 0;

@@ -38,9 +38,10 @@ class QLinear:
                  w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
                  bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda",
                  bwd_tag: Optional[int] = None, collect_y_amax: bool = False, transposed_copies: Optional[bool] = None):
-        """transposed_copies: INT8 only.  False: the activation and gradient codes are kept row-major only and the
-        weight-gradient GEMM reads them as they are (qsync_qlinear_bwd_rm; needs M % 128 == 0, N % 16 == 0,
-        K % 16 == 0); True: the quantizer also writes the transposed copies xqT / dyqT for qsync_qlinear_bwd.
+        """transposed_copies: INT8 and FP16 tags.  False: the activation and gradient operands are kept row-major only
+        and the weight-gradient GEMM reads them as they are (qsync_qlinear_bwd_rm; needs M % 128 == 0 and N, K
+        multiples of 16 -- 8 for FP16); True: the conversion also writes the transposed copies xqT / dyqT for
+        qsync_qlinear_bwd.
         None picks False when the shape allows it and the copies are large enough to be worth it: the row-major
         weight-gradient GEMM is 6-8 % slower on 256-wide tiles and loses the 64-wide tile, the quantizer saves one
         byte written per element (measured on MI355X: 16384x4096x1024 operators 0.803 -> 0.749 ms per step,
@@ -53,9 +54,11 @@ class QLinear:
             raise ValueError("bwd_tag: only the FP16 backward of an INT8 forward differs from the forward tag")
         self.w_gran, self.dy_round, self.seed, self.bits = w_gran, dy_round, philox_seed, bits
         self.offset = 0
-        rm_ok = tag == Q.INT8 and self.bwd_tag == Q.INT8 and M % 128 == 0 and N % 16 == 0 and K % 16 == 0
+        mult = 16 if tag == Q.INT8 else 8
+        rm_ok = tag in (Q.INT8, Q.FP16) and self.bwd_tag == tag and M % 128 == 0 and N % mult == 0 and K % mult == 0
         if transposed_copies is False and not rm_ok:
-            raise ValueError("transposed_copies=False needs tag INT8 with INT8 backward, M % 128 == 0, N % 16 == 0, K % 16 == 0")
+            raise ValueError("transposed_copies=False needs tag INT8 or FP16 with the same backward tag, M % 128 == 0, "
+                             "N and K multiples of 16 (FP16: 8)")
         self.rowmajor_bwd = (rm_ok and M * (N + K) >= (32 << 20)) if transposed_copies is None else not transposed_copies
         dy_dtype = dy_dtype or x_dtype
         dev = device
@@ -88,7 +91,7 @@ class QLinear:
                                    Q.qsync_absmax_workspace_bytes(N, K, Q.PER_TENSOR)), dev)
         self.ws_fwd = _ws(Q.qsync_qlinear_workspace_bytes(tag, M, N, K), dev)
         self.ws_bwd = _ws(max(Q.qsync_qlinear_bwd_workspace_bytes(self.bwd_tag, M, N, K),
-                              Q.qsync_qlinear_bwd_rm_workspace_bytes(M, N, K) if self.rowmajor_bwd else 0), dev)
+                              Q.qsync_qlinear_bwd_rm_workspace_bytes(tag, M, N, K) if self.rowmajor_bwd else 0), dev)
         if self.bwd_tag != tag:
             # FP16 backward of the INT8 forward: one C-ABI call; its workspace receives the binary16 operands
             # (dequantized X^T, dequantized W and its transpose, cast dY and its transpose)
@@ -112,9 +115,10 @@ class QLinear:
             Q.qsync_quantize(x, M, K, K, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq,
                              self.xqT, stream)
         elif x.dtype == _TORCH_OF_TAG[self.tag] and x.is_contiguous():
-            # already in the operand type: the tensor itself is the saved operand, only its transpose is written
+            # already in the operand type: the tensor itself is the saved operand, only its transpose (if kept) is written
             self.xq = x
-            Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, None, self.xqT, stream)
+            if self.xqT is not None:
+                Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, None, self.xqT, stream)
         else:
             Q.qsync_quantize(x, M, K, K, self.tag, 0, 0, 0, 0, 0, None, self.xq, self.xqT, stream)
 
@@ -163,7 +167,8 @@ class QLinear:
             self.offset += (M * N + 7) // 8
         elif dy.dtype == _TORCH_OF_TAG[self.tag] and dy.is_contiguous():
             self.dyq = dy
-            Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, None, self.dyqT, stream)
+            if self.dyqT is not None:
+                Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, None, self.dyqT, stream)
         else:
             Q.qsync_quantize(dy, M, N, N, self.tag, 0, 0, 0, 0, 0, None, self.dyq, self.dyqT, stream)
 
@@ -197,12 +202,13 @@ class QLinear:
         if self.bwd_tag != self.tag:
             self._fp16_backward(dy, self.dx, self.dw, self.db, stream)
             return
-        if self.rowmajor_bwd:      # (db already came out of the absmax pass over dY)
-            Q.qsync_qlinear_bwd_rm(self.M, self.N, self.K, self.dyq, self.sdy, self.xq, self.sx, self.wqbT, self.swb,
-                                   self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW, self.dx, self.dw, None, None,
+        want_db = dy is not None and self.tag != Q.INT8      # INT8: db already came out of the absmax pass over dY
+        if self.rowmajor_bwd:
+            Q.qsync_qlinear_bwd_rm(self.tag, self.M, self.N, self.K, self.dyq, self.sdy, self.xq, self.sx, self.wqbT, self.swb,
+                                   self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW, self.dx, self.dw,
+                                   self.db if want_db else None, dy if want_db else None,
                                    self.acc_dx, self.acc_dw, self.ws_bwd, stream)
             return
-        want_db = dy is not None and self.tag != Q.INT8      # INT8: db already came out of the absmax pass over dY
         Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
                             self.wqbT, self.swb, self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW,
                             self.dx, self.dw, self.db if want_db else None, dy if want_db else None, self.acc_dx,
@@ -229,13 +235,14 @@ class QLinear:
         if self.bwd_tag != self.tag:
             self._fp16_backward(dy, dx, dw, self.db if dw is not None else None, stream)
             return
+        want_db = dy is not None and self.tag != Q.INT8 and dw is not None
         if self.rowmajor_bwd:
-            Q.qsync_qlinear_bwd_rm(self.M, self.N, self.K, self.dyq, self.sdy, self.xq, self.sx, self.wqbT, self.swb,
-                                   self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW, dx, dw, None, None,
+            Q.qsync_qlinear_bwd_rm(self.tag, self.M, self.N, self.K, self.dyq, self.sdy, self.xq, self.sx, self.wqbT, self.swb,
+                                   self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW, dx, dw,
+                                   self.db if want_db else None, dy if want_db else None,
                                    self.acc_dx if dx is not None else None, self.acc_dw if dw is not None else None,
                                    self.ws_bwd, stream)
             return
-        want_db = dy is not None and self.tag != Q.INT8 and dw is not None
         Q.qsync_qlinear_bwd(self.tag, self.M, self.N, self.K, self.dyq, self.dyqT, self.sdy, self.xqT, self.sx,
                             self.wqbT, self.swb, self.w_gran if self.w_gran == Q.PER_TENSOR else Q.PER_ROW,
                             dx, dw, self.db if want_db else None, dy if want_db else None,

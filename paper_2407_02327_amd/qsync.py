@@ -44,9 +44,9 @@ SIGNATURES = {
     "qsync_qlinear_bwd": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i,
                                _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]),
     "qsync_qlinear_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
-    "qsync_qlinear_bwd_rm": (_i, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _i, _vp, _vp,
+    "qsync_qlinear_bwd_rm": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _i, _vp, _vp,
                                  _vp, _sz, _vp]),
-    "qsync_qlinear_bwd_rm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "qsync_qlinear_bwd_rm_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_qlinear_bwd_fp16_of_int8": (_i, [_i64, _i64, _i64, _vp, _i, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _sz,
                                            ctypes.POINTER(ctypes.c_size_t), _vp]),
     "qsync_qlinear_bwd_fp16_of_int8_workspace_bytes": (_sz, [_i64, _i64, _i64, _i]),
@@ -192,13 +192,13 @@ def qsync_qlinear_bwd(tag, M, N, K, dyq, dyqT, sdy, xqT, sx, wqbT, swb, wbgran, 
                                  _stream(stream)))
 
 
-def qsync_qlinear_bwd_rm_workspace_bytes(M: int, N: int, K: int) -> int:
-    return int(lib.qsync_qlinear_bwd_rm_workspace_bytes(M, N, K))
+def qsync_qlinear_bwd_rm_workspace_bytes(tag: int, M: int, N: int, K: int) -> int:
+    return int(lib.qsync_qlinear_bwd_rm_workspace_bytes(tag, M, N, K))
 
 
-def qsync_qlinear_bwd_rm(M, N, K, dyq, sdy, xq, sx, wqbT, swb, wbgran, dx_opt, dw_opt, db_opt, dy_float_opt, acc_dx_dump_opt,
+def qsync_qlinear_bwd_rm(tag, M, N, K, dyq, sdy, xq, sx, wqbT, swb, wbgran, dx_opt, dw_opt, db_opt, dy_float_opt, acc_dx_dump_opt,
                          acc_dw_dump_opt, workspace, stream=None) -> None:
-    _check(lib.qsync_qlinear_bwd_rm(M, N, K, _ptr(dyq), _ptr(sdy), _ptr(xq), _ptr(sx), _ptr(wqbT), _ptr(swb), wbgran,
+    _check(lib.qsync_qlinear_bwd_rm(tag, M, N, K, _ptr(dyq), _ptr(sdy), _ptr(xq), _ptr(sx), _ptr(wqbT), _ptr(swb), wbgran,
                                     _ptr(dx_opt), dtype_code(dx_opt) if dx_opt is not None else F32,
                                     _ptr(dw_opt), dtype_code(dw_opt) if dw_opt is not None else F32, _ptr(db_opt),
                                     _ptr(dy_float_opt), dtype_code(dy_float_opt) if dy_float_opt is not None else F32,

@@ -446,12 +446,13 @@ def test_fp16_backward_of_int8_forward_validation():
 
 def test_row_major_backward_validation():
     f = lib.qsync_qlinear_bwd_rm
-    need = lib.qsync_qlinear_bwd_rm_workspace_bytes(256, 32, 48)
+    need = lib.qsync_qlinear_bwd_rm_workspace_bytes(qsync.INT8, 256, 32, 48)
     assert need >= lib.qsync_qlinear_bwd_workspace_bytes(qsync.INT8, 256, 32, 48)
-    assert lib.qsync_qlinear_bwd_rm_workspace_bytes(-1, 32, 48) == 0
+    assert lib.qsync_qlinear_bwd_rm_workspace_bytes(qsync.INT8, -1, 32, 48) == 0
+    assert lib.qsync_qlinear_bwd_rm_workspace_bytes(qsync.FP32, 256, 32, 48) == 0
     W = P(1 << 20)
-    ok = (256, 32, 48, A, A, A, A, A, A, qsync.PER_ROW, A, qsync.F16, A, qsync.F32, None, None, qsync.F32, None, None, W, 1 << 20, None)
-    names = "M N K dyq sdy xq sx wqbT swb wbgran dx dxdt dw dwdt db dyf dydt accdx accdw ws wsb st".split()
+    ok = (qsync.INT8, 256, 32, 48, A, A, A, A, A, A, qsync.PER_ROW, A, qsync.F16, A, qsync.F32, None, None, qsync.F32, None, None, W, 1 << 20, None)
+    names = "tag M N K dyq sdy xq sx wqbT swb wbgran dx dxdt dw dwdt db dyf dydt accdx accdw ws wsb st".split()
     chg = lambda **kw: tuple(kw.get(i, v) for i, v in zip(names, ok))
     assert f(*chg(dyq=None)) == qsync.ERR_NULL
     assert f(*chg(xq=None)) == qsync.ERR_NULL
@@ -467,3 +468,9 @@ def test_row_major_backward_validation():
     assert f(*chg(xq=U)) == qsync.ERR_ALIGN
     assert f(*chg(M=0)) in (qsync.OK, qsync.ERR_HIP)                   # empty batch: dW is written as zeros
     assert f(*chg()) in (qsync.OK, qsync.ERR_HIP)
+    assert f(*chg(tag=7)) == qsync.ERR_BAD_ENUM
+    assert f(*chg(tag=qsync.FP32)) == qsync.ERR_UNSUPPORTED
+    assert f(*chg(tag=qsync.FP16, N=24, sdy=None, sx=None, swb=None)) in (qsync.OK, qsync.ERR_HIP)   # binary16: multiples of 8, no scales
+    assert f(*chg(tag=qsync.FP16, N=20)) == qsync.ERR_ALIGN
+    assert f(*chg(tag=qsync.FP16, accdw=A)) == qsync.ERR_UNSUPPORTED
+    assert f(*chg(sdy=None)) == qsync.ERR_NULL                         # INT8 needs its scales

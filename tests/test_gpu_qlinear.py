@@ -63,7 +63,11 @@ def run_case(case: wl.LinearCase, tag: int, y_dtype=np.float32, dx_dtype=np.floa
     elif check_codes:
         assert_bits_equal(host(op.xq), ref["xq"], "x cast")
         assert_bits_equal(host(op.wqbT), ref["wq"].T, "w cast transposed")
-        assert_bits_equal(host(op.dyqT), ref["dyq"].T, "dy cast transposed")
+        assert_bits_equal(host(op.dyq), ref["dyq"], "dy cast")
+        if op.dyqT is not None:
+            assert_bits_equal(host(op.dyqT), ref["dyq"].T, "dy cast transposed")
+        if op.xqT is not None:
+            assert_bits_equal(host(op.xqT), ref["xq"].T, "x cast transposed")
     assert_close(host(op.y), ref["y"], "Y")
     assert_close(host(op.dx), ref["dx"], "dX")
     assert_close(host(op.dw), ref["dw"], "dW")
@@ -631,9 +635,9 @@ def test_weight_gradient_from_row_major_codes(tile):
             assert not (o1 or o2)
             dx, dw = torch.empty((M, K), dtype=torch.float16, device="cuda"), torch.empty((N, K), dtype=torch.float32, device="cuda")
             adx, adw = torch.empty((M, K), dtype=torch.int32, device="cuda"), torch.empty((N, K), dtype=torch.int32, device="cuda")
-            w = torch.zeros(max(Q.qsync_qlinear_bwd_rm_workspace_bytes(M, N, K), 256), dtype=torch.uint8, device="cuda")
+            w = torch.zeros(max(Q.qsync_qlinear_bwd_rm_workspace_bytes(Q.INT8, M, N, K), 256), dtype=torch.uint8, device="cuda")
             wqbT = dev(np.ascontiguousarray(wqb.T))
-            Q.qsync_qlinear_bwd_rm(M, N, K, dev(dyq), dev(sdy), dev(xq), dev(sx), wqbT, dev(swb), Q.PER_ROW, dx, dw, None, None,
+            Q.qsync_qlinear_bwd_rm(Q.INT8, M, N, K, dev(dyq), dev(sdy), dev(xq), dev(sx), wqbT, dev(swb), Q.PER_ROW, dx, dw, None, None,
                                    adx, adw, w)
             assert_bits_equal(host(adw), acc_dw, "dW accumulators (row-major operands)")
             assert_bits_equal(host(adx), acc_dx, "dX accumulators")
@@ -642,8 +646,42 @@ def test_weight_gradient_from_row_major_codes(tile):
             # the production epilogue (no accumulator dump), fp32 and binary16 outputs
             for dt in (torch.float32, torch.float16):
                 dw2 = torch.empty((N, K), dtype=dt, device="cuda")
-                Q.qsync_qlinear_bwd_rm(M, N, K, dev(dyq), dev(sdy), dev(xq), dev(sx), None, None, Q.PER_ROW, None, dw2, None, None,
+                Q.qsync_qlinear_bwd_rm(Q.INT8, M, N, K, dev(dyq), dev(sdy), dev(xq), dev(sx), None, None, Q.PER_ROW, None, dw2, None, None,
                                        None, None, w)
                 assert_close(host(dw2), want_dw, f"dW {dt} without dump")
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 1, 2])
+def test_weight_gradient_from_row_major_binary16_operands(tile):
+    """qsync_qlinear_bwd_rm under the FP16 tag: dW = dY^T X from the row-major binary16 operands (16-bit transposing
+    LDS reads), dX and db as in qsync_qlinear_bwd; against the oracle's float64 sums of the same binary16 values, on
+    every tile shape, ragged N and K (multiples of 8), one and several K tiles, split K."""
+    rng = np.random.default_rng(321)
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        for (M, N, K) in [(128, 8, 8), (128, 256, 256), (256, 264, 136), (384, 40, 520), (1024, 520, 264), (4096, 136, 72),
+                          (8192, 1032, 776), (2048, 2056, 64)]:
+            say("bwd_rm fp16 tile", tile, "MNK", M, N, K)
+            dyh = (rng.standard_normal((M, N)) * 0.01).astype(np.float16)
+            xh = rng.standard_normal((M, K)).astype(np.float16)
+            wh = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+            want_dw = orc.float_gemm_nt(np.ascontiguousarray(dyh.T), np.ascontiguousarray(xh.T))
+            want_dx = orc.float_gemm_nt(dyh, np.ascontiguousarray(wh.T))
+            want_db = dyh.astype(np.float64).sum(axis=0)
+            dx, dw = torch.empty((M, K), dtype=torch.float16, device="cuda"), torch.empty((N, K), dtype=torch.float32, device="cuda")
+            db = torch.empty(N, dtype=torch.float32, device="cuda")
+            w = torch.zeros(max(Q.qsync_qlinear_bwd_rm_workspace_bytes(Q.FP16, M, N, K), 256), dtype=torch.uint8, device="cuda")
+            d_dy = dev(dyh)
+            Q.qsync_qlinear_bwd_rm(Q.FP16, M, N, K, d_dy, None, dev(xh), None, dev(np.ascontiguousarray(wh.T)), None, Q.PER_TENSOR,
+                                   dx, dw, db, d_dy, None, None, w)
+            assert_close(host(dw), want_dw, "dW (row-major binary16 operands)")
+            assert_close(host(dx), want_dx, "dX")
+            assert_close(host(db), want_db, "db")
+            dw16 = torch.empty((N, K), dtype=torch.float16, device="cuda")
+            Q.qsync_qlinear_bwd_rm(Q.FP16, M, N, K, d_dy, None, dev(xh), None, None, None, Q.PER_TENSOR, None, dw16, None, None,
+                                   None, None, w)
+            assert_close(host(dw16), want_dw, "dW binary16 output")
     finally:
         Q.qsync_debug_set_gemm_tile(-1)
