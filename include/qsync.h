@@ -340,17 +340,24 @@ size_t qsync_qlinear_bwd_rm_workspace_bytes(int tag, int64_t M, int64_t N, int64
  * One call runs the dequantizers, the casts / transposes and both FP16 GEMMs (the per-operator tag of the
  * backward is thereby a parameter of the C boundary, not of the caller's sequencing).
  * dy    [M,N] of dydt (QSYNC_F32 or QSYNC_F16), 16-byte aligned; a binary16 gradient is used in place.
- * xqT   [K,M] int8: the transposed activation codes the forward kept; sx 1 float.
+ * xq_or_xqT, x_rowmajor   the activation codes the forward kept; sx 1 float.
+ *        x_rowmajor 0: xqT [K,M], the transposed codes; x_hat^T and dY16^T are formed and the weight gradient is
+ *        the NT GEMM of qsync_qlinear_bwd.
+ *        x_rowmajor 1: xq [M,K], the forward's own operand; x_hat [M,K] is formed, no transpose of dY is written
+ *        and the weight gradient reads the row-major operands (qsync_qlinear_bwd_rm): needs M % 128 == 0 and
+ *        N, K multiples of 8 (QSYNC_ERR_ALIGN otherwise).  Same dW up to the order of the fp32 sums.
  * wq    [N,K] int8: the forward's weight codes; sw 1 float (wgran PER_TENSOR) or N floats (PER_ROW).
  * dx_opt [M,K] of dxdt, dw_opt [N,K] of dwdt, db_opt N floats; each may be NULL (its inputs may then be NULL).
  * workspace  at least qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M, N, K, dydt) bytes, 256-byte aligned
  *        (QSYNC_ERR_WORKSPACE / QSYNC_ERR_ALIGN otherwise); it receives the binary16 operands.
- * operand_offsets_opt  HOST array of 5 or NULL: byte offsets in the workspace of x_hat^T [K,M], w_hat [N,K],
- *        w_hat^T [K,N], dY16 [M,N] (unused when dy is binary16) and dY16^T [N,M] (verification aid).
+ * operand_offsets_opt  HOST array of 5 or NULL: byte offsets in the workspace of x_hat^T [K,M] (x_hat [M,K] when
+ *        x_rowmajor), w_hat [N,K], w_hat^T [K,N], dY16 [M,N] (unused when dy is binary16) and dY16^T [N,M] (unused
+ *        when x_rowmajor) (verification aid).
  * FP16 alignment rules as for qsync_qlinear_bwd: N % 8 == 0 for dX, M % 8 == 0 for dW.
  */
 int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* dy, int dydt,
-                                   const void* xqT, const float* sx, const void* wq, const float* sw, int wgran,
+                                   const void* xq_or_xqT, int x_rowmajor, const float* sx,
+                                   const void* wq, const float* sw, int wgran,
                                    void* dx_opt, int dxdt, void* dw_opt, int dwdt, float* db_opt,
                                    void* workspace, size_t workspace_bytes, size_t* operand_offsets_opt, void* stream);
 size_t qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(int64_t M, int64_t N, int64_t K, int dydt);

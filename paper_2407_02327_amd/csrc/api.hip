@@ -442,7 +442,8 @@ Fp16BwdLayout fp16_bwd_layout(int64_t M, int64_t N, int64_t K, int dydt)
     l.off_dyh  = take(dydt == QSYNC_F16 ? 0 : M * N);          // a binary16 gradient is used in place
     l.off_dyhT = take(N * M);
     l.off_gemm = at;
-    l.total    = at + qsync_qlinear_bwd_workspace_bytes(QSYNC_FP16, M, N, K);
+    const size_t nt = qsync_qlinear_bwd_workspace_bytes(QSYNC_FP16, M, N, K), rm = qsync_qlinear_bwd_rm_workspace_bytes(QSYNC_FP16, M, N, K);
+    l.total    = at + (nt > rm ? nt : rm);
     return l;
 }
 }  // namespace
@@ -454,7 +455,7 @@ size_t qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(int64_t M, int64_t N, int6
 }
 
 int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* dy, int dydt, const void* xqT,
-                                   const float* sx, const void* wq, const float* sw, int wgran, void* dx_opt, int dxdt,
+                                   int x_rowmajor, const float* sx, const void* wq, const float* sw, int wgran, void* dx_opt, int dxdt,
                                    void* dw_opt, int dwdt, float* db_opt, void* workspace, size_t workspace_bytes,
                                    size_t* operand_offsets_opt, void* stream)
 {
@@ -465,7 +466,9 @@ int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* 
     if(dx_opt && (!is_float_dtype(dxdt) || (wgran != QSYNC_PER_TENSOR && wgran != QSYNC_PER_ROW))) return QSYNC_ERR_BAD_ENUM;
     if(dw_opt && !is_float_dtype(dwdt)) return QSYNC_ERR_BAD_ENUM;
     if(!count_ok(M, N) || !count_ok(M, K) || !count_ok(N, K)) return QSYNC_ERR_BAD_SHAPE;
+    if(x_rowmajor != 0 && x_rowmajor != 1) return QSYNC_ERR_BAD_ENUM;
     if((dx_opt && N % 8 != 0) || (dw_opt && M % 8 != 0) || !aligned16(dy)) return QSYNC_ERR_ALIGN;
+    if(dw_opt && x_rowmajor && (M % 128 != 0 || N % 8 != 0 || K % 8 != 0)) return QSYNC_ERR_ALIGN;
     const Fp16BwdLayout l = fp16_bwd_layout(M, N, K, dydt);
     if(workspace_bytes < l.total) return QSYNC_ERR_WORKSPACE;
     if((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return QSYNC_ERR_ALIGN;
@@ -483,7 +486,9 @@ int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* 
     void *xhT = base + l.off_xhT, *wh = base + l.off_wh, *whT = base + l.off_whT, *dyhT = base + l.off_dyhT;
     const void* dyh = dydt == QSYNC_F16 ? dy : base + l.off_dyh;
     hipError_t e = hipSuccess;
-    if(dw_opt)      // x_hat^T = code * q_x narrowed to binary16, straight from the saved transposed codes
+    if(dw_opt && x_rowmajor)      // x_hat = code * q_x narrowed to binary16, [M,K] like the codes (xqT holds xq here)
+        e = launch_dequantize(xqT, kI8, M, K, K, nullptr, nullptr, 1.0f, sx, nullptr, xhT, kF16, st);
+    else if(dw_opt)      // x_hat^T, straight from the saved transposed codes
         e = launch_dequantize(xqT, kI8, K, M, M, nullptr, nullptr, 1.0f, sx, nullptr, xhT, kF16, st);
     if(e == hipSuccess && dx_opt)
     {   // w_hat with the forward's scales (one per output channel, or one), then its transpose for dX
@@ -492,10 +497,14 @@ int qsync_qlinear_bwd_fp16_of_int8(int64_t M, int64_t N, int64_t K, const void* 
         if(e == hipSuccess) e = launch_convert(wh, kF16, N, K, K, kF16, nullptr, whT, st);
     }
     void* const dyh_out  = dydt == QSYNC_F16 ? nullptr : const_cast<void*>(dyh);
-    void* const dyhT_out = dw_opt ? dyhT : nullptr;
+    void* const dyhT_out = (dw_opt && !x_rowmajor) ? dyhT : nullptr;
     if(e == hipSuccess && (dyh_out || dyhT_out))      // dY narrowed to binary16 (or used in place) and transposed
         e = launch_convert(dy, dydt == QSYNC_F16 ? kF16 : kF32, M, N, N, kF16, dyh_out, dyhT_out, st);
     if(e != hipSuccess) return hip_status(e);
+    if(x_rowmajor)
+        return qsync_qlinear_bwd_rm(QSYNC_FP16, M, N, K, dyh, nullptr, xhT, nullptr, whT, nullptr, QSYNC_PER_TENSOR, dx_opt, dxdt,
+                                    dw_opt, dwdt, db_opt, dy, dydt, nullptr, nullptr, base + l.off_gemm,
+                                    workspace_bytes - l.off_gemm, stream);
     return qsync_qlinear_bwd(QSYNC_FP16, M, N, K, dyh, dyhT, nullptr, xhT, nullptr, whT, nullptr, QSYNC_PER_TENSOR, dx_opt, dxdt,
                              dw_opt, dwdt, db_opt, dy, dydt, nullptr, nullptr, base + l.off_gemm, workspace_bytes - l.off_gemm,
                              stream);

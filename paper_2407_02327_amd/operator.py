@@ -55,7 +55,7 @@ class QLinear:
         self.w_gran, self.dy_round, self.seed, self.bits = w_gran, dy_round, philox_seed, bits
         self.offset = 0
         mult = 16 if tag == Q.INT8 else 8
-        rm_ok = tag in (Q.INT8, Q.FP16) and self.bwd_tag == tag and M % 128 == 0 and N % mult == 0 and K % mult == 0
+        rm_ok = tag in (Q.INT8, Q.FP16) and M % 128 == 0 and N % mult == 0 and K % mult == 0      # (either backward tag)
         if transposed_copies is False and not rm_ok:
             raise ValueError("transposed_copies=False needs tag INT8 or FP16 with the same backward tag, M % 128 == 0, "
                              "N and K multiples of 16 (FP16: 8)")
@@ -66,10 +66,11 @@ class QLinear:
         qd = _TORCH_OF_TAG[tag]
         f32 = torch.float32
         # operands in the layouts the GEMMs consume (contraction axis contiguous)
-        keep_t = not self.rowmajor_bwd or (tag == Q.INT8 and self.bwd_tag != tag)      # the FP16 backward reads xqT
-        self.xq, self.xqT = e(M, K, dt=qd), (e(K, M, dt=qd) if keep_t else None)
+        self.xq, self.xqT = e(M, K, dt=qd), (e(K, M, dt=qd) if not self.rowmajor_bwd else None)
         self.wq, self.wqbT = e(N, K, dt=qd), e(K, N, dt=qd)
-        self.dyq, self.dyqT = e(M, N, dt=qd), (e(N, M, dt=qd) if not self.rowmajor_bwd else None)
+        fp16_bwd = self.bwd_tag != tag           # that backward converts dY itself: no gradient operands are kept here
+        self.dyq = e(M, N, dt=qd) if not fp16_bwd else None
+        self.dyqT = e(N, M, dt=qd) if not (self.rowmajor_bwd or fp16_bwd) else None
         # scales (amax/qmax), inverse scales, and the raw maxima
         self.sx, self.ix, self.ax = e(1, dt=f32), e(1, dt=f32), e(1, dt=f32)
         nsw = N if w_gran == Q.PER_ROW else 1
@@ -218,14 +219,16 @@ class QLinear:
         M, N, K = self.M, self.N, self.K
         if not dy.is_contiguous():
             dy = dy.contiguous()
-        offs = Q.qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, self.xqT, self.sx, self.wq, self.sw, self.w_gran, dx, dw, db,
-                                                self.ws_bwd16, stream)
+        rm = self.rowmajor_bwd
+        offs = Q.qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, self.xq if rm else self.xqT, rm, self.sx, self.wq, self.sw,
+                                                self.w_gran, dx, dw, db, self.ws_bwd16, stream)
         h = torch.float16
         view = lambda off, r, c: self.ws_bwd16[off:off + 2 * r * c].view(h).view(r, c)
         # the binary16 operands as the call left them in its workspace (for inspection and tests)
-        self.xhT, self.wh, self.whT = view(offs[0], K, M), view(offs[1], N, K), view(offs[2], K, N)
+        self.xh, self.xhT = (view(offs[0], M, K), None) if rm else (None, view(offs[0], K, M))
+        self.wh, self.whT = view(offs[1], N, K), view(offs[2], K, N)
         self.dyh = dy if dy.dtype == h else view(offs[3], M, N)
-        self.dyhT = view(offs[4], N, M)
+        self.dyhT = None if rm else view(offs[4], N, M)
 
     def gemm_bwd_part(self, which: str, dy: Optional[torch.Tensor], stream=None) -> None:
         """One of the two independent backward GEMMs ("dx" or "dw", the latter with the bias gradient when the tag

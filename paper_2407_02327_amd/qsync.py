@@ -47,7 +47,7 @@ SIGNATURES = {
     "qsync_qlinear_bwd_rm": (_i, [_i, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _i, _vp, _vp,
                                  _vp, _sz, _vp]),
     "qsync_qlinear_bwd_rm_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
-    "qsync_qlinear_bwd_fp16_of_int8": (_i, [_i64, _i64, _i64, _vp, _i, _vp, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _sz,
+    "qsync_qlinear_bwd_fp16_of_int8": (_i, [_i64, _i64, _i64, _vp, _i, _vp, _i, _vp, _vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _sz,
                                            ctypes.POINTER(ctypes.c_size_t), _vp]),
     "qsync_qlinear_bwd_fp16_of_int8_workspace_bytes": (_sz, [_i64, _i64, _i64, _i]),
     "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
@@ -210,10 +210,13 @@ def qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M: int, N: int, K: int, dy_dt
     return int(lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(M, N, K, dy_dtype_code))
 
 
-def qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, xqT, sx, wq, sw, wgran, dx_opt, dw_opt, db_opt, workspace, stream=None):
-    """Returns the five byte offsets of the binary16 operands inside the workspace (x_hat^T, w_hat, w_hat^T, dY16, dY16^T)."""
+def qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, xq_or_xqT, x_rowmajor, sx, wq, sw, wgran, dx_opt, dw_opt, db_opt, workspace,
+                                   stream=None):
+    """Returns the five byte offsets of the binary16 operands inside the workspace (x_hat^T -- x_hat when x_rowmajor --,
+    w_hat, w_hat^T, dY16, dY16^T)."""
     offs = (ctypes.c_size_t * 5)()
-    _check(lib.qsync_qlinear_bwd_fp16_of_int8(M, N, K, _ptr(dy), dtype_code(dy), _ptr(xqT), _ptr(sx), _ptr(wq), _ptr(sw), wgran,
+    _check(lib.qsync_qlinear_bwd_fp16_of_int8(M, N, K, _ptr(dy), dtype_code(dy), _ptr(xq_or_xqT), int(bool(x_rowmajor)), _ptr(sx),
+                                              _ptr(wq), _ptr(sw), wgran,
                                               _ptr(dx_opt), dtype_code(dx_opt) if dx_opt is not None else F32,
                                               _ptr(dw_opt), dtype_code(dw_opt) if dw_opt is not None else F32, _ptr(db_opt),
                                               _ptr(workspace), _bytes(workspace), offs, _stream(stream)))

@@ -425,8 +425,11 @@ def test_fp16_backward_of_int8_forward_validation():
     assert lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(64, 32, 48, qsync.F16) < need      # binary16 dY is used in place
     assert lib.qsync_qlinear_bwd_fp16_of_int8_workspace_bytes(64, 32, 48, qsync.I8) == 0
     W = P(1 << 20)                                     # 256-byte aligned fake workspace
-    ok = (64, 32, 48, A, qsync.F32, A, A, A, A, qsync.PER_ROW, A, qsync.F16, A, qsync.F32, A, W, need, None, None)
-    chg = lambda **kw: tuple(kw.get(i, v) for i, v in zip("M N K dy dydt xqT sx wq sw wgran dx dxdt dw dwdt db ws wsb offs st".split(), ok))
+    ok = (64, 32, 48, A, qsync.F32, A, 0, A, A, A, qsync.PER_ROW, A, qsync.F16, A, qsync.F32, A, W, need, None, None)
+    chg = lambda **kw: tuple(kw.get(i, v) for i, v in zip("M N K dy dydt xqT xrm sx wq sw wgran dx dxdt dw dwdt db ws wsb offs st".split(), ok))
+    assert f(*chg(xrm=2)) == qsync.ERR_BAD_ENUM
+    assert f(*chg(xrm=1)) == qsync.ERR_ALIGN           # row-major activation codes: whole tiles of 128 contraction rows
+    assert f(*chg(xrm=1, M=128, wsb=1 << 20)) in (qsync.OK, qsync.ERR_HIP)
     assert f(*chg(dy=None)) == qsync.ERR_NULL
     assert f(*chg(wq=None)) == qsync.ERR_NULL
     assert f(*chg(sx=None)) == qsync.ERR_NULL

@@ -325,13 +325,14 @@ def test_config3_resnet_conv_full_size_fp16_tag():
     run_case(wl.config3(), Q.FP16, y_dtype=np.float16)
 
 
-def run_case_fp16_backward(case: wl.LinearCase, y_dtype=np.float32):
+def run_case_fp16_backward(case: wl.LinearCase, y_dtype=np.float32, transposed_copies=None):
     """INT8 forward with the paper's FP16 backward on the dequantized saved codes, stage by stage."""
     M, N, K = case.mnk
     say(case.name, "INT8 forward / FP16 backward", "MNK", M, N, K, "w_gran", case.w_gran)
     op = QLinear(Q.INT8, M, N, K, x_dtype=TORCH[case.x.dtype], w_dtype=TORCH[case.w.dtype],
                  dy_dtype=TORCH[case.dy.dtype], y_dtype=TORCH[np.dtype(y_dtype)], dx_dtype=torch.float16,
-                 dw_dtype=torch.float32, w_gran=GRAN[case.w_gran], philox_seed=case.philox_seed, bwd_tag=Q.FP16)
+                 dw_dtype=torch.float32, w_gran=GRAN[case.w_gran], philox_seed=case.philox_seed, bwd_tag=Q.FP16,
+                 transposed_copies=transposed_copies)
     op.bias.copy_(dev(case.bias))
     op.forward(dev(case.x), dev(case.w))
     op.backward(dev(case.dy))
@@ -340,11 +341,15 @@ def run_case_fp16_backward(case: wl.LinearCase, y_dtype=np.float32):
     assert_bits_equal(host(op.xq), ref["xq"], "xq")
     assert_bits_equal(host(op.wq), ref["wq"], "wq")
     # dequantized binary16 operands: the exact product code * scale rounded once to binary16
-    assert_bits_equal(host(op.xhT), ref["xh"].T, "x_hat transposed")
+    if op.rowmajor_bwd:       # the weight gradient reads x_hat and dY16 as they are: no transposed operands exist
+        assert op.xqT is None and op.dyhT is None
+        assert_bits_equal(host(op.xh), ref["xh"], "x_hat")
+    else:
+        assert_bits_equal(host(op.xhT), ref["xh"].T, "x_hat transposed")
+        assert_bits_equal(host(op.dyhT), ref["dyh"].T, "dY cast transposed")
     assert_bits_equal(host(op.wh), ref["wh"], "w_hat")
     assert_bits_equal(host(op.whT), ref["wh"].T, "w_hat transposed")
     assert_bits_equal(host(op.dyh), ref["dyh"], "dY cast")
-    assert_bits_equal(host(op.dyhT), ref["dyh"].T, "dY cast transposed")
     assert_close(host(op.y), ref["y"], "Y")
     assert_close(host(op.dx), ref["dx"], "dX (FP16 backward)")
     assert_close(host(op.dw), ref["dw"], "dW (FP16 backward)")
@@ -360,8 +365,17 @@ def test_int8_forward_fp16_backward_small_and_ragged(w_gran):
         run_case_fp16_backward(case)
 
 
-def test_int8_forward_fp16_backward_config2_full_size():
-    run_case_fp16_backward(wl.config2(), y_dtype=np.float16)
+@pytest.mark.parametrize("transposed_copies", [False, True])
+def test_int8_forward_fp16_backward_config2_full_size(transposed_copies):
+    """Both operand forms of the FP16 backward: x_hat [M,K] and dY16 read row-major by the weight-gradient GEMM, and the
+    transposed copies x_hat^T, dY16^T for the NT GEMM."""
+    op, _ = run_case_fp16_backward(wl.config2(), y_dtype=np.float16, transposed_copies=transposed_copies)
+    assert op.rowmajor_bwd == (not transposed_copies)
+
+
+def test_int8_forward_fp16_backward_row_major_small():
+    for shape in [(128, 128, 128), (256, 144, 272), (640, 272, 400)]:
+        run_case_fp16_backward(wl.ragged_case(*shape, seed=sum(shape) + 2), transposed_copies=False)
 
 
 def test_conv_activation_quantized_once_then_expanded():
