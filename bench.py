@@ -525,7 +525,8 @@ def run(args):
         mfma_probe["forward_gemm_frac_of_random_operand_rate"] = round(achieved / mfma_probe["random_operands"], 4)
     # HBM-bound side: absmax + quantize of dY (read twice, write the codes, and their transpose when that is kept)
     esz = cases[0].dy.dtype.itemsize
-    ncopies = [1 if getattr(o, "rowmajor_bwd", False) else 2 for o in ops_objs]
+    # (the convolution operator keeps its codes in NHWC only; its weight gradient gathers them)
+    ncopies = [1 if (getattr(o, "rowmajor_bwd", False) or not hasattr(o, "rowmajor_bwd")) else 2 for o in ops_objs]
     dy_bytes = sum(c.dy.size * (2 * esz + n) for c, n in zip(cases, ncopies))
     quant_gbs = dy_bytes / (per_step["convert_dy"] * 1e-3) / 1e9 if "convert_dy" in per_step else None
 

@@ -387,12 +387,15 @@ int qsync_prepare_weights(const void* w, int wdt, int64_t N, int64_t K, int bits
  * (paper: Appendix, proof of Prop. 1, backward of an operator from the saved, compressed context):
  *   dw[n, (kh*3+kw)*C + c] = sdy * sx * sum_{b,h,w} dyq[b,h,w,n] * xq[b, h+kh-1, w+kw-1, c]   (0 outside the image)
  * (tag FP16: the same sum over binary16 operands with fp32 accumulation, no scales).
- * The contraction runs over the pixels, so both operands are needed pixel-contiguous.  They are written to
- * the workspace transposed over a zero-padded pixel axis (a zero row in front of every image, rows padded
- * with zeros to a multiple of 16 pixels) on which every window offset is a plain displacement: the gradient
- * once, the activation three times (displaced by -1, 0, +1 pixel, so that every tap reads 16-byte aligned
- * rows), about 3.5 elements per activation element instead of the 9 of a materialised patch matrix.  The MFMA
- * GEMM then reads the nine taps as displaced rows of those copies.
+ * The contraction runs over the pixels.  When nimg*H*W is a multiple of 128 (and nimg*H*W*C*element size < 2^31)
+ * the GEMM reads both operands as they are: the row-major gradient, and the patch matrix [pixels, 9*C] formed by
+ * its own loads from the NHWC activation (padding taps read a zero block); transposing LDS reads feed the matrix
+ * instructions, no copy of either operand is made, and the workspace holds split-K partials only.
+ * Otherwise both operands are written to the workspace transposed over a zero-padded pixel axis (a zero row in
+ * front of every image, rows padded with zeros to a multiple of 16 pixels) on which every window offset is a plain
+ * displacement: the gradient once, the activation three times (displaced by -1, 0, +1 pixel, so that every tap
+ * reads 16-byte aligned rows), about 3.5 elements per activation element instead of the 9 of a materialised patch
+ * matrix, and the GEMM reads the nine taps as displaced rows of those copies.  Same int32 accumulators either way.
  *
  * tag  QSYNC_INT8 or QSYNC_FP16 (QSYNC_FP32: QSYNC_ERR_UNSUPPORTED).
  * xq   [nimg, H, W, C] and dyq [nimg*H*W, N], int8 or binary16, device, 16-byte aligned; C and N times the

@@ -544,6 +544,14 @@ WgradLayout wgrad_layout(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C,
     l.total    = l.off_part + l.plan.workspace;
     return l;
 }
+// The gathering form: the weight-gradient GEMM reads the row-major gradient and the NHWC activation themselves (TN
+// form, patches formed by its loads).  Needs whole K tiles of 128 pixels and 32-bit byte offsets into the activation.
+bool wgrad_gathers(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
+{
+    const int64_t esz = tag == QSYNC_INT8 ? 1 : 2, M = nimg * H * W;
+    return M > 0 && M % 128 == 0 && M * C * esz < (int64_t(1) << 31) && N < (int64_t(1) << 24) && 9 * C < (int64_t(1) << 24)
+           && H <= 65535 && W <= 65535;
+}
 bool wgrad_shape_ok(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N)
 {
     const int64_t esz = tag == QSYNC_INT8 ? 1 : 2;
@@ -561,6 +569,16 @@ size_t qsync_conv3x3_wgrad_workspace_bytes(int tag, int64_t nimg, int64_t H, int
     if((tag != QSYNC_INT8 && tag != QSYNC_FP16) || nimg <= 0 || H <= 0 || W <= 0 || C <= 0 || N <= 0
        || !wgrad_shape_ok(tag, nimg, H, W, C, N))
         return 0;
+    if(wgrad_gathers(tag, nimg, H, W, C, N))
+    {   // split-K partials only (the largest over the tile shapes, so that a pinned tile fits too)
+        size_t need = plan_gemm(tag, N, 9 * C, nimg * H * W, -1, -1, true, true).workspace;
+        for(int t = 0; t < 3; ++t)
+        {
+            const size_t w = plan_gemm(tag, N, 9 * C, nimg * H * W, t, 0, true, true).workspace;
+            need = w > need ? w : need;
+        }
+        return round256(need);
+    }
     return wgrad_layout(tag, nimg, H, W, C, N).total;
 }
 
@@ -577,10 +595,26 @@ int qsync_conv3x3_wgrad(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, 
     if(nimg == 0 || H == 0 || W == 0 || C == 0 || N == 0) return QSYNC_OK;
     const int esz = tag == QSYNC_INT8 ? 1 : 2;
     if((C * esz) % 16 != 0 || (N * esz) % 16 != 0 || !aligned16(xq) || !aligned16(dyq)) return QSYNC_ERR_ALIGN;
+    hipStream_t st  = static_cast<hipStream_t>(stream);
+    if(wgrad_gathers(tag, nimg, H, W, C, N))
+    {
+        const int64_t  M    = nimg * H * W;
+        const GemmPlan plan = plan_gemm(tag, N, 9 * C, M, -1, -1, true, /*tn=*/true);
+        if(plan.workspace > 0)
+        {
+            if(!workspace || workspace_bytes < plan.workspace) return QSYNC_ERR_WORKSPACE;
+            if((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return QSYNC_ERR_ALIGN;
+        }
+        GemmProblem p{};
+        p.prec = tag; p.M = N; p.N = 9 * C; p.K = M;
+        p.A = dyq; p.B = xq; p.C = dw; p.c_dtype = dwdt; p.tn = true;
+        p.conv_H = static_cast<int>(H); p.conv_W = static_cast<int>(W); p.conv_C = C;
+        if(tag == QSYNC_INT8) { p.s0 = sdy; p.s1 = sx; p.acc_dump = acc_dump_opt; }
+        return hip_status(launch_gemm(p, plan, workspace, st));
+    }
     const WgradLayout l = wgrad_layout(tag, nimg, H, W, C, N);
     if(!workspace || workspace_bytes < l.total) return QSYNC_ERR_WORKSPACE;
     if((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return QSYNC_ERR_ALIGN;
-    hipStream_t st  = static_cast<hipStream_t>(stream);
     uint8_t*    xT  = static_cast<uint8_t*>(workspace) + l.off_x;
     uint8_t*    dyT = static_cast<uint8_t*>(workspace) + l.off_dy;
     hipError_t  e   = launch_conv_padded_transpose(xq, esz, nimg, static_cast<int>(H), static_cast<int>(W), static_cast<int>(C), 3, xT, static_cast<int>(l.margin), st);

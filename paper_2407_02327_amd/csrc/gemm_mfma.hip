@@ -239,6 +239,39 @@ __device__ __forceinline__ void conv_sequence(std::integer_sequence<int, Ds...>,
     (conv_issue<Ds, DPW>(a, zero, pix_off[Ds], hw[Ds], t, H, W, lds_mid), ...);
 }
 
+// TN form with the B operand gathered from an NHWC tensor (weight gradient of the 3x3 convolution): stage row r of
+// K tile kt is pixel m = kt * KR + r, and a lane's 16-byte chunk lies in one tap (dh, dw) at channel offset c0, both
+// fixed per load slot; what changes from K tile to K tile is the pixel, i.e. (h, w).  `delta` holds the slot's whole
+// constant part ((dh W + dw) Cb + c0 + r Cb); `code` = (dh + 1) | (dw + 1) << 2 | valid << 4; `hw` = h << 16 | w of the
+// pixel of the NEXT K tile to be requested and is advanced by KR pixels here (dr = KR % W, hq = (KR / W) % H).
+template <int D, int DPW>
+__device__ __forceinline__ void conv_tn_issue(const uint8_t* x, const uint8_t* zero, int64_t pix_base, int delta, int code,
+                                              uint32_t& hw, int H, int W, int dr, int hq, uint8_t* lds_mid)
+{
+    constexpr int IMM = dma_imm<D, DPW>();
+    int        h = static_cast<int>(hw >> 16), w = static_cast<int>(hw & 0xffffu);
+    const int  hh = h + (code & 3) - 1, ww = w + ((code >> 2) & 3) - 1;
+    const bool inb = (code >> 4) != 0 && static_cast<unsigned>(hh) < static_cast<unsigned>(H)
+                     && static_cast<unsigned>(ww) < static_cast<unsigned>(W);
+    const uint8_t* src = inb ? x + (pix_base + delta) : zero;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src - IMM),
+                                     (__attribute__((address_space(3))) void*)(lds_mid + dma_lds_shift<D, DPW>()), 16, IMM, 0);
+    w += dr;
+    const int carry = w >= W ? 1 : 0;
+    w -= carry ? W : 0;
+    h += hq + carry;
+    h -= h >= H ? H : 0;
+    hw = (static_cast<uint32_t>(h) << 16) | static_cast<uint32_t>(w);
+}
+
+template <int DPW, int... Ds>
+__device__ __forceinline__ void conv_tn_sequence(std::integer_sequence<int, Ds...>, const uint8_t* x, const uint8_t* zero,
+                                                 int64_t pix_base, const int (&delta)[DPW], const int (&code)[DPW],
+                                                 uint32_t (&hw)[DPW], int H, int W, int dr, int hq, uint8_t* lds_mid)
+{
+    (conv_tn_issue<Ds, DPW>(x, zero, pix_base, delta[Ds], code[Ds], hw[Ds], H, W, dr, hq, lds_mid), ...);
+}
+
 template <int DPW, int... Ds>
 __device__ __forceinline__ void fill_dma_imms(int (&imm)[DPW], std::integer_sequence<int, Ds...>)
 {
@@ -329,8 +362,10 @@ __device__ __forceinline__ void frag_reads(v4i32 (&dst)[F], uint32_t addr, std::
 template <typename TR, int BM, int BN, int WGM, int WGN, bool SPLIT, bool CONV = false, bool TN = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKernelArgs p)
 {
-    static_assert(!(SPLIT && CONV), "the implicit patch matrix is not combined with split K");
-    static_assert(!TN || (TR::kElemBytes <= 2 && !CONV && BM == BN && BM >= 64), "TN: int8 or binary16 operands, square tiles");
+    static_assert(!(SPLIT && CONV && !TN), "the implicit patch matrix of the forward is not combined with split K");
+    static_assert(!TN || (TR::kElemBytes <= 2 && BM == BN && BM >= 64), "TN: int8 or binary16 operands, square tiles");
+    constexpr bool CONVA  = CONV && !TN;       // NT form: the A operand is the implicit patch matrix (forward, data gradient)
+    constexpr bool CONVTN = CONV && TN;        // TN form: the B operand is gathered from the NHWC tensor (weight gradient)
     constexpr int ESZ = TR::kElemBytes;
     typedef typename TR::accv_t accv_t;
     typedef typename TR::acc_t  acc_t;
@@ -375,11 +410,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     static_assert(kUniformSide, "a wavefront must not straddle the A/B boundary of a stage");
     const bool     is_a      = wave * DPW < BM / 8;
     // TN: the panel starts at the tile's first column of the operand (its rows are contraction indices)
-    const uint8_t* gbase     = TN ? (is_a ? p.A + m0 * ESZ : p.B + n0 * ESZ)
+    const uint8_t* gbase     = TN ? (is_a ? p.A + m0 * ESZ : (CONVTN ? p.B : p.B + n0 * ESZ))
                                   : (is_a ? p.A + m0 * p.Kb : ((!CONV && p.remap_C > 0) ? p.B : p.B + n0 * p.Kb));
     const int64_t  rows_left = is_a ? p.M - m0 : p.N - n0;           // >= 1
     uint32_t       voff[DPW];                                         // lane offset + kDmaBias - immediate
-    uint32_t       hw[CONV ? DPW : 1];                                // CONV, A side: (h << 16) | w of the lane's pixels
+    uint32_t       hw[CONV ? DPW : 1];                                // CONV: (h << 16) | w of the lane's pixels
+    int            tnc_delta[CONVTN ? DPW : 1], tnc_code[CONVTN ? DPW : 1];      // CONVTN, B side (see conv_tn_issue)
     int            gchunk[2];                                         // the swizzle term depends on d%2 only
     {
         int imm[DPW];
@@ -397,6 +433,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                 const int o     = q * 1024 + lane * 16;
                 const int row   = o / RB, pos = (o % RB) / 16;
                 int       chunk = pos ^ tn_swizzle<ESZ, RB>(row);
+                if constexpr(CONVTN)
+                    if(!is_a)
+                    {   // B side: column byte (n0 * ESZ + 16 chunk) of the implicit [pixels, 9 C] matrix = tap, channel offset
+                        constexpr int KR = kRowBytes / ESZ;                       // pixels per K tile
+                        const int64_t colb  = n0 * ESZ + static_cast<int64_t>(chunk) * 16;
+                        const bool    valid = colb < static_cast<int64_t>(9) * p.conv_Cb;      // tile columns past 9 C: zeros, never stored
+                        const int     tap   = valid ? static_cast<int>(colb / p.conv_Cb) : 0;
+                        const int     c0    = valid ? static_cast<int>(colb - static_cast<int64_t>(tap) * p.conv_Cb) : 0;
+                        const int     kh = (tap * 11) >> 5, kw = tap - 3 * kh;          // tap / 3 for tap < 12
+                        tnc_delta[d] = ((kh - 1) * p.conv_W + (kw - 1)) * p.conv_Cb + c0 + row * p.conv_Cb;
+                        tnc_code[d]  = kh | (kw << 2) | (valid ? 16 : 0);
+                        const uint32_t m  = static_cast<uint32_t>(kt_begin) * KR + static_cast<uint32_t>(row);
+                        const uint32_t qq = m / static_cast<uint32_t>(p.conv_W);
+                        hw[d]   = ((qq % static_cast<uint32_t>(p.conv_H)) << 16) | (m - qq * static_cast<uint32_t>(p.conv_W));
+                        voff[d] = 0u;
+                        continue;
+                    }
                 if(static_cast<int64_t>(chunk) * 16 >= width) chunk = 0;    // columns past the matrix: any valid chunk, never stored
                 voff[d] = static_cast<uint32_t>(static_cast<int64_t>(row) * ld + chunk * 16 + kDmaBias - imm[d]);
             }
@@ -419,7 +472,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
                 voff[d] = static_cast<uint32_t>(static_cast<int64_t>(kw * p.remap_C + c) * p.Kb + (kh - 1) * p.remap_shift
                                                 + chunk * 16 + kDmaBias - imm[d]);
             }
-            if constexpr(CONV)
+            if constexpr(CONVA)
                 if(is_a)
                 {   // A side: voff holds the byte offset of output pixel m in the NHWC tensor instead
                     const uint32_t m = static_cast<uint32_t>(m0 + lrow), q = m / static_cast<uint32_t>(p.conv_W);
@@ -439,10 +492,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // slot through the instruction's immediate offset (d - DPW/2) KB.  Rewriting M0 between direct
     // loads would stall the wavefront until the previous load has left the issue queue
     // (measured: +20 % GEMM throughput without it).
+    // CONVTN: pixels per K tile, and how far (h, w) of a stage row move from one K tile to the next
+    constexpr int tnc_KR = kRowBytes / ESZ;
+    const int     tnc_dr = CONVTN ? tnc_KR % p.conv_W : 0, tnc_hq = CONVTN ? (tnc_KR / p.conv_W) % p.conv_H : 0;
     auto dma = [&](int stage, int kt) {
         const int64_t  kb    = static_cast<int64_t>(kt) * kRowBytes;
         uint8_t*       lbase = lds + stage * STAGE_BYTES + wave * (DPW * 1024) + (dma_group<DPW>() / 2) * 1024;
-        if constexpr(CONV)
+        if constexpr(CONVTN)
+            if(!is_a)
+            {   // (requested for consecutive K tiles only, starting at kt_begin: hw is advanced by every call)
+                conv_tn_sequence<DPW>(std::make_integer_sequence<int, DPW>{}, p.B, reinterpret_cast<const uint8_t*>(&g_zero_chunk),
+                                      static_cast<int64_t>(kt) * tnc_KR * p.conv_Cb, tnc_delta, tnc_code, hw, p.conv_H, p.conv_W,
+                                      tnc_dr, tnc_hq, lbase);
+                return;
+            }
+        if constexpr(CONVA)
             if(is_a)
             {
                 ConvTap t;
@@ -1295,16 +1359,22 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool
     constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float) + 64;   // + amax slots
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
     const dim3       block(64 * WGM * WGN);
-    static bool      attr_set[5] = {false, false, false, false, false};   // per instantiation; benign if set twice
+    static bool      attr_set[7] = {false, false, false, false, false, false, false};   // per instantiation; benign if set twice
     const bool       conv  = a.conv_H > 0;
-    const int        which = tn ? (splits > 1 ? 4 : 3) : (conv ? 2 : (splits > 1 ? 1 : 0));
-    if(conv && splits > 1) return hipErrorInvalidValue;
-    if(tn && (conv || TR::kElemBytes > 2)) return hipErrorInvalidValue;
+    const int        which = tn ? (conv ? (splits > 1 ? 6 : 5) : (splits > 1 ? 4 : 3)) : (conv ? 2 : (splits > 1 ? 1 : 0));
+    if(conv && !tn && splits > 1) return hipErrorInvalidValue;
+    if(tn && TR::kElemBytes > 2) return hipErrorInvalidValue;
     const void* fn = nullptr;
     if constexpr(TR::kElemBytes <= 2)
         if(tn)
-            fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, false, true>)
-                            : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, false, true>);
+        {
+            if(conv)
+                fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, true, true>)
+                                : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true, true>);
+            else
+                fn = splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, false, true>)
+                                : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, false, true>);
+        }
     if(!fn)
         fn = conv ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true>)
            : splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
@@ -1319,7 +1389,11 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool
     if constexpr(TR::kElemBytes <= 2)
         if(tn)
         {
-            if(splits > 1)
+            if(conv && splits > 1)
+                gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, true, true><<<grid, block, lds_bytes, st>>>(a);
+            else if(conv)
+                gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true, true><<<grid, block, lds_bytes, st>>>(a);
+            else if(splits > 1)
                 gemm_nt_kernel<TR, BM, BN, WGM, WGN, true, false, true><<<grid, block, lds_bytes, st>>>(a);
             else
                 gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, false, true><<<grid, block, lds_bytes, st>>>(a);
@@ -1466,7 +1540,7 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     if(p.tn)
     {   // A [K, M], B [K, N] row-major int8 or binary16: rows are contraction indices (128 bytes' worth per K tile),
         // 16-byte column chunks
-        if((p.prec != 8 && p.prec != 16) || p.conv_H > 0 || p.b_remap_C > 0 || (p.K * esz) % kRowBytes != 0
+        if((p.prec != 8 && p.prec != 16) || p.b_remap_C > 0 || (p.K * esz) % kRowBytes != 0
            || (p.M * esz) % 16 != 0 || (p.N * esz) % 16 != 0
            || p.M >= (int64_t(1) << 24) || p.N >= (int64_t(1) << 24)
            || ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) != 0)
@@ -1483,7 +1557,14 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
             return hipErrorInvalidValue;
         a.remap_C = static_cast<int>(p.b_remap_C); a.remap_shift = static_cast<int>(p.b_remap_shift);
     }
-    if(p.conv_H > 0)
+    if(p.conv_H > 0 && p.tn)
+    {   // B is the NHWC tensor [K = images*H*W pixels, C]; the [pixels, 9*C] patch matrix is formed by the loads
+        if(p.N != 9 * p.conv_C || p.K * p.conv_C * esz >= (int64_t(1) << 31) || p.conv_H > 65535 || p.conv_W > 65535
+           || (p.conv_C * esz) % 16 != 0 || p.K % (static_cast<int64_t>(p.conv_H) * p.conv_W) != 0)
+            return hipErrorInvalidValue;
+        a.conv_H = p.conv_H; a.conv_W = p.conv_W; a.conv_Cb = static_cast<int>(p.conv_C * esz);
+    }
+    else if(p.conv_H > 0)
     {   // A is the NHWC tensor [M = images*H*W, C]; its 3x3 patch matrix [M, 9*C] is formed by the loads
         if(p.K != 9 * p.conv_C || plan.splits > 1 || p.M * p.conv_C * esz >= (int64_t(1) << 31)
            || p.conv_H > 65535 || p.conv_W > 65535 || (p.conv_C * esz) % 16 != 0

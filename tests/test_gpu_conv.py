@@ -112,8 +112,11 @@ def test_weight_gradient_on_codes_bit_exact(tile):
     from tests.gpu_util import ws
     rng = np.random.default_rng(67)
     Q.qsync_debug_set_gemm_tile(tile)
+    # (pixel counts that are multiples of 128 take the gathering TN GEMM, the others the padded transposed copies)
     for (b, h, w, c, n) in [(1, 4, 4, 16, 16), (2, 7, 5, 16, 32), (3, 8, 8, 64, 64), (1, 13, 16, 48, 48), (2, 3, 70, 80, 16),
-                            (5, 9, 15, 32, 144), (1, 1, 1, 16, 16), (2, 31, 33, 16, 16)]:
+                            (5, 9, 15, 32, 144), (1, 1, 1, 16, 16), (2, 31, 33, 16, 16),
+                            (2, 8, 8, 16, 16), (4, 8, 8, 64, 64), (2, 16, 16, 48, 48), (8, 4, 4, 80, 16), (1, 16, 24, 32, 144),
+                            (128, 1, 1, 16, 16), (4, 32, 32, 64, 64), (64, 2, 3, 16, 32), (16, 28, 28, 128, 256)]:
         say("conv wgrad codes", "tile", tile, b, h, w, c, n)
         xq = rng.integers(-127, 128, (b, h, w, c)).astype(np.int8)
         dyq = rng.integers(-127, 128, (b, h, w, n)).astype(np.int8)
@@ -136,7 +139,9 @@ def test_weight_gradient_fp16(tile):
     rng = np.random.default_rng(69)
     Q.qsync_debug_set_gemm_tile(tile)
     for (b, h, w, c, n) in [(1, 4, 4, 8, 8), (2, 7, 5, 16, 24), (3, 8, 8, 64, 64), (1, 13, 16, 40, 48), (2, 3, 70, 8, 16),
-                            (1, 1, 1, 8, 8), (2, 31, 33, 16, 8)]:
+                            (1, 1, 1, 8, 8), (2, 31, 33, 16, 8),
+                            (2, 8, 8, 8, 8), (4, 8, 8, 64, 64), (2, 16, 16, 40, 48), (1, 16, 24, 32, 136), (128, 1, 1, 8, 8),
+                            (4, 32, 32, 64, 64), (64, 2, 3, 16, 24)]:
         say("conv wgrad fp16", "tile", tile, b, h, w, c, n)
         x = rng.standard_normal((b, h, w, c)).astype(np.float16)
         dy = (rng.standard_normal((b, h, w, n)) * 0.05).astype(np.float16)
