@@ -225,8 +225,12 @@ def test_conv_wgrad_validation():
     assert f(*a) == qsync.ERR_ALIGN
     a = list(ok); a[1] = 0
     assert f(*a) == qsync.OK
-    assert lib.qsync_conv3x3_wgrad_workspace_bytes(8, 64, 56, 56, 64, 64) > 3 * 64 * 64 * 57 * 64
-    assert lib.qsync_conv3x3_wgrad_workspace_bytes(16, 64, 56, 56, 64, 64) > 2 * 3 * 64 * 64 * 57 * 64
+    # 64 x 56 x 56 pixels are a multiple of 128: the GEMM gathers its operands itself, the workspace holds split-K
+    # partials only; 63 images are not: padded transposed copies (three of the activation, one of the gradient)
+    gather = lib.qsync_conv3x3_wgrad_workspace_bytes(8, 64, 56, 56, 64, 64)
+    assert 0 < gather < 3 * 64 * 64 * 57 * 64 // 2 and gather % (64 * 576 * 4) == 0
+    assert lib.qsync_conv3x3_wgrad_workspace_bytes(8, 63, 56, 56, 64, 64) > 3 * 63 * 64 * 57 * 64
+    assert lib.qsync_conv3x3_wgrad_workspace_bytes(16, 63, 56, 56, 64, 64) > 2 * 3 * 63 * 64 * 57 * 64
 
 
 def test_conv_prepare_weights_validation():
