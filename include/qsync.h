@@ -457,6 +457,18 @@ int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, in
                       const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt, void* stream);
 
 /*
+ * qsync_conv3x3_fwd_amax - qsync_conv3x3_fwd that also collects max |Y| in its epilogue (as qsync_qlinear_fwd_amax
+ * does for the linear operator; paper: Backend section, "Minimum and Maximum Optimization"), so that a convolution
+ * fed directly by Y takes its activation scale from that word (qsync_scale_from_amax) and quantizes Y without a
+ * pass of its own for the maximum.
+ * y_amax  device float, read and written: max(previous value, max |Y| as stored); 4-byte aligned; see
+ *         qsync_qlinear_fwd_amax.  All other arguments and errors as qsync_conv3x3_fwd.
+ */
+int qsync_conv3x3_fwd_amax(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N,
+                           const void* xq, const float* sx, const void* wq, const float* sw, int wgran,
+                           const float* bias_opt, void* y, int ydt, int32_t* acc_dump_opt, float* y_amax, void* stream);
+
+/*
  * qsync_conv3x3_wflip - weights of the data-gradient convolution:
  *   wflip[c, ((2-kh)*3 + (2-kw))*N + n] = w[n, (kh*3+kw)*C + c]
  * (window mirrored, channel roles exchanged), so that dX = conv3x3(dY, wflip).

@@ -667,9 +667,9 @@ int qsync_probe_mfma(int tag, int random_operands, int iters, void* out, double*
 void qsync_debug_set_gemm_tile(int tile) { set_gemm_tile_override(tile); }
 void qsync_debug_set_gemm_persistent(int mode) { set_gemm_persistent_mode(mode); }
 
-int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,
-                      const float* sx, const void* wq, const float* sw, int wgran, const float* bias_opt, void* y,
-                      int ydt, int32_t* acc_dump_opt, void* stream)
+static int conv3x3_fwd_impl(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,
+                            const float* sx, const void* wq, const float* sw, int wgran, const float* bias_opt, void* y,
+                            int ydt, int32_t* acc_dump_opt, float* y_amax_opt, void* stream)
 {
     if(!xq || !wq || !y) return QSYNC_ERR_NULL;
     if(!is_tag(tag) || !is_float_dtype(ydt)) return QSYNC_ERR_BAD_ENUM;
@@ -701,7 +701,24 @@ int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, in
         p.acc_dump = acc_dump_opt;
     }
     p.col_bias = bias_opt;
+    p.out_amax_bits = reinterpret_cast<unsigned int*>(y_amax_opt);
     return hip_status(launch_gemm(p, plan, nullptr, static_cast<hipStream_t>(stream)));
+}
+
+int qsync_conv3x3_fwd(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,
+                      const float* sx, const void* wq, const float* sw, int wgran, const float* bias_opt, void* y,
+                      int ydt, int32_t* acc_dump_opt, void* stream)
+{
+    return conv3x3_fwd_impl(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, ydt, acc_dump_opt, nullptr, stream);
+}
+
+int qsync_conv3x3_fwd_amax(int tag, int64_t nimg, int64_t H, int64_t W, int64_t C, int64_t N, const void* xq,
+                           const float* sx, const void* wq, const float* sw, int wgran, const float* bias_opt, void* y,
+                           int ydt, int32_t* acc_dump_opt, float* y_amax, void* stream)
+{
+    if(!y_amax) return QSYNC_ERR_NULL;
+    if((reinterpret_cast<uintptr_t>(y_amax) & 3u) != 0) return QSYNC_ERR_ALIGN;
+    return conv3x3_fwd_impl(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, ydt, acc_dump_opt, y_amax, stream);
 }
 
 int qsync_conv3x3_wflip(const void* w, int wdt, int64_t N, int64_t C, void* wflip, void* stream)

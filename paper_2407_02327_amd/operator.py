@@ -290,9 +290,12 @@ class QConv3x3:
     def __init__(self, tag: int, nimg: int, H: int, W: int, C: int, N: int, x_dtype=torch.float16, w_dtype=torch.float32,
                  dy_dtype=None, y_dtype=torch.float32, dx_dtype=torch.float16, dw_dtype=torch.float32,
                  w_gran: int = Q.PER_ROW, dy_round: int = Q.ROUND_STOCHASTIC, philox_seed: int = 0,
-                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda", wgrad_via_patches: bool = False):
+                 bias: bool = True, dump_acc: bool = False, bits: int = 8, device="cuda", wgrad_via_patches: bool = False,
+                 collect_y_amax: bool = False):
         if tag not in (Q.INT8, Q.FP16):
             raise ValueError("QConv3x3: tag INT8 or FP16")
+        # max |Y| collected by the forward GEMM's epilogue, for a convolution that quantizes Y as it is
+        self.y_amax = torch.zeros(1, dtype=torch.float32, device=device) if collect_y_amax else None
         self.wgrad_via_patches = wgrad_via_patches
         self.tag, self.nimg, self.H, self.W, self.C, self.N = tag, nimg, H, W, C, N
         M, K = nimg * H * W, 9 * C
@@ -326,9 +329,15 @@ class QConv3x3:
         self.ws_bwd = _ws(Q.qsync_qlinear_bwd_workspace_bytes(tag, M, N, K) if wgrad_via_patches
                           else Q.qsync_conv3x3_wgrad_workspace_bytes(tag, nimg, H, W, C, N), device)
 
-    def convert_x(self, act: torch.Tensor, stream=None) -> None:
+    def convert_x(self, act: torch.Tensor, stream=None, x_amax: Optional[torch.Tensor] = None) -> None:
+        """x_amax: device float holding max |act| already (the producer's `y_amax`); it replaces the pass over the
+        activation that finds the maximum and is left at zero for the producer's next step."""
         M, C = self.M, self.C
-        if self.tag == Q.INT8:
+        if self.tag == Q.INT8 and x_amax is not None:
+            Q.qsync_scale_from_amax(x_amax, self.bits, self.sx, self.ix, True, stream)
+            Q.qsync_quantize(act, M, C, C, Q.INT8, self.bits, Q.PER_TENSOR, Q.ROUND_NEAREST, 0, 0, self.ix, self.xq, None,
+                             stream)
+        elif self.tag == Q.INT8:
             Q.qsync_absmax_quantize(act, M, C, self.bits, Q.ROUND_NEAREST, 0, 0, self.sx, self.ix, self.ax, self.xq, None,
                                     self.ws_absmax, -1, stream)
         elif act.dtype == _TORCH_OF_TAG[self.tag] and act.is_contiguous():
@@ -354,6 +363,10 @@ class QConv3x3:
                                         self.ws_absmax_w, stream)
 
     def conv_fwd(self, stream=None) -> None:
+        if self.y_amax is not None:
+            Q.qsync_conv3x3_fwd_amax(self.tag, self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.wq, self.sw,
+                                     self.w_gran, self.bias, self.y, self.acc, self.y_amax, stream)
+            return
         Q.qsync_conv3x3_fwd(self.tag, self.nimg, self.H, self.W, self.C, self.N, self.xq, self.sx, self.wq, self.sw,
                             self.w_gran, self.bias, self.y, self.acc, stream)
 
@@ -383,9 +396,9 @@ class QConv3x3:
         Q.qsync_qlinear_bwd(Q.INT8, self.M, self.N, self.K, None, self.dyqT, self.sdy, self.xqTp, self.sx, None, None,
                             Q.PER_TENSOR, None, self.dw, None, None, None, self.acc_dw, self.ws_bwd, stream)
 
-    def forward(self, act: torch.Tensor, w: torch.Tensor, stream=None) -> torch.Tensor:
+    def forward(self, act: torch.Tensor, w: torch.Tensor, stream=None, x_amax: Optional[torch.Tensor] = None) -> torch.Tensor:
         self.convert_w(w, stream)
-        self.convert_x(act, stream)
+        self.convert_x(act, stream, x_amax)
         self.conv_fwd(stream)
         return self.y
 

@@ -53,6 +53,7 @@ SIGNATURES = {
     "qsync_qlinear_bwd_workspace_bytes": (_sz, [_i, _i64, _i64, _i64]),
     "qsync_im2col3x3_i8": (_i, [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "qsync_conv3x3_fwd": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp]),
+    "qsync_conv3x3_fwd_amax": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i, _vp, _vp, _i, _vp, _vp, _vp]),
     "qsync_debug_set_gemm_tile": (None, [_i]),
     "qsync_debug_set_gemm_persistent": (None, [_i]),
     "qsync_conv3x3_wgrad": (_i, [_i, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
@@ -226,6 +227,11 @@ def qsync_qlinear_bwd_fp16_of_int8(M, N, K, dy, xq_or_xqT, x_rowmajor, sx, wq, s
 def qsync_conv3x3_fwd(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt=None, stream=None) -> None:
     _check(lib.qsync_conv3x3_fwd(tag, nimg, H, W, C, N, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
                                  _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _stream(stream)))
+
+
+def qsync_conv3x3_fwd_amax(tag, nimg, H, W, C, N, xq, sx, wq, sw, wgran, bias_opt, y, acc_dump_opt, y_amax, stream=None) -> None:
+    _check(lib.qsync_conv3x3_fwd_amax(tag, nimg, H, W, C, N, _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), wgran, _ptr(bias_opt),
+                                      _ptr(y), dtype_code(y), _ptr(acc_dump_opt), _ptr(y_amax), _stream(stream)))
 
 
 def qsync_prepare_weights(w, N, K, bits, sw, iw, aw_opt, wq, swb, iwb, wqbT, workspace, stream=None) -> None:

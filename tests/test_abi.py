@@ -481,3 +481,15 @@ def test_row_major_backward_validation():
     assert f(*chg(tag=qsync.FP16, N=20)) == qsync.ERR_ALIGN
     assert f(*chg(tag=qsync.FP16, accdw=A)) == qsync.ERR_UNSUPPORTED
     assert f(*chg(sdy=None)) == qsync.ERR_NULL                         # INT8 needs its scales
+
+
+def test_conv_forward_with_maximum_validation():
+    f = lib.qsync_conv3x3_fwd_amax
+    ok = [8, 1, 4, 4, 16, 16, A, A, A, A, qsync.PER_ROW, None, A, qsync.F16, None, A, None]
+    assert f(*ok) in (qsync.OK, qsync.ERR_HIP)
+    a = list(ok); a[15] = None
+    assert f(*a) == qsync.ERR_NULL                              # the word that receives the maximum
+    a = list(ok); a[15] = P(4098)
+    assert f(*a) == qsync.ERR_ALIGN
+    a = list(ok); a[4] = 24
+    assert f(*a) == qsync.ERR_ALIGN                             # as qsync_conv3x3_fwd

@@ -236,3 +236,45 @@ def test_config3_resnet_conv_implicit_full_size_fp16_tag():
 def test_config3_resnet_conv_implicit_full_size():
     case = wl.config3()
     run_conv_operator(case.nhwc, case.w, case.bias, case.dy, case.w_gran, case.dy_round, seed=case.philox_seed)
+
+
+@pytest.mark.parametrize("tile", [-1, 1])
+def test_chained_convolution_takes_its_scale_from_the_producers_epilogue(tile):
+    """Two convolutions back to back: the producer's forward collects max |Y| where it stores Y
+    (qsync_conv3x3_fwd_amax), the consumer forms its activation scale from that word and quantizes Y without a
+    maximum pass of its own.  Y of the producer is unchanged bit for bit; scale, codes and accumulators of the
+    consumer equal those of a consumer that finds the maximum itself, and the oracle's on the same Y; the consumed
+    maximum starts the next step at zero."""
+    Q.qsync_debug_set_gemm_tile(tile)
+    try:
+        rng = np.random.default_rng(31)
+        b, h, w, c0, c1, c2 = 2, 12, 10, 32, 48, 16
+        act = np.abs(rng.standard_normal((b, h, w, c0))).astype(np.float16)
+        w0 = (rng.standard_normal((c1, 9 * c0)) * np.sqrt(2.0 / (9 * c0))).astype(np.float32)
+        w1 = (rng.standard_normal((c2, 9 * c1)) * np.sqrt(2.0 / (9 * c1))).astype(np.float32)
+        kw = dict(x_dtype=torch.float16, y_dtype=torch.float16)
+        prod = QConv3x3(Q.INT8, b, h, w, c0, c1, collect_y_amax=True, **kw)
+        plain = QConv3x3(Q.INT8, b, h, w, c0, c1, **kw)
+        cons = QConv3x3(Q.INT8, b, h, w, c1, c2, dump_acc=True, **kw)
+        base = QConv3x3(Q.INT8, b, h, w, c1, c2, dump_acc=True, **kw)
+        for step in range(2):
+            y0 = prod.forward(dev(act), dev(w0))
+            y0_plain = plain.forward(dev(act), dev(w0))
+            cons.forward(y0.view(b, h, w, c1), dev(w1), x_amax=prod.y_amax)
+            base.forward(y0.view(b, h, w, c1), dev(w1))
+            torch.cuda.synchronize()
+            assert torch.equal(y0, y0_plain), step
+            assert prod.y_amax.item() == 0.0
+            for name in ("sx", "ix", "xq", "acc", "y"):
+                assert torch.equal(getattr(cons, name), getattr(base, name)), (step, name)
+        y0h = host(y0).reshape(b, h, w, c1)
+        amax = np.abs(y0h.astype(np.float32)).max()
+        s_ref, i_ref = orc.scales_from_amax(np.array([amax], np.float32))
+        assert_bits_equal(host(cons.sx), s_ref, "consumer scale")
+        xq_ref = orc.quantize_int(y0h.reshape(-1, c1), i_ref, "tensor", "nearest")
+        assert_bits_equal(host(cons.xq), xq_ref, "consumer codes")
+        wq = host(cons.wq).reshape(c2, 3, 3, c1)
+        want_acc = orc.conv3x3_fwd_f64(xq_ref.reshape(b, h, w, c1), wq).reshape(-1, c2)
+        assert_bits_equal(host(cons.acc), want_acc.astype(np.int32), "consumer accumulators")
+    finally:
+        Q.qsync_debug_set_gemm_tile(-1)
