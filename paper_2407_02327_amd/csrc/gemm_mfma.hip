@@ -51,7 +51,7 @@ constexpr int kChunks     = 8;    // 16-byte chunks per LDS row
 constexpr int kNumXcd     = 8;
 constexpr int kNumCu      = 256;  // compute units of the target: one persistent workgroup each
 constexpr int kPersistentLdsBytes = 159744;   // two 64 KB stages, hand-over area, column parameters
-constexpr int kGroupM     = 8;    // tile rows walked together
+constexpr int kGroupM     = 8;    // tile rows walked together (default; GemmKernelArgs::group_m)
 
 struct I8Traits
 {
@@ -110,6 +110,7 @@ struct GemmKernelArgs
     void*          partial;      // split-K: [splits][M][N] raw accumulators
     int            ktiles_per_split;
     int            tiles_m, tiles_n;
+    int            group_m;      // tile rows that the tile walk keeps together (see item_of_block)
     int            conv_H, conv_W, conv_Cb;   // implicit 3x3 patch matrix: image height, width, bytes per pixel
     // B rows remapped (weight gradient of a 3x3 convolution): logical row (tap, c) = tap*remap_C + c is physical
     // row (tap%3)*remap_C + c of B, read with its K axis displaced by (tap/3 - 1)*remap_shift bytes
@@ -127,8 +128,8 @@ struct GemmKernelArgs
 // in launch order, each with its own L2, so XCD x takes the x-th contiguous eighth of the item
 // list (split-major, tiles in grouped row-major order inside a split): the workgroups that share
 // an L2 then read neighbouring operand panels, and with split K also the same K range.
-__device__ __forceinline__ void item_of_block(int lin, int tiles_m, int tiles_n, int splits, int& split, int& tm,
-                                              int& tn)
+__device__ __forceinline__ void item_of_block(int lin, int tiles_m, int tiles_n, int splits, int group_m, int& split,
+                                              int& tm, int& tn)
 {
     const int tiles = tiles_m * tiles_n, total = tiles * splits;
     const int per = total / kNumXcd, rem = total % kNumXcd;
@@ -136,9 +137,9 @@ __device__ __forceinline__ void item_of_block(int lin, int tiles_m, int tiles_n,
     const int item  = xcd * per + (xcd < rem ? xcd : rem) + loc;
     split           = item / tiles;
     const int L     = item - split * tiles;
-    const int width = kGroupM * tiles_n;
-    const int group = L / width, first = group * kGroupM;
-    const int gsz   = (tiles_m - first) < kGroupM ? (tiles_m - first) : kGroupM;
+    const int width = group_m * tiles_n;
+    const int group = L / width, first = group * group_m;
+    const int gsz   = (tiles_m - first) < group_m ? (tiles_m - first) : group_m;
     const int in    = L - group * width;
     // the divisions run on the vector unit; hand the (uniform) results back as scalars
     split = __builtin_amdgcn_readfirstlane(split);
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     int split, tm, tn;
-    item_of_block(static_cast<int>(blockIdx.y * gridDim.x + blockIdx.x), p.tiles_m, p.tiles_n, SPLIT ? static_cast<int>(gridDim.y) : 1,
+    item_of_block(static_cast<int>(blockIdx.y * gridDim.x + blockIdx.x), p.tiles_m, p.tiles_n, SPLIT ? static_cast<int>(gridDim.y) : 1, p.group_m,
                   split, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
     const int     tid = threadIdx.x, lane = tid % kWaveSize;
@@ -1068,7 +1069,7 @@ __global__ __launch_bounds__(512) void gemm_nt_persistent_kernel(const GemmKerne
     // ---- first tile: both stages requested, column parameters parked, first K tile awaited
     int lin = static_cast<int>(blockIdx.x);
     int split_unused, tm, tn;
-    item_of_block(lin, p.tiles_m, p.tiles_n, 1, split_unused, tm, tn);
+    item_of_block(lin, p.tiles_m, p.tiles_n, 1, p.group_m, split_unused, tm, tn);
     const uint8_t* cur = panel_base(tm, tn);
     if(loader)
     {
@@ -1086,7 +1087,7 @@ __global__ __launch_bounds__(512) void gemm_nt_persistent_kernel(const GemmKerne
         const int  nlin     = lin + G;
         const bool has_next = nlin < total_tiles;
         int        ntm = 0, ntn = 0;
-        if(has_next) item_of_block(nlin, p.tiles_m, p.tiles_n, 1, split_unused, ntm, ntn);
+        if(has_next) item_of_block(nlin, p.tiles_m, p.tiles_n, 1, p.group_m, split_unused, ntm, ntn);
         const uint8_t* nxt = has_next ? panel_base(ntm, ntn) : cur;
 
         // ---- K loop.  On entry K tile 0 is in stage 0 and published, K tile 1 is in flight towards stage 1.
@@ -1579,6 +1580,7 @@ hipError_t launch_gemm(const GemmProblem& p, const GemmPlan& plan, void* workspa
     const TileShape ts = kTiles[plan.tile];
     a.tiles_m = static_cast<int>((p.M + ts.bm - 1) / ts.bm);
     a.tiles_n = static_cast<int>((p.N + ts.bn - 1) / ts.bn);
+    a.group_m = kGroupM;      // (2, 4, 16 and 32 measured within noise of 8 on config 5's shapes, int8 and binary16)
     // The persistent kernel is opt-in.  Launched alone and back to back it beats the per-tile kernel by 7-20 % (the
     // write-back of a tile overlaps the next tile's K loop), but inside an operator sequence its fixed tile
     // assignment loses what it gains: workgroups that start late, behind the tail of the previous kernel, still
