@@ -1354,13 +1354,23 @@ struct TileShape { int bm, bn; };
 constexpr TileShape kTiles[] = {{256, 256}, {128, 128}, {64, 64}};
 constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
+// The dynamic-LDS attribute of a kernel is set once per device: flags indexed by the current device (a process
+// that drives several GPUs sets it on each; beyond kMaxDevices it is set before every launch).
+constexpr int kMaxDevices = 16;
+inline int current_device_slot()
+{
+    int dev = 0;
+    return (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) ? dev : -1;
+}
+
 template <typename TR, int BM, int BN, int WGM, int WGN>
 hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool tn = false)
 {
     constexpr size_t lds_bytes = 2 * static_cast<size_t>(BM + BN) * kRowBytes + 2 * BN * sizeof(float) + 64;   // + amax slots
     const dim3       grid(static_cast<unsigned>(a.tiles_m * a.tiles_n), static_cast<unsigned>(splits));
     const dim3       block(64 * WGM * WGN);
-    static bool      attr_set[7] = {false, false, false, false, false, false, false};   // per instantiation; benign if set twice
+    static bool      attr_set[kMaxDevices][7] = {};   // per instantiation and device; benign if set twice
+    const int        slot = current_device_slot();
     const bool       conv  = a.conv_H > 0;
     const int        which = tn ? (conv ? (splits > 1 ? 6 : 5) : (splits > 1 ? 4 : 3)) : (conv ? 2 : (splits > 1 ? 1 : 0));
     if(conv && !tn && splits > 1) return hipErrorInvalidValue;
@@ -1380,12 +1390,12 @@ hipError_t launch_tile(const GemmKernelArgs& a, int splits, hipStream_t st, bool
         fn = conv ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false, true>)
            : splits > 1 ? reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, true>)
                         : reinterpret_cast<const void*>(&gemm_nt_kernel<TR, BM, BN, WGM, WGN, false>);
-    if(!attr_set[which])
+    if(slot < 0 || !attr_set[slot][which])
     {
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  static_cast<int>(lds_bytes));
         if(e != hipSuccess) return e;
-        attr_set[which] = true;
+        if(slot >= 0) attr_set[slot][which] = true;
     }
     if constexpr(TR::kElemBytes <= 2)
         if(tn)
@@ -1430,13 +1440,14 @@ bool persistent_eligible(const GemmKernelArgs& a, int prec, int tile, int splits
 
 template <typename TR> hipError_t launch_persistent(const GemmKernelArgs& a, hipStream_t st)
 {
-    static bool      attr_set = false;      // per instantiation; benign if set twice
+    static bool      attr_set[kMaxDevices] = {};      // per instantiation and device; benign if set twice
+    const int        slot = current_device_slot();
     const void*      fn = reinterpret_cast<const void*>(&gemm_nt_persistent_kernel<TR>);
-    if(!attr_set)
+    if(slot < 0 || !attr_set[slot])
     {
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kPersistentLdsBytes);
         if(e != hipSuccess) return e;
-        attr_set = true;
+        if(slot >= 0) attr_set[slot] = true;
     }
     const int total = a.tiles_m * a.tiles_n;
     const int grid  = total < kNumCu ? total : kNumCu;
