@@ -54,7 +54,15 @@ def test_quantize_and_maximum_over_more_than_2_to_31_elements():
         want = orc.quantize_int(xr[None, :], io, "tensor", "stochastic", 21, 5 + (r * cols) // 8)
         assert_bits_equal(host(q[r])[None, :], want, f"codes of row {r}")
         assert_bits_equal(host(qT[:, r])[None, :], want, f"transposed codes of row {r}")
-    del x, q, qT
+    # the row-major-only form (streaming kernel: group indices beyond 2^28, byte offsets beyond 2^32) gives the same codes
+    del qT
+    q1 = torch.empty(rows, cols, dtype=torch.int8, device="cuda")
+    Q.qsync_quantize(x, rows, cols, cols, Q.INT8, 8, Q.PER_TENSOR, Q.ROUND_STOCHASTIC, 21, 5, iv, q1, None)
+    torch.cuda.synchronize()
+    for r in picks:
+        assert torch.equal(q1[r], q[r]), f"row-major-only codes of row {r}"
+    assert torch.equal(q1[rows // 2:rows // 2 + 4096], q[rows // 2:rows // 2 + 4096])
+    del x, q, q1
 
 
 def test_forward_gemm_with_more_than_2_to_31_outputs():
