@@ -649,12 +649,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
     // younger set's reads in flight.  At the tile boundary the wavefront (1) joins the barrier
     // that publishes the next stage (every wavefront's reads of the current stage have returned
     // by then: the barrier's fence waits for them), (2) requests the direct load of the tile
-    // after next into the stage just drained, (3) reads chunk 0 of the next tile, (4) issues
-    // chunk 3, whose operands are already in registers, and (5) reads chunk 1 of the next tile:
-    // barrier release, LDS latency and a whole K tile of memory latency hide behind matrix work.
+    // after next into the stage just drained (half of the wavefronts: behind step 4 instead, see
+    // below), (3) reads chunk 0 of the next tile, (4) issues chunk 3, whose operands are already
+    // in registers, and (5) reads chunk 1 of the next tile: barrier release, LDS latency and a
+    // whole K tile of memory latency hide behind matrix work.
     // Per-column epilogue parameters of this tile (alpha * column scale, column bias) are parked
     // in LDS behind the stages while the first direct loads are in flight; the epilogue reads them
     // back with a few 16-byte LDS reads instead of waiting on global memory.
+    // The direct loads of a K tile are not requested by all wavefronts at once.  A compute unit takes such an
+    // instruction (1 KB) at about 64 bytes per clock, and a wavefront issues nothing else while its loads
+    // queue up: with every wavefront requesting right behind the barrier, both wavefronts of every SIMD sit
+    // in that queue together and the matrix pipeline idles until the unit has taken all (BM + BN) / 8 of them.
+    // The upper half of the wavefronts (the second wavefront of each SIMD) therefore requests behind its chunk
+    // 3 instead: while one wavefront of a SIMD queues loads, its sibling issues matrix instructions
+    // (launched alone: 4-10 % fewer cycles per launch on every tile shape, int8 and binary16).
+    const bool late_loader = wave >= WGM * WGN / 2;
     float* colp = reinterpret_cast<float*>(lds + 2 * STAGE_BYTES);       // [2][BN]: scale, bias
     float  alpha = 1.0f, cp_scale = 1.0f, cp_bias = 0.0f;
     if(!SPLIT)
@@ -693,16 +702,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_nt_kernel(const GemmKerne
             load_frags(set1, stage, 3);
             __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
             mma(set0);
-            if(more)
-            {
-                land(stage ^ 1, kt + 1);
-                if(kt + 2 < kt_end) dma(stage, kt + 2);
-            }
+            if(more) land(stage ^ 1, kt + 1);
             // without a next tile the reads below fetch chunks 0 and 1 of the current stage again: in bounds, unused
-            const int nstage = more ? (stage ^ 1) : stage;
+            const int  nstage  = more ? (stage ^ 1) : stage;
+            const bool request = kt + 2 < kt_end;
+            if(request && !late_loader) dma(stage, kt + 2);
             load_frags(set0, nstage, 0);
             __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
             mma(set1);
+            if(request && late_loader) dma(stage, kt + 2);
             load_frags(set1, nstage, 1);
         }
         __builtin_amdgcn_s_waitcnt(kWaitAllLds);     // the unused reads of the last trip land before the registers are reused
@@ -1349,8 +1357,12 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const ACC* __re
 struct TileShape { int bm, bn; };
 // 0: 256x256, 8 wavefronts (2x4, 128x64 each)   1: 128x128, 4 wavefronts (2x2, 64x64 each)
 // 2: 64x64, 4 wavefronts (2x2, 32x32 each)
-// (256x256 with 4 wavefronts of 128x128 -- a third fewer LDS fragment reads per matrix instruction -- was
-//  measured 8-40 % slower: one wavefront per SIMD exposes barrier and LDS latency.)
+// (256x256 with 4 wavefronts of 128x128 -- a third fewer LDS fragment reads per matrix instruction, 256
+//  accumulator registers per lane -- needs matrix instructions written as inline assembly on accumulator
+//  registers, one loop body without branches around them, and fragment reads and direct loads placed one by one
+//  between them; the compiler's own allocation keeps the accumulators in scratch memory.  Built that way it is
+//  bit-identical and as fast as the 8-wavefront tile at 8192^3 but 7-14 % slower on 16384x4096x1024 and
+//  16384x1024x4096, where its longer epilogue counts: not kept.)
 constexpr TileShape kTiles[] = {{256, 256}, {128, 128}, {64, 64}};
 constexpr int       kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
