@@ -1491,45 +1491,61 @@ GemmPlan plan_gemm(int prec, int64_t M, int64_t N, int64_t K, int force_tile, in
     const double  kwork  = prec == 32 ? 8.0 : 1.0;
     const int64_t ktiles = (kb + kRowBytes - 1) / kRowBytes;
     auto ntiles = [&](int t) { return ((M + kTiles[t].bm - 1) / kTiles[t].bm) * ((N + kTiles[t].bn - 1) / kTiles[t].bn); };
-    // Plan = (tile, K splits) with the smallest estimated time.  The estimate is a small model
-    // calibrated on gfx950 measurements of this kernel (int8, random codes; binary16 scales alike):
-    //   a compute unit retires `rate` Mop/us of a tile's work (it grows with the workgroups that share
-    //   the unit, up to `rate_max`), every workgroup costs `ovh` us of launch, first-load latency and
-    //   epilogue (overlapped among co-resident workgroups), split K adds its reduction pass.
-    struct TileModel { double rate1, rate_max, ovh; int occ; int fill; };
-    const TileModel model[kNumTiles] = {{8.6, 8.6, 8.0, 1, 256}, {5.4, 6.5, 5.0, 2, 512}, {2.6, 6.0, 5.0, 4, 512}};
-    // Row-major (TN) operands: a K tile takes twice the LDS fragment reads, and a 64-wide tile loads 64-byte row
-    // pieces; measured slow-down of the main loop per tile shape.
-    const double    tn_rate[kNumTiles] = {0.93, 0.88, 0.68};
+    // Plan = (tile, K splits) with the smallest estimated time.  The estimate is a small model fitted to gfx950
+    // measurements of this kernel (int8, the step's code distribution, 17 shapes x up to 10 plans, launched alone;
+    // rms error 6 %; binary16 scales alike):
+    //   a compute unit retires `r1` Mop/us per resident workgroup of a tile shape, up to `rmax` with `occ` of them
+    //   sharing it; the chip as a whole retires at most `cap` Mop/us (the power limit: 256 busy units do not
+    //   each reach `rmax`); every round of co-resident workgroups costs `ovh` us of launch, first-load latency
+    //   and epilogue; split K adds its reduction pass.
+    struct TileModel { double r1, rmax, ovh, cap; int occ; };
+    const TileModel model[kNumTiles] = {{14.9, 15.5, 9.2, 2555.0, 1}, {6.56, 8.42, 4.4, 2000.0, 2}, {2.89, 5.03, 2.5, 2035.0, 4}};
+    // Row-major (TN) operands: a K tile takes twice the LDS fragment reads, and a 64-wide tile of int8 operands
+    // loads 64-byte row pieces (binary16: 128 bytes, no penalty); fitted slow-down of the main loop per tile shape.
+    const double    tn_rate[kNumTiles] = {0.89, 0.99, prec == 8 ? 0.66 : 0.95};
     const double    cus = 256.0;
     auto estimate = [&](int t, int64_t s) {
-        TileModel m = model[t];
-        if(tn) { m.rate1 *= tn_rate[t]; m.rate_max *= tn_rate[t]; }
-        const double     wgs   = static_cast<double>(ntiles(t)) * static_cast<double>(s);
-        const double     per   = std::ceil(wgs / cus);                                   // workgroups per unit
+        const TileModel& m    = model[t];
+        const double     tnf  = tn ? tn_rate[t] : 1.0;
+        const double     wgs  = static_cast<double>(ntiles(t)) * static_cast<double>(s);
+        const double     per  = std::ceil(wgs / cus);                                    // workgroups of the busiest unit
         const double     share = per < m.occ ? per : m.occ;                              // co-resident ones
-        const double     rate  = m.rate1 * share < m.rate_max ? m.rate1 * share : m.rate_max;
-        const double     kt    = std::ceil(static_cast<double>(ktiles) / static_cast<double>(s));
-        const double     mop   = 2.0 * kTiles[t].bm * kTiles[t].bn * kRowBytes * 1e-6 * kwork;   // per K tile (int8 ops)
-        double           us    = per * kt * mop / rate + m.ovh * std::ceil(per / m.occ);
-        if(s > 1) us += 3.0 + static_cast<double>(s + 1) * static_cast<double>(M) * static_cast<double>(N) * 4.0 / 5e6;
+        const double     rate = (m.r1 * share < m.rmax ? m.r1 * share : m.rmax) * tnf;
+        const double     kt   = std::ceil(static_cast<double>(ktiles) / static_cast<double>(s));
+        const double     mop  = 2.0 * kTiles[t].bm * kTiles[t].bn * kRowBytes * 1e-6 * kwork;    // per K tile (int8 ops)
+        const double     unit = per * kt * mop / rate, chip = wgs * kt * mop / (m.cap * tnf);
+        double           us   = (unit > chip ? unit : chip) + m.ovh * std::ceil(wgs / (cus * m.occ));
+        if(s > 1) us += 4.2 + static_cast<double>(s + 1) * static_cast<double>(M) * static_cast<double>(N) * 4.0 / 6.35e6;
         return us;
     };
+    // Candidates: no split, and the split counts that fill the units once, twice or up to their co-residency.  Tiles are
+    // visited from large to small and splits from few to many; a later candidate must win by 5 % (the larger tile
+    // moves fewer bytes per operation, and estimates that close are inside the model's error) -- unless the
+    // incumbent's tiles overhang the output by a quarter more than the candidate's: padding is where the model
+    // errs in the larger tile's favour.
     int     tile = 0, splits = 1;
-    double  best = -1.0;
+    double  best = -1.0, best_area = 0.0;
     for(int t = 0; t < kNumTiles; ++t)
     {
         if(force_tile >= 0 && force_tile < kNumTiles && t != force_tile) continue;
-        int64_t cand[2] = {1, 1};
-        int64_t s       = model[t].fill / ntiles(t);
-        if(s > ktiles / 8) s = ktiles / 8;                    // keep at least 8 K tiles per split
-        if(s > 128) s = 128;
-        if(s >= 2 && allow_split && !(force_tile >= 0 && force_splits < 0)) cand[1] = s;
-        for(int c = 0; c < 2; ++c)
+        int64_t cand[4] = {1, 1, 1, 1};
+        int     ncand   = 1;
+        if(allow_split && !(force_tile >= 0 && force_splits < 0))
+            for(int f = 0; f < 3; ++f)
+            {
+                const int64_t fill = f == 0 ? 256 : (f == 1 ? 512 : 256 * model[t].occ);
+                if(fill > 256 * model[t].occ) continue;
+                int64_t       s    = fill / ntiles(t);
+                if(s > ktiles / 8) s = ktiles / 8;                // keep at least 8 K tiles per split
+                if(s > 128) s = 128;
+                if(s >= 2 && s != cand[ncand - 1]) cand[ncand++] = s;
+            }
+        const double area = static_cast<double>(ntiles(t)) * kTiles[t].bm * kTiles[t].bn;
+        for(int c = 0; c < ncand; ++c)
         {
-            if(c == 1 && cand[1] == 1) break;
-            const double us = estimate(t, cand[c]);
-            if(best < 0.0 || us < best) { best = us; tile = t; splits = static_cast<int>(cand[c]); }
+            const double us     = estimate(t, cand[c]);
+            const double margin = best_area > 1.25 * area ? 1.0 : 0.95;
+            if(best < 0.0 || us < margin * best) { best = us; best_area = area; tile = t; splits = static_cast<int>(cand[c]); }
         }
     }
     if(force_splits >= 1 && allow_split) splits = force_splits;
