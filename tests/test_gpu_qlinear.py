@@ -88,6 +88,24 @@ def test_ragged_shapes_span_tiles_and_tails(tag, shape):
     run_case(case, tag, y_dtype=np.float16 if tag == Q.FP16 else np.float32)
 
 
+def test_seeded_random_shapes_with_the_planners_own_choices():
+    """Forty operator shapes drawn from a seeded generator (multiples of 16, from one tile to several tile rows
+    and K tiles, narrow and wide outputs), each with a drawn tag, weight granularity, rounding, input dtype and
+    epilogue; tile and K splits are the planner's.  Every stage is compared with the oracle as in `run_case`."""
+    import random
+    rnd = random.Random(2407)
+    for i in range(40):
+        m = rnd.choice([128, 256, 384, 512, 640, 1024, 1152, 2048, 3200, 144, 528, 1008, 4096])
+        n = rnd.choice([64, 128, 192, 256, 576, 768, 1024, 1536, 80, 208, 1344])
+        k = rnd.choice([64, 128, 256, 384, 640, 1024, 2048, 3072, 208, 336])
+        tag = rnd.choice([Q.INT8, Q.INT8, Q.FP16])
+        dump = rnd.choice([True, False])
+        case = wl.ragged_case(m, n, k, seed=1000 + i, dtype=rnd.choice([np.float32, np.float16]))
+        case.w_gran = rnd.choice(["tensor", "row"])
+        case.dy_round = rnd.choice(["nearest", "stochastic"])
+        run_case(case, tag, y_dtype=np.float16 if not dump else np.float32, dump_acc=dump)
+
+
 @pytest.mark.parametrize("tile", [0, 1, 2])
 @pytest.mark.parametrize("tag", [Q.INT8, Q.FP16, Q.FP32])
 def test_every_gemm_tile_shape_on_ragged_operators(tile, tag):
