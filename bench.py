@@ -245,6 +245,21 @@ def run(args):
             op.gemm_bwd_part("dx", dy, main)
         main.wait_stream(side)
 
+    def step_dw_beside_next():
+        """The serial step, except that every weight-gradient GEMM (nothing downstream needs it before the
+        optimizer) runs on a side stream (default priority) beside whatever the main stream does next: the data
+        gradient, then the next operator's conversions."""
+        side = side_streams[0]
+        for op, (x, w, dy) in zip(ops_objs, dev_in):
+            op.convert_w(w, main)
+            op.convert_act(x, main)
+            op.gemm_fwd(main)
+            op.convert_dy(dy, main)
+            side.wait_stream(main)
+            op.gemm_bwd_part("dw", dy, side)
+            op.gemm_bwd_part("dx", dy, main)
+        main.wait_stream(side)
+
     def step_weights_ahead():
         """The serial step, except that the weight conversions of the second and later operators (they depend on
         the weights only, which a training step knows from its start) run on a side stream (default priority)
@@ -344,6 +359,19 @@ def run(args):
         model_order = {"schedule": "forward of every operator, then backward in reverse order; each weight-gradient GEMM on "
                                    "a side stream beside the next operator's gradient conversion", "ms_per_step": round(ms3, 4),
                        "value": round(gemm_ops / (ms3 * 1e-3) / 1e12, 3), "unit": "TOPS"}
+    dw_beside = None
+    if len(ops_objs) > 1 and not args.no_extra_passes and all(hasattr(o, "gemm_bwd_part") for o in ops_objs):
+        for _ in range(max(2, args.warmup)):
+            step_dw_beside_next()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step_dw_beside_next()
+        torch.cuda.synchronize()
+        ms6 = (time.perf_counter() - t1) * 1e3 / args.steps
+        dw_beside = {"schedule": "serial step; each weight-gradient GEMM on a side stream beside the data gradient and the "
+                                 "next operator's conversions", "ms_per_step": round(ms6, 4),
+                     "value": round(gemm_ops / (ms6 * 1e-3) / 1e12, 3), "unit": "TOPS"}
     weights_ahead = None
     if len(ops_objs) > 1 and not args.no_extra_passes and not args.w_side_stream:
         for _ in range(max(2, args.warmup)):
@@ -596,6 +624,7 @@ def run(args):
         "hip_graph_replay": graph_replay,
         "model_order_dw_on_side_stream": model_order,
         "weights_converted_ahead_on_side_stream": weights_ahead,
+        "dw_on_side_stream_beside_next_operator": dw_beside,
         "epilogue_maximum": epilogue_max,
         "epilogue_codes": epilogue_codes,
     }
