@@ -451,6 +451,20 @@ def test_fp16_backward_of_int8_forward_validation():
     assert list(offs) == sorted(offs) and offs[0] == 0 and all(o % 256 == 0 for o in offs)
 
 
+def test_workspace_sizes_reflect_the_plans_of_the_benchmarked_shapes():
+    """The workspace a backward asks for is the sum of its split-K partial sums (plus column-sum partials), so it
+    shows which plan the GEMM planner picked.  Config 5's weight gradients (4096 x 1024 outputs, 16384 rows
+    contracted) take four K splits of the 256x256 tile and its data gradients none; the BERT-base shapes at 8192
+    tokens split their 768 x 3072 weight gradients into at most four."""
+    mib = 1 << 20
+    for (M, N, K) in ((16384, 4096, 1024), (16384, 1024, 4096)):
+        for tag in (qsync.INT8, qsync.FP16):
+            need = lib.qsync_qlinear_bwd_rm_workspace_bytes(tag, M, N, K)
+            assert 4 * 16 * mib <= need < 5 * 16 * mib, (tag, M, N, K, need)
+    small = lib.qsync_qlinear_bwd_rm_workspace_bytes(qsync.INT8, 8192, 3072, 768)
+    assert 2 * 9 * mib <= small <= 4 * 9 * mib + 4 * mib, small
+
+
 def test_row_major_backward_validation():
     f = lib.qsync_qlinear_bwd_rm
     need = lib.qsync_qlinear_bwd_rm_workspace_bytes(qsync.INT8, 256, 32, 48)
